@@ -1,0 +1,164 @@
+/*
+ * r3.h - C ABI of the replayed-routing MoE layer for AMD MI355X (gfx950).
+ *
+ * The calls follow Section 4.1 ("Implementation") of "Stabilizing MoE
+ * Reinforcement Learning by Aligning Training and Inference Routers"
+ * (arxiv 2510.11370): the MoE layer of the training pass is run with the
+ * expert mask recorded at inference, while the softmax is still taken over the
+ * training logits so that the router keeps its gradient.
+ *
+ * Notation: T tokens, d hidden size, E experts (the paper's M), K selected
+ * experts per token, F width of one SwiGLU expert.  A slot is one (token t, j)
+ * pair with id t*K + j; there are T*K slots.  "row" is a slot's position after
+ * the slots are sorted by expert.
+ *
+ * Conventions for every call
+ *  - All data pointers are DEVICE pointers owned by the caller.  The library
+ *    allocates nothing, frees nothing and keeps no state between calls.
+ *    Scratch comes from a caller workspace of at least
+ *    r3_workspace_bytes(desc, op) bytes, 256-byte aligned.
+ *  - `stream` is a hipStream_t (NULL = the default stream).  Calls enqueue work
+ *    and return; there is no hidden synchronisation.
+ *  - Matrices are row-major and dense.  Activations and weights have the dtype
+ *    desc->act (bf16 or f32); gates, logits and weight gradients are f32;
+ *    counts, offsets and permutations are int32.
+ *  - The return value is an r3_status.  Errors the host can see (NULL pointer,
+ *    bad sizes, misaligned pointer, small workspace) are returned before
+ *    anything is launched.  Errors only the device can see (an expert id >= E,
+ *    a duplicate id inside a token, a non-finite logit) OR bits into the
+ *    optional device word `status_word` (R3_DATA_*); the affected token's
+ *    outputs are then unspecified but no access goes out of bounds.
+ *  - Every result is deterministic: the same inputs give the same bits.
+ */
+#ifndef R3_H
+#define R3_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum r3_status {
+    R3_OK = 0,
+    R3_ERR_INVALID_ARG = 1, /* NULL pointer, size <= 0, K > E, misaligned pointer  */
+    R3_ERR_UNSUPPORTED = 2, /* index dtype too narrow for E, E or K above a kernel limit */
+    R3_ERR_WORKSPACE = 3,   /* workspace NULL or smaller than r3_workspace_bytes   */
+    R3_ERR_HIP = 4          /* a launch failed                                     */
+} r3_status;
+
+enum { R3_BF16 = 0, R3_F32 = 1 };     /* desc->act   */
+enum { R3_IDX_U8 = 0, R3_IDX_U16 = 1 }; /* desc->idx   */
+
+/* bits of the device status word */
+enum { R3_DATA_IDX_RANGE = 1, R3_DATA_IDX_DUP = 2, R3_DATA_NONFINITE = 4 };
+
+typedef enum r3_op {
+    R3_OP_REPLAY_GATE = 0,
+    R3_OP_PERMUTE = 1,
+    R3_OP_GROUPED_FFN = 2,
+    R3_OP_BACKWARD = 3
+} r3_op;
+
+typedef struct r3_layer_desc {
+    int32_t T, d, E, K, F;
+    int32_t act;              /* R3_BF16 or R3_F32                                  */
+    int32_t idx;              /* R3_IDX_U8 (E <= 256) or R3_IDX_U16 (E <= 65536)     */
+    int32_t reserved;         /* must be 0                                          */
+    int64_t idx_token_stride; /* elements between two tokens' records; 0 means K.
+                                 K gives a layer-major record [L][T][K]; L*K a
+                                 token-major one [T][L][K] (Section 4.2: the
+                                 inference side appends per token).               */
+} r3_layer_desc;
+
+/* Limits of this build: E <= 4096, K <= 64, K <= E. */
+
+/* Bytes of workspace `op` needs for this layer (0 is possible). */
+size_t r3_workspace_bytes(const r3_layer_desc *desc, r3_op op);
+
+/* Human-readable build string. */
+const char *r3_version(void);
+
+/*
+ * TopKMask(s, K) of Section 4.1 (second equation; used on the inference logits
+ * to make the record I_infer).  For each of the T rows of `logits` ([T, ld]
+ * f32, first E columns used) write the ids of the K largest entries to
+ * `idx_out` ([T] records of K ids, stride desc->idx_token_stride), ascending by
+ * id.  Ties go to the lower id; NaN ranks below every number; -0 equals +0.
+ * A NaN or infinity sets R3_DATA_NONFINITE.
+ */
+int r3_record_topk(const r3_layer_desc *desc, const float *logits, int64_t ld,
+                   void *idx_out, int32_t *status_word, void *stream);
+
+/*
+ * Router logits and replay gate of Section 4.1: s = x W_r (+ bias), then
+ * g[t,j] = exp(s[t,idx[t,j]]) / sum_i exp(s[t,idx[t,i]]) over the K recorded
+ * experts (replay-gate equation).  x [T,d] act, W_r [d,E] act, bias [E] f32 or
+ * NULL, idx the record, gates [T,K] f32 aligned with idx.  Logits are
+ * accumulated and kept in f32.  Optional outputs: logits_out [T,E] f32;
+ * agree_out int64[2] which is INCREMENTED by {tokens whose own top-K set equals
+ * the recorded set, total experts the two sets share} (Section 3.2, router
+ * level; zero it before the first call).
+ */
+int r3_replay_gate(const r3_layer_desc *desc, const void *x, const void *W_r,
+                   const float *bias, const void *idx, float *gates,
+                   float *logits_out, int64_t *agree_out, int32_t *status_word,
+                   void *ws, size_t ws_bytes, void *stream);
+
+/*
+ * Dispatch implied by the replay-output equation of Section 4.1: sort the T*K
+ * slots by recorded expert, stably (ascending slot id inside an expert).
+ * counts [E], offsets [E+1] (exclusive prefix sum), inv_perm [T*K] slot -> row,
+ * perm [T*K] row -> slot, Xp [T*K,d] act with Xp[row] = x[perm[row] / K]
+ * (Xp may be NULL to skip the row gather).  Sets R3_DATA_IDX_RANGE /
+ * R3_DATA_IDX_DUP for a bad record.
+ */
+int r3_permute(const r3_layer_desc *desc, const void *x, const void *idx,
+               int32_t *counts, int32_t *offsets, int32_t *inv_perm, int32_t *perm,
+               void *Xp, int32_t *status_word, void *ws, size_t ws_bytes,
+               void *stream);
+
+/*
+ * The expert networks E_i of the replay-output equation, as bias-free SwiGLU:
+ * for expert e and its rows r in [offsets[e], offsets[e+1]):
+ *   A = Xp W_gate[e], B = Xp W_up[e], H = silu(A) * B, Yp = H W_down[e].
+ * Xp [T*K,d]; W_gate, W_up [E,d,F]; W_down [E,F,d]; Yp [T*K,d]; H [T*K,F]
+ * (required: it is the second GEMM's input and the backward's saved value);
+ * A_save, B_save [T*K,F] or both NULL (forward only).  All act dtype; f32
+ * accumulation; `offsets` is read on the device.
+ */
+int r3_grouped_ffn(const r3_layer_desc *desc, const void *Xp, const int32_t *offsets,
+                   const void *W_gate, const void *W_up, const void *W_down,
+                   void *Yp, void *H, void *A_save, void *B_save, void *ws,
+                   size_t ws_bytes, void *stream);
+
+/*
+ * Replay output of Section 4.1: y[t] = sum_j gates[t,j] * Yp[inv_perm[t*K+j]],
+ * j ascending, f32 accumulation, one rounding to act.  y [T,d].
+ */
+int r3_combine(const r3_layer_desc *desc, const void *Yp, const float *gates,
+               const int32_t *inv_perm, void *y, void *stream);
+
+/*
+ * Backward of the replayed layer (Section 4.1, purpose (b): the gradient still
+ * reaches the router logits through the softmax; the recorded mask is a
+ * constant).  Given dy [T,d] act and the forward's tensors, writes the
+ * gradient of sum(dy*y):  dx [T,d] act;  dW_r [d,E], dW_gate, dW_up [E,d,F],
+ * dW_down [E,F,d] f32;  dbias [E] f32 or NULL.  accumulate = 0 overwrites the
+ * weight gradients, 1 adds to them.  Experts outside a token's recorded set get
+ * exactly zero router gradient from that token.
+ */
+int r3_moe_backward(const r3_layer_desc *desc, const void *dy, const void *x,
+                    const void *W_r, const void *idx, const float *gates,
+                    const int32_t *inv_perm, const int32_t *perm,
+                    const int32_t *offsets, const void *Xp, const void *A,
+                    const void *B, const void *H, const void *Yp, const void *W_gate,
+                    const void *W_up, const void *W_down, void *dx, float *dW_r,
+                    float *dW_gate, float *dW_up, float *dW_down, float *dbias,
+                    int accumulate, void *ws, size_t ws_bytes, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* R3_H */

@@ -185,3 +185,34 @@ def agreement(idx_a, idx_b):
     out = np.zeros(2, np.int64)
     lib().oracle_agreement(T, K, _p(idx_a), _p(idx_b), _p(out))
     return int(out[0]), int(out[1])
+
+
+def gate_backward(dy, o, g, idx, inv_perm, E):
+    """Backward through combine and masked softmax: returns dO, dz, ds."""
+    dy, o, g, idx, inv_perm = _f32(dy), _f64(o), _f64(g), _i32(idx), _i32(inv_perm)
+    T, d = dy.shape
+    K = idx.shape[1]
+    dO = np.zeros((T * K, d), np.float64)
+    dz = np.empty((T, K), np.float64)
+    ds = np.empty((T, E), np.float64)
+    lib().oracle_gate_backward(T, d, E, K, _p(dy), _p(o), _p(g), _p(idx), _p(inv_perm), _p(dO), _p(dz),
+                               _p(ds))
+    return dO, dz, ds
+
+
+def grouped_ffn_backward(Xp, offsets, Wg, Wu, Wd, a, b, h, dO):
+    """Expert backward on row segments: returns da, db, dXp, dWg, dWu, dWd."""
+    Xp, offsets = _f32(Xp), _i32(offsets)
+    Wg, Wu, Wd = _f32(Wg), _f32(Wu), _f32(Wd)
+    E, d, F = Wg.shape
+    S = Xp.shape[0]
+    da = np.zeros((S, F), np.float64)
+    db = np.zeros((S, F), np.float64)
+    dXp = np.zeros((S, d), np.float64)
+    dWg = np.zeros((E, d, F), np.float64)
+    dWu = np.zeros((E, d, F), np.float64)
+    dWd = np.zeros((E, F, d), np.float64)
+    lib().oracle_grouped_ffn_backward(E, d, F, _p(offsets), _p(Xp), _p(Wg), _p(Wu), _p(Wd), _p(_f64(a)),
+                                      _p(_f64(b)), _p(_f64(h)), _p(_f64(dO)), _p(da), _p(db), _p(dXp),
+                                      _p(dWg), _p(dWu), _p(dWd))
+    return da, db, dXp, dWg, dWu, dWd

@@ -1,0 +1,231 @@
+// C ABI of the replayed MoE layer: argument checks, workspace carving and the
+// launch sequence of each call.  See include/r3.h for the contract.
+#include <cstdlib>
+#include <cstring>
+
+#include "r3_kernels.h"
+
+using namespace r3;
+
+namespace {
+
+struct Dims {
+    int T, d, E, K, F, act, idx;
+    int64_t stride, S;
+    int eb;  // bytes per activation element
+};
+
+int check_desc(const r3_layer_desc *D, Dims &m) {
+    if (!D) return R3_ERR_INVALID_ARG;
+    if (D->T <= 0 || D->d <= 0 || D->E <= 0 || D->K <= 0 || D->F <= 0 || D->K > D->E || D->reserved != 0)
+        return R3_ERR_INVALID_ARG;
+    if (D->act != R3_BF16 && D->act != R3_F32) return R3_ERR_INVALID_ARG;
+    if (D->idx != R3_IDX_U8 && D->idx != R3_IDX_U16) return R3_ERR_INVALID_ARG;
+    if (D->idx_token_stride != 0 && D->idx_token_stride < D->K) return R3_ERR_INVALID_ARG;
+    if ((D->idx == R3_IDX_U8 && D->E > 256) || D->E > kMaxE || D->K > kMaxK) return R3_ERR_UNSUPPORTED;
+    if ((int64_t)D->T * D->K > 0x7fffffffLL / 2) return R3_ERR_UNSUPPORTED;
+    m.T = D->T; m.d = D->d; m.E = D->E; m.K = D->K; m.F = D->F; m.act = D->act; m.idx = D->idx;
+    m.stride = D->idx_token_stride ? D->idx_token_stride : D->K;
+    m.S = (int64_t)D->T * D->K;
+    m.eb = D->act == R3_BF16 ? 2 : 4;
+    return R3_OK;
+}
+
+bool aligned(const void *p, size_t a) { return ((uintptr_t)p % a) == 0; }
+bool force_simt() {
+    const char *v = getenv("R3_FORCE_SIMT");
+    return v && v[0] == '1';
+}
+bool use_mfma_ffn(const Dims &m) { return m.act == R3_BF16 && mfma_ffn_supported(m.d, m.F) && !force_simt(); }
+bool use_mfma_router(const Dims &m) { return m.act == R3_BF16 && mfma_router_supported(m.d, m.E) && !force_simt(); }
+
+struct BwdWs {
+    size_t dYp, dz, ds, WrT, dA, dB, tiles, part, total;
+};
+BwdWs bwd_layout(const Dims &m) {
+    BwdWs w;
+    size_t o = 0;
+    auto take = [&](size_t bytes) { size_t at = o; o += align_up(bytes, 256); return at; };
+    w.dYp = take((size_t)m.S * m.d * m.eb);  // later reused for dXp
+    w.dz = take((size_t)m.T * m.K * sizeof(float));
+    w.ds = take((size_t)m.T * m.E * m.eb);
+    w.WrT = take((size_t)m.E * m.d * m.eb);
+    w.dA = take((size_t)m.S * m.F * m.eb);
+    w.dB = take((size_t)m.S * m.F * m.eb);
+    w.tiles = take(use_mfma_ffn(m) ? mfma_tiles_bytes(m.S, m.E) : 0);
+    w.part = take(use_mfma_router(m) ? mfma_dwr_ws_bytes(m.T, m.d, m.E) : 0);
+    w.total = o;
+    return w;
+}
+
+int hip_rc(hipError_t e) { return e == hipSuccess ? R3_OK : R3_ERR_HIP; }
+
+}  // namespace
+
+extern "C" {
+
+const char *r3_version(void) { return "r3-mi355x 0.1 (gfx950, bf16 MFMA + f32 SIMT)"; }
+
+size_t r3_workspace_bytes(const r3_layer_desc *desc, r3_op op) {
+    Dims m;
+    if (check_desc(desc, m) != R3_OK) return 0;
+    switch (op) {
+        case R3_OP_REPLAY_GATE: return align_up((size_t)m.T * m.E * sizeof(float), 256);
+        case R3_OP_PERMUTE: return permute_ws_bytes(m.T, m.E, m.K);
+        case R3_OP_GROUPED_FFN: return use_mfma_ffn(m) ? mfma_tiles_bytes(m.S, m.E) : 0;
+        case R3_OP_BACKWARD: return bwd_layout(m).total;
+    }
+    return 0;
+}
+
+int r3_record_topk(const r3_layer_desc *desc, const float *logits, int64_t ld, void *idx_out,
+                   int32_t *status_word, void *stream) {
+    Dims m;
+    int rc = check_desc(desc, m);
+    if (rc) return rc;
+    if (!logits || !idx_out || ld < m.E || !aligned(logits, 4)) return R3_ERR_INVALID_ARG;
+    if (m.idx == R3_IDX_U16 && !aligned(idx_out, 2)) return R3_ERR_INVALID_ARG;
+    return hip_rc(launch_record_topk(m.T, m.E, m.K, logits, ld, idx_out, m.idx, m.stride, status_word,
+                                     (hipStream_t)stream));
+}
+
+int r3_replay_gate(const r3_layer_desc *desc, const void *x, const void *W_r, const float *bias,
+                   const void *idx, float *gates, float *logits_out, int64_t *agree_out,
+                   int32_t *status_word, void *ws, size_t ws_bytes, void *stream) {
+    (void)status_word;
+    Dims m;
+    int rc = check_desc(desc, m);
+    if (rc) return rc;
+    if (!x || !W_r || !idx || !gates) return R3_ERR_INVALID_ARG;
+    if (!aligned(x, 16) || !aligned(W_r, 16) || !aligned(gates, 4) || (logits_out && !aligned(logits_out, 16)) ||
+        (bias && !aligned(bias, 16)) || (agree_out && !aligned(agree_out, 8)))
+        return R3_ERR_INVALID_ARG;
+    hipStream_t s = (hipStream_t)stream;
+    float *logits = logits_out;
+    if (!logits) {
+        if (!ws || ws_bytes < r3_workspace_bytes(desc, R3_OP_REPLAY_GATE) || !aligned(ws, 256))
+            return R3_ERR_WORKSPACE;
+        logits = (float *)ws;
+    }
+    hipError_t e;
+    if (use_mfma_router(m)) e = mfma_router_logits(m.T, m.d, m.E, x, W_r, bias, logits, s);
+    else e = simt_router_logits(m.T, m.d, m.E, m.act, x, W_r, bias, logits, s);
+    if (e != hipSuccess) return R3_ERR_HIP;
+    e = launch_gate(m.T, m.E, m.K, logits, idx, m.idx, m.stride, gates, s);
+    if (e != hipSuccess) return R3_ERR_HIP;
+    if (agree_out) e = launch_agreement(m.T, m.E, m.K, logits, idx, m.idx, m.stride, agree_out, s);
+    return hip_rc(e);
+}
+
+int r3_permute(const r3_layer_desc *desc, const void *x, const void *idx, int32_t *counts,
+               int32_t *offsets, int32_t *inv_perm, int32_t *perm, void *Xp, int32_t *status_word,
+               void *ws, size_t ws_bytes, void *stream) {
+    Dims m;
+    int rc = check_desc(desc, m);
+    if (rc) return rc;
+    if (!idx || !counts || !offsets || !inv_perm || !perm || (Xp && !x)) return R3_ERR_INVALID_ARG;
+    if ((Xp && (!aligned(Xp, 16) || !aligned(x, 16))) || !aligned(counts, 4) || !aligned(offsets, 4) ||
+        !aligned(inv_perm, 4) || !aligned(perm, 4))
+        return R3_ERR_INVALID_ARG;
+    if (!ws || ws_bytes < permute_ws_bytes(m.T, m.E, m.K) || !aligned(ws, 256)) return R3_ERR_WORKSPACE;
+    return hip_rc(launch_permute(m.T, m.d, m.E, m.K, m.eb, x, idx, m.idx, m.stride, counts, offsets, inv_perm,
+                                 perm, Xp, status_word, ws, (hipStream_t)stream));
+}
+
+int r3_grouped_ffn(const r3_layer_desc *desc, const void *Xp, const int32_t *offsets, const void *W_gate,
+                   const void *W_up, const void *W_down, void *Yp, void *H, void *A_save, void *B_save,
+                   void *ws, size_t ws_bytes, void *stream) {
+    Dims m;
+    int rc = check_desc(desc, m);
+    if (rc) return rc;
+    if (!Xp || !offsets || !W_gate || !W_up || !W_down || !Yp || !H || ((A_save == nullptr) != (B_save == nullptr)))
+        return R3_ERR_INVALID_ARG;
+    if (!aligned(Xp, 16) || !aligned(W_gate, 16) || !aligned(W_up, 16) || !aligned(W_down, 16) ||
+        !aligned(Yp, 16) || !aligned(H, 16) || !aligned(A_save, 16) || !aligned(B_save, 16))
+        return R3_ERR_INVALID_ARG;
+    hipStream_t s = (hipStream_t)stream;
+    if (use_mfma_ffn(m)) {
+        if (!ws || ws_bytes < mfma_tiles_bytes(m.S, m.E) || !aligned(ws, 256)) return R3_ERR_WORKSPACE;
+        int32_t *tiles = (int32_t *)ws;
+        if (mfma_build_tiles(m.E, offsets, tiles, s) != hipSuccess) return R3_ERR_HIP;
+        return hip_rc(mfma_ffn_forward(m.S, m.d, m.E, m.F, Xp, offsets, tiles, W_gate, W_up, W_down, Yp, H,
+                                       A_save, B_save, s));
+    }
+    if (simt_ffn1((int)m.S, m.d, m.E, m.F, m.act, Xp, offsets, W_gate, W_up, H, A_save, B_save, s) != hipSuccess)
+        return R3_ERR_HIP;
+    return hip_rc(simt_ffn2((int)m.S, m.d, m.E, m.F, m.act, H, offsets, W_down, Yp, s));
+}
+
+int r3_combine(const r3_layer_desc *desc, const void *Yp, const float *gates, const int32_t *inv_perm,
+               void *y, void *stream) {
+    Dims m;
+    int rc = check_desc(desc, m);
+    if (rc) return rc;
+    if (!Yp || !gates || !inv_perm || !y) return R3_ERR_INVALID_ARG;
+    if (!aligned(Yp, 16) || !aligned(y, 16) || !aligned(gates, 4) || !aligned(inv_perm, 4))
+        return R3_ERR_INVALID_ARG;
+    return hip_rc(launch_combine(m.T, m.d, m.K, m.act, Yp, gates, inv_perm, y, (hipStream_t)stream));
+}
+
+int r3_moe_backward(const r3_layer_desc *desc, const void *dy, const void *x, const void *W_r,
+                    const void *idx, const float *gates, const int32_t *inv_perm, const int32_t *perm,
+                    const int32_t *offsets, const void *Xp, const void *A, const void *B, const void *H,
+                    const void *Yp, const void *W_gate, const void *W_up, const void *W_down, void *dx,
+                    float *dW_r, float *dW_gate, float *dW_up, float *dW_down, float *dbias,
+                    int accumulate, void *ws, size_t ws_bytes, void *stream) {
+    (void)perm;
+    Dims m;
+    int rc = check_desc(desc, m);
+    if (rc) return rc;
+    const void *ptrs[] = {dy, x, W_r, idx, gates, inv_perm, offsets, Xp, A, B, H, Yp, W_gate, W_up, W_down,
+                          dx, dW_r, dW_gate, dW_up, dW_down};
+    for (const void *p : ptrs)
+        if (!p) return R3_ERR_INVALID_ARG;
+    const void *a16[] = {dy, x, W_r, Xp, A, B, H, Yp, W_gate, W_up, W_down, dx, dW_r, dW_gate, dW_up, dW_down};
+    for (const void *p : a16)
+        if (!aligned(p, 16)) return R3_ERR_INVALID_ARG;
+    if (accumulate != 0 && accumulate != 1) return R3_ERR_INVALID_ARG;
+    const BwdWs w = bwd_layout(m);
+    if (!ws || ws_bytes < w.total || !aligned(ws, 256)) return R3_ERR_WORKSPACE;
+    hipStream_t s = (hipStream_t)stream;
+    char *base = (char *)ws;
+    void *dYp = base + w.dYp, *ds = base + w.ds, *WrT = base + w.WrT, *dA = base + w.dA, *dB = base + w.dB;
+    void *dXp = dYp;  // dYp is dead once dW_down and dH are done
+    float *dz = (float *)(base + w.dz);
+    const int S = (int)m.S;
+
+    // combine and masked softmax:  dYp, dz, dense ds
+    if (launch_gate_backward(m.T, m.d, m.E, m.K, m.act, dy, Yp, gates, inv_perm, idx, m.idx, m.stride, dYp, dz,
+                             ds, s) != hipSuccess)
+        return R3_ERR_HIP;
+    // router:  dW_r = x^T ds, dbias = column sums
+    hipError_t e;
+    if (use_mfma_router(m)) e = mfma_dwr(m.T, m.d, m.E, x, ds, (float *)(base + w.part), dW_r, accumulate, s);
+    else e = simt_dwr(m.T, m.d, m.E, m.act, x, ds, dW_r, accumulate, s);
+    if (e != hipSuccess) return R3_ERR_HIP;
+    if (dbias && launch_colsum(m.T, m.E, m.act, ds, dbias, accumulate, s) != hipSuccess) return R3_ERR_HIP;
+    if (launch_transpose(m.d, m.E, m.act, W_r, WrT, s) != hipSuccess) return R3_ERR_HIP;
+    // experts
+    if (use_mfma_ffn(m)) {
+        int32_t *tiles = (int32_t *)(base + w.tiles);
+        if (mfma_build_tiles(m.E, offsets, tiles, s) != hipSuccess) return R3_ERR_HIP;
+        if (mfma_ffn_dh(m.S, m.d, m.E, m.F, dYp, offsets, tiles, W_down, A, B, dA, dB, s) != hipSuccess)
+            return R3_ERR_HIP;
+        if (mfma_wgrad(m.E, m.F, m.d, H, dYp, offsets, dW_down, accumulate, s) != hipSuccess) return R3_ERR_HIP;
+        if (mfma_wgrad(m.E, m.d, m.F, Xp, dA, offsets, dW_gate, accumulate, s) != hipSuccess) return R3_ERR_HIP;
+        if (mfma_wgrad(m.E, m.d, m.F, Xp, dB, offsets, dW_up, accumulate, s) != hipSuccess) return R3_ERR_HIP;
+        if (mfma_ffn_dxp(m.S, m.d, m.E, m.F, dA, dB, offsets, tiles, W_gate, W_up, dXp, s) != hipSuccess)
+            return R3_ERR_HIP;
+    } else {
+        if (simt_dh(S, m.d, m.E, m.F, m.act, dYp, offsets, W_down, A, B, dA, dB, s) != hipSuccess) return R3_ERR_HIP;
+        if (simt_wgrad(m.E, m.F, m.d, m.act, H, dYp, offsets, dW_down, accumulate, s) != hipSuccess) return R3_ERR_HIP;
+        if (simt_wgrad(m.E, m.d, m.F, m.act, Xp, dA, offsets, dW_gate, accumulate, s) != hipSuccess) return R3_ERR_HIP;
+        if (simt_wgrad(m.E, m.d, m.F, m.act, Xp, dB, offsets, dW_up, accumulate, s) != hipSuccess) return R3_ERR_HIP;
+        if (simt_dxp(S, m.d, m.E, m.F, m.act, dA, dB, offsets, W_gate, W_up, dXp, s) != hipSuccess) return R3_ERR_HIP;
+    }
+    // dx = un-permuted expert gradients + router term
+    return hip_rc(launch_dx_finish(m.T, m.d, m.E, m.K, m.act, dXp, WrT, dz, inv_perm, idx, m.idx, m.stride, dx,
+                                   s));
+}
+
+}  // extern "C"

@@ -1,0 +1,427 @@
+// Dense steps of the replayed MoE layer on bf16 MFMA (gfx950):
+//   router logits  s = x W_r                       (Section 4.1, first equation)
+//   grouped SwiGLU expert FFN, forward              (the E_i of the output equation)
+//   its data gradients and weight gradients, and the router weight gradient.
+// Every kernel is one instance of the tile loop in r3_mfma.h with its own
+// operand addressing and epilogue.  Expert segments are ragged: a small kernel
+// turns `offsets` into a list of (expert, first row) row tiles on the device, so
+// nothing returns to the host between the permutation and the contractions.
+#include "r3_kernels.h"
+#include "r3_mfma.h"
+
+namespace r3 {
+
+// ---------------------------------------------------------------------------
+// Row-tile table: tiles[0] = number of tiles, then (expert, row0) pairs from
+// tiles[2].  One block; experts in ascending order, rows ascending.
+// ---------------------------------------------------------------------------
+__global__ void __launch_bounds__(1024)
+build_row_tiles_kernel(int E, int BQ, const int32_t *__restrict__ offsets, int32_t *__restrict__ tiles) {
+    __shared__ int32_t start[kMaxE + 1];
+    if (threadIdx.x == 0) {
+        int run = 0;
+        for (int e = 0; e < E; ++e) {
+            start[e] = run;
+            run += (offsets[e + 1] - offsets[e] + BQ - 1) / BQ;
+        }
+        start[E] = run;
+        tiles[0] = run;
+        tiles[1] = 0;
+    }
+    __syncthreads();
+    for (int e = threadIdx.x; e < E; e += blockDim.x) {
+        const int n = start[e + 1] - start[e];
+        for (int i = 0; i < n; ++i) {
+            tiles[2 + 2 * (start[e] + i)] = e;
+            tiles[3 + 2 * (start[e] + i)] = offsets[e] + i * BQ;
+        }
+    }
+}
+
+static inline int max_row_tiles(int64_t S, int E, int BQ) { return (int)(S / BQ) + E; }
+static inline int grid_for(int64_t tiles) { return (int)((tiles + 7) / 8 * 8); }
+
+__device__ __forceinline__ uint2 pack4(float a, float b, float c, float d) {
+    return make_uint2(pack_bf16x2(a, b), pack_bf16x2(c, d));
+}
+__device__ __forceinline__ void unpack4(uint2 v, float *f) {
+    f[0] = __uint_as_float(v.x << 16);
+    f[1] = __uint_as_float(v.x & 0xffff0000u);
+    f[2] = __uint_as_float(v.y << 16);
+    f[3] = __uint_as_float(v.y & 0xffff0000u);
+}
+
+// ---------------------------------------------------------------------------
+// FFN, first contraction + SwiGLU:  A = Xp Wg, B = Xp Wu, H = silu(A) * B.
+// The P tile interleaves 32-feature blocks of W_gate and W_up so that a wave
+// holds both pre-activations of the same (row, feature) in the same lane.
+// ---------------------------------------------------------------------------
+template <class TL>
+__global__ void __launch_bounds__(TL::NT, 2)
+ffn1_kernel(int S, int d, int F, const bf16_t *__restrict__ Xp, const int32_t *__restrict__ offsets,
+            const int32_t *__restrict__ tiles, const bf16_t *__restrict__ Wg, const bf16_t *__restrict__ Wu,
+            bf16_t *__restrict__ H, bf16_t *__restrict__ A, bf16_t *__restrict__ B) {
+    extern __shared__ __attribute__((aligned(16))) char lds[];
+    constexpr int BF = TL::BP / 2;  // features per tile
+    const int npt = F / BF;
+    const int id = xcd_tile_id(tiles[0] * npt);
+    if (id < 0) return;
+    const int tile = id / npt, pt = id - tile * npt;
+    const int e = tiles[2 + 2 * tile], row0 = tiles[3 + 2 * tile];
+    const int row_end = offsets[e + 1];
+    const int f0 = pt * BF;
+    const bf16_t *wg = Wg + (int64_t)e * d * F, *wu = Wu + (int64_t)e * d * F;
+
+    auto fp = [&](int kt, int k, int c) -> uint4 {
+        const int blk = c >> 2;
+        const bf16_t *src = (blk & 1) ? wu : wg;
+        return ld16(src + (int64_t)(kt * TL::BK + k) * F + f0 + (blk >> 1) * 32 + (c & 3) * 8);
+    };
+    auto fq = [&](int kt, int r, int c) -> uint4 {
+        const int row = min(row0 + r, S - 1);  // rows past the segment are never stored
+        return ld16(Xp + (int64_t)row * d + kt * TL::BK + c * 8);
+    };
+    f32x16_t acc[TL::TP][TL::TQ];
+    zero_acc<TL>(acc);
+    mfma_mainloop<TL, true, false>(acc, d / TL::BK, fp, fq, lds);
+
+    const int wave = threadIdx.x >> 6, lane = lane_id();
+    const int wp = wave % TL::WP, wq = wave / TL::WP;
+#pragma unroll
+    for (int tp = 0; tp < TL::TP; tp += 2)
+#pragma unroll
+        for (int tq = 0; tq < TL::TQ; ++tq) {
+            const int row = row0 + wq * TL::WTQ + tq * 32 + (lane & 31);
+            if (row >= row_end) continue;
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                const int f = f0 + (wp * TL::WTP + tp * 32) / 2 + g * 8 + (lane >> 5) * 4;
+                float a[4], b[4], h[4];
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    a[i] = acc[tp][tq][4 * g + i];
+                    b[i] = acc[tp + 1][tq][4 * g + i];
+                    h[i] = a[i] * sigmoidf_(a[i]) * b[i];
+                }
+                const int64_t o = (int64_t)row * F + f;
+                *(uint2 *)(H + o) = pack4(h[0], h[1], h[2], h[3]);
+                if (A) *(uint2 *)(A + o) = pack4(a[0], a[1], a[2], a[3]);
+                if (B) *(uint2 *)(B + o) = pack4(b[0], b[1], b[2], b[3]);
+            }
+        }
+}
+
+// ---------------------------------------------------------------------------
+// Row-ragged contraction with a plain or SwiGLU-backward epilogue:
+//   out[row][c0+p] = sum_k Q[row][k] * Pmat[e](p, k)
+// MODE 0: Yp = H Wd          P from Wd[e] [F,d]  (TR: k rows, features c), K = F
+// MODE 1: dH = dYp Wd^T      P from Wd[e] [F,d]  (KC: feature rows f),      K = d
+//         epilogue dA = dh*B*silu'(A), dB = dh*silu(A)
+// MODE 2: dXp = dA Wg^T + dB Wu^T   P from Wg[e], Wu[e] [d,F] (KC: rows c), K = 2F
+// ---------------------------------------------------------------------------
+template <class TL, int MODE>
+__global__ void __launch_bounds__(TL::NT, 2)
+rowgemm_kernel(int S, int d, int F, const bf16_t *__restrict__ Q0, const bf16_t *__restrict__ Q1,
+               const int32_t *__restrict__ offsets, const int32_t *__restrict__ tiles,
+               const bf16_t *__restrict__ W0, const bf16_t *__restrict__ W1, const bf16_t *__restrict__ A,
+               const bf16_t *__restrict__ B, bf16_t *__restrict__ out0, bf16_t *__restrict__ out1) {
+    extern __shared__ __attribute__((aligned(16))) char lds[];
+    const int NOUT = (MODE == 1) ? F : d;  // width of the output
+    const int npt = NOUT / TL::BP;
+    const int id = xcd_tile_id(tiles[0] * npt);
+    if (id < 0) return;
+    const int tile = id / npt, pt = id - tile * npt;
+    const int e = tiles[2 + 2 * tile], row0 = tiles[3 + 2 * tile];
+    const int row_end = offsets[e + 1];
+    const int p0 = pt * TL::BP;
+    const bf16_t *w0 = W0 + (int64_t)e * d * F;
+    const bf16_t *w1 = (MODE == 2) ? W1 + (int64_t)e * d * F : nullptr;
+    const int nk_half = F / TL::BK;
+
+    f32x16_t acc[TL::TP][TL::TQ];
+    zero_acc<TL>(acc);
+    if constexpr (MODE == 0) {
+        auto fp = [&](int kt, int k, int c) -> uint4 {
+            return ld16(w0 + (int64_t)(kt * TL::BK + k) * d + p0 + c * 8);
+        };
+        auto fq = [&](int kt, int r, int c) -> uint4 {
+            return ld16(Q0 + (int64_t)min(row0 + r, S - 1) * F + kt * TL::BK + c * 8);
+        };
+        mfma_mainloop<TL, true, false>(acc, F / TL::BK, fp, fq, lds);
+    } else if constexpr (MODE == 1) {
+        auto fp = [&](int kt, int r, int c) -> uint4 {
+            return ld16(w0 + (int64_t)(p0 + r) * d + kt * TL::BK + c * 8);
+        };
+        auto fq = [&](int kt, int r, int c) -> uint4 {
+            return ld16(Q0 + (int64_t)min(row0 + r, S - 1) * d + kt * TL::BK + c * 8);
+        };
+        mfma_mainloop<TL, false, false>(acc, d / TL::BK, fp, fq, lds);
+    } else {
+        auto fp = [&](int kt, int r, int c) -> uint4 {
+            const bool up = kt >= nk_half;
+            const bf16_t *src = up ? w1 : w0;
+            return ld16(src + (int64_t)(p0 + r) * F + (kt - (up ? nk_half : 0)) * TL::BK + c * 8);
+        };
+        auto fq = [&](int kt, int r, int c) -> uint4 {
+            const bool up = kt >= nk_half;
+            const bf16_t *src = up ? Q1 : Q0;
+            return ld16(src + (int64_t)min(row0 + r, S - 1) * F + (kt - (up ? nk_half : 0)) * TL::BK + c * 8);
+        };
+        mfma_mainloop<TL, false, false>(acc, 2 * nk_half, fp, fq, lds);
+    }
+
+    for_each_quad<TL>([&](int tp, int tq, int g, int p, int q) {
+        const int row = row0 + q;
+        if (row >= row_end) return;
+        const int64_t o = (int64_t)row * NOUT + p0 + p;
+        const float v0 = acc[tp][tq][4 * g], v1 = acc[tp][tq][4 * g + 1], v2 = acc[tp][tq][4 * g + 2],
+                    v3 = acc[tp][tq][4 * g + 3];
+        if constexpr (MODE == 1) {
+            float a[4], b[4], da[4], db[4];
+            const float dh[4] = {v0, v1, v2, v3};
+            unpack4(*(const uint2 *)(A + o), a);
+            unpack4(*(const uint2 *)(B + o), b);
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const float sg = sigmoidf_(a[i]);
+                da[i] = dh[i] * b[i] * sg * (1.0f + a[i] * (1.0f - sg));
+                db[i] = dh[i] * a[i] * sg;
+            }
+            *(uint2 *)(out0 + o) = pack4(da[0], da[1], da[2], da[3]);
+            *(uint2 *)(out1 + o) = pack4(db[0], db[1], db[2], db[3]);
+        } else {
+            *(uint2 *)(out0 + o) = pack4(v0, v1, v2, v3);
+        }
+    });
+}
+
+// ---------------------------------------------------------------------------
+// Weight gradients:  out[e][q][p] (+)= sum_{r in expert e} Qs[r][q] * Ps[r][p]
+// Both operands are [row][feature] matrices, so both tiles are TR; the k loop
+// runs over the expert's rows and the tail past the segment is zero-filled.
+// ---------------------------------------------------------------------------
+template <class TL>
+__global__ void __launch_bounds__(TL::NT, 2)
+wgrad_kernel(int E, int NQd, int NPd, const bf16_t *__restrict__ Qs, const bf16_t *__restrict__ Ps,
+             const int32_t *__restrict__ offsets, float *__restrict__ out, int accumulate) {
+    extern __shared__ __attribute__((aligned(16))) char lds[];
+    const int nqt = NQd / TL::BQ, npt = NPd / TL::BP;
+    const int id = xcd_tile_id(E * nqt * npt);
+    if (id < 0) return;
+    const int e = id / (nqt * npt);
+    const int rem = id - e * nqt * npt;
+    const int qt = rem / npt, pt = rem - qt * npt;
+    const int r0 = offsets[e], r1 = offsets[e + 1];
+    const int q0 = qt * TL::BQ, p0 = pt * TL::BP;
+
+    auto fp = [&](int kt, int k, int c) -> uint4 {
+        const int r = r0 + kt * TL::BK + k;
+        return r < r1 ? ld16(Ps + (int64_t)r * NPd + p0 + c * 8) : zero16();
+    };
+    auto fq = [&](int kt, int k, int c) -> uint4 {
+        const int r = r0 + kt * TL::BK + k;
+        return r < r1 ? ld16(Qs + (int64_t)r * NQd + q0 + c * 8) : zero16();
+    };
+    f32x16_t acc[TL::TP][TL::TQ];
+    zero_acc<TL>(acc);
+    mfma_mainloop<TL, true, true>(acc, (r1 - r0 + TL::BK - 1) / TL::BK, fp, fq, lds);
+
+    float *o = out + (int64_t)e * NQd * NPd;
+    for_each_quad<TL>([&](int tp, int tq, int g, int p, int q) {
+        float4 *dst = (float4 *)(o + (int64_t)(q0 + q) * NPd + p0 + p);
+        float4 v = make_float4(acc[tp][tq][4 * g], acc[tp][tq][4 * g + 1], acc[tp][tq][4 * g + 2],
+                               acc[tp][tq][4 * g + 3]);
+        if (accumulate) {
+            const float4 old = *dst;
+            v.x += old.x; v.y += old.y; v.z += old.z; v.w += old.w;
+        }
+        *dst = v;
+    });
+}
+
+// ---------------------------------------------------------------------------
+// Router logits  s[t][e] = sum_c x[t][c] Wr[c][e] (+ bias[e]), f32 out.
+// ---------------------------------------------------------------------------
+template <class TL>
+__global__ void __launch_bounds__(TL::NT)
+logits_kernel(int T, int d, int E, const bf16_t *__restrict__ x, const bf16_t *__restrict__ Wr,
+              const float *__restrict__ bias, float *__restrict__ logits) {
+    extern __shared__ __attribute__((aligned(16))) char lds[];
+    const int npt = E / TL::BP;
+    const int nqt = (T + TL::BQ - 1) / TL::BQ;
+    const int id = blockIdx.x;
+    if (id >= nqt * npt) return;
+    const int qt = id / npt, pt = id - qt * npt;
+    const int t0 = qt * TL::BQ, p0 = pt * TL::BP;
+    auto fp = [&](int kt, int k, int c) -> uint4 {
+        return ld16(Wr + (int64_t)(kt * TL::BK + k) * E + p0 + c * 8);
+    };
+    auto fq = [&](int kt, int r, int c) -> uint4 {
+        return ld16(x + (int64_t)min(t0 + r, T - 1) * d + kt * TL::BK + c * 8);
+    };
+    f32x16_t acc[TL::TP][TL::TQ];
+    zero_acc<TL>(acc);
+    mfma_mainloop<TL, true, false>(acc, d / TL::BK, fp, fq, lds);
+    for_each_quad<TL>([&](int tp, int tq, int g, int p, int q) {
+        const int t = t0 + q;
+        if (t >= T) return;
+        float4 v = make_float4(acc[tp][tq][4 * g], acc[tp][tq][4 * g + 1], acc[tp][tq][4 * g + 2],
+                               acc[tp][tq][4 * g + 3]);
+        if (bias) {
+            const float4 b = *(const float4 *)(bias + p0 + p);
+            v.x += b.x; v.y += b.y; v.z += b.z; v.w += b.w;
+        }
+        *(float4 *)(logits + (int64_t)t * E + p0 + p) = v;
+    });
+}
+
+// ---------------------------------------------------------------------------
+// Router weight gradient, split over tokens:
+//   part[s][c][e] = sum_{t in split s} x[t][c] * ds[t][e]
+// followed by a fixed-order sum over the splits.
+// ---------------------------------------------------------------------------
+template <class TL>
+__global__ void __launch_bounds__(TL::NT)
+dwr_partial_kernel(int T, int d, int E, int rows_per_split, const bf16_t *__restrict__ x,
+                   const bf16_t *__restrict__ ds, float *__restrict__ part) {
+    extern __shared__ __attribute__((aligned(16))) char lds[];
+    const int nqt = d / TL::BQ, npt = E / TL::BP;
+    const int id = blockIdx.x;
+    const int sp = id / (nqt * npt);
+    const int rem = id - sp * nqt * npt;
+    const int qt = rem / npt, pt = rem - qt * npt;
+    const int r0 = sp * rows_per_split, r1 = min(T, r0 + rows_per_split);
+    const int q0 = qt * TL::BQ, p0 = pt * TL::BP;
+    auto fp = [&](int kt, int k, int c) -> uint4 {
+        const int r = r0 + kt * TL::BK + k;
+        return r < r1 ? ld16(ds + (int64_t)r * E + p0 + c * 8) : zero16();
+    };
+    auto fq = [&](int kt, int k, int c) -> uint4 {
+        const int r = r0 + kt * TL::BK + k;
+        return r < r1 ? ld16(x + (int64_t)r * d + q0 + c * 8) : zero16();
+    };
+    f32x16_t acc[TL::TP][TL::TQ];
+    zero_acc<TL>(acc);
+    mfma_mainloop<TL, true, true>(acc, (max(r1 - r0, 0) + TL::BK - 1) / TL::BK, fp, fq, lds);
+    float *o = part + (int64_t)sp * d * E;
+    for_each_quad<TL>([&](int tp, int tq, int g, int p, int q) {
+        *(float4 *)(o + (int64_t)(q0 + q) * E + p0 + p) =
+            make_float4(acc[tp][tq][4 * g], acc[tp][tq][4 * g + 1], acc[tp][tq][4 * g + 2],
+                        acc[tp][tq][4 * g + 3]);
+    });
+}
+
+__global__ void __launch_bounds__(256)
+split_reduce_kernel(int64_t n, int nsplit, const float *__restrict__ part, float *__restrict__ out,
+                    int accumulate) {
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n) return;
+    float acc = accumulate ? out[i] : 0.0f;
+    for (int s = 0; s < nsplit; ++s) acc += part[(int64_t)s * n + i];
+    out[i] = acc;
+}
+
+// ---------------------------------------------------------------------------
+// host side
+// ---------------------------------------------------------------------------
+typedef TileCfg<256, 128, 2, 2, 32> TLMain;    // experts: 256 features x 128 rows
+typedef TileCfg<128, 64, 2, 2, 64> TLLogits;   // router: 128 experts x 64 tokens
+typedef TileCfg<128, 128, 2, 2, 64> TLDwr;     // router wgrad: 128 experts x 128 hidden
+
+bool mfma_ffn_supported(int d, int F) { return d % 256 == 0 && F % 256 == 0 && d >= 256 && F >= 256; }
+bool mfma_router_supported(int d, int E) { return E % 128 == 0 && d % 128 == 0; }
+
+size_t mfma_tiles_bytes(int64_t S, int E) {
+    return align_up((size_t)(2 + 2 * (size_t)max_row_tiles(S, E, TLMain::BQ)) * sizeof(int32_t), 256);
+}
+
+template <class K>
+static void allow_lds(K kernel, int bytes) {
+    (void)hipFuncSetAttribute((const void *)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+}
+
+hipError_t mfma_build_tiles(int E, const int32_t *offsets, int32_t *tiles, hipStream_t s) {
+    build_row_tiles_kernel<<<1, 1024, 0, s>>>(E, TLMain::BQ, offsets, tiles);
+    return hipGetLastError();
+}
+
+hipError_t mfma_ffn_forward(int64_t S, int d, int E, int F, const void *Xp, const int32_t *offsets,
+                            const int32_t *tiles, const void *Wg, const void *Wu, const void *Wd, void *Yp,
+                            void *H, void *A, void *B, hipStream_t s) {
+    typedef TLMain TL;
+    const int mt = max_row_tiles(S, E, TL::BQ);
+    allow_lds(ffn1_kernel<TL>, TL::LDS_BYTES);
+    ffn1_kernel<TL><<<grid_for((int64_t)mt * (F / (TL::BP / 2))), TL::NT, TL::LDS_BYTES, s>>>(
+        (int)S, d, F, (const bf16_t *)Xp, offsets, tiles, (const bf16_t *)Wg, (const bf16_t *)Wu, (bf16_t *)H,
+        (bf16_t *)A, (bf16_t *)B);
+    allow_lds(rowgemm_kernel<TL, 0>, TL::LDS_BYTES);
+    rowgemm_kernel<TL, 0><<<grid_for((int64_t)mt * (d / TL::BP)), TL::NT, TL::LDS_BYTES, s>>>(
+        (int)S, d, F, (const bf16_t *)H, nullptr, offsets, tiles, (const bf16_t *)Wd, nullptr, nullptr, nullptr,
+        (bf16_t *)Yp, nullptr);
+    return hipGetLastError();
+}
+
+hipError_t mfma_ffn_dh(int64_t S, int d, int E, int F, const void *dYp, const int32_t *offsets,
+                       const int32_t *tiles, const void *Wd, const void *A, const void *B, void *dA, void *dB,
+                       hipStream_t s) {
+    typedef TLMain TL;
+    const int mt = max_row_tiles(S, E, TL::BQ);
+    allow_lds(rowgemm_kernel<TL, 1>, TL::LDS_BYTES);
+    rowgemm_kernel<TL, 1><<<grid_for((int64_t)mt * (F / TL::BP)), TL::NT, TL::LDS_BYTES, s>>>(
+        (int)S, d, F, (const bf16_t *)dYp, nullptr, offsets, tiles, (const bf16_t *)Wd, nullptr,
+        (const bf16_t *)A, (const bf16_t *)B, (bf16_t *)dA, (bf16_t *)dB);
+    return hipGetLastError();
+}
+
+hipError_t mfma_ffn_dxp(int64_t S, int d, int E, int F, const void *dA, const void *dB, const int32_t *offsets,
+                        const int32_t *tiles, const void *Wg, const void *Wu, void *dXp, hipStream_t s) {
+    typedef TLMain TL;
+    const int mt = max_row_tiles(S, E, TL::BQ);
+    allow_lds(rowgemm_kernel<TL, 2>, TL::LDS_BYTES);
+    rowgemm_kernel<TL, 2><<<grid_for((int64_t)mt * (d / TL::BP)), TL::NT, TL::LDS_BYTES, s>>>(
+        (int)S, d, F, (const bf16_t *)dA, (const bf16_t *)dB, offsets, tiles, (const bf16_t *)Wg,
+        (const bf16_t *)Wu, nullptr, nullptr, (bf16_t *)dXp, nullptr);
+    return hipGetLastError();
+}
+
+hipError_t mfma_wgrad(int E, int NQd, int NPd, const void *Qs, const void *Ps, const int32_t *offsets,
+                      float *out, int accumulate, hipStream_t s) {
+    typedef TLMain TL;
+    allow_lds(wgrad_kernel<TL>, TL::LDS_BYTES);
+    const int64_t tiles = (int64_t)E * (NQd / TL::BQ) * (NPd / TL::BP);
+    wgrad_kernel<TL><<<grid_for(tiles), TL::NT, TL::LDS_BYTES, s>>>(E, NQd, NPd, (const bf16_t *)Qs,
+                                                                  (const bf16_t *)Ps, offsets, out, accumulate);
+    return hipGetLastError();
+}
+
+hipError_t mfma_router_logits(int T, int d, int E, const void *x, const void *Wr, const float *bias,
+                              float *logits, hipStream_t s) {
+    typedef TLLogits TL;
+    allow_lds(logits_kernel<TL>, TL::LDS_BYTES);
+    const int tiles = ((T + TL::BQ - 1) / TL::BQ) * (E / TL::BP);
+    logits_kernel<TL><<<tiles, TL::NT, TL::LDS_BYTES, s>>>(T, d, E, (const bf16_t *)x, (const bf16_t *)Wr, bias,
+                                                         logits);
+    return hipGetLastError();
+}
+
+static int dwr_splits(int T) {
+    int s = (T + 511) / 512;
+    return s < 1 ? 1 : (s > 64 ? 64 : s);
+}
+size_t mfma_dwr_ws_bytes(int T, int d, int E) { return align_up((size_t)dwr_splits(T) * d * E * sizeof(float), 256); }
+
+hipError_t mfma_dwr(int T, int d, int E, const void *x, const void *ds, float *part, float *dWr, int accumulate,
+                    hipStream_t s) {
+    typedef TLDwr TL;
+    const int ns = dwr_splits(T);
+    int rows = (T + ns - 1) / ns;
+    rows = (rows + TL::BK - 1) / TL::BK * TL::BK;
+    allow_lds(dwr_partial_kernel<TL>, TL::LDS_BYTES);
+    dwr_partial_kernel<TL><<<ns * (d / TL::BQ) * (E / TL::BP), TL::NT, TL::LDS_BYTES, s>>>(
+        T, d, E, rows, (const bf16_t *)x, (const bf16_t *)ds, part);
+    const int64_t n = (int64_t)d * E;
+    split_reduce_kernel<<<(int)((n + 255) / 256), 256, 0, s>>>(n, ns, part, dWr, accumulate);
+    return hipGetLastError();
+}
+
+}  // namespace r3

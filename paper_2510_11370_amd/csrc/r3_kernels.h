@@ -1,0 +1,68 @@
+// Internal launch interface between the C ABI (r3_api.hip) and the kernel files.
+#pragma once
+#include "r3_common.h"
+
+namespace r3 {
+
+// r3_route.hip
+hipError_t launch_record_topk(int T, int E, int K, const float *logits, int64_t ld, void *idx,
+                              int idx_dtype, int64_t stride, int32_t *status, hipStream_t s);
+hipError_t launch_gate(int T, int E, int K, const float *logits, const void *idx, int idx_dtype,
+                       int64_t stride, float *gates, hipStream_t s);
+hipError_t launch_agreement(int T, int E, int K, const float *logits, const void *idx, int idx_dtype,
+                            int64_t stride, int64_t *agree, hipStream_t s);
+size_t permute_ws_bytes(int T, int E, int K);
+hipError_t launch_permute(int T, int d, int E, int K, int elem_bytes, const void *x, const void *idx,
+                          int idx_dtype, int64_t stride, int32_t *counts, int32_t *offsets,
+                          int32_t *inv_perm, int32_t *perm, void *Xp, int32_t *status, void *ws,
+                          hipStream_t s);
+hipError_t launch_combine(int T, int d, int K, int act, const void *Yp, const float *gates,
+                          const int32_t *inv_perm, void *y, hipStream_t s);
+hipError_t launch_gate_backward(int T, int d, int E, int K, int act, const void *dy, const void *Yp,
+                                const float *gates, const int32_t *inv_perm, const void *idx,
+                                int idx_dtype, int64_t stride, void *dYp, float *dz, void *ds_dense,
+                                hipStream_t s);
+hipError_t launch_dx_finish(int T, int d, int E, int K, int act, const void *dXp, const void *WrT,
+                            const float *dz, const int32_t *inv_perm, const void *idx, int idx_dtype,
+                            int64_t stride, void *dx, hipStream_t s);
+hipError_t launch_transpose(int R, int C, int act, const void *in, void *out, hipStream_t s);
+hipError_t launch_colsum(int T, int E, int act, const void *ds, float *out, int accumulate, hipStream_t s);
+
+// r3_simt.hip
+hipError_t simt_router_logits(int T, int d, int E, int act, const void *x, const void *Wr, const float *bias,
+                              float *logits, hipStream_t s);
+hipError_t simt_ffn1(int S, int d, int E, int F, int act, const void *Xp, const int32_t *offsets, const void *Wg,
+                     const void *Wu, void *H, void *A, void *B, hipStream_t s);
+hipError_t simt_ffn2(int S, int d, int E, int F, int act, const void *H, const int32_t *offsets, const void *Wd,
+                     void *Yp, hipStream_t s);
+hipError_t simt_dh(int S, int d, int E, int F, int act, const void *dYp, const int32_t *offsets, const void *Wd,
+                   const void *A, const void *B, void *dA, void *dB, hipStream_t s);
+hipError_t simt_dxp(int S, int d, int E, int F, int act, const void *dA, const void *dB, const int32_t *offsets,
+                    const void *Wg, const void *Wu, void *dXp, hipStream_t s);
+hipError_t simt_wgrad(int E, int NP, int NQ, int act, const void *P, const void *Q, const int32_t *offsets,
+                      float *out, int accumulate, hipStream_t s);
+hipError_t simt_dwr(int T, int d, int E, int act, const void *x, const void *ds, float *dWr, int accumulate,
+                    hipStream_t s);
+
+// r3_gemm.hip (bf16 MFMA)
+bool mfma_ffn_supported(int d, int F);
+bool mfma_router_supported(int d, int E);
+size_t mfma_tiles_bytes(int64_t S, int E);
+size_t mfma_dwr_ws_bytes(int T, int d, int E);
+hipError_t mfma_build_tiles(int E, const int32_t *offsets, int32_t *tiles, hipStream_t s);
+hipError_t mfma_ffn_forward(int64_t S, int d, int E, int F, const void *Xp, const int32_t *offsets,
+                            const int32_t *tiles, const void *Wg, const void *Wu, const void *Wd, void *Yp,
+                            void *H, void *A, void *B, hipStream_t s);
+hipError_t mfma_ffn_dh(int64_t S, int d, int E, int F, const void *dYp, const int32_t *offsets,
+                       const int32_t *tiles, const void *Wd, const void *A, const void *B, void *dA, void *dB,
+                       hipStream_t s);
+hipError_t mfma_ffn_dxp(int64_t S, int d, int E, int F, const void *dA, const void *dB, const int32_t *offsets,
+                        const int32_t *tiles, const void *Wg, const void *Wu, void *dXp, hipStream_t s);
+hipError_t mfma_wgrad(int E, int NQd, int NPd, const void *Qs, const void *Ps, const int32_t *offsets,
+                      float *out, int accumulate, hipStream_t s);
+hipError_t mfma_router_logits(int T, int d, int E, const void *x, const void *Wr, const float *bias,
+                              float *logits, hipStream_t s);
+hipError_t mfma_dwr(int T, int d, int E, const void *x, const void *ds, float *part, float *dWr, int accumulate,
+                    hipStream_t s);
+
+}  // namespace r3

@@ -1,0 +1,772 @@
+// Routing kernels of the replayed MoE layer (arxiv 2510.11370, Section 4.1):
+// TopKMask record, replay gate, dispatch permutation, weighted combine, and the
+// element-wise parts of the backward.  All of them are bound by HBM traffic, so
+// they move 16-byte vectors per lane, read every input once and use wave-level
+// reductions; none uses floating-point atomics (results are bit-reproducible).
+#include "r3_kernels.h"
+
+namespace r3 {
+
+// ---------------------------------------------------------------------------
+// TopKMask
+// ---------------------------------------------------------------------------
+// Order-preserving map float -> uint32 (larger float = larger key), with
+// -0 == +0 and every NaN mapped to 0, below -inf.
+__device__ __forceinline__ uint32_t order_key(float v, bool &nonfinite) {
+    uint32_t u = __float_as_uint(v);
+    uint32_t mag = u & 0x7fffffffu;
+    nonfinite = mag >= 0x7f800000u;
+    if (mag > 0x7f800000u) return 0u;      // NaN
+    if (mag == 0u) u = 0u;                 // -0 -> +0
+    return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+
+// One lane scans one row of E keys (row staged in LDS as floats) and keeps the
+// KL largest keys, sorted descending, with min/max network insertion.
+// Returns the K-th largest key (threshold) and how many keys are above it.
+template <int KL>
+__device__ __forceinline__ void lane_topk_threshold(const float *row, int E, int K,
+                                                    uint32_t &thr, int &above, bool &bad) {
+    uint32_t top[KL];
+#pragma unroll
+    for (int j = 0; j < KL; ++j) top[j] = 0u;
+    bad = false;
+    for (int e = 0; e < E; ++e) {
+        bool nf;
+        uint32_t v = order_key(row[e], nf);
+        bad |= nf;
+#pragma unroll
+        for (int j = 0; j < KL; ++j) {
+            uint32_t hi = max(top[j], v);
+            v = min(top[j], v);
+            top[j] = hi;
+        }
+    }
+    thr = 0u;
+#pragma unroll
+    for (int j = 0; j < KL; ++j)
+        if (j == K - 1) thr = top[j];
+    above = 0;
+#pragma unroll
+    for (int j = 0; j < KL; ++j)
+        if (j < K && top[j] > thr) ++above;
+}
+
+// Stage 64 rows of logits (one per lane) into LDS, coalesced.  Row stride in LDS
+// is E+4 floats so that 16 lanes reading 16 bytes at the same column hit
+// distinct banks.
+__device__ __forceinline__ void stage_rows(float *lds, const float *logits, int64_t ld, int t0,
+                                           int T, int E) {
+    const int lane = threadIdx.x;
+    const int total = kWave * E;
+    for (int i = lane; i < total; i += kWave) {
+        int r = i / E, c = i - r * E;
+        int t = t0 + r;
+        lds[r * (E + 4) + c] = (t < T) ? logits[(int64_t)t * ld + c] : 0.0f;
+    }
+    __syncthreads();
+}
+
+// Fast record: one lane per token, K <= 8, E <= 512.  blockDim = 64.
+template <typename IdxT>
+__global__ void __launch_bounds__(64)
+record_topk_lane_kernel(int T, int E, int K, const float *__restrict__ logits, int64_t ld,
+                        IdxT *__restrict__ idx, int64_t stride, int32_t *status) {
+    extern __shared__ float lds[];
+    const int t0 = blockIdx.x * kWave;
+    stage_rows(lds, logits, ld, t0, T, E);
+    const int t = t0 + (int)threadIdx.x;
+    const float *row = lds + threadIdx.x * (E + 4);
+    uint32_t thr;
+    int above;
+    bool bad;
+    lane_topk_threshold<8>(row, E, K, thr, above, bad);
+    if (t < T) {
+        int quota = K - above;  // how many keys equal to thr are taken, lowest ids first
+        int n = 0;
+        IdxT *out = idx + (int64_t)t * stride;
+        for (int e = 0; e < E && n < K; ++e) {
+            bool nf;
+            uint32_t v = order_key(row[e], nf);
+            bool take = v > thr;
+            if (v == thr && quota > 0) {
+                take = true;
+                --quota;
+            }
+            if (take) out[n++] = (IdxT)e;
+        }
+        if (bad && status) atomicOr(status, R3_DATA_NONFINITE);
+    }
+}
+
+// General record: one wave per token, rank counting, E <= 4096, K <= 64.
+// key of element e beats key of element f if larger, or equal with lower id.
+template <typename IdxT>
+__global__ void __launch_bounds__(256)
+record_topk_wave_kernel(int T, int E, int K, const float *__restrict__ logits, int64_t ld,
+                        IdxT *__restrict__ idx, int64_t stride, int32_t *status) {
+    extern __shared__ uint32_t keys_all[];
+    const int w = threadIdx.x / kWave, lane = lane_id();
+    const int t = blockIdx.x * 4 + w;
+    uint32_t *keys = keys_all + w * E;
+    bool bad = false;
+    if (t < T)
+        for (int e = lane; e < E; e += kWave) {
+            bool nf;
+            keys[e] = order_key(logits[(int64_t)t * ld + e], nf);
+            bad |= nf;
+        }
+    __syncthreads();
+    if (t >= T) return;
+    int emitted = 0;  // wave-uniform
+    for (int base = 0; base < E; base += kWave) {
+        int e = base + lane;
+        bool sel = false;
+        if (e < E) {
+            uint32_t mine = keys[e];
+            int ahead = 0;
+            for (int f = 0; f < E; ++f) {
+                uint32_t kf = keys[f];
+                ahead += (kf > mine || (kf == mine && f < e)) ? 1 : 0;
+            }
+            sel = ahead < K;
+        }
+        uint64_t m = __ballot(sel);
+        if (sel) {
+            int pos = emitted + __popcll(m & ((1ull << lane) - 1ull));
+            idx[(int64_t)t * stride + pos] = (IdxT)e;
+        }
+        emitted += __popcll(m);
+    }
+    if (__ballot(bad) && lane == 0 && status) atomicOr(status, R3_DATA_NONFINITE);
+}
+
+hipError_t launch_record_topk(int T, int E, int K, const float *logits, int64_t ld, void *idx,
+                              int idx_dtype, int64_t stride, int32_t *status, hipStream_t s) {
+    if (K <= 8 && E <= 512) {
+        size_t lds = (size_t)kWave * (E + 4) * sizeof(float);
+        int grid = (T + kWave - 1) / kWave;
+        if (idx_dtype == R3_IDX_U8) {
+            (void)hipFuncSetAttribute((const void *)record_topk_lane_kernel<uint8_t>,
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+            record_topk_lane_kernel<uint8_t><<<grid, 64, lds, s>>>(T, E, K, logits, ld, (uint8_t *)idx,
+                                                                  stride, status);
+        } else {
+            (void)hipFuncSetAttribute((const void *)record_topk_lane_kernel<uint16_t>,
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+            record_topk_lane_kernel<uint16_t><<<grid, 64, lds, s>>>(T, E, K, logits, ld,
+                                                                   (uint16_t *)idx, stride, status);
+        }
+    } else {
+        size_t lds = (size_t)4 * E * sizeof(uint32_t);
+        int grid = (T + 3) / 4;
+        if (idx_dtype == R3_IDX_U8)
+            record_topk_wave_kernel<uint8_t><<<grid, 256, lds, s>>>(T, E, K, logits, ld, (uint8_t *)idx,
+                                                                   stride, status);
+        else
+            record_topk_wave_kernel<uint16_t><<<grid, 256, lds, s>>>(T, E, K, logits, ld,
+                                                                    (uint16_t *)idx, stride, status);
+    }
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------
+// Replay gate from logits in memory: one thread per token.
+// g_j = exp(s[idx_j] - m) / sum_i exp(s[idx_i] - m), m = max over the set.
+// ---------------------------------------------------------------------------
+template <typename IdxT>
+__global__ void __launch_bounds__(256)
+gate_kernel(int T, int E, int K, const float *__restrict__ logits, const IdxT *__restrict__ idx,
+            int64_t stride, float *__restrict__ gates) {
+    const int t = blockIdx.x * blockDim.x + threadIdx.x;
+    if (t >= T) return;
+    const IdxT *id = idx + (int64_t)t * stride;
+    const float *row = logits + (int64_t)t * E;
+    float m = -INFINITY;
+    for (int j = 0; j < K; ++j) {
+        int e = min((int)id[j], E - 1);
+        m = fmaxf(m, row[e]);
+    }
+    float den = 0.0f;
+    for (int j = 0; j < K; ++j) {
+        int e = min((int)id[j], E - 1);
+        float p = expf(row[e] - m);
+        gates[(int64_t)t * K + j] = p;
+        den += p;
+    }
+    float inv = 1.0f / den;
+    for (int j = 0; j < K; ++j) gates[(int64_t)t * K + j] *= inv;
+}
+
+hipError_t launch_gate(int T, int E, int K, const float *logits, const void *idx, int idx_dtype,
+                       int64_t stride, float *gates, hipStream_t s) {
+    int grid = (T + 255) / 256;
+    if (idx_dtype == R3_IDX_U8)
+        gate_kernel<uint8_t><<<grid, 256, 0, s>>>(T, E, K, logits, (const uint8_t *)idx, stride, gates);
+    else
+        gate_kernel<uint16_t><<<grid, 256, 0, s>>>(T, E, K, logits, (const uint16_t *)idx, stride, gates);
+    return hipGetLastError();
+}
+
+// Routing agreement (Section 3.2, router level): per token compare the top-K
+// set of the training logits with the recorded set.  One wave per token, rank
+// counting as in the general record kernel.  agree[0] += tokens with equal
+// sets, agree[1] += shared experts.  Integer atomics only.
+template <typename IdxT>
+__global__ void __launch_bounds__(256)
+agreement_kernel(int T, int E, int K, const float *__restrict__ logits, const IdxT *__restrict__ idx,
+                 int64_t stride, unsigned long long *agree) {
+    extern __shared__ uint32_t keys_all[];
+    const int w = threadIdx.x / kWave, lane = lane_id();
+    const int t = blockIdx.x * 4 + w;
+    uint32_t *keys = keys_all + w * E;
+    if (t < T)
+        for (int e = lane; e < E; e += kWave) {
+            bool nf;
+            keys[e] = order_key(logits[(int64_t)t * E + e], nf);
+        }
+    __syncthreads();
+    if (t >= T) return;
+    int shared = 0;
+    for (int base = 0; base < K; base += kWave) {
+        int j = base + lane;
+        bool sel = false;
+        if (j < K) {
+            int e = min((int)idx[(int64_t)t * stride + j], E - 1);
+            uint32_t mine = keys[e];
+            int ahead = 0;
+            for (int f = 0; f < E; ++f) {
+                uint32_t kf = keys[f];
+                ahead += (kf > mine || (kf == mine && f < e)) ? 1 : 0;
+            }
+            sel = ahead < K;
+        }
+        shared += __popcll(__ballot(sel));
+    }
+    if (lane == 0) {
+        atomicAdd(agree + 1, (unsigned long long)shared);
+        if (shared == K) atomicAdd(agree, 1ull);
+    }
+}
+
+hipError_t launch_agreement(int T, int E, int K, const float *logits, const void *idx, int idx_dtype,
+                            int64_t stride, int64_t *agree, hipStream_t s) {
+    size_t lds = (size_t)4 * E * sizeof(uint32_t);
+    int grid = (T + 3) / 4;
+    if (idx_dtype == R3_IDX_U8)
+        agreement_kernel<uint8_t><<<grid, 256, lds, s>>>(T, E, K, logits, (const uint8_t *)idx, stride,
+                                                        (unsigned long long *)agree);
+    else
+        agreement_kernel<uint16_t><<<grid, 256, lds, s>>>(T, E, K, logits, (const uint16_t *)idx, stride,
+                                                         (unsigned long long *)agree);
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------
+// Dispatch permutation: stable counting sort of the T*K slots by expert.
+//   pass 1: per-chunk expert histograms (one wave per chunk of slots)
+//   pass 2: exclusive scan over (expert, chunk) -> offsets and chunk bases
+//   pass 3: every wave walks its chunk in slot order and places slots
+//   pass 4: row gather, one read of x[t] feeding its K destination rows
+// The placement never depends on arrival order, so perm is unique.
+// ---------------------------------------------------------------------------
+template <typename IdxT>
+__global__ void __launch_bounds__(256)
+permute_hist_kernel(int T, int E, int K, const IdxT *__restrict__ idx, int64_t stride, int chunk,
+                    int nchunks, int32_t *__restrict__ chunk_hist, int32_t *status) {
+    extern __shared__ int32_t hist_all[];
+    const int w = threadIdx.x / kWave, lane = lane_id();
+    const int c = blockIdx.x * 4 + w;
+    int32_t *hist = hist_all + w * E;
+    for (int e = lane; e < E; e += kWave) hist[e] = 0;
+    __syncthreads();
+    if (c >= nchunks) return;
+    const int64_t S = (int64_t)T * K;
+    const int64_t s0 = (int64_t)c * chunk;
+    int bad = 0;
+    for (int i = lane; i < chunk; i += kWave) {
+        int64_t sl = s0 + i;
+        if (sl < S) {
+            int t = (int)(sl / K), j = (int)(sl - (int64_t)t * K);
+            int e = (int)idx[(int64_t)t * stride + j];
+            if (e >= E) {
+                bad |= R3_DATA_IDX_RANGE;
+                e = E - 1;
+            }
+            for (int jj = 0; jj < j; ++jj)
+                if ((int)idx[(int64_t)t * stride + jj] == e) bad |= R3_DATA_IDX_DUP;
+            atomicAdd(&hist[e], 1);
+        }
+    }
+    // LDS atomics of one wave are complete before its later LDS reads
+    __builtin_amdgcn_s_waitcnt(0);
+    __builtin_amdgcn_wave_barrier();
+    for (int e = lane; e < E; e += kWave) chunk_hist[(int64_t)c * E + e] = hist[e];
+    if (bad && status) atomicOr(status, bad);
+}
+
+// One block of 1024 threads.  chunk_hist [nchunks,E] becomes the exclusive
+// running count over chunks (in place); counts/offsets are written.
+__global__ void __launch_bounds__(1024)
+permute_scan_kernel(int E, int nchunks, int32_t *__restrict__ chunk_hist, int32_t *__restrict__ counts,
+                    int32_t *__restrict__ offsets) {
+    __shared__ int32_t tot[kMaxE];
+    __shared__ int32_t part[1024];
+    for (int e = threadIdx.x; e < E; e += blockDim.x) {
+        int32_t run = 0;
+        for (int c = 0; c < nchunks; ++c) {
+            int32_t h = chunk_hist[(int64_t)c * E + e];
+            chunk_hist[(int64_t)c * E + e] = run;
+            run += h;
+        }
+        tot[e] = run;
+        counts[e] = run;
+    }
+    __syncthreads();
+    // exclusive scan of tot[0..E): each thread owns a contiguous span
+    const int per = (E + blockDim.x - 1) / blockDim.x;
+    const int b = threadIdx.x * per;
+    int32_t sum = 0;
+    for (int i = 0; i < per; ++i)
+        if (b + i < E) sum += tot[b + i];
+    part[threadIdx.x] = sum;
+    __syncthreads();
+    for (int o = 1; o < (int)blockDim.x; o <<= 1) {
+        int32_t v = (threadIdx.x >= (unsigned)o) ? part[threadIdx.x - o] : 0;
+        __syncthreads();
+        part[threadIdx.x] += v;
+        __syncthreads();
+    }
+    int32_t run = part[threadIdx.x] - sum;
+    for (int i = 0; i < per; ++i)
+        if (b + i < E) {
+            offsets[b + i] = run;
+            run += tot[b + i];
+        }
+    if (threadIdx.x == blockDim.x - 1) offsets[E] = part[threadIdx.x];
+}
+
+template <typename IdxT>
+__global__ void __launch_bounds__(256)
+permute_place_kernel(int T, int E, int K, const IdxT *__restrict__ idx, int64_t stride, int chunk,
+                     int nchunks, const int32_t *__restrict__ chunk_base,
+                     const int32_t *__restrict__ offsets, int32_t *__restrict__ inv_perm,
+                     int32_t *__restrict__ perm) {
+    extern __shared__ int32_t cnt_all[];
+    const int w = threadIdx.x / kWave, lane = lane_id();
+    const int c = blockIdx.x * 4 + w;
+    int32_t *cnt = cnt_all + w * E;
+    if (c < nchunks)
+        for (int e = lane; e < E; e += kWave) cnt[e] = offsets[e] + chunk_base[(int64_t)c * E + e];
+    __syncthreads();
+    if (c >= nchunks) return;
+    const int64_t S = (int64_t)T * K;
+    const int64_t s0 = (int64_t)c * chunk;
+    int ebits = 1;
+    while ((1 << ebits) < E) ++ebits;
+    const uint64_t lt = (1ull << lane) - 1ull;
+    for (int i = 0; i < chunk; i += kWave) {
+        int64_t sl = s0 + i + lane;
+        bool live = sl < S;
+        int e = 0;
+        if (live) {
+            int t = (int)(sl / K), j = (int)(sl - (int64_t)t * K);
+            e = min((int)idx[(int64_t)t * stride + j], E - 1);
+        }
+        // lanes holding the same expert
+        uint64_t same = __ballot(live);
+        for (int b = 0; b < ebits; ++b) {
+            uint64_t bal = __ballot((e >> b) & 1);
+            same &= ((e >> b) & 1) ? bal : ~bal;
+        }
+        if (live) {
+            int row = cnt[e] + __popcll(same & lt);
+            inv_perm[sl] = row;
+            perm[row] = (int32_t)sl;
+        }
+        __builtin_amdgcn_s_waitcnt(0);
+        __builtin_amdgcn_wave_barrier();
+        // the highest lane of each group advances the group's counter
+        if (live && (same >> lane) == 1ull) cnt[e] += __popcll(same);
+        __builtin_amdgcn_s_waitcnt(0);
+        __builtin_amdgcn_wave_barrier();
+    }
+}
+
+// Row gather by token: the block reads x[t] once and writes its K copies.
+// V is the vector type moved per thread (uint4 when rows are 16-byte multiples).
+template <typename V>
+__global__ void __launch_bounds__(256)
+gather_rows_kernel(int T, int K, int row_vecs, const V *__restrict__ x,
+                   const int32_t *__restrict__ inv_perm, V *__restrict__ Xp) {
+    const int t = blockIdx.x;
+    __shared__ int32_t rows[kMaxK];
+    if (threadIdx.x < (unsigned)K) rows[threadIdx.x] = inv_perm[(int64_t)t * K + threadIdx.x];
+    __syncthreads();
+    for (int c = threadIdx.x; c < row_vecs; c += blockDim.x) {
+        V v = x[(int64_t)t * row_vecs + c];
+        for (int j = 0; j < K; ++j) Xp[(int64_t)rows[j] * row_vecs + c] = v;
+    }
+}
+
+static int pick_chunk(int64_t S) {
+    // slots per wave-chunk: at least 1024, at most 512 chunks in total
+    int64_t c = 1024;
+    while ((S + c - 1) / c > 512) c *= 2;
+    return (int)c;
+}
+
+size_t permute_ws_bytes(int T, int E, int K) {
+    int64_t S = (int64_t)T * K;
+    int chunk = pick_chunk(S);
+    int64_t nchunks = (S + chunk - 1) / chunk;
+    return align_up((size_t)nchunks * E * sizeof(int32_t), 256);
+}
+
+hipError_t launch_permute(int T, int d, int E, int K, int elem_bytes, const void *x, const void *idx,
+                          int idx_dtype, int64_t stride, int32_t *counts, int32_t *offsets,
+                          int32_t *inv_perm, int32_t *perm, void *Xp, int32_t *status, void *ws,
+                          hipStream_t s) {
+    const int64_t S = (int64_t)T * K;
+    const int chunk = pick_chunk(S);
+    const int nchunks = (int)((S + chunk - 1) / chunk);
+    int32_t *chunk_hist = (int32_t *)ws;
+    const int grid = (nchunks + 3) / 4;
+    const size_t lds = (size_t)4 * E * sizeof(int32_t);
+    if (idx_dtype == R3_IDX_U8)
+        permute_hist_kernel<uint8_t><<<grid, 256, lds, s>>>(T, E, K, (const uint8_t *)idx, stride, chunk,
+                                                           nchunks, chunk_hist, status);
+    else
+        permute_hist_kernel<uint16_t><<<grid, 256, lds, s>>>(T, E, K, (const uint16_t *)idx, stride,
+                                                            chunk, nchunks, chunk_hist, status);
+    permute_scan_kernel<<<1, 1024, 0, s>>>(E, nchunks, chunk_hist, counts, offsets);
+    if (idx_dtype == R3_IDX_U8)
+        permute_place_kernel<uint8_t><<<grid, 256, lds, s>>>(T, E, K, (const uint8_t *)idx, stride, chunk,
+                                                            nchunks, chunk_hist, offsets, inv_perm, perm);
+    else
+        permute_place_kernel<uint16_t><<<grid, 256, lds, s>>>(T, E, K, (const uint16_t *)idx, stride,
+                                                             chunk, nchunks, chunk_hist, offsets,
+                                                             inv_perm, perm);
+    if (Xp) {
+        const int64_t row_bytes = (int64_t)d * elem_bytes;
+        if (row_bytes % 16 == 0)
+            gather_rows_kernel<uint4><<<T, 256, 0, s>>>(T, K, (int)(row_bytes / 16), (const uint4 *)x,
+                                                       inv_perm, (uint4 *)Xp);
+        else if (row_bytes % 4 == 0)
+            gather_rows_kernel<uint32_t><<<T, 256, 0, s>>>(T, K, (int)(row_bytes / 4),
+                                                          (const uint32_t *)x, inv_perm, (uint32_t *)Xp);
+        else
+            gather_rows_kernel<uint16_t><<<T, 256, 0, s>>>(T, K, (int)(row_bytes / 2),
+                                                          (const uint16_t *)x, inv_perm, (uint16_t *)Xp);
+    }
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------
+// Combine: y[t] = sum_j g[t,j] * Yp[inv_perm[t*K+j]], j ascending, f32.
+// One block per token; each thread owns VEC consecutive columns.
+// ---------------------------------------------------------------------------
+template <typename T, int VEC> struct VecIO;
+template <> struct VecIO<bf16_t, 8> {
+    typedef uint4 V;
+    static __device__ __forceinline__ void unpack(const V &v, float *f) {
+        const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            f[2 * i] = __uint_as_float(w[i] << 16);
+            f[2 * i + 1] = __uint_as_float(w[i] & 0xffff0000u);
+        }
+    }
+    static __device__ __forceinline__ V pack(const float *f) {
+        V v;
+        v.x = pack_bf16x2(f[0], f[1]);
+        v.y = pack_bf16x2(f[2], f[3]);
+        v.z = pack_bf16x2(f[4], f[5]);
+        v.w = pack_bf16x2(f[6], f[7]);
+        return v;
+    }
+};
+template <> struct VecIO<float, 4> {
+    typedef float4 V;
+    static __device__ __forceinline__ void unpack(const V &v, float *f) {
+        f[0] = v.x; f[1] = v.y; f[2] = v.z; f[3] = v.w;
+    }
+    static __device__ __forceinline__ V pack(const float *f) { return make_float4(f[0], f[1], f[2], f[3]); }
+};
+template <> struct VecIO<bf16_t, 1> {
+    typedef bf16_t V;
+    static __device__ __forceinline__ void unpack(const V &v, float *f) { f[0] = bf16_to_f32(v); }
+    static __device__ __forceinline__ V pack(const float *f) { return f32_to_bf16(f[0]); }
+};
+template <> struct VecIO<float, 1> {
+    typedef float V;
+    static __device__ __forceinline__ void unpack(const V &v, float *f) { f[0] = v; }
+    static __device__ __forceinline__ V pack(const float *f) { return f[0]; }
+};
+
+template <typename T, int VEC>
+__global__ void __launch_bounds__(256)
+combine_kernel(int K, int row_vecs, const typename VecIO<T, VEC>::V *__restrict__ Yp,
+               const float *__restrict__ gates, const int32_t *__restrict__ inv_perm,
+               typename VecIO<T, VEC>::V *__restrict__ y) {
+    typedef VecIO<T, VEC> IO;
+    const int t = blockIdx.x;
+    __shared__ int32_t rows[kMaxK];
+    __shared__ float g[kMaxK];
+    if (threadIdx.x < (unsigned)K) {
+        rows[threadIdx.x] = inv_perm[(int64_t)t * K + threadIdx.x];
+        g[threadIdx.x] = gates[(int64_t)t * K + threadIdx.x];
+    }
+    __syncthreads();
+    for (int c = threadIdx.x; c < row_vecs; c += blockDim.x) {
+        float acc[VEC];
+#pragma unroll
+        for (int i = 0; i < VEC; ++i) acc[i] = 0.0f;
+        for (int j = 0; j < K; ++j) {
+            float f[VEC];
+            IO::unpack(Yp[(int64_t)rows[j] * row_vecs + c], f);
+            const float gj = g[j];
+#pragma unroll
+            for (int i = 0; i < VEC; ++i) acc[i] = fmaf(gj, f[i], acc[i]);
+        }
+        y[(int64_t)t * row_vecs + c] = IO::pack(acc);
+    }
+}
+
+hipError_t launch_combine(int T, int d, int K, int act, const void *Yp, const float *gates,
+                          const int32_t *inv_perm, void *y, hipStream_t s) {
+    if (act == R3_BF16) {
+        if (d % 8 == 0)
+            combine_kernel<bf16_t, 8><<<T, 256, 0, s>>>(K, d / 8, (const uint4 *)Yp, gates, inv_perm,
+                                                       (uint4 *)y);
+        else
+            combine_kernel<bf16_t, 1><<<T, 256, 0, s>>>(K, d, (const bf16_t *)Yp, gates, inv_perm,
+                                                       (bf16_t *)y);
+    } else {
+        if (d % 4 == 0)
+            combine_kernel<float, 4><<<T, 256, 0, s>>>(K, d / 4, (const float4 *)Yp, gates, inv_perm,
+                                                      (float4 *)y);
+        else
+            combine_kernel<float, 1><<<T, 256, 0, s>>>(K, d, (const float *)Yp, gates, inv_perm,
+                                                      (float *)y);
+    }
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------
+// Backward through combine and masked softmax, one block per token:
+//   dg_j = <dy_t, Yp[row_j]>,  dYp[row_j] = g_j * dy_t,
+//   dz_j = g_j (dg_j - sum_i g_i dg_i).
+// Writes dz [T,K] f32 and, when ds_dense != NULL, the dense row ds[t,:] (act
+// dtype, zero off the recorded set) that the router weight gradient contracts.
+// ---------------------------------------------------------------------------
+template <typename T, int VEC, typename IdxT>
+__global__ void __launch_bounds__(256)
+gate_backward_kernel(int E, int K, int row_vecs, const typename VecIO<T, VEC>::V *__restrict__ dy,
+                     const typename VecIO<T, VEC>::V *__restrict__ Yp, const float *__restrict__ gates,
+                     const int32_t *__restrict__ inv_perm, const IdxT *__restrict__ idx, int64_t stride,
+                     typename VecIO<T, VEC>::V *__restrict__ dYp, float *__restrict__ dz,
+                     T *__restrict__ ds_dense) {
+    typedef VecIO<T, VEC> IO;
+    const int t = blockIdx.x;
+    const int nw = blockDim.x / kWave, w = threadIdx.x / kWave, lane = lane_id();
+    __shared__ int32_t rows[kMaxK];
+    __shared__ float g[kMaxK];
+    __shared__ float part[4][kMaxK];
+    __shared__ float dgs[kMaxK];
+    if (threadIdx.x < (unsigned)K) {
+        rows[threadIdx.x] = inv_perm[(int64_t)t * K + threadIdx.x];
+        g[threadIdx.x] = gates[(int64_t)t * K + threadIdx.x];
+    }
+    if (ds_dense)
+        for (int e = threadIdx.x; e < E; e += blockDim.x) Elem<T>::st(ds_dense + (int64_t)t * E + e, 0.0f);
+    __syncthreads();
+    for (int j = 0; j < K; ++j) {
+        float dot = 0.0f;
+        const float gj = g[j];
+        for (int c = threadIdx.x; c < row_vecs; c += blockDim.x) {
+            float a[VEC], b[VEC], o[VEC];
+            IO::unpack(dy[(int64_t)t * row_vecs + c], a);
+            IO::unpack(Yp[(int64_t)rows[j] * row_vecs + c], b);
+#pragma unroll
+            for (int i = 0; i < VEC; ++i) {
+                dot = fmaf(a[i], b[i], dot);
+                o[i] = gj * a[i];
+            }
+            dYp[(int64_t)rows[j] * row_vecs + c] = IO::pack(o);
+        }
+        dot = wave_sum(dot);
+        if (lane == 0) part[w][j] = dot;
+    }
+    __syncthreads();
+    if (threadIdx.x < (unsigned)K) {
+        float v = 0.0f;
+        for (int i = 0; i < nw; ++i) v += part[i][threadIdx.x];
+        dgs[threadIdx.x] = v;
+    }
+    __syncthreads();
+    if (threadIdx.x < (unsigned)K) {
+        float mix = 0.0f;
+        for (int j = 0; j < K; ++j) mix = fmaf(g[j], dgs[j], mix);
+        float v = g[threadIdx.x] * (dgs[threadIdx.x] - mix);
+        dz[(int64_t)t * K + threadIdx.x] = v;
+        if (ds_dense) {
+            int e = min((int)idx[(int64_t)t * stride + threadIdx.x], E - 1);
+            Elem<T>::st(ds_dense + (int64_t)t * E + e, v);
+        }
+    }
+}
+
+template <typename T, int VEC>
+static hipError_t gate_backward_dispatch(int Tn, int E, int K, int row_vecs, const void *dy, const void *Yp,
+                                         const float *gates, const int32_t *inv_perm, const void *idx,
+                                         int idx_dtype, int64_t stride, void *dYp, float *dz,
+                                         void *ds_dense, hipStream_t s) {
+    typedef typename VecIO<T, VEC>::V V;
+    if (idx_dtype == R3_IDX_U8)
+        gate_backward_kernel<T, VEC, uint8_t><<<Tn, 256, 0, s>>>(E, K, row_vecs, (const V *)dy, (const V *)Yp,
+                                                               gates, inv_perm, (const uint8_t *)idx,
+                                                               stride, (V *)dYp, dz, (T *)ds_dense);
+    else
+        gate_backward_kernel<T, VEC, uint16_t><<<Tn, 256, 0, s>>>(E, K, row_vecs, (const V *)dy,
+                                                                (const V *)Yp, gates, inv_perm,
+                                                                (const uint16_t *)idx, stride, (V *)dYp,
+                                                                dz, (T *)ds_dense);
+    return hipGetLastError();
+}
+
+hipError_t launch_gate_backward(int T, int d, int E, int K, int act, const void *dy, const void *Yp,
+                                const float *gates, const int32_t *inv_perm, const void *idx,
+                                int idx_dtype, int64_t stride, void *dYp, float *dz, void *ds_dense,
+                                hipStream_t s) {
+    if (act == R3_BF16) {
+        if (d % 8 == 0)
+            return gate_backward_dispatch<bf16_t, 8>(T, E, K, d / 8, dy, Yp, gates, inv_perm, idx, idx_dtype,
+                                                     stride, dYp, dz, ds_dense, s);
+        return gate_backward_dispatch<bf16_t, 1>(T, E, K, d, dy, Yp, gates, inv_perm, idx, idx_dtype, stride,
+                                                 dYp, dz, ds_dense, s);
+    }
+    if (d % 4 == 0)
+        return gate_backward_dispatch<float, 4>(T, E, K, d / 4, dy, Yp, gates, inv_perm, idx, idx_dtype,
+                                                stride, dYp, dz, ds_dense, s);
+    return gate_backward_dispatch<float, 1>(T, E, K, d, dy, Yp, gates, inv_perm, idx, idx_dtype, stride, dYp,
+                                            dz, ds_dense, s);
+}
+
+// ---------------------------------------------------------------------------
+// Final input gradient, one block per token:
+//   dx[t] = sum_j dXp[row_j]  +  sum_j dz[t,j] * W_r[:, idx_j]
+// WrT is W_r transposed ([E,d], act dtype) so that the router term reads rows.
+// ---------------------------------------------------------------------------
+template <typename T, int VEC, typename IdxT>
+__global__ void __launch_bounds__(256)
+dx_finish_kernel(int E, int K, int row_vecs, const typename VecIO<T, VEC>::V *__restrict__ dXp,
+                 const typename VecIO<T, VEC>::V *__restrict__ WrT, const float *__restrict__ dz,
+                 const int32_t *__restrict__ inv_perm, const IdxT *__restrict__ idx, int64_t stride,
+                 typename VecIO<T, VEC>::V *__restrict__ dx) {
+    typedef VecIO<T, VEC> IO;
+    const int t = blockIdx.x;
+    __shared__ int32_t rows[kMaxK];
+    __shared__ int32_t ids[kMaxK];
+    __shared__ float z[kMaxK];
+    if (threadIdx.x < (unsigned)K) {
+        rows[threadIdx.x] = inv_perm[(int64_t)t * K + threadIdx.x];
+        ids[threadIdx.x] = min((int)idx[(int64_t)t * stride + threadIdx.x], E - 1);
+        z[threadIdx.x] = dz[(int64_t)t * K + threadIdx.x];
+    }
+    __syncthreads();
+    for (int c = threadIdx.x; c < row_vecs; c += blockDim.x) {
+        float acc[VEC];
+#pragma unroll
+        for (int i = 0; i < VEC; ++i) acc[i] = 0.0f;
+        for (int j = 0; j < K; ++j) {
+            float f[VEC];
+            IO::unpack(dXp[(int64_t)rows[j] * row_vecs + c], f);
+#pragma unroll
+            for (int i = 0; i < VEC; ++i) acc[i] += f[i];
+        }
+        for (int j = 0; j < K; ++j) {
+            float f[VEC];
+            IO::unpack(WrT[(int64_t)ids[j] * row_vecs + c], f);
+            const float zj = z[j];
+#pragma unroll
+            for (int i = 0; i < VEC; ++i) acc[i] = fmaf(zj, f[i], acc[i]);
+        }
+        dx[(int64_t)t * row_vecs + c] = IO::pack(acc);
+    }
+}
+
+template <typename T, int VEC>
+static hipError_t dx_finish_dispatch(int Tn, int E, int K, int row_vecs, const void *dXp, const void *WrT,
+                                     const float *dz, const int32_t *inv_perm, const void *idx,
+                                     int idx_dtype, int64_t stride, void *dx, hipStream_t s) {
+    typedef typename VecIO<T, VEC>::V V;
+    if (idx_dtype == R3_IDX_U8)
+        dx_finish_kernel<T, VEC, uint8_t><<<Tn, 256, 0, s>>>(E, K, row_vecs, (const V *)dXp, (const V *)WrT, dz,
+                                                           inv_perm, (const uint8_t *)idx, stride, (V *)dx);
+    else
+        dx_finish_kernel<T, VEC, uint16_t><<<Tn, 256, 0, s>>>(E, K, row_vecs, (const V *)dXp, (const V *)WrT,
+                                                            dz, inv_perm, (const uint16_t *)idx, stride,
+                                                            (V *)dx);
+    return hipGetLastError();
+}
+
+hipError_t launch_dx_finish(int T, int d, int E, int K, int act, const void *dXp, const void *WrT,
+                            const float *dz, const int32_t *inv_perm, const void *idx, int idx_dtype,
+                            int64_t stride, void *dx, hipStream_t s) {
+    if (act == R3_BF16) {
+        if (d % 8 == 0)
+            return dx_finish_dispatch<bf16_t, 8>(T, E, K, d / 8, dXp, WrT, dz, inv_perm, idx, idx_dtype, stride,
+                                                 dx, s);
+        return dx_finish_dispatch<bf16_t, 1>(T, E, K, d, dXp, WrT, dz, inv_perm, idx, idx_dtype, stride, dx, s);
+    }
+    if (d % 4 == 0)
+        return dx_finish_dispatch<float, 4>(T, E, K, d / 4, dXp, WrT, dz, inv_perm, idx, idx_dtype, stride, dx,
+                                            s);
+    return dx_finish_dispatch<float, 1>(T, E, K, d, dXp, WrT, dz, inv_perm, idx, idx_dtype, stride, dx, s);
+}
+
+// transpose a small [R,C] matrix (W_r) into [C,R]
+template <typename T>
+__global__ void transpose_kernel(int R, int C, const T *__restrict__ in, T *__restrict__ out) {
+    __shared__ T tile[32][33];
+    int c = blockIdx.x * 32 + threadIdx.x, r0 = blockIdx.y * 32;
+    for (int i = threadIdx.y; i < 32; i += blockDim.y)
+        if (r0 + i < R && c < C) tile[i][threadIdx.x] = in[(int64_t)(r0 + i) * C + c];
+    __syncthreads();
+    int r = r0 + threadIdx.x, c0 = blockIdx.x * 32;
+    for (int i = threadIdx.y; i < 32; i += blockDim.y)
+        if (c0 + i < C && r < R) out[(int64_t)(c0 + i) * R + r] = tile[threadIdx.x][i];
+}
+
+hipError_t launch_transpose(int R, int C, int act, const void *in, void *out, hipStream_t s) {
+    dim3 grid((C + 31) / 32, (R + 31) / 32), block(32, 8);
+    if (act == R3_BF16)
+        transpose_kernel<bf16_t><<<grid, block, 0, s>>>(R, C, (const bf16_t *)in, (bf16_t *)out);
+    else
+        transpose_kernel<float><<<grid, block, 0, s>>>(R, C, (const float *)in, (float *)out);
+    return hipGetLastError();
+}
+
+// column sums of the dense ds [T,E] -> dbias[E] (f32), fixed order: one thread
+// per expert walks the tokens in ascending order in 64 interleaved partials,
+// combined in a fixed tree.
+template <typename T>
+__global__ void __launch_bounds__(64)
+colsum_kernel(int Tn, int E, const T *__restrict__ ds, float *__restrict__ out, int accumulate) {
+    const int e = blockIdx.x, lane = threadIdx.x;
+    float acc = 0.0f;
+    for (int t = lane; t < Tn; t += kWave) acc += Elem<T>::ld(ds + (int64_t)t * E + e);
+    acc = wave_sum(acc);
+    if (lane == 0) out[e] = accumulate ? out[e] + acc : acc;
+}
+
+hipError_t launch_colsum(int T, int E, int act, const void *ds, float *out, int accumulate, hipStream_t s) {
+    if (act == R3_BF16)
+        colsum_kernel<bf16_t><<<E, 64, 0, s>>>(T, E, (const bf16_t *)ds, out, accumulate);
+    else
+        colsum_kernel<float><<<E, 64, 0, s>>>(T, E, (const float *)ds, out, accumulate);
+    return hipGetLastError();
+}
+
+}  // namespace r3

@@ -1,0 +1,172 @@
+"""Thin ctypes binding over libr3.so (the C ABI in include/r3.h).
+
+Argument marshalling only: torch supplies device memory and the current HIP
+stream; every step of the layer runs in the library's kernels.  There is no
+fallback: if the library is missing or a call fails, an exception is raised.
+"""
+import ctypes as C
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libr3.so")
+
+BF16, F32 = 0, 1
+IDX_U8, IDX_U16 = 0, 1
+OP_REPLAY_GATE, OP_PERMUTE, OP_GROUPED_FFN, OP_BACKWARD = 0, 1, 2, 3
+DATA_IDX_RANGE, DATA_IDX_DUP, DATA_NONFINITE = 1, 2, 4
+_STATUS = {1: "R3_ERR_INVALID_ARG", 2: "R3_ERR_UNSUPPORTED", 3: "R3_ERR_WORKSPACE", 4: "R3_ERR_HIP"}
+
+EXPORTS = ["r3_version", "r3_workspace_bytes", "r3_record_topk", "r3_replay_gate", "r3_permute",
+           "r3_grouped_ffn", "r3_combine", "r3_moe_backward"]
+
+
+class LayerDesc(C.Structure):
+    _fields_ = [("T", C.c_int32), ("d", C.c_int32), ("E", C.c_int32), ("K", C.c_int32),
+                ("F", C.c_int32), ("act", C.c_int32), ("idx", C.c_int32), ("reserved", C.c_int32),
+                ("idx_token_stride", C.c_int64)]
+
+
+class R3Error(RuntimeError):
+    pass
+
+
+_lib = None
+
+
+def lib():
+    """Load libr3.so; build it first with paper_2510_11370_amd/build.py."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise R3Error("libr3.so is not built: run `python -m paper_2510_11370_amd.build` "
+                          "(or __graft_entry__.build()); there is no fallback path")
+        L = C.CDLL(LIB_PATH)
+        L.r3_version.restype = C.c_char_p
+        L.r3_workspace_bytes.restype = C.c_size_t
+        L.r3_workspace_bytes.argtypes = [C.POINTER(LayerDesc), C.c_int]
+        for name in EXPORTS[2:]:
+            getattr(L, name).restype = C.c_int
+        _lib = L
+    return _lib
+
+
+def desc(T, d, E, K, F, act="bf16", idx_dtype=None, idx_token_stride=0):
+    if idx_dtype is None:
+        idx_dtype = torch.uint8 if E <= 256 else torch.uint16
+    return LayerDesc(T, d, E, K, F, BF16 if act in ("bf16", torch.bfloat16) else F32,
+                     IDX_U8 if idx_dtype == torch.uint8 else IDX_U16, 0, idx_token_stride)
+
+
+def act_dtype(D):
+    return torch.bfloat16 if D.act == BF16 else torch.float32
+
+
+def idx_torch_dtype(D):
+    return torch.uint8 if D.idx == IDX_U8 else torch.uint16
+
+
+def _p(t):
+    return C.c_void_p(0 if t is None else t.data_ptr())
+
+
+def _stream():
+    return C.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _check(rc, what):
+    if rc != 0:
+        raise R3Error("%s failed: %s" % (what, _STATUS.get(rc, rc)))
+
+
+def workspace_bytes(D, op):
+    return int(lib().r3_workspace_bytes(C.byref(D), op))
+
+
+def workspace(D, op, device="cuda"):
+    """A fresh workspace tensor for `op` (torch's allocator aligns to 256 bytes)."""
+    return torch.empty(max(workspace_bytes(D, op), 256), dtype=torch.uint8, device=device)
+
+
+def record_topk(D, logits, idx_out, status=None):
+    _check(lib().r3_record_topk(C.byref(D), _p(logits), C.c_int64(logits.stride(0)), _p(idx_out),
+                                _p(status), _stream()), "r3_record_topk")
+
+
+def replay_gate(D, x, W_r, idx, gates, bias=None, logits_out=None, agree_out=None, status=None, ws=None):
+    _check(lib().r3_replay_gate(C.byref(D), _p(x), _p(W_r), _p(bias), _p(idx), _p(gates), _p(logits_out),
+                                _p(agree_out), _p(status), _p(ws),
+                                C.c_size_t(0 if ws is None else ws.numel()), _stream()), "r3_replay_gate")
+
+
+def permute(D, x, idx, counts, offsets, inv_perm, perm, Xp, ws, status=None):
+    _check(lib().r3_permute(C.byref(D), _p(x), _p(idx), _p(counts), _p(offsets), _p(inv_perm), _p(perm),
+                            _p(Xp), _p(status), _p(ws), C.c_size_t(ws.numel()), _stream()), "r3_permute")
+
+
+def grouped_ffn(D, Xp, offsets, W_gate, W_up, W_down, Yp, H, A_save=None, B_save=None, ws=None):
+    _check(lib().r3_grouped_ffn(C.byref(D), _p(Xp), _p(offsets), _p(W_gate), _p(W_up), _p(W_down), _p(Yp),
+                                _p(H), _p(A_save), _p(B_save), _p(ws),
+                                C.c_size_t(0 if ws is None else ws.numel()), _stream()), "r3_grouped_ffn")
+
+
+def combine(D, Yp, gates, inv_perm, y):
+    _check(lib().r3_combine(C.byref(D), _p(Yp), _p(gates), _p(inv_perm), _p(y), _stream()), "r3_combine")
+
+
+def moe_backward(D, dy, x, W_r, idx, gates, inv_perm, perm, offsets, Xp, A, B, H, Yp, W_gate, W_up, W_down,
+                 dx, dW_r, dW_gate, dW_up, dW_down, ws, dbias=None, accumulate=False):
+    _check(lib().r3_moe_backward(C.byref(D), _p(dy), _p(x), _p(W_r), _p(idx), _p(gates), _p(inv_perm),
+                                 _p(perm), _p(offsets), _p(Xp), _p(A), _p(B), _p(H), _p(Yp), _p(W_gate),
+                                 _p(W_up), _p(W_down), _p(dx), _p(dW_r), _p(dW_gate), _p(dW_up), _p(dW_down),
+                                 _p(dbias), C.c_int(1 if accumulate else 0), _p(ws), C.c_size_t(ws.numel()),
+                                 _stream()), "r3_moe_backward")
+
+
+class LayerBuffers:
+    """Caller-owned buffers of one layer (everything the C ABI reads or writes)."""
+
+    def __init__(self, D, device="cuda", backward=True):
+        T, d, E, K, F = D.T, D.d, D.E, D.K, D.F
+        S = T * K
+        a = act_dtype(D)
+        e = lambda *s, dt=a: torch.empty(*s, dtype=dt, device=device)
+        self.D = D
+        self.gates = e(T, K, dt=torch.float32)
+        self.counts = e(E, dt=torch.int32)
+        self.offsets = e(E + 1, dt=torch.int32)
+        self.inv_perm = e(S, dt=torch.int32)
+        self.perm = e(S, dt=torch.int32)
+        self.Xp, self.Yp, self.H, self.y = e(S, d), e(S, d), e(S, F), e(T, d)
+        self.status = torch.zeros(1, dtype=torch.int32, device=device)
+        self.ws_gate = workspace(D, OP_REPLAY_GATE, device)
+        self.ws_perm = workspace(D, OP_PERMUTE, device)
+        self.ws_ffn = workspace(D, OP_GROUPED_FFN, device)
+        self.A = self.B = None
+        if backward:
+            self.A, self.B = e(S, F), e(S, F)
+            self.dx = e(T, d)
+            self.dW_r = e(d, E, dt=torch.float32)
+            self.dW_gate = e(E, d, F, dt=torch.float32)
+            self.dW_up = e(E, d, F, dt=torch.float32)
+            self.dW_down = e(E, F, d, dt=torch.float32)
+            self.ws_bwd = workspace(D, OP_BACKWARD, device)
+
+
+def forward(buf, x, W_r, idx, W_gate, W_up, W_down, bias=None, logits_out=None, agree_out=None):
+    """The replayed forward: gate -> permute -> grouped FFN -> combine (four C calls)."""
+    D = buf.D
+    replay_gate(D, x, W_r, idx, buf.gates, bias=bias, logits_out=logits_out, agree_out=agree_out,
+                status=buf.status, ws=buf.ws_gate)
+    permute(D, x, idx, buf.counts, buf.offsets, buf.inv_perm, buf.perm, buf.Xp, buf.ws_perm, status=buf.status)
+    grouped_ffn(D, buf.Xp, buf.offsets, W_gate, W_up, W_down, buf.Yp, buf.H, buf.A, buf.B, ws=buf.ws_ffn)
+    combine(D, buf.Yp, buf.gates, buf.inv_perm, buf.y)
+    return buf.y
+
+
+def backward(buf, dy, x, W_r, idx, W_gate, W_up, W_down, dbias=None, accumulate=False):
+    D = buf.D
+    moe_backward(D, dy, x, W_r, idx, buf.gates, buf.inv_perm, buf.perm, buf.offsets, buf.Xp, buf.A, buf.B,
+                 buf.H, buf.Yp, W_gate, W_up, W_down, buf.dx, buf.dW_r, buf.dW_gate, buf.dW_up, buf.dW_down,
+                 buf.ws_bwd, dbias=dbias, accumulate=accumulate)
