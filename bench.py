@@ -1,0 +1,158 @@
+#!/usr/bin/env python3
+"""Throughput of the replayed MoE layer (record + replay gate + permute + grouped SwiGLU FFN +
+combine + backward) on one MI355X, with the dominant kernel's roofline and the CPU oracle beside it.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload fwdbwd_16k]
+
+One step = one pass of the whole hot path over one batch of seeded synthetic input that is
+already resident in HBM:  r3_record_topk (inference logits -> record), r3_replay_gate,
+r3_permute, r3_grouped_ffn, r3_combine, r3_moe_backward.  Prints ONE JSON line.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA, published
+PEAK_HBM_GBS = 8000.0       # MI355X HBM3E, published
+
+
+def kernel_work(sh, idx_bytes=1):
+    """Algorithmic work of one launch of each timed kernel: (kind, flops or bytes)."""
+    T, d, E, K, F = sh.T, sh.d, sh.E, sh.K, sh.F
+    S = T * K
+    eb = 2  # bf16
+    return {
+        "record_topk": ("hbm", T * (E * 4 + K * idx_bytes)),
+        "router_logits": ("hbm", T * (d * eb + E * 4) + d * E * eb),
+        "replay_gate": ("hbm", T * (K * idx_bytes + K * 4 + K * 4)),
+        "permute_index": ("hbm", T * K * (2 * idx_bytes + 8)),
+        "gather_rows": ("hbm", T * (d * eb + K * d * eb + K * 4)),
+        "combine": ("hbm", T * (K * d * eb + d * eb + K * 8)),
+        "gate_backward": ("hbm", T * (d * eb + 2 * K * d * eb + K * 12 + E * eb)),
+        "dx_finish": ("hbm", T * (K * d * eb + d * eb + K * 12) + E * d * eb),
+        "router_wgrad": ("mfma", 2.0 * T * d * E),
+        "ffn1_swiglu": ("mfma", 4.0 * S * d * F),
+        "ffn2_down": ("mfma", 2.0 * S * d * F),
+        "ffn_dh": ("mfma", 2.0 * S * d * F),
+        "ffn_dxp": ("mfma", 4.0 * S * d * F),
+        "ffn_wgrad": ("mfma", 2.0 * S * d * F),   # per launch; three launches per step
+    }
+
+
+def cpu_baseline(sh, tokens):
+    """The oracle, as it stands, on a bounded sample of the same workload (forward + backward)."""
+    import numpy as np
+    from oracle import sparse
+    from paper_2510_11370_amd import synth
+    sub = sh.with_(T=tokens)
+    L = {k: (None if v is None else v.numpy()) for k, v in synth.make_layer(sub).items()}
+    s = sparse.router_logits(L["x"], L["Wr"], L["bias"])
+    idx = sparse.topk_mask((s + L["noise"]).astype(np.float32), sh.K)
+    t0 = time.perf_counter()
+    fwd = sparse.forward(L["x"], L["Wr"], idx, L["Wg"], L["Wu"], L["Wd"], L["bias"])
+    sparse.backward(L["dy"], L["x"], L["Wr"], idx, L["Wg"], L["Wu"], L["Wd"], fwd)
+    dt = time.perf_counter() - t0
+    return {"value": tokens / dt, "unit": "tokens/s", "cores": sparse.num_threads(), "kind": "oracle",
+            "sample": "%d tokens of the same layer (all %d experts' weights), forward+backward, f64, %.1f s"
+                      % (tokens, sh.E, dt)}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="fwdbwd_16k")
+    ap.add_argument("--cpu-tokens", type=int, default=4096, help="tokens of the oracle's timed sample (0 = skip)")
+    ap.add_argument("--forward-only", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on one GPU only (no sharding, no collectives); use --gpus 1")
+
+    import torch
+    from paper_2510_11370_amd import r3, synth
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: no GPU visible")
+    sh = synth.CONFIGS[args.workload]
+    dev = "cuda"
+    torch.cuda.set_device(0)
+    bwd = not args.forward_only
+    D = r3.desc(sh.T, sh.d, sh.E, sh.K, sh.F, sh.act)
+    adt = r3.act_dtype(D)
+    t = {k: synth.draw(sh, k, dev).to(adt) for k in ("x", "Wr", "Wg", "Wu", "Wd")}
+    dy = synth.draw(sh, "dy", dev).to(adt) if bwd else None
+    bias = synth.draw(sh, "bias", dev)
+    noise = synth.draw(sh, "noise", dev)
+    buf = r3.LayerBuffers(D, backward=bwd)
+    idx = torch.zeros(sh.T, sh.K, dtype=r3.idx_torch_dtype(D), device=dev)
+    # inference logits = training logits + noise (the rollout engine's view), made once
+    logits = torch.empty(sh.T, sh.E, dtype=torch.float32, device=dev)
+    r3.replay_gate(D, t["x"], t["Wr"], idx, buf.gates, bias=bias, logits_out=logits, ws=buf.ws_gate)
+    s_infer = logits + noise
+    del logits, noise
+
+    def step():
+        r3.record_topk(D, s_infer, idx, buf.status)
+        r3.forward(buf, t["x"], t["Wr"], idx, t["Wg"], t["Wu"], t["Wd"], bias=bias)
+        if bwd:
+            r3.backward(buf, dy, t["x"], t["Wr"], idx, t["Wg"], t["Wu"], t["Wd"])
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    # timed region: exactly --steps steps, per-kernel HIP events recorded inside the library
+    r3.profile_enable(True)
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    prof = r3.profile_read()
+    r3.profile_enable(False)
+    assert int(buf.status.item()) == 0, "device status word set"
+    counts = buf.counts.cpu()
+
+    ms_per_step = wall * 1e3 / args.steps
+    work = kernel_work(sh, 1 if D.idx == r3.IDX_U8 else 2)
+    kernels = {}
+    for name, (ms, n) in prof.items():
+        kind, amount = work[name]
+        avg_ms = ms / n
+        if kind == "mfma":
+            ach, peak, unit = amount / avg_ms * 1e-9, PEAK_BF16_TFLOPS, "TFLOP/s"
+        else:
+            ach, peak, unit = amount / avg_ms * 1e-6, PEAK_HBM_GBS, "GB/s"
+        kernels[name] = {"bound": kind, "avg_ms": round(avg_ms, 4), "launches_per_step": n // args.steps,
+                         "achieved": round(ach, 1), "unit": unit, "frac": round(ach / peak, 4)}
+    mfma = {k: v for k, v in kernels.items() if v["bound"] == "mfma" and k.startswith("ffn")}
+    dom = max(mfma, key=lambda k: mfma[k]["avg_ms"] * mfma[k]["launches_per_step"]) if mfma else None
+    roofline = None
+    if dom:
+        kd = kernels[dom]
+        roofline = {"kernel": dom, "bound": "mfma", "achieved": kd["achieved"], "peak": PEAK_BF16_TFLOPS,
+                    "unit": "TFLOP/s", "frac": kd["frac"], "traffic": None}
+    out = {
+        "metric": "tokens/sec for R3 replayed MoE layer fwd+bwd at 1 GPU",
+        "value": round(sh.T / (ms_per_step * 1e-3), 1), "unit": "tokens/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": sh.act,
+        "data": "synthetic (seeded; shape of a 128-expert top-8 MoE layer)",
+        "config": {"workload": "%s: T=%d d=%d E=%d K=%d F=%d %s, record+forward%s" % (
+            args.workload, sh.T, sh.d, sh.E, sh.K, sh.F, sh.act, "+backward" if bwd else ""),
+            "rows_per_expert_min_mean_max": [int(counts.min()), float(counts.float().mean()), int(counts.max())]},
+        "roofline": roofline, "kernels": kernels,
+    }
+    if args.cpu_tokens > 0:
+        del buf
+        torch.cuda.empty_cache()
+        out["cpu_baseline"] = cpu_baseline(sh, args.cpu_tokens)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -158,6 +158,19 @@ int r3_moe_backward(const r3_layer_desc *desc, const void *dy, const void *x,
                     float *dW_gate, float *dW_up, float *dW_down, float *dbias,
                     int accumulate, void *ws, size_t ws_bytes, void *stream);
 
+/*
+ * Measurement aid (not part of the method): per-kernel timing with HIP events
+ * recorded on the launch stream.  r3_profile_enable(1) clears the counters and
+ * starts recording (at most 512 launches per kernel are kept), (0) stops.
+ * r3_profile_read waits for the recorded events and returns the summed
+ * duration in milliseconds and the number of launches of kernel `tag`
+ * (0 <= tag < r3_profile_tags()); r3_profile_name names it.
+ */
+int r3_profile_enable(int on);
+int r3_profile_tags(void);
+const char *r3_profile_name(int tag);
+int r3_profile_read(int tag, double *total_ms, int *launches);
+
 #ifdef __cplusplus
 }
 #endif

@@ -48,7 +48,7 @@ BwdWs bwd_layout(const Dims &m) {
     auto take = [&](size_t bytes) { size_t at = o; o += align_up(bytes, 256); return at; };
     w.dYp = take((size_t)m.S * m.d * m.eb);  // later reused for dXp
     w.dz = take((size_t)m.T * m.K * sizeof(float));
-    w.ds = take((size_t)m.T * m.E * m.eb);
+    w.ds = take((size_t)m.T * m.E * (m.act == R3_BF16 ? 2 : 1) * m.eb);  // bf16: (hi, lo) halves
     w.WrT = take((size_t)m.E * m.d * m.eb);
     w.dA = take((size_t)m.S * m.F * m.eb);
     w.dB = take((size_t)m.S * m.F * m.eb);

@@ -276,9 +276,11 @@ logits_kernel(int T, int d, int E, const bf16_t *__restrict__ x, const bf16_t *_
 }
 
 // ---------------------------------------------------------------------------
-// Router weight gradient, split over tokens:
-//   part[s][c][e] = sum_{t in split s} x[t][c] * ds[t][e]
-// followed by a fixed-order sum over the splits.
+// Router weight gradient, split over tokens.  ds arrives as [T, 2E] bf16 with
+// dz split into hi (columns 0..E) and lo (columns E..2E) halves:
+//   part[s][c][e'] = sum_{t in split s} x[t][c] * ds[t][e'],   e' in [0, 2E)
+// followed by a fixed-order sum over the splits and over (hi, lo).
+// (E below is the width of ds, i.e. twice the number of experts.)
 // ---------------------------------------------------------------------------
 template <class TL>
 __global__ void __launch_bounds__(TL::NT)
@@ -311,13 +313,18 @@ dwr_partial_kernel(int T, int d, int E, int rows_per_split, const bf16_t *__rest
     });
 }
 
+// out[c][e] (+)= sum_s part[s][c][e] + part[s][c][E+e]
 __global__ void __launch_bounds__(256)
-split_reduce_kernel(int64_t n, int nsplit, const float *__restrict__ part, float *__restrict__ out,
+split_reduce_kernel(int d, int E, int nsplit, const float *__restrict__ part, float *__restrict__ out,
                     int accumulate) {
     const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i >= n) return;
+    if (i >= (int64_t)d * E) return;
+    const int c = (int)(i / E), e = (int)(i - (int64_t)c * E);
     float acc = accumulate ? out[i] : 0.0f;
-    for (int s = 0; s < nsplit; ++s) acc += part[(int64_t)s * n + i];
+    for (int s = 0; s < nsplit; ++s) {
+        const float *row = part + ((int64_t)s * d + c) * 2 * E;
+        acc += row[e] + row[E + e];
+    }
     out[i] = acc;
 }
 
@@ -329,7 +336,7 @@ typedef TileCfg<128, 64, 2, 2, 64> TLLogits;   // router: 128 experts x 64 token
 typedef TileCfg<128, 128, 2, 2, 64> TLDwr;     // router wgrad: 128 experts x 128 hidden
 
 bool mfma_ffn_supported(int d, int F) { return d % 256 == 0 && F % 256 == 0 && d >= 256 && F >= 256; }
-bool mfma_router_supported(int d, int E) { return E % 128 == 0 && d % 128 == 0; }
+bool mfma_router_supported(int d, int E) { return E % 128 == 0 && d % 128 == 0; }  // 2E % 128 for ds
 
 size_t mfma_tiles_bytes(int64_t S, int E) {
     return align_up((size_t)(2 + 2 * (size_t)max_row_tiles(S, E, TLMain::BQ)) * sizeof(int32_t), 256);
@@ -351,10 +358,14 @@ hipError_t mfma_ffn_forward(int64_t S, int d, int E, int F, const void *Xp, cons
     typedef TLMain TL;
     const int mt = max_row_tiles(S, E, TL::BQ);
     allow_lds(ffn1_kernel<TL>, TL::LDS_BYTES);
-    ffn1_kernel<TL><<<grid_for((int64_t)mt * (F / (TL::BP / 2))), TL::NT, TL::LDS_BYTES, s>>>(
+    {
+        ProfScope ps(PROF_FFN1, s);
+        ffn1_kernel<TL><<<grid_for((int64_t)mt * (F / (TL::BP / 2))), TL::NT, TL::LDS_BYTES, s>>>(
         (int)S, d, F, (const bf16_t *)Xp, offsets, tiles, (const bf16_t *)Wg, (const bf16_t *)Wu, (bf16_t *)H,
         (bf16_t *)A, (bf16_t *)B);
+    }
     allow_lds(rowgemm_kernel<TL, 0>, TL::LDS_BYTES);
+    ProfScope ps(PROF_FFN2, s);
     rowgemm_kernel<TL, 0><<<grid_for((int64_t)mt * (d / TL::BP)), TL::NT, TL::LDS_BYTES, s>>>(
         (int)S, d, F, (const bf16_t *)H, nullptr, offsets, tiles, (const bf16_t *)Wd, nullptr, nullptr, nullptr,
         (bf16_t *)Yp, nullptr);
@@ -367,6 +378,7 @@ hipError_t mfma_ffn_dh(int64_t S, int d, int E, int F, const void *dYp, const in
     typedef TLMain TL;
     const int mt = max_row_tiles(S, E, TL::BQ);
     allow_lds(rowgemm_kernel<TL, 1>, TL::LDS_BYTES);
+    ProfScope ps(PROF_DH, s);
     rowgemm_kernel<TL, 1><<<grid_for((int64_t)mt * (F / TL::BP)), TL::NT, TL::LDS_BYTES, s>>>(
         (int)S, d, F, (const bf16_t *)dYp, nullptr, offsets, tiles, (const bf16_t *)Wd, nullptr,
         (const bf16_t *)A, (const bf16_t *)B, (bf16_t *)dA, (bf16_t *)dB);
@@ -378,6 +390,7 @@ hipError_t mfma_ffn_dxp(int64_t S, int d, int E, int F, const void *dA, const vo
     typedef TLMain TL;
     const int mt = max_row_tiles(S, E, TL::BQ);
     allow_lds(rowgemm_kernel<TL, 2>, TL::LDS_BYTES);
+    ProfScope ps(PROF_DXP, s);
     rowgemm_kernel<TL, 2><<<grid_for((int64_t)mt * (d / TL::BP)), TL::NT, TL::LDS_BYTES, s>>>(
         (int)S, d, F, (const bf16_t *)dA, (const bf16_t *)dB, offsets, tiles, (const bf16_t *)Wg,
         (const bf16_t *)Wu, nullptr, nullptr, (bf16_t *)dXp, nullptr);
@@ -389,6 +402,7 @@ hipError_t mfma_wgrad(int E, int NQd, int NPd, const void *Qs, const void *Ps, c
     typedef TLMain TL;
     allow_lds(wgrad_kernel<TL>, TL::LDS_BYTES);
     const int64_t tiles = (int64_t)E * (NQd / TL::BQ) * (NPd / TL::BP);
+    ProfScope ps(PROF_WGRAD, s);
     wgrad_kernel<TL><<<grid_for(tiles), TL::NT, TL::LDS_BYTES, s>>>(E, NQd, NPd, (const bf16_t *)Qs,
                                                                   (const bf16_t *)Ps, offsets, out, accumulate);
     return hipGetLastError();
@@ -399,6 +413,7 @@ hipError_t mfma_router_logits(int T, int d, int E, const void *x, const void *Wr
     typedef TLLogits TL;
     allow_lds(logits_kernel<TL>, TL::LDS_BYTES);
     const int tiles = ((T + TL::BQ - 1) / TL::BQ) * (E / TL::BP);
+    ProfScope ps(PROF_LOGITS, s);
     logits_kernel<TL><<<tiles, TL::NT, TL::LDS_BYTES, s>>>(T, d, E, (const bf16_t *)x, (const bf16_t *)Wr, bias,
                                                          logits);
     return hipGetLastError();
@@ -408,7 +423,9 @@ static int dwr_splits(int T) {
     int s = (T + 511) / 512;
     return s < 1 ? 1 : (s > 64 ? 64 : s);
 }
-size_t mfma_dwr_ws_bytes(int T, int d, int E) { return align_up((size_t)dwr_splits(T) * d * E * sizeof(float), 256); }
+size_t mfma_dwr_ws_bytes(int T, int d, int E) {
+    return align_up((size_t)dwr_splits(T) * d * 2 * E * sizeof(float), 256);
+}
 
 hipError_t mfma_dwr(int T, int d, int E, const void *x, const void *ds, float *part, float *dWr, int accumulate,
                     hipStream_t s) {
@@ -417,10 +434,11 @@ hipError_t mfma_dwr(int T, int d, int E, const void *x, const void *ds, float *p
     int rows = (T + ns - 1) / ns;
     rows = (rows + TL::BK - 1) / TL::BK * TL::BK;
     allow_lds(dwr_partial_kernel<TL>, TL::LDS_BYTES);
-    dwr_partial_kernel<TL><<<ns * (d / TL::BQ) * (E / TL::BP), TL::NT, TL::LDS_BYTES, s>>>(
-        T, d, E, rows, (const bf16_t *)x, (const bf16_t *)ds, part);
+    ProfScope ps(PROF_DWR, s);
+    dwr_partial_kernel<TL><<<ns * (d / TL::BQ) * (2 * E / TL::BP), TL::NT, TL::LDS_BYTES, s>>>(
+        T, d, 2 * E, rows, (const bf16_t *)x, (const bf16_t *)ds, part);
     const int64_t n = (int64_t)d * E;
-    split_reduce_kernel<<<(int)((n + 255) / 256), 256, 0, s>>>(n, ns, part, dWr, accumulate);
+    split_reduce_kernel<<<(int)((n + 255) / 256), 256, 0, s>>>(d, E, ns, part, dWr, accumulate);
     return hipGetLastError();
 }
 

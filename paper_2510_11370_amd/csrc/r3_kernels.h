@@ -4,6 +4,19 @@
 
 namespace r3 {
 
+// Optional per-kernel timing with HIP events on the launch stream (off by default).
+// A ProfScope brackets one kernel launch; r3_profile_read() sums what was recorded.
+enum ProfTag {
+    PROF_RECORD = 0, PROF_LOGITS, PROF_GATE, PROF_PERMUTE_INDEX, PROF_GATHER_ROWS, PROF_FFN1, PROF_FFN2,
+    PROF_COMBINE, PROF_GATE_BWD, PROF_DWR, PROF_DH, PROF_WGRAD, PROF_DXP, PROF_DX_FINISH, PROF_NTAGS
+};
+struct ProfScope {
+    int tag, slot;
+    hipStream_t s;
+    ProfScope(int tag, hipStream_t s);
+    ~ProfScope();
+};
+
 // r3_route.hip
 hipError_t launch_record_topk(int T, int E, int K, const float *logits, int64_t ld, void *idx,
                               int idx_dtype, int64_t stride, int32_t *status, hipStream_t s);

@@ -1,0 +1,75 @@
+// Per-kernel timing with HIP events (measurement aid, see include/r3.h).
+#include <mutex>
+#include <vector>
+
+#include "r3_kernels.h"
+
+namespace r3 {
+namespace {
+constexpr int kPool = 512;
+struct TagState {
+    std::vector<hipEvent_t> start, stop;
+    int used = 0;
+};
+std::mutex g_mu;
+bool g_on = false;
+TagState g_tags[PROF_NTAGS];
+const char *kNames[PROF_NTAGS] = {"record_topk", "router_logits", "replay_gate", "permute_index",
+                                  "gather_rows", "ffn1_swiglu", "ffn2_down", "combine", "gate_backward",
+                                  "router_wgrad", "ffn_dh", "ffn_wgrad", "ffn_dxp", "dx_finish"};
+}  // namespace
+
+ProfScope::ProfScope(int tag_, hipStream_t s_) : tag(tag_), slot(-1), s(s_) {
+    std::lock_guard<std::mutex> lk(g_mu);
+    if (!g_on) return;
+    TagState &t = g_tags[tag];
+    if (t.used >= kPool) return;
+    if ((int)t.start.size() <= t.used) {
+        hipEvent_t a, b;
+        if (hipEventCreate(&a) != hipSuccess || hipEventCreate(&b) != hipSuccess) return;
+        t.start.push_back(a);
+        t.stop.push_back(b);
+    }
+    slot = t.used++;
+    (void)hipEventRecord(t.start[slot], s);
+}
+
+ProfScope::~ProfScope() {
+    if (slot < 0) return;
+    std::lock_guard<std::mutex> lk(g_mu);
+    (void)hipEventRecord(g_tags[tag].stop[slot], s);
+}
+}  // namespace r3
+
+using namespace r3;
+
+extern "C" {
+
+int r3_profile_enable(int on) {
+    std::lock_guard<std::mutex> lk(g_mu);
+    g_on = on != 0;
+    if (g_on)
+        for (auto &t : g_tags) t.used = 0;
+    return R3_OK;
+}
+
+int r3_profile_tags(void) { return PROF_NTAGS; }
+
+const char *r3_profile_name(int tag) { return (tag >= 0 && tag < PROF_NTAGS) ? kNames[tag] : ""; }
+
+int r3_profile_read(int tag, double *total_ms, int *launches) {
+    if (tag < 0 || tag >= PROF_NTAGS || !total_ms || !launches) return R3_ERR_INVALID_ARG;
+    std::lock_guard<std::mutex> lk(g_mu);
+    TagState &t = g_tags[tag];
+    double sum = 0.0;
+    for (int i = 0; i < t.used; ++i) {
+        if (hipEventSynchronize(t.stop[i]) != hipSuccess) return R3_ERR_HIP;
+        float ms = 0.0f;
+        if (hipEventElapsedTime(&ms, t.start[i], t.stop[i]) != hipSuccess) return R3_ERR_HIP;
+        sum += ms;
+    }
+    *total_ms = sum;
+    *launches = t.used;
+    return R3_OK;
+}
+}

@@ -143,6 +143,7 @@ record_topk_wave_kernel(int T, int E, int K, const float *__restrict__ logits, i
 
 hipError_t launch_record_topk(int T, int E, int K, const float *logits, int64_t ld, void *idx,
                               int idx_dtype, int64_t stride, int32_t *status, hipStream_t s) {
+    ProfScope ps(PROF_RECORD, s);
     if (K <= 8 && E <= 512) {
         size_t lds = (size_t)kWave * (E + 4) * sizeof(float);
         int grid = (T + kWave - 1) / kWave;
@@ -200,6 +201,7 @@ gate_kernel(int T, int E, int K, const float *__restrict__ logits, const IdxT *_
 
 hipError_t launch_gate(int T, int E, int K, const float *logits, const void *idx, int idx_dtype,
                        int64_t stride, float *gates, hipStream_t s) {
+    ProfScope ps(PROF_GATE, s);
     int grid = (T + 255) / 256;
     if (idx_dtype == R3_IDX_U8)
         gate_kernel<uint8_t><<<grid, 256, 0, s>>>(T, E, K, logits, (const uint8_t *)idx, stride, gates);
@@ -433,6 +435,8 @@ hipError_t launch_permute(int T, int d, int E, int K, int elem_bytes, const void
     int32_t *chunk_hist = (int32_t *)ws;
     const int grid = (nchunks + 3) / 4;
     const size_t lds = (size_t)4 * E * sizeof(int32_t);
+    {
+    ProfScope ps(PROF_PERMUTE_INDEX, s);
     if (idx_dtype == R3_IDX_U8)
         permute_hist_kernel<uint8_t><<<grid, 256, lds, s>>>(T, E, K, (const uint8_t *)idx, stride, chunk,
                                                            nchunks, chunk_hist, status);
@@ -447,7 +451,9 @@ hipError_t launch_permute(int T, int d, int E, int K, int elem_bytes, const void
         permute_place_kernel<uint16_t><<<grid, 256, lds, s>>>(T, E, K, (const uint16_t *)idx, stride,
                                                              chunk, nchunks, chunk_hist, offsets,
                                                              inv_perm, perm);
+    }
     if (Xp) {
+        ProfScope ps(PROF_GATHER_ROWS, s);
         const int64_t row_bytes = (int64_t)d * elem_bytes;
         if (row_bytes % 16 == 0)
             gather_rows_kernel<uint4><<<T, 256, 0, s>>>(T, K, (int)(row_bytes / 16), (const uint4 *)x,
@@ -535,6 +541,7 @@ combine_kernel(int K, int row_vecs, const typename VecIO<T, VEC>::V *__restrict_
 
 hipError_t launch_combine(int T, int d, int K, int act, const void *Yp, const float *gates,
                           const int32_t *inv_perm, void *y, hipStream_t s) {
+    ProfScope ps(PROF_COMBINE, s);
     if (act == R3_BF16) {
         if (d % 8 == 0)
             combine_kernel<bf16_t, 8><<<T, 256, 0, s>>>(K, d / 8, (const uint4 *)Yp, gates, inv_perm,
@@ -557,8 +564,9 @@ hipError_t launch_combine(int T, int d, int K, int act, const void *Yp, const fl
 // Backward through combine and masked softmax, one block per token:
 //   dg_j = <dy_t, Yp[row_j]>,  dYp[row_j] = g_j * dy_t,
 //   dz_j = g_j (dg_j - sum_i g_i dg_i).
-// Writes dz [T,K] f32 and, when ds_dense != NULL, the dense row ds[t,:] (act
-// dtype, zero off the recorded set) that the router weight gradient contracts.
+// Writes dz [T,K] f32 and, when ds_dense != NULL, the dense row ds[t,:] (zero off
+// the recorded set) that the router weight gradient contracts: [T,E] f32, or for
+// bf16 activations [T,2E] holding dz as hi and lo bf16 halves.
 // ---------------------------------------------------------------------------
 template <typename T, int VEC, typename IdxT>
 __global__ void __launch_bounds__(256)
@@ -578,8 +586,11 @@ gate_backward_kernel(int E, int K, int row_vecs, const typename VecIO<T, VEC>::V
         rows[threadIdx.x] = inv_perm[(int64_t)t * K + threadIdx.x];
         g[threadIdx.x] = gates[(int64_t)t * K + threadIdx.x];
     }
+    // bf16 activations: ds is stored as a (hi, lo) pair of bf16 rows [hi(E) | lo(E)] so that the
+    // router weight gradient sees dz to about 16 bits instead of 8
+    const int dsw = (sizeof(T) == 2) ? 2 * E : E;
     if (ds_dense)
-        for (int e = threadIdx.x; e < E; e += blockDim.x) Elem<T>::st(ds_dense + (int64_t)t * E + e, 0.0f);
+        for (int e = threadIdx.x; e < dsw; e += blockDim.x) Elem<T>::st(ds_dense + (int64_t)t * dsw + e, 0.0f);
     __syncthreads();
     for (int j = 0; j < K; ++j) {
         float dot = 0.0f;
@@ -612,7 +623,9 @@ gate_backward_kernel(int E, int K, int row_vecs, const typename VecIO<T, VEC>::V
         dz[(int64_t)t * K + threadIdx.x] = v;
         if (ds_dense) {
             int e = min((int)idx[(int64_t)t * stride + threadIdx.x], E - 1);
-            Elem<T>::st(ds_dense + (int64_t)t * E + e, v);
+            T *row = ds_dense + (int64_t)t * dsw;
+            Elem<T>::st(row + e, v);
+            if (sizeof(T) == 2) Elem<T>::st(row + E + e, v - Elem<T>::ld(row + e));
         }
     }
 }
@@ -639,6 +652,7 @@ hipError_t launch_gate_backward(int T, int d, int E, int K, int act, const void 
                                 const float *gates, const int32_t *inv_perm, const void *idx,
                                 int idx_dtype, int64_t stride, void *dYp, float *dz, void *ds_dense,
                                 hipStream_t s) {
+    ProfScope ps(PROF_GATE_BWD, s);
     if (act == R3_BF16) {
         if (d % 8 == 0)
             return gate_backward_dispatch<bf16_t, 8>(T, E, K, d / 8, dy, Yp, gates, inv_perm, idx, idx_dtype,
@@ -714,6 +728,7 @@ static hipError_t dx_finish_dispatch(int Tn, int E, int K, int row_vecs, const v
 hipError_t launch_dx_finish(int T, int d, int E, int K, int act, const void *dXp, const void *WrT,
                             const float *dz, const int32_t *inv_perm, const void *idx, int idx_dtype,
                             int64_t stride, void *dx, hipStream_t s) {
+    ProfScope ps(PROF_DX_FINISH, s);
     if (act == R3_BF16) {
         if (d % 8 == 0)
             return dx_finish_dispatch<bf16_t, 8>(T, E, K, d / 8, dXp, WrT, dz, inv_perm, idx, idx_dtype, stride,
@@ -755,8 +770,12 @@ template <typename T>
 __global__ void __launch_bounds__(64)
 colsum_kernel(int Tn, int E, const T *__restrict__ ds, float *__restrict__ out, int accumulate) {
     const int e = blockIdx.x, lane = threadIdx.x;
+    const int dsw = (sizeof(T) == 2) ? 2 * E : E;
     float acc = 0.0f;
-    for (int t = lane; t < Tn; t += kWave) acc += Elem<T>::ld(ds + (int64_t)t * E + e);
+    for (int t = lane; t < Tn; t += kWave) {
+        acc += Elem<T>::ld(ds + (int64_t)t * dsw + e);
+        if (sizeof(T) == 2) acc += Elem<T>::ld(ds + (int64_t)t * dsw + E + e);
+    }
     acc = wave_sum(acc);
     if (lane == 0) out[e] = accumulate ? out[e] + acc : acc;
 }

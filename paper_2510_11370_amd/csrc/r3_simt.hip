@@ -127,8 +127,13 @@ simt_dwr_kernel(int Tn, int d, int E, const T *__restrict__ x, const T *__restri
     int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (i >= (int64_t)d * E) return;
     int c = (int)(i / E), e = (int)(i - (int64_t)c * E);
+    const int dsw = (sizeof(T) == 2) ? 2 * E : E;  // bf16: ds rows are [hi(E) | lo(E)]
     float acc = 0.0f;
-    for (int t = 0; t < Tn; ++t) acc = fmaf(Elem<T>::ld(x + (int64_t)t * d + c), Elem<T>::ld(ds + (int64_t)t * E + e), acc);
+    for (int t = 0; t < Tn; ++t) {
+        float dv = Elem<T>::ld(ds + (int64_t)t * dsw + e);
+        if (sizeof(T) == 2) dv += Elem<T>::ld(ds + (int64_t)t * dsw + E + e);
+        acc = fmaf(Elem<T>::ld(x + (int64_t)t * d + c), dv, acc);
+    }
     dWr[i] = accumulate ? dWr[i] + acc : acc;
 }
 

@@ -19,7 +19,8 @@ DATA_IDX_RANGE, DATA_IDX_DUP, DATA_NONFINITE = 1, 2, 4
 _STATUS = {1: "R3_ERR_INVALID_ARG", 2: "R3_ERR_UNSUPPORTED", 3: "R3_ERR_WORKSPACE", 4: "R3_ERR_HIP"}
 
 EXPORTS = ["r3_version", "r3_workspace_bytes", "r3_record_topk", "r3_replay_gate", "r3_permute",
-           "r3_grouped_ffn", "r3_combine", "r3_moe_backward"]
+           "r3_grouped_ffn", "r3_combine", "r3_moe_backward", "r3_profile_enable", "r3_profile_tags",
+           "r3_profile_name", "r3_profile_read"]
 
 
 class LayerDesc(C.Structure):
@@ -48,6 +49,7 @@ def lib():
         L.r3_workspace_bytes.argtypes = [C.POINTER(LayerDesc), C.c_int]
         for name in EXPORTS[2:]:
             getattr(L, name).restype = C.c_int
+        L.r3_profile_name.restype = C.c_char_p
         _lib = L
     return _lib
 
@@ -170,3 +172,18 @@ def backward(buf, dy, x, W_r, idx, W_gate, W_up, W_down, dbias=None, accumulate=
     moe_backward(D, dy, x, W_r, idx, buf.gates, buf.inv_perm, buf.perm, buf.offsets, buf.Xp, buf.A, buf.B,
                  buf.H, buf.Yp, W_gate, W_up, W_down, buf.dx, buf.dW_r, buf.dW_gate, buf.dW_up, buf.dW_down,
                  buf.ws_bwd, dbias=dbias, accumulate=accumulate)
+
+
+def profile_enable(on=True):
+    lib().r3_profile_enable(C.c_int(1 if on else 0))
+
+
+def profile_read():
+    """{kernel name: (total milliseconds, launches)} recorded since profile_enable(True)."""
+    out = {}
+    for tag in range(lib().r3_profile_tags()):
+        ms, n = C.c_double(0.0), C.c_int(0)
+        _check(lib().r3_profile_read(tag, C.byref(ms), C.byref(n)), "r3_profile_read")
+        if n.value:
+            out[lib().r3_profile_name(tag).decode()] = (ms.value, n.value)
+    return out

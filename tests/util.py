@@ -11,7 +11,15 @@ REL = {"bf16": 1e-2, "f32": 2e-4}
 
 
 def assert_close(gpu, ref, name, rel):
-    """Norm-wise |gpu-ref|_2 <= rel |ref|_2 and element-wise |gpu-ref| <= rel|ref| + rel*rms(ref)."""
+    """The floating-point bar for tensors in the activation dtype and for weight gradients.
+
+    1. whole tensor, norm-wise:  |gpu-ref|_2 <= rel |ref|_2                (the stated bar)
+    2. every row (last dim), norm-wise: <= 2 rel |row|_2 + rel rms(ref) sqrt(n)
+       (a single wrong token or feature row cannot hide in the tensor norm)
+    3. every element: |gpu-ref| <= rel |ref| + 5 rel rms(ref)
+       (outlier guard; bf16 rounding noise of a multi-stage chain has several-sigma tails
+       of a few percent of the rms, a misplaced element is off by about one rms)
+    """
     gpu = np.asarray(gpu, np.float64)
     ref = np.asarray(ref, np.float64)
     assert gpu.shape == ref.shape, (name, gpu.shape, ref.shape)
@@ -20,9 +28,17 @@ def assert_close(gpu, ref, name, rel):
     err = np.linalg.norm(gpu - ref)
     assert err <= rel * nref + 1e-30, "%s: normwise rel err %.3e > %.1e" % (name, err / max(nref, 1e-300), rel)
     rms = nref / np.sqrt(max(ref.size, 1))
-    bad = np.abs(gpu - ref) > rel * np.abs(ref) + rel * rms
+    if ref.ndim >= 2:
+        n = ref.shape[-1]
+        rerr = np.linalg.norm((gpu - ref).reshape(-1, n), axis=1)
+        rref = np.linalg.norm(ref.reshape(-1, n), axis=1)
+        badrow = rerr > 2 * rel * rref + rel * rms * np.sqrt(n)
+        assert not badrow.any(), "%s: %d rows outside tolerance (worst row rel err %.3e)" % (
+            name, badrow.sum(), (rerr / np.maximum(rref, 1e-300)).max())
+    bad = np.abs(gpu - ref) > rel * np.abs(ref) + 5 * rel * rms
     assert not bad.any(), "%s: %d of %d elements outside tolerance (max abs err %.3e, rms %.3e)" % (
         name, bad.sum(), bad.size, np.abs(gpu - ref).max(), rms)
+    return err / max(nref, 1e-300)
 
 
 def assert_gates_close(gpu, ref):
