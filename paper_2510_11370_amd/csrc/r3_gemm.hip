@@ -8,6 +8,7 @@
 // nothing returns to the host between the permutation and the contractions.
 #include "r3_kernels.h"
 #include "r3_mfma.h"
+#include "r3_mfma2.h"
 
 namespace r3 {
 
@@ -53,16 +54,17 @@ __device__ __forceinline__ void unpack4(uint2 v, float *f) {
 
 // ---------------------------------------------------------------------------
 // FFN, first contraction + SwiGLU:  A = Xp Wg, B = Xp Wu, H = silu(A) * B.
-// The P tile interleaves 32-feature blocks of W_gate and W_up so that a wave
-// holds both pre-activations of the same (row, feature) in the same lane.
+// The P operand is two 128-feature sub-tiles, one of W_gate and one of W_up, at
+// the same features, so a wave holds both pre-activations of a (row, feature)
+// pair in the same lane: MFMA tiles 0,1 are gate, tiles 2,3 the matching up.
 // ---------------------------------------------------------------------------
-template <class TL>
-__global__ void __launch_bounds__(TL::NT, 2)
+__global__ void __launch_bounds__(kThreads2, 2)
 ffn1_kernel(int S, int d, int F, const bf16_t *__restrict__ Xp, const int32_t *__restrict__ offsets,
             const int32_t *__restrict__ tiles, const bf16_t *__restrict__ Wg, const bf16_t *__restrict__ Wu,
             bf16_t *__restrict__ H, bf16_t *__restrict__ A, bf16_t *__restrict__ B) {
-    extern __shared__ __attribute__((aligned(16))) char lds[];
-    constexpr int BF = TL::BP / 2;  // features per tile
+    __shared__ __attribute__((aligned(1024))) char s0[kStageBytes];
+    __shared__ __attribute__((aligned(1024))) char s1[kStageBytes];
+    constexpr int BF = 128;  // features per tile
     const int npt = F / BF;
     const int id = xcd_tile_id(tiles[0] * npt);
     if (id < 0) return;
@@ -70,37 +72,37 @@ ffn1_kernel(int S, int d, int F, const bf16_t *__restrict__ Xp, const int32_t *_
     const int e = tiles[2 + 2 * tile], row0 = tiles[3 + 2 * tile];
     const int row_end = offsets[e + 1];
     const int f0 = pt * BF;
-    const bf16_t *wg = Wg + (int64_t)e * d * F, *wu = Wu + (int64_t)e * d * F;
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int wp = wave % kWP2, wq = wave / kWP2;
 
-    auto fp = [&](int kt, int k, int c) -> uint4 {
-        const int blk = c >> 2;
-        const bf16_t *src = (blk & 1) ? wu : wg;
-        return ld16(src + (int64_t)(kt * TL::BK + k) * F + f0 + (blk >> 1) * 32 + (c & 3) * 8);
-    };
-    auto fq = [&](int kt, int r, int c) -> uint4 {
-        const int row = min(row0 + r, S - 1);  // rows past the segment are never stored
-        return ld16(Xp + (int64_t)row * d + kt * TL::BK + c * 8);
-    };
-    f32x16_t acc[TL::TP][TL::TQ];
-    zero_acc<TL>(acc);
-    mfma_mainloop<TL, true, false>(acc, d / TL::BK, fp, fq, lds);
+    OpTR128x2 P;
+    P.src[0] = Src{(const char *)(Wg + (int64_t)e * d * F), clamp_bytes((int64_t)d * F * 2), (uint32_t)(kBK2 * F * 2)};
+    P.src[1] = Src{(const char *)(Wu + (int64_t)e * d * F), clamp_bytes((int64_t)d * F * 2), (uint32_t)(kBK2 * F * 2)};
+    P.init(F * 2, f0 * 2, 64 * wp);
+    OpKC256 Q;
+    Q.src[0] = Src{(const char *)(Xp + (int64_t)row0 * d), clamp_bytes((int64_t)(S - row0) * d * 2), kBK2 * 2};
+    Q.src[1] = Q.src[0];
+    Q.kswitch = 0x7fffffff;
+    Q.init(d * 2, 64 * wq);
 
-    const int wave = threadIdx.x >> 6, lane = lane_id();
-    const int wp = wave % TL::WP, wq = wave / TL::WP;
+    Acc2 acc;
+    zero_acc2(acc);
+    mfma_mainloop2(acc, d / kBK2, P, Q, s0, s1);
+
 #pragma unroll
-    for (int tp = 0; tp < TL::TP; tp += 2)
+    for (int tp = 0; tp < 2; ++tp)
 #pragma unroll
-        for (int tq = 0; tq < TL::TQ; ++tq) {
-            const int row = row0 + wq * TL::WTQ + tq * 32 + (lane & 31);
+        for (int tq = 0; tq < kTQ2; ++tq) {
+            const int row = row0 + wq * 64 + tq * 32 + (lane & 31);
             if (row >= row_end) continue;
 #pragma unroll
             for (int g = 0; g < 4; ++g) {
-                const int f = f0 + (wp * TL::WTP + tp * 32) / 2 + g * 8 + (lane >> 5) * 4;
+                const int f = f0 + wp * 64 + tp * 32 + g * 8 + (lane >> 5) * 4;
                 float a[4], b[4], h[4];
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
                     a[i] = acc[tp][tq][4 * g + i];
-                    b[i] = acc[tp + 1][tq][4 * g + i];
+                    b[i] = acc[tp + 2][tq][4 * g + i];
                     h[i] = a[i] * sigmoidf_(a[i]) * b[i];
                 }
                 const int64_t o = (int64_t)row * F + f;
@@ -113,64 +115,71 @@ ffn1_kernel(int S, int d, int F, const bf16_t *__restrict__ Xp, const int32_t *_
 
 // ---------------------------------------------------------------------------
 // Row-ragged contraction with a plain or SwiGLU-backward epilogue:
-//   out[row][c0+p] = sum_k Q[row][k] * Pmat[e](p, k)
+//   out[row][p0+p] = sum_k Q[row][k] * Pmat[e](p, k)
 // MODE 0: Yp = H Wd          P from Wd[e] [F,d]  (TR: k rows, features c), K = F
 // MODE 1: dH = dYp Wd^T      P from Wd[e] [F,d]  (KC: feature rows f),      K = d
 //         epilogue dA = dh*B*silu'(A), dB = dh*silu(A)
 // MODE 2: dXp = dA Wg^T + dB Wu^T   P from Wg[e], Wu[e] [d,F] (KC: rows c), K = 2F
+//         (two-phase reduction: first F over (dA, Wg), then F over (dB, Wu))
 // ---------------------------------------------------------------------------
-template <class TL, int MODE>
-__global__ void __launch_bounds__(TL::NT, 2)
+template <int MODE>
+__global__ void __launch_bounds__(kThreads2, 2)
 rowgemm_kernel(int S, int d, int F, const bf16_t *__restrict__ Q0, const bf16_t *__restrict__ Q1,
                const int32_t *__restrict__ offsets, const int32_t *__restrict__ tiles,
                const bf16_t *__restrict__ W0, const bf16_t *__restrict__ W1, const bf16_t *__restrict__ A,
                const bf16_t *__restrict__ B, bf16_t *__restrict__ out0, bf16_t *__restrict__ out1) {
-    extern __shared__ __attribute__((aligned(16))) char lds[];
+    __shared__ __attribute__((aligned(1024))) char s0[kStageBytes];
+    __shared__ __attribute__((aligned(1024))) char s1[kStageBytes];
     const int NOUT = (MODE == 1) ? F : d;  // width of the output
-    const int npt = NOUT / TL::BP;
+    const int KQ = (MODE == 1) ? d : F;    // width of the Q source rows
+    const int npt = NOUT / kTile;
     const int id = xcd_tile_id(tiles[0] * npt);
     if (id < 0) return;
     const int tile = id / npt, pt = id - tile * npt;
     const int e = tiles[2 + 2 * tile], row0 = tiles[3 + 2 * tile];
     const int row_end = offsets[e + 1];
-    const int p0 = pt * TL::BP;
+    const int p0 = pt * kTile;
+    const int wave = threadIdx.x >> 6;
+    const int wp = wave % kWP2, wq = wave / kWP2;
     const bf16_t *w0 = W0 + (int64_t)e * d * F;
-    const bf16_t *w1 = (MODE == 2) ? W1 + (int64_t)e * d * F : nullptr;
-    const int nk_half = F / TL::BK;
 
-    f32x16_t acc[TL::TP][TL::TQ];
-    zero_acc<TL>(acc);
+    OpKC256 Q;
+    Q.src[0] = Src{(const char *)(Q0 + (int64_t)row0 * KQ), clamp_bytes((int64_t)(S - row0) * KQ * 2), kBK2 * 2};
+    Q.src[1] = Q.src[0];
+    Q.kswitch = 0x7fffffff;
+    if constexpr (MODE == 2) {
+        Q.src[1] = Src{(const char *)(Q1 + (int64_t)row0 * KQ), clamp_bytes((int64_t)(S - row0) * KQ * 2), kBK2 * 2};
+        Q.kswitch = F / kBK2;
+    }
+    Q.init(KQ * 2, 64 * wq);
+
+    Acc2 acc;
+    zero_acc2(acc);
     if constexpr (MODE == 0) {
-        auto fp = [&](int kt, int k, int c) -> uint4 {
-            return ld16(w0 + (int64_t)(kt * TL::BK + k) * d + p0 + c * 8);
-        };
-        auto fq = [&](int kt, int r, int c) -> uint4 {
-            return ld16(Q0 + (int64_t)min(row0 + r, S - 1) * F + kt * TL::BK + c * 8);
-        };
-        mfma_mainloop<TL, true, false>(acc, F / TL::BK, fp, fq, lds);
+        OpTR256 P;
+        P.src[0] = Src{(const char *)w0, clamp_bytes((int64_t)d * F * 2), (uint32_t)(kBK2 * d * 2)};
+        P.src[1] = P.src[0];
+        P.kswitch = 0x7fffffff;
+        P.init(d * 2, p0 * 2, 128 * wp);
+        mfma_mainloop2(acc, F / kBK2, P, Q, s0, s1);
     } else if constexpr (MODE == 1) {
-        auto fp = [&](int kt, int r, int c) -> uint4 {
-            return ld16(w0 + (int64_t)(p0 + r) * d + kt * TL::BK + c * 8);
-        };
-        auto fq = [&](int kt, int r, int c) -> uint4 {
-            return ld16(Q0 + (int64_t)min(row0 + r, S - 1) * d + kt * TL::BK + c * 8);
-        };
-        mfma_mainloop<TL, false, false>(acc, d / TL::BK, fp, fq, lds);
+        OpKC256 P;
+        P.src[0] = Src{(const char *)(w0 + (int64_t)p0 * d), clamp_bytes((int64_t)(F - p0) * d * 2), kBK2 * 2};
+        P.src[1] = P.src[0];
+        P.kswitch = 0x7fffffff;
+        P.init(d * 2, 128 * wp);
+        mfma_mainloop2(acc, d / kBK2, P, Q, s0, s1);
     } else {
-        auto fp = [&](int kt, int r, int c) -> uint4 {
-            const bool up = kt >= nk_half;
-            const bf16_t *src = up ? w1 : w0;
-            return ld16(src + (int64_t)(p0 + r) * F + (kt - (up ? nk_half : 0)) * TL::BK + c * 8);
-        };
-        auto fq = [&](int kt, int r, int c) -> uint4 {
-            const bool up = kt >= nk_half;
-            const bf16_t *src = up ? Q1 : Q0;
-            return ld16(src + (int64_t)min(row0 + r, S - 1) * F + (kt - (up ? nk_half : 0)) * TL::BK + c * 8);
-        };
-        mfma_mainloop<TL, false, false>(acc, 2 * nk_half, fp, fq, lds);
+        const bf16_t *w1 = W1 + (int64_t)e * d * F;
+        OpKC256 P;
+        P.src[0] = Src{(const char *)(w0 + (int64_t)p0 * F), clamp_bytes((int64_t)(d - p0) * F * 2), kBK2 * 2};
+        P.src[1] = Src{(const char *)(w1 + (int64_t)p0 * F), clamp_bytes((int64_t)(d - p0) * F * 2), kBK2 * 2};
+        P.kswitch = F / kBK2;
+        P.init(F * 2, 128 * wp);
+        mfma_mainloop2(acc, 2 * (F / kBK2), P, Q, s0, s1);
     }
 
-    for_each_quad<TL>([&](int tp, int tq, int g, int p, int q) {
+    for_each_quad2([&](int tp, int tq, int g, int p, int q) {
         const int row = row0 + q;
         if (row >= row_end) return;
         const int64_t o = (int64_t)row * NOUT + p0 + p;
@@ -198,36 +207,42 @@ rowgemm_kernel(int S, int d, int F, const bf16_t *__restrict__ Q0, const bf16_t 
 // ---------------------------------------------------------------------------
 // Weight gradients:  out[e][q][p] (+)= sum_{r in expert e} Qs[r][q] * Ps[r][p]
 // Both operands are [row][feature] matrices, so both tiles are TR; the k loop
-// runs over the expert's rows and the tail past the segment is zero-filled.
+// runs over the expert's rows and the buffer bound zero-fills the tail.
 // ---------------------------------------------------------------------------
-template <class TL>
-__global__ void __launch_bounds__(TL::NT, 2)
+__global__ void __launch_bounds__(kThreads2, 2)
 wgrad_kernel(int E, int NQd, int NPd, const bf16_t *__restrict__ Qs, const bf16_t *__restrict__ Ps,
              const int32_t *__restrict__ offsets, float *__restrict__ out, int accumulate) {
-    extern __shared__ __attribute__((aligned(16))) char lds[];
-    const int nqt = NQd / TL::BQ, npt = NPd / TL::BP;
+    __shared__ __attribute__((aligned(1024))) char s0[kStageBytes];
+    __shared__ __attribute__((aligned(1024))) char s1[kStageBytes];
+    const int nqt = NQd / kTile, npt = NPd / kTile;
     const int id = xcd_tile_id(E * nqt * npt);
     if (id < 0) return;
     const int e = id / (nqt * npt);
     const int rem = id - e * nqt * npt;
     const int qt = rem / npt, pt = rem - qt * npt;
     const int r0 = offsets[e], r1 = offsets[e + 1];
-    const int q0 = qt * TL::BQ, p0 = pt * TL::BP;
+    const int q0 = qt * kTile, p0 = pt * kTile;
+    const int wave = threadIdx.x >> 6;
+    const int wp = wave % kWP2, wq = wave / kWP2;
 
-    auto fp = [&](int kt, int k, int c) -> uint4 {
-        const int r = r0 + kt * TL::BK + k;
-        return r < r1 ? ld16(Ps + (int64_t)r * NPd + p0 + c * 8) : zero16();
-    };
-    auto fq = [&](int kt, int k, int c) -> uint4 {
-        const int r = r0 + kt * TL::BK + k;
-        return r < r1 ? ld16(Qs + (int64_t)r * NQd + q0 + c * 8) : zero16();
-    };
-    f32x16_t acc[TL::TP][TL::TQ];
-    zero_acc<TL>(acc);
-    mfma_mainloop<TL, true, true>(acc, (r1 - r0 + TL::BK - 1) / TL::BK, fp, fq, lds);
+    OpTR256 P, Q;
+    P.src[0] = Src{(const char *)(Ps + (int64_t)r0 * NPd), clamp_bytes((int64_t)(r1 - r0) * NPd * 2),
+                   (uint32_t)(kBK2 * NPd * 2)};
+    P.src[1] = P.src[0];
+    P.kswitch = 0x7fffffff;
+    P.init(NPd * 2, p0 * 2, 128 * wp);
+    Q.src[0] = Src{(const char *)(Qs + (int64_t)r0 * NQd), clamp_bytes((int64_t)(r1 - r0) * NQd * 2),
+                   (uint32_t)(kBK2 * NQd * 2)};
+    Q.src[1] = Q.src[0];
+    Q.kswitch = 0x7fffffff;
+    Q.init(NQd * 2, q0 * 2, 64 * wq);
+
+    Acc2 acc;
+    zero_acc2(acc);
+    mfma_mainloop2(acc, (r1 - r0 + kBK2 - 1) / kBK2, P, Q, s0, s1);
 
     float *o = out + (int64_t)e * NQd * NPd;
-    for_each_quad<TL>([&](int tp, int tq, int g, int p, int q) {
+    for_each_quad2([&](int tp, int tq, int g, int p, int q) {
         float4 *dst = (float4 *)(o + (int64_t)(q0 + q) * NPd + p0 + p);
         float4 v = make_float4(acc[tp][tq][4 * g], acc[tp][tq][4 * g + 1], acc[tp][tq][4 * g + 2],
                                acc[tp][tq][4 * g + 3]);
@@ -331,7 +346,6 @@ split_reduce_kernel(int d, int E, int nsplit, const float *__restrict__ part, fl
 // ---------------------------------------------------------------------------
 // host side
 // ---------------------------------------------------------------------------
-typedef TileCfg<256, 128, 2, 2, 32> TLMain;    // experts: 256 features x 128 rows
 typedef TileCfg<128, 64, 2, 2, 64> TLLogits;   // router: 128 experts x 64 tokens
 typedef TileCfg<128, 128, 2, 2, 64> TLDwr;     // router wgrad: 128 experts x 128 hidden
 
@@ -339,7 +353,7 @@ bool mfma_ffn_supported(int d, int F) { return d % 256 == 0 && F % 256 == 0 && d
 bool mfma_router_supported(int d, int E) { return E % 128 == 0 && d % 128 == 0; }  // 2E % 128 for ds
 
 size_t mfma_tiles_bytes(int64_t S, int E) {
-    return align_up((size_t)(2 + 2 * (size_t)max_row_tiles(S, E, TLMain::BQ)) * sizeof(int32_t), 256);
+    return align_up((size_t)(2 + 2 * (size_t)max_row_tiles(S, E, kTile)) * sizeof(int32_t), 256);
 }
 
 template <class K>
@@ -348,25 +362,22 @@ static void allow_lds(K kernel, int bytes) {
 }
 
 hipError_t mfma_build_tiles(int E, const int32_t *offsets, int32_t *tiles, hipStream_t s) {
-    build_row_tiles_kernel<<<1, 1024, 0, s>>>(E, TLMain::BQ, offsets, tiles);
+    build_row_tiles_kernel<<<1, 1024, 0, s>>>(E, kTile, offsets, tiles);
     return hipGetLastError();
 }
 
 hipError_t mfma_ffn_forward(int64_t S, int d, int E, int F, const void *Xp, const int32_t *offsets,
                             const int32_t *tiles, const void *Wg, const void *Wu, const void *Wd, void *Yp,
                             void *H, void *A, void *B, hipStream_t s) {
-    typedef TLMain TL;
-    const int mt = max_row_tiles(S, E, TL::BQ);
-    allow_lds(ffn1_kernel<TL>, TL::LDS_BYTES);
+    const int mt = max_row_tiles(S, E, kTile);
     {
         ProfScope ps(PROF_FFN1, s);
-        ffn1_kernel<TL><<<grid_for((int64_t)mt * (F / (TL::BP / 2))), TL::NT, TL::LDS_BYTES, s>>>(
-        (int)S, d, F, (const bf16_t *)Xp, offsets, tiles, (const bf16_t *)Wg, (const bf16_t *)Wu, (bf16_t *)H,
-        (bf16_t *)A, (bf16_t *)B);
+        ffn1_kernel<<<grid_for((int64_t)mt * (F / 128)), kThreads2, 0, s>>>(
+            (int)S, d, F, (const bf16_t *)Xp, offsets, tiles, (const bf16_t *)Wg, (const bf16_t *)Wu,
+            (bf16_t *)H, (bf16_t *)A, (bf16_t *)B);
     }
-    allow_lds(rowgemm_kernel<TL, 0>, TL::LDS_BYTES);
     ProfScope ps(PROF_FFN2, s);
-    rowgemm_kernel<TL, 0><<<grid_for((int64_t)mt * (d / TL::BP)), TL::NT, TL::LDS_BYTES, s>>>(
+    rowgemm_kernel<0><<<grid_for((int64_t)mt * (d / kTile)), kThreads2, 0, s>>>(
         (int)S, d, F, (const bf16_t *)H, nullptr, offsets, tiles, (const bf16_t *)Wd, nullptr, nullptr, nullptr,
         (bf16_t *)Yp, nullptr);
     return hipGetLastError();
@@ -375,11 +386,9 @@ hipError_t mfma_ffn_forward(int64_t S, int d, int E, int F, const void *Xp, cons
 hipError_t mfma_ffn_dh(int64_t S, int d, int E, int F, const void *dYp, const int32_t *offsets,
                        const int32_t *tiles, const void *Wd, const void *A, const void *B, void *dA, void *dB,
                        hipStream_t s) {
-    typedef TLMain TL;
-    const int mt = max_row_tiles(S, E, TL::BQ);
-    allow_lds(rowgemm_kernel<TL, 1>, TL::LDS_BYTES);
+    const int mt = max_row_tiles(S, E, kTile);
     ProfScope ps(PROF_DH, s);
-    rowgemm_kernel<TL, 1><<<grid_for((int64_t)mt * (F / TL::BP)), TL::NT, TL::LDS_BYTES, s>>>(
+    rowgemm_kernel<1><<<grid_for((int64_t)mt * (F / kTile)), kThreads2, 0, s>>>(
         (int)S, d, F, (const bf16_t *)dYp, nullptr, offsets, tiles, (const bf16_t *)Wd, nullptr,
         (const bf16_t *)A, (const bf16_t *)B, (bf16_t *)dA, (bf16_t *)dB);
     return hipGetLastError();
@@ -387,11 +396,9 @@ hipError_t mfma_ffn_dh(int64_t S, int d, int E, int F, const void *dYp, const in
 
 hipError_t mfma_ffn_dxp(int64_t S, int d, int E, int F, const void *dA, const void *dB, const int32_t *offsets,
                         const int32_t *tiles, const void *Wg, const void *Wu, void *dXp, hipStream_t s) {
-    typedef TLMain TL;
-    const int mt = max_row_tiles(S, E, TL::BQ);
-    allow_lds(rowgemm_kernel<TL, 2>, TL::LDS_BYTES);
+    const int mt = max_row_tiles(S, E, kTile);
     ProfScope ps(PROF_DXP, s);
-    rowgemm_kernel<TL, 2><<<grid_for((int64_t)mt * (d / TL::BP)), TL::NT, TL::LDS_BYTES, s>>>(
+    rowgemm_kernel<2><<<grid_for((int64_t)mt * (d / kTile)), kThreads2, 0, s>>>(
         (int)S, d, F, (const bf16_t *)dA, (const bf16_t *)dB, offsets, tiles, (const bf16_t *)Wg,
         (const bf16_t *)Wu, nullptr, nullptr, (bf16_t *)dXp, nullptr);
     return hipGetLastError();
@@ -399,12 +406,10 @@ hipError_t mfma_ffn_dxp(int64_t S, int d, int E, int F, const void *dA, const vo
 
 hipError_t mfma_wgrad(int E, int NQd, int NPd, const void *Qs, const void *Ps, const int32_t *offsets,
                       float *out, int accumulate, hipStream_t s) {
-    typedef TLMain TL;
-    allow_lds(wgrad_kernel<TL>, TL::LDS_BYTES);
-    const int64_t tiles = (int64_t)E * (NQd / TL::BQ) * (NPd / TL::BP);
+    const int64_t tiles = (int64_t)E * (NQd / kTile) * (NPd / kTile);
     ProfScope ps(PROF_WGRAD, s);
-    wgrad_kernel<TL><<<grid_for(tiles), TL::NT, TL::LDS_BYTES, s>>>(E, NQd, NPd, (const bf16_t *)Qs,
-                                                                  (const bf16_t *)Ps, offsets, out, accumulate);
+    wgrad_kernel<<<grid_for(tiles), kThreads2, 0, s>>>(E, NQd, NPd, (const bf16_t *)Qs, (const bf16_t *)Ps,
+                                                      offsets, out, accumulate);
     return hipGetLastError();
 }
 
