@@ -61,12 +61,14 @@ struct DmaKC {
             voff[i] = row * ld_bytes + c * 16;
         }
     }
-    __device__ __forceinline__ void issue(__amdgpu_buffer_rsrc_t r, char *tile) const {
+    __device__ __forceinline__ void issue_one(__amdgpu_buffer_rsrc_t r, char *tile, int i) const {
         const int w = threadIdx.x >> 6;
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(r, (lds_void_ptr)(tile + 1024 * (w + kWaves2 * i)), 16, voff[i],
+                                                 0, 0, 0);
+    }
+    __device__ __forceinline__ void issue(__amdgpu_buffer_rsrc_t r, char *tile) const {
 #pragma unroll
-        for (int i = 0; i < 4; ++i)
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(r, (lds_void_ptr)(tile + 1024 * (w + kWaves2 * i)), 16,
-                                                     voff[i], 0, 0, 0);
+        for (int i = 0; i < 4; ++i) issue_one(r, tile, i);
     }
 };
 
@@ -89,12 +91,14 @@ struct DmaTR {
             voff[i] = k * ld_bytes + col_bytes + c16 * 16;
         }
     }
-    __device__ __forceinline__ void issue(__amdgpu_buffer_rsrc_t r, char *tile) const {
+    __device__ __forceinline__ void issue_one(__amdgpu_buffer_rsrc_t r, char *tile, int i) const {
         const int w = threadIdx.x >> 6;
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(r, (lds_void_ptr)(tile + 1024 * (w + kWaves2 * i)), 16, voff[i],
+                                                 0, 0, 0);
+    }
+    __device__ __forceinline__ void issue(__amdgpu_buffer_rsrc_t r, char *tile) const {
 #pragma unroll
-        for (int i = 0; i < PER; ++i)
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(r, (lds_void_ptr)(tile + 1024 * (w + kWaves2 * i)), 16,
-                                                     voff[i], 0, 0, 0);
+        for (int i = 0; i < PER; ++i) issue_one(r, tile, i);
     }
 };
 
@@ -105,6 +109,7 @@ struct DmaTR {
 //            wave come from sub-tile 0 and tiles 2,3 from sub-tile 1 at the same features
 // A second Src set takes over from k-tile `kswitch` on (two-phase reductions).
 struct OpKC256 {
+    static constexpr int kDsReads = kTP2, kDsReadsQ = kTQ2;  // ds_read_b128 per sub-step as P / as Q
     Src src[2];
     int kswitch;
     DmaKC dma;
@@ -118,10 +123,17 @@ struct OpKC256 {
         const Src &s = second ? src[1] : src[0];
         dma.issue(src_rsrc(s, second ? kt - kswitch : kt), tile);
     }
+    // one quarter (part = 0..3) of the tile's loads
+    __device__ __forceinline__ void issue_part(int kt, char *tile, int part) const {
+        const bool second = kt >= kswitch;
+        const Src &s = second ? src[1] : src[0];
+        dma.issue_one(src_rsrc(s, second ? kt - kswitch : kt), tile, part);
+    }
     __device__ __forceinline__ bf16x8_t frag(const char *tile, int t, int s) const { return fr.read(tile, t, s); }
 };
 
 struct OpTR256 {
+    static constexpr int kDsReads = 2 * kTP2, kDsReadsQ = 2 * kTQ2;  // two ds_read_b64_tr_b16 per fragment
     Src src[2];
     int kswitch;
     DmaTR<256> dma;
@@ -135,10 +147,16 @@ struct OpTR256 {
         const Src &s = second ? src[1] : src[0];
         dma.issue(src_rsrc(s, second ? kt - kswitch : kt), tile);
     }
+    __device__ __forceinline__ void issue_part(int kt, char *tile, int part) const {
+        const bool second = kt >= kswitch;
+        const Src &s = second ? src[1] : src[0];
+        dma.issue_one(src_rsrc(s, second ? kt - kswitch : kt), tile, part);
+    }
     __device__ __forceinline__ bf16x8_t frag(const char *tile, int t, int s) const { return fr.read(tile, t, s); }
 };
 
 struct OpTR128x2 {
+    static constexpr int kDsReads = 2 * kTP2, kDsReadsQ = 2 * kTQ2;
     Src src[2];  // sub-tile 0, sub-tile 1
     DmaTR<128> dma;
     TrFrag<128> fr;
@@ -149,6 +167,9 @@ struct OpTR128x2 {
     __device__ __forceinline__ void issue(int kt, char *tile) const {
         dma.issue(src_rsrc(src[0], kt), tile);
         dma.issue(src_rsrc(src[1], kt), tile + kOperandBytes / 2);
+    }
+    __device__ __forceinline__ void issue_part(int kt, char *tile, int part) const {
+        dma.issue_one(src_rsrc(src[part >> 1], kt), tile + (part >> 1) * (kOperandBytes / 2), part & 1);
     }
     __device__ __forceinline__ bf16x8_t frag(const char *tile, int t, int s) const {
         return fr.read(tile + (t >> 1) * (kOperandBytes / 2), t & 1, s);
@@ -166,32 +187,63 @@ __device__ __forceinline__ void zero_acc2(Acc2 &acc) {
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
 }
 
+struct Frags {
+    bf16x8_t a[kTP2], b[kTQ2];
+};
+
 template <class POp, class QOp>
-__device__ __forceinline__ void stage_compute(Acc2 &acc, const POp &P, const QOp &Q, const char *stage) {
-    const char *pt = stage, *qt = stage + kOperandBytes;
-    bf16x8_t a[2][kTP2], b[2][kTQ2];
+__device__ __forceinline__ void read_frags(Frags &f, const POp &P, const QOp &Q, const char *stage, int s) {
 #pragma unroll
-    for (int i = 0; i < kTP2; ++i) a[0][i] = P.frag(pt, i, 0);
+    for (int i = 0; i < kTP2; ++i) f.a[i] = P.frag(stage, i, s);
 #pragma unroll
-    for (int j = 0; j < kTQ2; ++j) b[0][j] = Q.frag(qt, j, 0);
+    for (int j = 0; j < kTQ2; ++j) f.b[j] = Q.frag(stage + kOperandBytes, j, s);
+}
+
+__device__ __forceinline__ void mfma_block(Acc2 &acc, const Frags &f) {
 #pragma unroll
-    for (int s = 0; s < kBK2 / 16; ++s) {
-        const int cur = s & 1, nxt = cur ^ 1;
-        if (s + 1 < kBK2 / 16) {
+    for (int i = 0; i < kTP2; ++i)
 #pragma unroll
-            for (int i = 0; i < kTP2; ++i) a[nxt][i] = P.frag(pt, i, s + 1);
-#pragma unroll
-            for (int j = 0; j < kTQ2; ++j) b[nxt][j] = Q.frag(qt, j, s + 1);
-        }
-#pragma unroll
-        for (int i = 0; i < kTP2; ++i)
-#pragma unroll
-            for (int j = 0; j < kTQ2; ++j)
-                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[cur][i], b[cur][j], acc[i][j], 0, 0, 0);
-        // keep the next sub-step's fragment reads from being hoisted further up: more than two
-        // fragment sets in flight would push the 128 accumulator registers into scratch
-        __builtin_amdgcn_sched_barrier(0);
+        for (int j = 0; j < kTQ2; ++j)
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.a[i], f.b[j], acc[i][j], 0, 0, 0);
+}
+
+// One resident stage.  On entry `x` may hold the last fragment set of the previous stage
+// (pending = true): its MFMAs are issued right after this stage's first fragment reads, so
+// the MFMA pipe has work while those reads are in flight just after the barrier.  On exit
+// `x` holds this stage's last fragment set, not yet multiplied.
+// The sched_barriers keep at most two fragment sets live next to the 128 accumulators.
+// One sub-step: the fragment reads of the next 16 k go out first, then (first sub-step only)
+// the next stage's global->LDS loads, then the 8 MFMAs of the current fragments, so the reads
+// have 8 MFMAs (256 cycles) to land.  (Left alone the compiler sinks the reads below the
+// MFMAs and every sub-step starts by waiting on LDS.  Spreading the loads over the four
+// sub-steps was measured slower: the late ones are not back before the stage ends.)
+template <class POp, class QOp>
+__device__ __forceinline__ void sub_step(Acc2 &acc, Frags &next, const Frags &cur, const POp &P, const QOp &Q,
+                                         const char *stage, int s, bool prefetch, int kt_next, char *stage_next) {
+    read_frags(next, P, Q, stage, s);
+    if (prefetch && s == 0) {
+        P.issue(kt_next, stage_next);
+        Q.issue(kt_next, stage_next + kOperandBytes);
     }
+    mfma_block(acc, cur);
+    __builtin_amdgcn_sched_group_barrier(0x100, POp::kDsReads + QOp::kDsReadsQ, 0);  // DS reads
+    if (s == 0) __builtin_amdgcn_sched_group_barrier(0x020, 8, 0);                   // VMEM reads
+    __builtin_amdgcn_sched_group_barrier(0x008, kTP2 * kTQ2, 0);                     // MFMA
+    __builtin_amdgcn_sched_barrier(0);
+}
+
+// One resident stage.  On entry `x` holds the last fragment set of the previous stage (zeros
+// on the very first stage): its MFMAs are issued right behind this stage's first fragment
+// reads, so the MFMA pipe has work while those reads are in flight just after the barrier.
+// On exit `x` holds this stage's last fragment set, not yet multiplied.  At most two fragment
+// sets are live next to the 128 accumulator registers.
+template <class POp, class QOp>
+__device__ __forceinline__ void stage_compute(Acc2 &acc, Frags &x, Frags &y, const POp &P, const QOp &Q,
+                                              const char *stage, bool prefetch, int kt_next, char *stage_next) {
+    sub_step(acc, y, x, P, Q, stage, 0, prefetch, kt_next, stage_next);
+    sub_step(acc, x, y, P, Q, stage, 1, prefetch, kt_next, stage_next);
+    sub_step(acc, y, x, P, Q, stage, 2, prefetch, kt_next, stage_next);
+    sub_step(acc, x, y, P, Q, stage, 3, prefetch, kt_next, stage_next);
 }
 
 // nk k-tiles of 64.  s0, s1: the two 64 KB LDS stages (distinct arrays).
@@ -202,23 +254,22 @@ __device__ __forceinline__ void mfma_mainloop2(Acc2 &acc, int nk, const POp &P, 
     Q.issue(0, s0 + kOperandBytes);
     __builtin_amdgcn_s_waitcnt(0);
     __syncthreads();
+    Frags x, y;
+#pragma unroll
+    for (int i = 0; i < kTP2; ++i) x.a[i] = bf16x8_t{};
+#pragma unroll
+    for (int j = 0; j < kTQ2; ++j) x.b[j] = bf16x8_t{};
     for (int kt = 0; kt < nk; kt += 2) {
         const bool has1 = kt + 1 < nk, has2 = kt + 2 < nk;
-        if (has1) {
-            P.issue(kt + 1, s1);
-            Q.issue(kt + 1, s1 + kOperandBytes);
-        }
-        stage_compute(acc, P, Q, s0);
+        stage_compute(acc, x, y, P, Q, s0, has1, kt + 1, s1);
         __builtin_amdgcn_s_waitcnt(0);
         __syncthreads();
-        if (has2) {
-            P.issue(kt + 2, s0);
-            Q.issue(kt + 2, s0 + kOperandBytes);
-        }
-        if (has1) stage_compute(acc, P, Q, s1);  // single loop exit: keeps the accumulators in place
+        // single loop exit (no break) keeps the accumulators in place
+        if (has1) stage_compute(acc, x, y, P, Q, s1, has2, kt + 2, s0);
         __builtin_amdgcn_s_waitcnt(0);
         __syncthreads();
     }
+    mfma_block(acc, x);
 }
 
 // Visit the wave's results as groups of 4 consecutive p for one q (tile-local p, q).
