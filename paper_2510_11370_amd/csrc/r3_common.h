@@ -40,6 +40,12 @@ template <> struct Elem<bf16_t> {
 
 __device__ __forceinline__ float sigmoidf_(float a) { return 1.0f / (1.0f + expf(-a)); }
 
+// sigmoid from the hardware exp2 and reciprocal (about 2 ulp): for results that are rounded
+// to bf16 right away.  exp(-a) = exp2(-a * log2(e)).
+__device__ __forceinline__ float sigmoid_fast(float a) {
+    return __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(a * -1.44269504088896f));
+}
+
 __device__ __forceinline__ int lane_id() { return threadIdx.x & (kWave - 1); }
 
 template <typename T> __device__ __forceinline__ T wave_sum(T v) {

@@ -12,6 +12,32 @@
 
 namespace r3 {
 
+// Per-work-group time stamps, compiled in only for the kernel lab (-DR3_TIMELINE).
+#ifdef R3_TIMELINE
+__device__ long long *r3_timeline_buf = nullptr;
+#define R3_TL_DECL long long tl_[6] = {0, 0, 0, 0, 0, 0}
+#define R3_TL(i)                                  \
+    do {                                          \
+        tl_[i] = clock64();                       \
+        if ((i) == 0) tl_[4] = wall_clock64();    \
+    } while (0)
+#define R3_TL_FLUSH()                                                                   \
+    do {                                                                                \
+        __builtin_amdgcn_s_waitcnt(0);                                                  \
+        tl_[3] = clock64();                                                             \
+        tl_[5] = wall_clock64();                                                        \
+        if (r3_timeline_buf && threadIdx.x == 0) {                                      \
+            for (int i_ = 0; i_ < 6; ++i_) r3_timeline_buf[blockIdx.x * 8 + i_] = tl_[i_]; \
+            r3_timeline_buf[blockIdx.x * 8 + 6] = __builtin_amdgcn_s_getreg((4 << 0) | (0 << 6) | (31 << 11));  \
+            r3_timeline_buf[blockIdx.x * 8 + 7] = __builtin_amdgcn_s_getreg((20 << 0) | (0 << 6) | (31 << 11)); \
+        }                                                                               \
+    } while (0)
+#else
+#define R3_TL_DECL
+#define R3_TL(i)
+#define R3_TL_FLUSH()
+#endif
+
 // ---------------------------------------------------------------------------
 // Row-tile table: tiles[0] = number of tiles, then (expert, row0) pairs from
 // tiles[2].  One block; experts in ascending order, rows ascending.
@@ -64,7 +90,11 @@ ffn1_kernel(int S, int d, int F, const bf16_t *__restrict__ Xp, const int32_t *_
             bf16_t *__restrict__ H, bf16_t *__restrict__ A, bf16_t *__restrict__ B) {
     __shared__ __attribute__((aligned(1024))) char s0[kStageBytes];
     __shared__ __attribute__((aligned(1024))) char s1[kStageBytes];
+    __shared__ __attribute__((aligned(1024))) char s2[kStageBytes];
+    __shared__ __attribute__((aligned(1024))) char s3[kStageBytes];
     constexpr int BF = 128;  // features per tile
+    R3_TL_DECL;
+    R3_TL(0);
     const int npt = F / BF;
     const int id = xcd_tile_id(tiles[0] * npt);
     if (id < 0) return;
@@ -87,7 +117,9 @@ ffn1_kernel(int S, int d, int F, const bf16_t *__restrict__ Xp, const int32_t *_
 
     Acc2 acc;
     zero_acc2(acc);
-    mfma_mainloop2(acc, d / kBK2, P, Q, s0, s1);
+    R3_TL(1);
+    mfma_mainloop2(acc, d / kBK2, P, Q, s0, s1, s2, s3);
+    R3_TL(2);
 
 #pragma unroll
     for (int tp = 0; tp < 2; ++tp)
@@ -103,7 +135,7 @@ ffn1_kernel(int S, int d, int F, const bf16_t *__restrict__ Xp, const int32_t *_
                 for (int i = 0; i < 4; ++i) {
                     a[i] = acc[tp][tq][4 * g + i];
                     b[i] = acc[tp + 2][tq][4 * g + i];
-                    h[i] = a[i] * sigmoidf_(a[i]) * b[i];
+                    h[i] = a[i] * sigmoid_fast(a[i]) * b[i];
                 }
                 const int64_t o = (int64_t)row * F + f;
                 *(uint2 *)(H + o) = pack4(h[0], h[1], h[2], h[3]);
@@ -111,6 +143,7 @@ ffn1_kernel(int S, int d, int F, const bf16_t *__restrict__ Xp, const int32_t *_
                 if (B) *(uint2 *)(B + o) = pack4(b[0], b[1], b[2], b[3]);
             }
         }
+    R3_TL_FLUSH();
 }
 
 // ---------------------------------------------------------------------------
@@ -130,6 +163,8 @@ rowgemm_kernel(int S, int d, int F, const bf16_t *__restrict__ Q0, const bf16_t 
                const bf16_t *__restrict__ B, bf16_t *__restrict__ out0, bf16_t *__restrict__ out1) {
     __shared__ __attribute__((aligned(1024))) char s0[kStageBytes];
     __shared__ __attribute__((aligned(1024))) char s1[kStageBytes];
+    __shared__ __attribute__((aligned(1024))) char s2[kStageBytes];
+    __shared__ __attribute__((aligned(1024))) char s3[kStageBytes];
     const int NOUT = (MODE == 1) ? F : d;  // width of the output
     const int KQ = (MODE == 1) ? d : F;    // width of the Q source rows
     const int npt = NOUT / kTile;
@@ -161,14 +196,14 @@ rowgemm_kernel(int S, int d, int F, const bf16_t *__restrict__ Q0, const bf16_t 
         P.src[1] = P.src[0];
         P.kswitch = 0x7fffffff;
         P.init(d * 2, p0 * 2, 128 * wp);
-        mfma_mainloop2(acc, F / kBK2, P, Q, s0, s1);
+        mfma_mainloop2(acc, F / kBK2, P, Q, s0, s1, s2, s3);
     } else if constexpr (MODE == 1) {
         OpKC256 P;
         P.src[0] = Src{(const char *)(w0 + (int64_t)p0 * d), clamp_bytes((int64_t)(F - p0) * d * 2), kBK2 * 2};
         P.src[1] = P.src[0];
         P.kswitch = 0x7fffffff;
         P.init(d * 2, 128 * wp);
-        mfma_mainloop2(acc, d / kBK2, P, Q, s0, s1);
+        mfma_mainloop2(acc, d / kBK2, P, Q, s0, s1, s2, s3);
     } else {
         const bf16_t *w1 = W1 + (int64_t)e * d * F;
         OpKC256 P;
@@ -176,7 +211,7 @@ rowgemm_kernel(int S, int d, int F, const bf16_t *__restrict__ Q0, const bf16_t 
         P.src[1] = Src{(const char *)(w1 + (int64_t)p0 * F), clamp_bytes((int64_t)(d - p0) * F * 2), kBK2 * 2};
         P.kswitch = F / kBK2;
         P.init(F * 2, 128 * wp);
-        mfma_mainloop2(acc, 2 * (F / kBK2), P, Q, s0, s1);
+        mfma_mainloop2(acc, 2 * (F / kBK2), P, Q, s0, s1, s2, s3);
     }
 
     for_each_quad2([&](int tp, int tq, int g, int p, int q) {
@@ -192,7 +227,7 @@ rowgemm_kernel(int S, int d, int F, const bf16_t *__restrict__ Q0, const bf16_t 
             unpack4(*(const uint2 *)(B + o), b);
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
-                const float sg = sigmoidf_(a[i]);
+                const float sg = sigmoid_fast(a[i]);
                 da[i] = dh[i] * b[i] * sg * (1.0f + a[i] * (1.0f - sg));
                 db[i] = dh[i] * a[i] * sg;
             }
@@ -214,6 +249,8 @@ wgrad_kernel(int E, int NQd, int NPd, const bf16_t *__restrict__ Qs, const bf16_
              const int32_t *__restrict__ offsets, float *__restrict__ out, int accumulate) {
     __shared__ __attribute__((aligned(1024))) char s0[kStageBytes];
     __shared__ __attribute__((aligned(1024))) char s1[kStageBytes];
+    __shared__ __attribute__((aligned(1024))) char s2[kStageBytes];
+    __shared__ __attribute__((aligned(1024))) char s3[kStageBytes];
     const int nqt = NQd / kTile, npt = NPd / kTile;
     const int id = xcd_tile_id(E * nqt * npt);
     if (id < 0) return;
@@ -239,7 +276,7 @@ wgrad_kernel(int E, int NQd, int NPd, const bf16_t *__restrict__ Qs, const bf16_
 
     Acc2 acc;
     zero_acc2(acc);
-    mfma_mainloop2(acc, (r1 - r0 + kBK2 - 1) / kBK2, P, Q, s0, s1);
+    mfma_mainloop2(acc, (r1 - r0 + kBK2 - 1) / kBK2, P, Q, s0, s1, s2, s3);
 
     float *o = out + (int64_t)e * NQd * NPd;
     for_each_quad2([&](int tp, int tq, int g, int p, int q) {

@@ -1,34 +1,40 @@
-// 256x256x64 bf16 MFMA tile loop for gfx950 with direct global->LDS loads.
+// 256x256 bf16 MFMA tile loop for gfx950 with direct global->LDS loads and a four-stage
+// LDS ring (32 k per stage, loads issued three stages ahead).
 //
 // D[p][q] = sum_k P[p][k] * Q[q][k], f32 accumulation; P feeds the MFMA A operand
 // (output's contiguous dimension), Q the B operand (output rows).  8 waves, arranged
 // 2 (P) x 4 (Q), each owning a 128 x 64 block as 4 x 2 MFMA 32x32x16 tiles.
 //
-// Operand tiles (32 KB each) are fetched with buffer_load_dwordx4 ... lds: a wave's
-// 64 lanes deposit 64 x 16 B at consecutive LDS addresses, so LDS writes are
+// Operand tiles (16 KB each per stage) are fetched with buffer_load_dwordx4 ... lds: a
+// wave's 64 lanes deposit 64 x 16 B at consecutive LDS addresses, so LDS writes are
 // conflict-free by construction and need no VGPR staging; the XOR swizzle that makes the
 // later fragment reads conflict-free is applied on the global side (each lane fetches the
 // 16-byte chunk that belongs in its LDS slot).  Buffer descriptors give bounds checking:
 // rows past the end of an expert's segment read as zero, which is exactly what the ragged
 // reduction of the weight gradients needs, and keeps every access in bounds.
 //
-// Tile forms in LDS:
-//   KC   [256 rows][64 k]          row = 128 B; 16-B chunk c of row r sits at c ^ ((r>>1)&7)
-//   TR   [64 k][R features]        k-row = 2R B; 64-B group g of k-row k sits at g ^ (k&3);
+// Tile forms in LDS (per stage):
+//   KC   [256 rows][32 k]     row = 64 B; 16-B chunk c of row r sits at c ^ ((r>>2)&3)
+//   TR   [32 k][R features]   k-row = 2R B; 64-B group g of k-row k sits at g ^ (k&3);
 //        fragments come out through ds_read_b64_tr_b16 (4 consecutive k of one feature).
-// Two LDS stages are separate arrays so that the compiler can see that the loads in
+// The four stages are separate LDS arrays so that the compiler can see that loads in
 // flight never alias the stage being read (no vmcnt wait in front of the fragment reads).
+// Every stage issues exactly the same number of loads per wave (a stage past the end of the
+// reduction gets a zero-length descriptor), so "s_waitcnt vmcnt(2 stages' worth)" at the end
+// of stage kt is exactly "stage kt+1 has landed".
 #pragma once
 #include "r3_mfma.h"
 
 namespace r3 {
 
-constexpr int kBK2 = 64;
+constexpr int kBK2 = 32;
 constexpr int kTile = 256;
-constexpr int kOperandBytes = kTile * kBK2 * 2;  // 32 KB
-constexpr int kStageBytes = 2 * kOperandBytes;   // 64 KB
+constexpr int kStages2 = 4;
+constexpr int kOperandBytes = kTile * kBK2 * 2;  // 16 KB
+constexpr int kStageBytes = 2 * kOperandBytes;   // 32 KB
 constexpr int kWaves2 = 8, kThreads2 = 512;
 constexpr int kWP2 = 2, kWQ2 = 4, kTP2 = 4, kTQ2 = 2;
+constexpr int kLoadsPerStage = 4;                // buffer loads per wave per stage (2 per operand)
 constexpr uint32_t kRsrcFlags = 0x00020000u;
 
 typedef __attribute__((address_space(3))) void *lds_void_ptr;
@@ -42,41 +48,58 @@ struct Src {
     uint32_t step;
 };
 
-__device__ __forceinline__ __amdgpu_buffer_rsrc_t src_rsrc(const Src &s, int kt) {
+typedef int rsrc_t __attribute__((ext_vector_type(4)));  // buffer descriptor words (wave-uniform)
+
+__device__ __forceinline__ rsrc_t src_rsrc(const Src &s, int kt) {
     const uint64_t adv = (uint64_t)kt * s.step;
     const uint32_t left = adv < s.nbytes ? (uint32_t)(s.nbytes - adv) : 0u;
-    return __builtin_amdgcn_make_buffer_rsrc((void *)(s.base + adv), (short)0, (int)left, (int)kRsrcFlags);
+    const uint64_t b = (uint64_t)(s.base + adv);
+    // the words are wave-uniform by construction; readfirstlane makes that visible to the
+    // compiler so that they live in SGPRs
+    rsrc_t r = {__builtin_amdgcn_readfirstlane((int)(uint32_t)b),
+                __builtin_amdgcn_readfirstlane((int)((uint32_t)(b >> 32) & 0xffffu)),
+                __builtin_amdgcn_readfirstlane((int)left), (int)kRsrcFlags};
+    return r;
 }
 
-// K-contiguous 256-row tile.  ld_bytes = row pitch of the source, col_bytes = byte offset
-// of k = 0 inside a source row.
+// LDS byte address of a __shared__ object (the low half of its generic address)
+__device__ __forceinline__ uint32_t lds_addr(const void *p) { return (uint32_t)(uintptr_t)(lds_void_ptr)p; }
+
+// buffer_load_dwordx4 ... lds: lane i's 16 bytes go to LDS address dst_wave + 16 i.
+// Written as inline asm on purpose: the compiler then neither tracks these loads nor puts
+// conservative vmcnt waits in front of later LDS reads (it cannot tell that a read of the
+// resident stage does not alias a load three stages ahead); stage_barrier() does the
+// counting.  No other instruction in these kernels uses M0.
+__device__ __forceinline__ void lds_load16(rsrc_t r, uint32_t dst_wave, int voff) {
+    const uint32_t m0v = __builtin_amdgcn_readfirstlane(dst_wave);
+    asm volatile("s_mov_b32 m0, %0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds" ::"s"(m0v), "v"(voff), "s"(r)
+                 : "memory");
+}
+
+// K-contiguous 256-row tile: 16 chunks of 1 KB (16 rows x 64 B), two per wave.
 struct DmaKC {
-    int voff[4];
+    int voff[2];
     __device__ __forceinline__ void init(int ld_bytes) {
         const int w = threadIdx.x >> 6, lane = threadIdx.x & 63;
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const int row = 8 * (w + kWaves2 * i) + (lane >> 3);
-            const int c = (lane & 7) ^ ((row >> 1) & 7);
+        for (int i = 0; i < 2; ++i) {
+            const int row = 16 * (w + kWaves2 * i) + (lane >> 2);
+            const int c = (lane & 3) ^ ((row >> 2) & 3);
             voff[i] = row * ld_bytes + c * 16;
         }
     }
-    __device__ __forceinline__ void issue_one(__amdgpu_buffer_rsrc_t r, char *tile, int i) const {
+    __device__ __forceinline__ void issue(rsrc_t r, uint32_t tile) const {
         const int w = threadIdx.x >> 6;
-        __builtin_amdgcn_raw_ptr_buffer_load_lds(r, (lds_void_ptr)(tile + 1024 * (w + kWaves2 * i)), 16, voff[i],
-                                                 0, 0, 0);
-    }
-    __device__ __forceinline__ void issue(__amdgpu_buffer_rsrc_t r, char *tile) const {
 #pragma unroll
-        for (int i = 0; i < 4; ++i) issue_one(r, tile, i);
+        for (int i = 0; i < 2; ++i) lds_load16(r, tile + 1024 * (w + kWaves2 * i), voff[i]);
     }
 };
 
-// Transposed tile: 64 k-rows of R features (R = 256: one tile of 32 KB; R = 128: 16 KB).
-// col_bytes = byte offset of the tile's first feature inside a source row.
+// Transposed tile: 32 k-rows of R features.  R = 256: 16 chunks (2 k-rows each), two per
+// wave.  R = 128: 8 chunks (4 k-rows each), one per wave.
 template <int R>
 struct DmaTR {
-    static constexpr int NCH = R / 8;             // 1 KB chunks in the tile
+    static constexpr int NCH = R / 16;            // 1 KB chunks in the tile
     static constexpr int PER = NCH / kWaves2;     // chunks per wave
     static constexpr int LPR = R / 8;             // lanes (16-B slots) per k-row
     static constexpr int KR = 64 / LPR;           // k-rows per chunk
@@ -91,21 +114,18 @@ struct DmaTR {
             voff[i] = k * ld_bytes + col_bytes + c16 * 16;
         }
     }
-    __device__ __forceinline__ void issue_one(__amdgpu_buffer_rsrc_t r, char *tile, int i) const {
+    __device__ __forceinline__ void issue(rsrc_t r, uint32_t tile) const {
         const int w = threadIdx.x >> 6;
-        __builtin_amdgcn_raw_ptr_buffer_load_lds(r, (lds_void_ptr)(tile + 1024 * (w + kWaves2 * i)), 16, voff[i],
-                                                 0, 0, 0);
-    }
-    __device__ __forceinline__ void issue(__amdgpu_buffer_rsrc_t r, char *tile) const {
 #pragma unroll
-        for (int i = 0; i < PER; ++i) issue_one(r, tile, i);
+        for (int i = 0; i < PER; ++i) lds_load16(r, tile + 1024 * (w + kWaves2 * i), voff[i]);
     }
 };
 
-// Operand kinds.  Each provides: init, issue(kt, stage_tile), frag(stage_tile, t, s).
+// Operand kinds.  Each provides: init, issue(kt, stage_tile), frag(stage_tile, t, s) and
+// issues exactly two loads per wave per stage.
 //   KC256  : one Src
 //   TR256  : one Src
-//   TR128x2: two Src (sub-tile 0 at tile+0, sub-tile 1 at tile+16 KB); MFMA tiles 0,1 of a
+//   TR128x2: two Src (sub-tile 0 at tile+0, sub-tile 1 at tile+8 KB); MFMA tiles 0,1 of a
 //            wave come from sub-tile 0 and tiles 2,3 from sub-tile 1 at the same features
 // A second Src set takes over from k-tile `kswitch` on (two-phase reductions).
 struct OpKC256 {
@@ -118,16 +138,10 @@ struct OpKC256 {
         dma.init(ld_bytes);
         fr.init(wave_base);
     }
-    __device__ __forceinline__ void issue(int kt, char *tile) const {
+    __device__ __forceinline__ void issue(int kt, uint32_t tile) const {
         const bool second = kt >= kswitch;
         const Src &s = second ? src[1] : src[0];
         dma.issue(src_rsrc(s, second ? kt - kswitch : kt), tile);
-    }
-    // one quarter (part = 0..3) of the tile's loads
-    __device__ __forceinline__ void issue_part(int kt, char *tile, int part) const {
-        const bool second = kt >= kswitch;
-        const Src &s = second ? src[1] : src[0];
-        dma.issue_one(src_rsrc(s, second ? kt - kswitch : kt), tile, part);
     }
     __device__ __forceinline__ bf16x8_t frag(const char *tile, int t, int s) const { return fr.read(tile, t, s); }
 };
@@ -142,15 +156,10 @@ struct OpTR256 {
         dma.init(ld_bytes, col_bytes);
         fr.init(wave_base);
     }
-    __device__ __forceinline__ void issue(int kt, char *tile) const {
+    __device__ __forceinline__ void issue(int kt, uint32_t tile) const {
         const bool second = kt >= kswitch;
         const Src &s = second ? src[1] : src[0];
         dma.issue(src_rsrc(s, second ? kt - kswitch : kt), tile);
-    }
-    __device__ __forceinline__ void issue_part(int kt, char *tile, int part) const {
-        const bool second = kt >= kswitch;
-        const Src &s = second ? src[1] : src[0];
-        dma.issue_one(src_rsrc(s, second ? kt - kswitch : kt), tile, part);
     }
     __device__ __forceinline__ bf16x8_t frag(const char *tile, int t, int s) const { return fr.read(tile, t, s); }
 };
@@ -164,12 +173,9 @@ struct OpTR128x2 {
         dma.init(ld_bytes, col_bytes);
         fr.init(wave_base);
     }
-    __device__ __forceinline__ void issue(int kt, char *tile) const {
+    __device__ __forceinline__ void issue(int kt, uint32_t tile) const {
         dma.issue(src_rsrc(src[0], kt), tile);
         dma.issue(src_rsrc(src[1], kt), tile + kOperandBytes / 2);
-    }
-    __device__ __forceinline__ void issue_part(int kt, char *tile, int part) const {
-        dma.issue_one(src_rsrc(src[part >> 1], kt), tile + (part >> 1) * (kOperandBytes / 2), part & 1);
     }
     __device__ __forceinline__ bf16x8_t frag(const char *tile, int t, int s) const {
         return fr.read(tile + (t >> 1) * (kOperandBytes / 2), t & 1, s);
@@ -207,69 +213,87 @@ __device__ __forceinline__ void mfma_block(Acc2 &acc, const Frags &f) {
             acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.a[i], f.b[j], acc[i][j], 0, 0, 0);
 }
 
-// One resident stage.  On entry `x` may hold the last fragment set of the previous stage
-// (pending = true): its MFMAs are issued right after this stage's first fragment reads, so
-// the MFMA pipe has work while those reads are in flight just after the barrier.  On exit
-// `x` holds this stage's last fragment set, not yet multiplied.
-// The sched_barriers keep at most two fragment sets live next to the 128 accumulators.
-// One sub-step: the fragment reads of the next 16 k go out first, then (first sub-step only)
-// the next stage's global->LDS loads, then the 8 MFMAs of the current fragments, so the reads
-// have 8 MFMAs (256 cycles) to land.  (Left alone the compiler sinks the reads below the
-// MFMAs and every sub-step starts by waiting on LDS.  Spreading the loads over the four
-// sub-steps was measured slower: the late ones are not back before the stage ends.)
+// 8 MFMAs with the next fragment reads threaded between them: one MFMA, two LDS reads, one
+// MFMA, ...  The first MFMA goes out at once (right after a barrier the matrix pipe would
+// otherwise idle while a wave issues its reads), and the reads ride in the shadow of the
+// MFMAs.  Left alone the compiler sinks the reads below the MFMAs and every sub-step starts
+// by waiting on LDS.
 template <class POp, class QOp>
 __device__ __forceinline__ void sub_step(Acc2 &acc, Frags &next, const Frags &cur, const POp &P, const QOp &Q,
-                                         const char *stage, int s, bool prefetch, int kt_next, char *stage_next) {
+                                         const char *stage, int s) {
     read_frags(next, P, Q, stage, s);
-    if (prefetch && s == 0) {
-        P.issue(kt_next, stage_next);
-        Q.issue(kt_next, stage_next + kOperandBytes);
-    }
     mfma_block(acc, cur);
-    __builtin_amdgcn_sched_group_barrier(0x100, POp::kDsReads + QOp::kDsReadsQ, 0);  // DS reads
-    if (s == 0) __builtin_amdgcn_sched_group_barrier(0x020, 8, 0);                   // VMEM reads
-    __builtin_amdgcn_sched_group_barrier(0x008, kTP2 * kTQ2, 0);                     // MFMA
+#pragma unroll
+    for (int i = 0; i < kTP2 * kTQ2; ++i) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);  // MFMA
+        __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);  // DS read
+    }
     __builtin_amdgcn_sched_barrier(0);
 }
 
-// One resident stage.  On entry `x` holds the last fragment set of the previous stage (zeros
-// on the very first stage): its MFMAs are issued right behind this stage's first fragment
-// reads, so the MFMA pipe has work while those reads are in flight just after the barrier.
-// On exit `x` holds this stage's last fragment set, not yet multiplied.  At most two fragment
-// sets are live next to the 128 accumulator registers.
+// One resident stage (two 16-k sub-steps).  On entry `x` holds the last fragment set of the
+// previous stage (zeros before the first): its MFMAs open this stage, so the matrix pipe has
+// work while this stage's first fragment reads are in flight.  On exit `x` holds this
+// stage's last fragment set, not yet multiplied.  The loads of the stage three ahead are
+// issued between the two sub-steps (inline asm, stays where it is written).  At most two
+// fragment sets are live next to the 128 accumulator registers.
 template <class POp, class QOp>
 __device__ __forceinline__ void stage_compute(Acc2 &acc, Frags &x, Frags &y, const POp &P, const QOp &Q,
-                                              const char *stage, bool prefetch, int kt_next, char *stage_next) {
-    sub_step(acc, y, x, P, Q, stage, 0, prefetch, kt_next, stage_next);
-    sub_step(acc, x, y, P, Q, stage, 1, prefetch, kt_next, stage_next);
-    sub_step(acc, y, x, P, Q, stage, 2, prefetch, kt_next, stage_next);
-    sub_step(acc, x, y, P, Q, stage, 3, prefetch, kt_next, stage_next);
+                                              const char *stage, int kt_load, uint32_t stage_load) {
+    sub_step(acc, y, x, P, Q, stage, 0);
+#ifndef R3_LAB_SKIP_DMA
+    P.issue(kt_load, stage_load);
+    Q.issue(kt_load, stage_load + kOperandBytes);
+#endif
+    __builtin_amdgcn_sched_barrier(0);
+    sub_step(acc, x, y, P, Q, stage, 1);
 }
 
-// nk k-tiles of 64.  s0, s1: the two 64 KB LDS stages (distinct arrays).
+// End of a stage: wait until at most two stages' loads of this wave are outstanding (i.e. its
+// share of the next stage has landed) and all its LDS reads are back, then meet the other
+// waves.  A bare s_barrier is used on purpose: __syncthreads() carries a fence for which the
+// compiler drains every outstanding load, including the ones just issued three stages ahead.
+__device__ __forceinline__ void stage_barrier() {
+    // s_waitcnt simm16: vmcnt[3:0] | expcnt[6:4] | lgkmcnt[11:8] | vmcnt_hi[15:14]
+    __builtin_amdgcn_s_waitcnt((2 * kLoadsPerStage) | (7 << 4) | (0 << 8));
+#ifndef R3_LAB_SKIP_BARRIER
+    __builtin_amdgcn_s_barrier();
+#endif
+}
+
+// nk k-tiles of 32.  st0..st3: the four 32 KB LDS stages (distinct arrays).
 template <class POp, class QOp>
-__device__ __forceinline__ void mfma_mainloop2(Acc2 &acc, int nk, const POp &P, const QOp &Q, char *s0, char *s1) {
+__device__ __forceinline__ void mfma_mainloop2(Acc2 &acc, int nk, const POp &P, const QOp &Q, char *st0, char *st1,
+                                               char *st2, char *st3) {
     if (nk <= 0) return;
-    P.issue(0, s0);
-    Q.issue(0, s0 + kOperandBytes);
-    __builtin_amdgcn_s_waitcnt(0);
-    __syncthreads();
+    const uint32_t a0 = lds_addr(st0), a1 = lds_addr(st1), a2 = lds_addr(st2), a3 = lds_addr(st3);
+    // prologue: stages 0, 1, 2 (a stage >= nk loads nothing useful but still counts)
+    P.issue(0, a0);
+    Q.issue(0, a0 + kOperandBytes);
+    P.issue(1, a1);
+    Q.issue(1, a1 + kOperandBytes);
+    P.issue(2, a2);
+    Q.issue(2, a2 + kOperandBytes);
+    stage_barrier();
     Frags x, y;
 #pragma unroll
     for (int i = 0; i < kTP2; ++i) x.a[i] = bf16x8_t{};
 #pragma unroll
     for (int j = 0; j < kTQ2; ++j) x.b[j] = bf16x8_t{};
-    for (int kt = 0; kt < nk; kt += 2) {
-        const bool has1 = kt + 1 < nk, has2 = kt + 2 < nk;
-        stage_compute(acc, x, y, P, Q, s0, has1, kt + 1, s1);
-        __builtin_amdgcn_s_waitcnt(0);
-        __syncthreads();
-        // single loop exit (no break) keeps the accumulators in place
-        if (has1) stage_compute(acc, x, y, P, Q, s1, has2, kt + 2, s0);
-        __builtin_amdgcn_s_waitcnt(0);
-        __syncthreads();
+    // single loop exit (no break) keeps the accumulators in place
+    for (int kt = 0; kt < nk; kt += 4) {
+        stage_compute(acc, x, y, P, Q, st0, kt + 3, a3);
+        stage_barrier();
+        if (kt + 1 < nk) stage_compute(acc, x, y, P, Q, st1, kt + 4, a0);
+        stage_barrier();
+        if (kt + 2 < nk) stage_compute(acc, x, y, P, Q, st2, kt + 5, a1);
+        stage_barrier();
+        if (kt + 3 < nk) stage_compute(acc, x, y, P, Q, st3, kt + 6, a2);
+        stage_barrier();
     }
     mfma_block(acc, x);
+    // loads issued for stages past the end are still in flight: drain them before the LDS goes away
+    __builtin_amdgcn_s_waitcnt(0 | (7 << 4) | (15 << 8));
 }
 
 // Visit the wave's results as groups of 4 consecutive p for one q (tile-local p, q).
