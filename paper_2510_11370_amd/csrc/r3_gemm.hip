@@ -121,28 +121,33 @@ ffn1_kernel(int S, int d, int F, const bf16_t *__restrict__ Xp, const int32_t *_
     mfma_mainloop2(acc, d / kBK2, P, Q, s0, s1, s2, s3);
     R3_TL(2);
 
+    // per wave: 64 rows x 64 features of H (and A, B), 32 rows at a time through LDS
+    RowStage<128> st{wave_patch(s0, s1, s2, s3)};
+    const int q = lane & 31;
 #pragma unroll
-    for (int tp = 0; tp < 2; ++tp)
+    for (int tq = 0; tq < kTQ2; ++tq) {
+        const int brow = row0 + wq * 64 + tq * 32;            // first row of this block
+        const int valid = min(32, row_end - brow);             // may be <= 0
+        const int64_t o = ((int64_t)brow * F + f0 + wp * 64) * 2;  // byte offset of the block
 #pragma unroll
-        for (int tq = 0; tq < kTQ2; ++tq) {
-            const int row = row0 + wq * 64 + tq * 32 + (lane & 31);
-            if (row >= row_end) continue;
+        for (int which = 0; which < 3; ++which) {              // 0: H, 1: A, 2: B
+            bf16_t *dst = which == 0 ? H : which == 1 ? A : B;
+            if (!dst) continue;
 #pragma unroll
-            for (int g = 0; g < 4; ++g) {
-                const int f = f0 + wp * 64 + tp * 32 + g * 8 + (lane >> 5) * 4;
-                float a[4], b[4], h[4];
+            for (int tp = 0; tp < 2; ++tp)
 #pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    a[i] = acc[tp][tq][4 * g + i];
-                    b[i] = acc[tp + 2][tq][4 * g + i];
-                    h[i] = a[i] * sigmoid_fast(a[i]) * b[i];
+                for (int g = 0; g < 4; ++g) {
+                    float v[4];
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        const float a = acc[tp][tq][4 * g + i], b = acc[tp + 2][tq][4 * g + i];
+                        v[i] = which == 0 ? a * sigmoid_fast(a) * b : which == 1 ? a : b;
+                    }
+                    st.put8(q, (tp * 32 + g * 8 + (lane >> 5) * 4) * 2, pack4(v[0], v[1], v[2], v[3]));
                 }
-                const int64_t o = (int64_t)row * F + f;
-                *(uint2 *)(H + o) = pack4(h[0], h[1], h[2], h[3]);
-                if (A) *(uint2 *)(A + o) = pack4(a[0], a[1], a[2], a[3]);
-                if (B) *(uint2 *)(B + o) = pack4(b[0], b[1], b[2], b[3]);
-            }
+            st.flush((char *)dst + o, (int64_t)F * 2, valid);
         }
+    }
     R3_TL_FLUSH();
 }
 
@@ -214,29 +219,58 @@ rowgemm_kernel(int S, int d, int F, const bf16_t *__restrict__ Q0, const bf16_t 
         mfma_mainloop2(acc, 2 * (F / kBK2), P, Q, s0, s1, s2, s3);
     }
 
-    for_each_quad2([&](int tp, int tq, int g, int p, int q) {
-        const int row = row0 + q;
-        if (row >= row_end) return;
-        const int64_t o = (int64_t)row * NOUT + p0 + p;
-        const float v0 = acc[tp][tq][4 * g], v1 = acc[tp][tq][4 * g + 1], v2 = acc[tp][tq][4 * g + 2],
-                    v3 = acc[tp][tq][4 * g + 3];
-        if constexpr (MODE == 1) {
-            float a[4], b[4], da[4], db[4];
-            const float dh[4] = {v0, v1, v2, v3};
-            unpack4(*(const uint2 *)(A + o), a);
-            unpack4(*(const uint2 *)(B + o), b);
+    // per wave: 64 rows x 128 features, 32 rows at a time through LDS
+    const int lane = threadIdx.x & 63;
+    RowStage<256> st{wave_patch(s0, s1, s2, s3)};
+    const int q = lane & 31;
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const float sg = sigmoid_fast(a[i]);
-                da[i] = dh[i] * b[i] * sg * (1.0f + a[i] * (1.0f - sg));
-                db[i] = dh[i] * a[i] * sg;
+    for (int tq = 0; tq < kTQ2; ++tq) {
+        const int brow = row0 + wq * 64 + tq * 32;
+        const int valid = min(32, row_end - brow);
+        const int64_t o = ((int64_t)brow * NOUT + p0 + wp * 128) * 2;
+        if constexpr (MODE == 1) {
+            // saved pre-activations come in row-contiguously into two patches (A and B), 64
+            // features at a time so that both fit the wave's 16 KB; each lane then replaces
+            // exactly the quads it read with dA (first patch) and dB (second patch)
+            RowStage<128> sa{st.base}, sb{st.base + RowStage<128>::BYTES};
+#pragma unroll
+            for (int half = 0; half < 2; ++half) {
+                const int64_t oh = o + half * 128;
+                sa.fill((const char *)A + oh, (int64_t)NOUT * 2, valid);
+                sb.fill((const char *)B + oh, (int64_t)NOUT * 2, valid);
+#pragma unroll
+                for (int t = 0; t < 2; ++t)
+#pragma unroll
+                    for (int g = 0; g < 4; ++g) {
+                        const int tp = half * 2 + t;
+                        const int bo = (t * 32 + g * 8 + (lane >> 5) * 4) * 2;
+                        float a[4], b[4], da[4], db[4];
+                        unpack4(sa.get8(q, bo), a);
+                        unpack4(sb.get8(q, bo), b);
+#pragma unroll
+                        for (int i = 0; i < 4; ++i) {
+                            const float dh = acc[tp][tq][4 * g + i];
+                            const float sg = sigmoid_fast(a[i]);
+                            da[i] = dh * b[i] * sg * (1.0f + a[i] * (1.0f - sg));
+                            db[i] = dh * a[i] * sg;
+                        }
+                        sa.put8(q, bo, pack4(da[0], da[1], da[2], da[3]));
+                        sb.put8(q, bo, pack4(db[0], db[1], db[2], db[3]));
+                    }
+                sa.flush((char *)out0 + oh, (int64_t)NOUT * 2, valid);
+                sb.flush((char *)out1 + oh, (int64_t)NOUT * 2, valid);
             }
-            *(uint2 *)(out0 + o) = pack4(da[0], da[1], da[2], da[3]);
-            *(uint2 *)(out1 + o) = pack4(db[0], db[1], db[2], db[3]);
         } else {
-            *(uint2 *)(out0 + o) = pack4(v0, v1, v2, v3);
+#pragma unroll
+            for (int tp = 0; tp < kTP2; ++tp)
+#pragma unroll
+                for (int g = 0; g < 4; ++g)
+                    st.put8(q, (tp * 32 + g * 8 + (lane >> 5) * 4) * 2,
+                            pack4(acc[tp][tq][4 * g], acc[tp][tq][4 * g + 1], acc[tp][tq][4 * g + 2],
+                                  acc[tp][tq][4 * g + 3]));
+            st.flush((char *)out0 + o, (int64_t)NOUT * 2, valid);
         }
-    });
+    }
 }
 
 // ---------------------------------------------------------------------------
@@ -278,17 +312,27 @@ wgrad_kernel(int E, int NQd, int NPd, const bf16_t *__restrict__ Qs, const bf16_
     zero_acc2(acc);
     mfma_mainloop2(acc, (r1 - r0 + kBK2 - 1) / kBK2, P, Q, s0, s1, s2, s3);
 
-    float *o = out + (int64_t)e * NQd * NPd;
-    for_each_quad2([&](int tp, int tq, int g, int p, int q) {
-        float4 *dst = (float4 *)(o + (int64_t)(q0 + q) * NPd + p0 + p);
-        float4 v = make_float4(acc[tp][tq][4 * g], acc[tp][tq][4 * g + 1], acc[tp][tq][4 * g + 2],
-                               acc[tp][tq][4 * g + 3]);
-        if (accumulate) {
-            const float4 old = *dst;
-            v.x += old.x; v.y += old.y; v.z += old.z; v.w += old.w;
+    // per wave: 64 rows (q) x 128 features (p) of f32, as 32-row x 64-feature blocks through LDS
+    const int lane = threadIdx.x & 63;
+    RowStage<256> st{wave_patch(s0, s1, s2, s3)};
+    const int q = lane & 31;
+    char *o = (char *)(out + (int64_t)e * NQd * NPd);
+#pragma unroll
+    for (int tq = 0; tq < kTQ2; ++tq)
+#pragma unroll
+        for (int half = 0; half < 2; ++half) {
+#pragma unroll
+            for (int t = 0; t < 2; ++t)
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    const int tp = half * 2 + t;
+                    st.put16(q, (t * 32 + g * 8 + (lane >> 5) * 4) * 4,
+                             make_float4(acc[tp][tq][4 * g], acc[tp][tq][4 * g + 1], acc[tp][tq][4 * g + 2],
+                                         acc[tp][tq][4 * g + 3]));
+                }
+            const int64_t off = ((int64_t)(q0 + wq * 64 + tq * 32) * NPd + p0 + wp * 128 + half * 64) * 4;
+            st.flush_f32(o + off, (int64_t)NPd * 4, 32, accumulate);
         }
-        *dst = v;
-    });
 }
 
 // ---------------------------------------------------------------------------

@@ -19,9 +19,12 @@
 //        fragments come out through ds_read_b64_tr_b16 (4 consecutive k of one feature).
 // The four stages are separate LDS arrays so that the compiler can see that loads in
 // flight never alias the stage being read (no vmcnt wait in front of the fragment reads).
-// Every stage issues exactly the same number of loads per wave (a stage past the end of the
+// Wave roles.  All 8 waves multiply.  Waves 0-3 ("loaders") also issue every tile load and
+// count them: each issues the same number of loads per stage (a stage past the end of the
 // reduction gets a zero-length descriptor), so "s_waitcnt vmcnt(2 stages' worth)" at the end
-// of stage kt is exactly "stage kt+1 has landed".
+// of stage kt is exactly "stage kt+1 has landed".  (Having waves 4-7 touch the lines of
+// later stages to warm L2 was tried and measured slower: the extra requests cost more in the
+// vector memory path than the shorter load latency gave back.)
 #pragma once
 #include "r3_mfma.h"
 
@@ -34,7 +37,8 @@ constexpr int kOperandBytes = kTile * kBK2 * 2;  // 16 KB
 constexpr int kStageBytes = 2 * kOperandBytes;   // 32 KB
 constexpr int kWaves2 = 8, kThreads2 = 512;
 constexpr int kWP2 = 2, kWQ2 = 4, kTP2 = 4, kTQ2 = 2;
-constexpr int kLoadsPerStage = 4;                // buffer loads per wave per stage (2 per operand)
+constexpr int kLoaderWaves = 4;
+constexpr int kLoadsPerStage = 8;                // buffer loads per loader wave per stage (4 per operand)
 constexpr uint32_t kRsrcFlags = 0x00020000u;
 
 typedef __attribute__((address_space(3))) void *lds_void_ptr;
@@ -76,14 +80,14 @@ __device__ __forceinline__ void lds_load16(rsrc_t r, uint32_t dst_wave, int voff
                  : "memory");
 }
 
-// K-contiguous 256-row tile: 16 chunks of 1 KB (16 rows x 64 B), two per wave.
+// K-contiguous 256-row tile: 16 chunks of 1 KB (16 rows x 64 B), four per loader wave.
 struct DmaKC {
-    int voff[2];
+    int voff[4];
     __device__ __forceinline__ void init(int ld_bytes) {
         const int w = threadIdx.x >> 6, lane = threadIdx.x & 63;
 #pragma unroll
-        for (int i = 0; i < 2; ++i) {
-            const int row = 16 * (w + kWaves2 * i) + (lane >> 2);
+        for (int i = 0; i < 4; ++i) {
+            const int row = 16 * ((w & 3) + kLoaderWaves * i) + (lane >> 2);
             const int c = (lane & 3) ^ ((row >> 2) & 3);
             voff[i] = row * ld_bytes + c * 16;
         }
@@ -91,7 +95,7 @@ struct DmaKC {
     __device__ __forceinline__ void issue(rsrc_t r, uint32_t tile) const {
         const int w = threadIdx.x >> 6;
 #pragma unroll
-        for (int i = 0; i < 2; ++i) lds_load16(r, tile + 1024 * (w + kWaves2 * i), voff[i]);
+        for (int i = 0; i < 4; ++i) lds_load16(r, tile + 1024 * ((w & 3) + kLoaderWaves * i), voff[i]);
     }
 };
 
@@ -100,7 +104,7 @@ struct DmaKC {
 template <int R>
 struct DmaTR {
     static constexpr int NCH = R / 16;            // 1 KB chunks in the tile
-    static constexpr int PER = NCH / kWaves2;     // chunks per wave
+    static constexpr int PER = NCH / kLoaderWaves;  // chunks per loader wave
     static constexpr int LPR = R / 8;             // lanes (16-B slots) per k-row
     static constexpr int KR = 64 / LPR;           // k-rows per chunk
     int voff[PER];
@@ -108,7 +112,7 @@ struct DmaTR {
         const int w = threadIdx.x >> 6, lane = threadIdx.x & 63;
 #pragma unroll
         for (int i = 0; i < PER; ++i) {
-            const int k = KR * (w + kWaves2 * i) + lane / LPR;
+            const int k = KR * ((w & 3) + kLoaderWaves * i) + lane / LPR;
             const int pc = lane % LPR;
             const int c16 = (((pc >> 2) ^ (k & 3)) << 2) | (pc & 3);
             voff[i] = k * ld_bytes + col_bytes + c16 * 16;
@@ -117,12 +121,12 @@ struct DmaTR {
     __device__ __forceinline__ void issue(rsrc_t r, uint32_t tile) const {
         const int w = threadIdx.x >> 6;
 #pragma unroll
-        for (int i = 0; i < PER; ++i) lds_load16(r, tile + 1024 * (w + kWaves2 * i), voff[i]);
+        for (int i = 0; i < PER; ++i) lds_load16(r, tile + 1024 * ((w & 3) + kLoaderWaves * i), voff[i]);
     }
 };
 
 // Operand kinds.  Each provides: init, issue(kt, stage_tile), frag(stage_tile, t, s) and
-// issues exactly two loads per wave per stage.
+// issues exactly four loads per loader wave per stage.
 //   KC256  : one Src
 //   TR256  : one Src
 //   TR128x2: two Src (sub-tile 0 at tile+0, sub-tile 1 at tile+8 KB); MFMA tiles 0,1 of a
@@ -239,23 +243,29 @@ __device__ __forceinline__ void sub_step(Acc2 &acc, Frags &next, const Frags &cu
 // fragment sets are live next to the 128 accumulator registers.
 template <class POp, class QOp>
 __device__ __forceinline__ void stage_compute(Acc2 &acc, Frags &x, Frags &y, const POp &P, const QOp &Q,
-                                              const char *stage, int kt_load, uint32_t stage_load) {
+                                              const char *stage, int kt_load, uint32_t stage_load, bool loader) {
     sub_step(acc, y, x, P, Q, stage, 0);
-#ifndef R3_LAB_SKIP_DMA
-    P.issue(kt_load, stage_load);
-    Q.issue(kt_load, stage_load + kOperandBytes);
-#endif
+    if (loader) {
+        P.issue(kt_load, stage_load);
+        Q.issue(kt_load, stage_load + kOperandBytes);
+    }
     __builtin_amdgcn_sched_barrier(0);
     sub_step(acc, x, y, P, Q, stage, 1);
 }
 
-// End of a stage: wait until at most two stages' loads of this wave are outstanding (i.e. its
-// share of the next stage has landed) and all its LDS reads are back, then meet the other
-// waves.  A bare s_barrier is used on purpose: __syncthreads() carries a fence for which the
-// compiler drains every outstanding load, including the ones just issued three stages ahead.
-__device__ __forceinline__ void stage_barrier() {
+// End of a stage.  Loaders wait until at most two stages' loads are outstanding (their share
+// of the next stage has landed); everyone waits for its LDS reads; then the waves meet.  A
+// bare s_barrier is used on purpose: __syncthreads() carries a fence for which the compiler
+// drains every outstanding load, including the ones just issued three stages ahead.
+__device__ __forceinline__ void stage_barrier(bool loader) {
     // s_waitcnt simm16: vmcnt[3:0] | expcnt[6:4] | lgkmcnt[11:8] | vmcnt_hi[15:14]
-    __builtin_amdgcn_s_waitcnt((2 * kLoadsPerStage) | (7 << 4) | (0 << 8));
+#ifdef R3_LAB_D2
+    constexpr int vm = 1 * kLoadsPerStage;
+#else
+    constexpr int vm = 2 * kLoadsPerStage;
+#endif
+    if (loader) __builtin_amdgcn_s_waitcnt((vm & 15) | (7 << 4) | (0 << 8) | ((vm >> 4) << 14));
+    else __builtin_amdgcn_s_waitcnt(15 | (7 << 4) | (0 << 8) | (3 << 14));
 #ifndef R3_LAB_SKIP_BARRIER
     __builtin_amdgcn_s_barrier();
 #endif
@@ -267,14 +277,20 @@ __device__ __forceinline__ void mfma_mainloop2(Acc2 &acc, int nk, const POp &P, 
                                                char *st2, char *st3) {
     if (nk <= 0) return;
     const uint32_t a0 = lds_addr(st0), a1 = lds_addr(st1), a2 = lds_addr(st2), a3 = lds_addr(st3);
-    // prologue: stages 0, 1, 2 (a stage >= nk loads nothing useful but still counts)
-    P.issue(0, a0);
-    Q.issue(0, a0 + kOperandBytes);
-    P.issue(1, a1);
-    Q.issue(1, a1 + kOperandBytes);
-    P.issue(2, a2);
-    Q.issue(2, a2 + kOperandBytes);
-    stage_barrier();
+    // wave-uniform, and visibly so (scalar branch instead of exec masking)
+    const bool loader = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6)) < kLoaderWaves;
+    if (loader) {
+        // stages 0, 1, 2 (a stage >= nk loads nothing useful but still counts)
+        P.issue(0, a0);
+        Q.issue(0, a0 + kOperandBytes);
+        P.issue(1, a1);
+        Q.issue(1, a1 + kOperandBytes);
+#ifndef R3_LAB_D2
+        P.issue(2, a2);
+        Q.issue(2, a2 + kOperandBytes);
+#endif
+    }
+    stage_barrier(loader);
     Frags x, y;
 #pragma unroll
     for (int i = 0; i < kTP2; ++i) x.a[i] = bf16x8_t{};
@@ -282,18 +298,96 @@ __device__ __forceinline__ void mfma_mainloop2(Acc2 &acc, int nk, const POp &P, 
     for (int j = 0; j < kTQ2; ++j) x.b[j] = bf16x8_t{};
     // single loop exit (no break) keeps the accumulators in place
     for (int kt = 0; kt < nk; kt += 4) {
-        stage_compute(acc, x, y, P, Q, st0, kt + 3, a3);
-        stage_barrier();
-        if (kt + 1 < nk) stage_compute(acc, x, y, P, Q, st1, kt + 4, a0);
-        stage_barrier();
-        if (kt + 2 < nk) stage_compute(acc, x, y, P, Q, st2, kt + 5, a1);
-        stage_barrier();
-        if (kt + 3 < nk) stage_compute(acc, x, y, P, Q, st3, kt + 6, a2);
-        stage_barrier();
+#ifdef R3_LAB_D2
+        stage_compute(acc, x, y, P, Q, st0, kt + 2, a2, loader);
+        stage_barrier(loader);
+        if (kt + 1 < nk) stage_compute(acc, x, y, P, Q, st1, kt + 3, a3, loader);
+        stage_barrier(loader);
+        if (kt + 2 < nk) stage_compute(acc, x, y, P, Q, st2, kt + 4, a0, loader);
+        stage_barrier(loader);
+        if (kt + 3 < nk) stage_compute(acc, x, y, P, Q, st3, kt + 5, a1, loader);
+        stage_barrier(loader);
+#else
+        stage_compute(acc, x, y, P, Q, st0, kt + 3, a3, loader);
+        stage_barrier(loader);
+        if (kt + 1 < nk) stage_compute(acc, x, y, P, Q, st1, kt + 4, a0, loader);
+        stage_barrier(loader);
+        if (kt + 2 < nk) stage_compute(acc, x, y, P, Q, st2, kt + 5, a1, loader);
+        stage_barrier(loader);
+        if (kt + 3 < nk) stage_compute(acc, x, y, P, Q, st3, kt + 6, a2, loader);
+        stage_barrier(loader);
+#endif
     }
     mfma_block(acc, x);
-    // loads issued for stages past the end are still in flight: drain them before the LDS goes away
+    // loads for stages past the end are still in flight: drain them, and meet, before anyone
+    // reuses the stage buffers (the epilogues stage their stores through them)
     __builtin_amdgcn_s_waitcnt(0 | (7 << 4) | (15 << 8));
+    __builtin_amdgcn_s_barrier();
+}
+
+// Epilogue staging.  The MFMA result layout gives a lane 4 consecutive features of ONE row
+// per register quad, so direct stores are 16-byte pieces scattered over 32 rows per
+// instruction and the vector memory path spends more time on them than the tile spent on
+// arithmetic.  Instead a wave drops a 32-row block into its private LDS patch (the stage
+// buffers are free by now) and stores it back out with consecutive lanes along a row:
+// full 128/256-byte row segments per instruction.  The same patch serves to bring in
+// row-contiguous loads (saved activations, old gradients) for per-quad use.
+// ROWB = payload bytes per row (128 or 256); rows are padded by 16 B against bank conflicts.
+template <int ROWB>
+struct RowStage {
+    static constexpr int PITCH = ROWB + 16;
+    static constexpr int LPR = ROWB / 16;   // lanes per row when moving rows
+    static constexpr int RPI = 64 / LPR;    // rows per instruction
+    static constexpr int BYTES = 32 * PITCH;
+    char *base;
+    __device__ __forceinline__ void put8(int q, int byte_off, uint2 v) const { *(uint2 *)(base + q * PITCH + byte_off) = v; }
+    __device__ __forceinline__ void put16(int q, int byte_off, float4 v) const { *(float4 *)(base + q * PITCH + byte_off) = v; }
+    __device__ __forceinline__ uint2 get8(int q, int byte_off) const { return *(const uint2 *)(base + q * PITCH + byte_off); }
+    // rows [0, valid) of the patch -> out (byte pointer at row 0), row pitch ld_bytes
+    __device__ __forceinline__ void flush(char *out, int64_t ld_bytes, int valid) const {
+        const int lane = threadIdx.x & 63, r = lane / LPR, c = lane % LPR;
+#pragma unroll
+        for (int i = 0; i < 32 / RPI; ++i) {
+            const int row = i * RPI + r;
+            const uint4 v = *(const uint4 *)(base + row * PITCH + c * 16);
+            if (row < valid) *(uint4 *)(out + row * ld_bytes + c * 16) = v;
+        }
+    }
+    // same for f32 rows, adding what is already in memory (accumulate != 0)
+    __device__ __forceinline__ void flush_f32(char *out, int64_t ld_bytes, int valid, int accumulate) const {
+        const int lane = threadIdx.x & 63, r = lane / LPR, c = lane % LPR;
+#pragma unroll 2
+        for (int i = 0; i < 32 / RPI; ++i) {
+            const int row = i * RPI + r;
+            float4 v = *(const float4 *)(base + row * PITCH + c * 16);
+            if (row < valid) {
+                float4 *dst = (float4 *)(out + row * ld_bytes + c * 16);
+                if (accumulate) {
+                    const float4 old = *dst;
+                    v.x += old.x; v.y += old.y; v.z += old.z; v.w += old.w;
+                }
+                *dst = v;
+            }
+        }
+    }
+    // in (byte pointer at row 0) -> rows [0, valid) of the patch
+    __device__ __forceinline__ void fill(const char *in, int64_t ld_bytes, int valid) const {
+        const int lane = threadIdx.x & 63, r = lane / LPR, c = lane % LPR;
+#pragma unroll
+        for (int i = 0; i < 32 / RPI; ++i) {
+            const int row = i * RPI + r;
+            uint4 v = make_uint4(0u, 0u, 0u, 0u);
+            if (row < valid) v = *(const uint4 *)(in + row * ld_bytes + c * 16);
+            *(uint4 *)(base + row * PITCH + c * 16) = v;
+        }
+    }
+};
+
+// the wave's private 16 KB of the (now idle) stage buffers
+__device__ __forceinline__ char *wave_patch(char *s0, char *s1, char *s2, char *s3) {
+    const int w = threadIdx.x >> 6;
+    char *b = (w >> 1) == 0 ? s0 : (w >> 1) == 1 ? s1 : (w >> 1) == 2 ? s2 : s3;
+    return b + (w & 1) * 16384;
 }
 
 // Visit the wave's results as groups of 4 consecutive p for one q (tile-local p, q).
