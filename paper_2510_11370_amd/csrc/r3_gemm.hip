@@ -118,7 +118,7 @@ ffn1_kernel(int S, int d, int F, const bf16_t *__restrict__ Xp, const int32_t *_
     Acc2 acc;
     zero_acc2(acc);
     R3_TL(1);
-    mfma_mainloop2(acc, d / kBK2, P, Q, s0, s1, s2, s3);
+    mfma_mainloop2(acc, d / kBK2, P, Q, s0, s1, s2, s3, row_end - row0 > 128);
     R3_TL(2);
 
     // per wave: 64 rows x 64 features of H (and A, B), 32 rows at a time through LDS
@@ -201,14 +201,14 @@ rowgemm_kernel(int S, int d, int F, const bf16_t *__restrict__ Q0, const bf16_t 
         P.src[1] = P.src[0];
         P.kswitch = 0x7fffffff;
         P.init(d * 2, p0 * 2, 128 * wp);
-        mfma_mainloop2(acc, F / kBK2, P, Q, s0, s1, s2, s3);
+        mfma_mainloop2(acc, F / kBK2, P, Q, s0, s1, s2, s3, row_end - row0 > 128);
     } else if constexpr (MODE == 1) {
         OpKC256 P;
         P.src[0] = Src{(const char *)(w0 + (int64_t)p0 * d), clamp_bytes((int64_t)(F - p0) * d * 2), kBK2 * 2};
         P.src[1] = P.src[0];
         P.kswitch = 0x7fffffff;
         P.init(d * 2, 128 * wp);
-        mfma_mainloop2(acc, d / kBK2, P, Q, s0, s1, s2, s3);
+        mfma_mainloop2(acc, d / kBK2, P, Q, s0, s1, s2, s3, row_end - row0 > 128);
     } else {
         const bf16_t *w1 = W1 + (int64_t)e * d * F;
         OpKC256 P;
@@ -216,7 +216,7 @@ rowgemm_kernel(int S, int d, int F, const bf16_t *__restrict__ Q0, const bf16_t 
         P.src[1] = Src{(const char *)(w1 + (int64_t)p0 * F), clamp_bytes((int64_t)(d - p0) * F * 2), kBK2 * 2};
         P.kswitch = F / kBK2;
         P.init(F * 2, 128 * wp);
-        mfma_mainloop2(acc, 2 * (F / kBK2), P, Q, s0, s1, s2, s3);
+        mfma_mainloop2(acc, 2 * (F / kBK2), P, Q, s0, s1, s2, s3, row_end - row0 > 128);
     }
 
     // per wave: 64 rows x 128 features, 32 rows at a time through LDS

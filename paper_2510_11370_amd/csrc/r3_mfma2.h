@@ -272,10 +272,24 @@ __device__ __forceinline__ void stage_barrier(bool loader) {
 }
 
 // nk k-tiles of 32.  st0..st3: the four 32 KB LDS stages (distinct arrays).
+// upper_half_live = false: output rows 128..255 of the tile are not needed (ragged tail of an
+// expert's segment); waves 4-7, which own them and load nothing, then only keep the barriers
+// company, and every SIMD is left with one multiplying wave instead of two.
 template <class POp, class QOp>
 __device__ __forceinline__ void mfma_mainloop2(Acc2 &acc, int nk, const POp &P, const QOp &Q, char *st0, char *st1,
-                                               char *st2, char *st3) {
+                                               char *st2, char *st3, bool upper_half_live = true) {
     if (nk <= 0) return;
+    if (!upper_half_live && __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6)) >= kLoaderWaves) {
+        for (int kt = 0; kt < nk; kt += 4) {
+            stage_barrier(false);
+            stage_barrier(false);
+            stage_barrier(false);
+            stage_barrier(false);
+        }
+        stage_barrier(false);  // the one after the prologue loads
+        __builtin_amdgcn_s_barrier();
+        return;
+    }
     const uint32_t a0 = lds_addr(st0), a1 = lds_addr(st1), a2 = lds_addr(st2), a3 = lds_addr(st3);
     // wave-uniform, and visibly so (scalar branch instead of exec masking)
     const bool loader = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6)) < kLoaderWaves;

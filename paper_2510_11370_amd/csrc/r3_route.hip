@@ -21,79 +21,108 @@ __device__ __forceinline__ uint32_t order_key(float v, bool &nonfinite) {
     return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
 }
 
-// One lane scans one row of E keys (row staged in LDS as floats) and keeps the
-// KL largest keys, sorted descending, with min/max network insertion.
-// Returns the K-th largest key (threshold) and how many keys are above it.
-template <int KL>
-__device__ __forceinline__ void lane_topk_threshold(const float *row, int E, int K,
-                                                    uint32_t &thr, int &above, bool &bad) {
-    uint32_t top[KL];
+// Fast record: 8 lanes per token (8 tokens per wave), K <= 8, E <= 512.
+// Lane `sub` of a token owns the contiguous id range [sub*EPL, (sub+1)*EPL) and keeps its 8
+// largest keys in a sorted register list; three butterfly rounds of bitonic merges leave every
+// lane with the token's 8 largest keys.  The K-th of them is the threshold: keys above it are
+// taken, keys equal to it are taken lowest id first until K are out (prefix counts over the
+// 8 lanes give each lane its quota and its output position, so ids come out ascending).
+__device__ __forceinline__ void cmpx_desc(uint32_t &a, uint32_t &b) {
+    const uint32_t hi = max(a, b), lo = min(a, b);
+    a = hi;
+    b = lo;
+}
+
+template <typename IdxT>
+__global__ void __launch_bounds__(256)
+record_topk_sub8_kernel(int T, int E, int K, int EPL, const float *__restrict__ logits, int64_t ld,
+                        IdxT *__restrict__ idx, int64_t stride, int32_t *status) {
+    const int t = blockIdx.x * 32 + (int)(threadIdx.x >> 3);
+    const int sub = threadIdx.x & 7;
+    const bool live = t < T;
+    const float *row = logits + (int64_t)(live ? t : 0) * ld;
+    const int e0 = sub * EPL;
+    uint32_t top[8];
 #pragma unroll
-    for (int j = 0; j < KL; ++j) top[j] = 0u;
-    bad = false;
-    for (int e = 0; e < E; ++e) {
-        bool nf;
-        uint32_t v = order_key(row[e], nf);
-        bad |= nf;
+    for (int j = 0; j < 8; ++j) top[j] = 0u;
+    bool bad = false;
+    for (int i = 0; i < EPL; ++i) {
+        const int e = e0 + i;
+        uint32_t v = 0u;
+        if (live && e < E) {
+            bool nf;
+            v = order_key(row[e], nf);
+            bad |= nf;
+        }
 #pragma unroll
-        for (int j = 0; j < KL; ++j) {
-            uint32_t hi = max(top[j], v);
+        for (int j = 0; j < 8; ++j) {
+            const uint32_t hi = max(top[j], v);
             v = min(top[j], v);
             top[j] = hi;
         }
     }
-    thr = 0u;
+    // butterfly merge over the token's 8 lanes: max(mine[i], partner[7-i]) is the top 8 of the
+    // union as a bitonic sequence; three compare-exchange stages sort it again
 #pragma unroll
-    for (int j = 0; j < KL; ++j)
-        if (j == K - 1) thr = top[j];
-    above = 0;
+    for (int m = 1; m < 8; m <<= 1) {
+        uint32_t other[8];
 #pragma unroll
-    for (int j = 0; j < KL; ++j)
-        if (j < K && top[j] > thr) ++above;
-}
-
-// Stage 64 rows of logits (one per lane) into LDS, coalesced.  Row stride in LDS
-// is E+4 floats so that 16 lanes reading 16 bytes at the same column hit
-// distinct banks.
-__device__ __forceinline__ void stage_rows(float *lds, const float *logits, int64_t ld, int t0,
-                                           int T, int E) {
-    const int lane = threadIdx.x;
-    const int total = kWave * E;
-    for (int i = lane; i < total; i += kWave) {
-        int r = i / E, c = i - r * E;
-        int t = t0 + r;
-        lds[r * (E + 4) + c] = (t < T) ? logits[(int64_t)t * ld + c] : 0.0f;
+        for (int j = 0; j < 8; ++j) other[j] = __shfl_xor(top[j], m, 8);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) top[j] = max(top[j], other[7 - j]);
+        cmpx_desc(top[0], top[4]); cmpx_desc(top[1], top[5]); cmpx_desc(top[2], top[6]); cmpx_desc(top[3], top[7]);
+        cmpx_desc(top[0], top[2]); cmpx_desc(top[1], top[3]); cmpx_desc(top[4], top[6]); cmpx_desc(top[5], top[7]);
+        cmpx_desc(top[0], top[1]); cmpx_desc(top[2], top[3]); cmpx_desc(top[4], top[5]); cmpx_desc(top[6], top[7]);
     }
-    __syncthreads();
-}
-
-// Fast record: one lane per token, K <= 8, E <= 512.  blockDim = 64.
-template <typename IdxT>
-__global__ void __launch_bounds__(64)
-record_topk_lane_kernel(int T, int E, int K, const float *__restrict__ logits, int64_t ld,
-                        IdxT *__restrict__ idx, int64_t stride, int32_t *status) {
-    extern __shared__ float lds[];
-    const int t0 = blockIdx.x * kWave;
-    stage_rows(lds, logits, ld, t0, T, E);
-    const int t = t0 + (int)threadIdx.x;
-    const float *row = lds + threadIdx.x * (E + 4);
-    uint32_t thr;
-    int above;
-    bool bad;
-    lane_topk_threshold<8>(row, E, K, thr, above, bad);
-    if (t < T) {
-        int quota = K - above;  // how many keys equal to thr are taken, lowest ids first
-        int n = 0;
-        IdxT *out = idx + (int64_t)t * stride;
-        for (int e = 0; e < E && n < K; ++e) {
+    uint32_t thr = 0u;
+    int above = 0;
+#pragma unroll
+    for (int j = 0; j < 8; ++j)
+        if (j == K - 1) thr = top[j];
+#pragma unroll
+    for (int j = 0; j < 8; ++j)
+        if (j < K && top[j] > thr) ++above;
+    // second pass over the lane's own ids
+    int n_gt = 0, n_eq = 0;
+    for (int i = 0; i < EPL; ++i) {
+        const int e = e0 + i;
+        if (live && e < E) {
             bool nf;
-            uint32_t v = order_key(row[e], nf);
-            bool take = v > thr;
-            if (v == thr && quota > 0) {
-                take = true;
-                --quota;
+            const uint32_t v = order_key(row[e], nf);
+            n_gt += v > thr;
+            n_eq += v == thr;
+        }
+    }
+    // exclusive prefix over the 8 lanes (ids ascend with the lane)
+    int eq_before = n_eq, gt_before = n_gt;
+#pragma unroll
+    for (int o = 1; o < 8; o <<= 1) {
+        const int a = __shfl_up(eq_before, o, 8), b = __shfl_up(gt_before, o, 8);
+        if (sub >= o) {
+            eq_before += a;
+            gt_before += b;
+        }
+    }
+    eq_before -= n_eq;
+    gt_before -= n_gt;
+    const int quota = K - above;                                   // equal keys taken in all
+    const int eq_taken_before = min(eq_before, quota);
+    int my_quota = max(0, min(n_eq, quota - eq_before));           // equal keys this lane takes
+    int pos = gt_before + eq_taken_before;
+    if (live) {
+        IdxT *out = idx + (int64_t)t * stride;
+        for (int i = 0; i < EPL; ++i) {
+            const int e = e0 + i;
+            if (e < E) {
+                bool nf;
+                const uint32_t v = order_key(row[e], nf);
+                bool take = v > thr;
+                if (v == thr && my_quota > 0) {
+                    take = true;
+                    --my_quota;
+                }
+                if (take) out[pos++] = (IdxT)e;
             }
-            if (take) out[n++] = (IdxT)e;
         }
         if (bad && status) atomicOr(status, R3_DATA_NONFINITE);
     }
@@ -145,19 +174,14 @@ hipError_t launch_record_topk(int T, int E, int K, const float *logits, int64_t 
                               int idx_dtype, int64_t stride, int32_t *status, hipStream_t s) {
     ProfScope ps(PROF_RECORD, s);
     if (K <= 8 && E <= 512) {
-        size_t lds = (size_t)kWave * (E + 4) * sizeof(float);
-        int grid = (T + kWave - 1) / kWave;
-        if (idx_dtype == R3_IDX_U8) {
-            (void)hipFuncSetAttribute((const void *)record_topk_lane_kernel<uint8_t>,
-                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-            record_topk_lane_kernel<uint8_t><<<grid, 64, lds, s>>>(T, E, K, logits, ld, (uint8_t *)idx,
+        const int EPL = (E + 7) / 8;
+        const int grid = (T + 31) / 32;
+        if (idx_dtype == R3_IDX_U8)
+            record_topk_sub8_kernel<uint8_t><<<grid, 256, 0, s>>>(T, E, K, EPL, logits, ld, (uint8_t *)idx, stride,
+                                                                 status);
+        else
+            record_topk_sub8_kernel<uint16_t><<<grid, 256, 0, s>>>(T, E, K, EPL, logits, ld, (uint16_t *)idx,
                                                                   stride, status);
-        } else {
-            (void)hipFuncSetAttribute((const void *)record_topk_lane_kernel<uint16_t>,
-                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-            record_topk_lane_kernel<uint16_t><<<grid, 64, lds, s>>>(T, E, K, logits, ld,
-                                                                   (uint16_t *)idx, stride, status);
-        }
     } else {
         size_t lds = (size_t)4 * E * sizeof(uint32_t);
         int grid = (T + 3) / 4;
@@ -307,18 +331,30 @@ permute_hist_kernel(int T, int E, int K, const IdxT *__restrict__ idx, int64_t s
     if (bad && status) atomicOr(status, bad);
 }
 
-// One block of 1024 threads.  chunk_hist [nchunks,E] becomes the exclusive
-// running count over chunks (in place); counts/offsets are written.
+// One block of 1024 threads.  chunk_base [nchunks,E] receives the exclusive running count of
+// chunk_hist over chunks (separate arrays, so the loads of one expert's column pipeline);
+// counts/offsets are written.
 __global__ void __launch_bounds__(1024)
-permute_scan_kernel(int E, int nchunks, int32_t *__restrict__ chunk_hist, int32_t *__restrict__ counts,
-                    int32_t *__restrict__ offsets) {
+permute_scan_kernel(int E, int nchunks, const int32_t *__restrict__ chunk_hist, int32_t *__restrict__ chunk_base,
+                    int32_t *__restrict__ counts, int32_t *__restrict__ offsets) {
     __shared__ int32_t tot[kMaxE];
     __shared__ int32_t part[1024];
     for (int e = threadIdx.x; e < E; e += blockDim.x) {
         int32_t run = 0;
-        for (int c = 0; c < nchunks; ++c) {
-            int32_t h = chunk_hist[(int64_t)c * E + e];
-            chunk_hist[(int64_t)c * E + e] = run;
+        int c = 0;
+        for (; c + 8 <= nchunks; c += 8) {
+            int32_t h[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) h[u] = chunk_hist[(int64_t)(c + u) * E + e];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                chunk_base[(int64_t)(c + u) * E + e] = run;
+                run += h[u];
+            }
+        }
+        for (; c < nchunks; ++c) {
+            const int32_t h = chunk_hist[(int64_t)c * E + e];
+            chunk_base[(int64_t)c * E + e] = run;
             run += h;
         }
         tot[e] = run;
@@ -422,7 +458,7 @@ size_t permute_ws_bytes(int T, int E, int K) {
     int64_t S = (int64_t)T * K;
     int chunk = pick_chunk(S);
     int64_t nchunks = (S + chunk - 1) / chunk;
-    return align_up((size_t)nchunks * E * sizeof(int32_t), 256);
+    return 2 * align_up((size_t)nchunks * E * sizeof(int32_t), 256);  // histograms + running bases
 }
 
 hipError_t launch_permute(int T, int d, int E, int K, int elem_bytes, const void *x, const void *idx,
@@ -433,6 +469,7 @@ hipError_t launch_permute(int T, int d, int E, int K, int elem_bytes, const void
     const int chunk = pick_chunk(S);
     const int nchunks = (int)((S + chunk - 1) / chunk);
     int32_t *chunk_hist = (int32_t *)ws;
+    int32_t *chunk_base = (int32_t *)((char *)ws + align_up((size_t)nchunks * E * sizeof(int32_t), 256));
     const int grid = (nchunks + 3) / 4;
     const size_t lds = (size_t)4 * E * sizeof(int32_t);
     {
@@ -443,13 +480,13 @@ hipError_t launch_permute(int T, int d, int E, int K, int elem_bytes, const void
     else
         permute_hist_kernel<uint16_t><<<grid, 256, lds, s>>>(T, E, K, (const uint16_t *)idx, stride,
                                                             chunk, nchunks, chunk_hist, status);
-    permute_scan_kernel<<<1, 1024, 0, s>>>(E, nchunks, chunk_hist, counts, offsets);
+    permute_scan_kernel<<<1, 1024, 0, s>>>(E, nchunks, chunk_hist, chunk_base, counts, offsets);
     if (idx_dtype == R3_IDX_U8)
         permute_place_kernel<uint8_t><<<grid, 256, lds, s>>>(T, E, K, (const uint8_t *)idx, stride, chunk,
-                                                            nchunks, chunk_hist, offsets, inv_perm, perm);
+                                                            nchunks, chunk_base, offsets, inv_perm, perm);
     else
         permute_place_kernel<uint16_t><<<grid, 256, lds, s>>>(T, E, K, (const uint16_t *)idx, stride,
-                                                             chunk, nchunks, chunk_hist, offsets,
+                                                             chunk, nchunks, chunk_base, offsets,
                                                              inv_perm, perm);
     }
     if (Xp) {
