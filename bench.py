@@ -44,6 +44,20 @@ def kernel_work(sh, idx_bytes=1):
     }
 
 
+def gemm_bytes(sh, backward):
+    """Algorithmic HBM bytes of one launch of each expert GEMM (operands once in, results once out)."""
+    d, E, F = sh.d, sh.E, sh.F
+    S = sh.T * sh.K
+    W = E * d * F * 2
+    return {
+        "ffn1_swiglu": S * d * 2 + 2 * W + (3 if backward else 1) * S * F * 2,
+        "ffn2_down": S * F * 2 + W + S * d * 2,
+        "ffn_dh": S * d * 2 + W + 4 * S * F * 2,
+        "ffn_wgrad": (S * d + S * F) * 2 + 2 * W,          # f32 gradient out
+        "ffn_dxp": 2 * S * F * 2 + 2 * W + S * d * 2,
+    }
+
+
 def cpu_baseline(sh, tokens):
     """The oracle, as it stands, on a bounded sample of the same workload (forward + backward)."""
     import numpy as np
@@ -62,6 +76,21 @@ def cpu_baseline(sh, tokens):
                       % (tokens, sh.E, dt)}
 
 
+def stored_traffic(workload, kernel):
+    """HBM bytes per launch (fetch + write) of `kernel` from the committed counter summary of this workload
+    (two rocprofv3 --pmc runs of this script, scaled by the calibration copy), or None if there is none."""
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "profiles", "%s_hbm_traffic.md" % workload)
+    try:
+        for line in open(path):
+            f = [c.strip() for c in line.split("|")]
+            if len(f) >= 5 and f[1] == kernel:
+                return {"fetch_bytes": float(f[2]), "write_bytes": float(f[3]), "bytes": float(f[4]),
+                        "source": "profiles/%s_hbm_traffic.md" % workload}
+    except (OSError, ValueError):
+        pass
+    return None
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -70,6 +99,9 @@ def main():
     ap.add_argument("--workload", default="fwdbwd_16k")
     ap.add_argument("--cpu-tokens", type=int, default=4096, help="tokens of the oracle's timed sample (0 = skip)")
     ap.add_argument("--forward-only", action="store_true")
+    ap.add_argument("--calib-copy", action="store_true",
+                    help="after the timed region, run one plain 256 MiB copy kernel (reference point for "
+                         "hardware traffic counters collected around this command)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU only (no sharding, no collectives); use --gpus 1")
@@ -81,26 +113,46 @@ def main():
     sh = synth.CONFIGS[args.workload]
     dev = "cuda"
     torch.cuda.set_device(0)
-    bwd = not args.forward_only
+    bwd = not args.forward_only and args.workload in ("fwdbwd_16k", "zipf_64k")
+    L = sh.layers
     D = r3.desc(sh.T, sh.d, sh.E, sh.K, sh.F, sh.act)
     adt = r3.act_dtype(D)
-    t = {k: synth.draw(sh, k, dev).to(adt) for k in ("x", "Wr", "Wg", "Wu", "Wd")}
+    t = {k: synth.draw(sh, k, dev).to(adt) for k in ("x", "Wg", "Wu", "Wd")}
+    Wr = [synth.draw(sh, "Wr", dev, layer=l).to(adt) for l in range(L)]
     dy = synth.draw(sh, "dy", dev).to(adt) if bwd else None
     bias = synth.draw(sh, "bias", dev)
-    noise = synth.draw(sh, "noise", dev)
     buf = r3.LayerBuffers(D, backward=bwd)
-    idx = torch.zeros(sh.T, sh.K, dtype=r3.idx_torch_dtype(D), device=dev)
-    # inference logits = training logits + noise (the rollout engine's view), made once
+    record = torch.zeros(L, sh.T, sh.K, dtype=r3.idx_torch_dtype(D), device=dev)   # layer-major record
+    agree = torch.zeros(L, 2, dtype=torch.int64, device=dev)
+
+    def next_x(x, y):
+        """Harness glue between stacked layers: residual, then unit RMS per token (stands in for the rest
+        of a transformer block; the expert FFN is quadratic in its input, a bare residual chain overflows)."""
+        r = x.float() + y.float()
+        return (r * torch.rsqrt(r.pow(2).mean(dim=1, keepdim=True) + 1e-6)).to(adt)
+
+    # the rollout engine's view, made once: inference logits = training logits + noise, per layer
+    s_infer = []
     logits = torch.empty(sh.T, sh.E, dtype=torch.float32, device=dev)
-    r3.replay_gate(D, t["x"], t["Wr"], idx, buf.gates, bias=bias, logits_out=logits, ws=buf.ws_gate)
-    s_infer = logits + noise
-    del logits, noise
+    x = t["x"]
+    for l in range(L):
+        r3.replay_gate(D, x, Wr[l], record[l], buf.gates, bias=bias, logits_out=logits, ws=buf.ws_gate)
+        s_infer.append(logits + synth.draw(sh, "noise", dev, layer=l))
+        if L > 1:
+            r3.record_topk(D, s_infer[l], record[l], buf.status)
+            x = next_x(x, r3.forward(buf, x, Wr[l], record[l], t["Wg"], t["Wu"], t["Wd"], bias=bias))
+    del logits
 
     def step():
-        r3.record_topk(D, s_infer, idx, buf.status)
-        r3.forward(buf, t["x"], t["Wr"], idx, t["Wg"], t["Wu"], t["Wd"], bias=bias)
-        if bwd:
-            r3.backward(buf, dy, t["x"], t["Wr"], idx, t["Wg"], t["Wu"], t["Wd"])
+        x = t["x"]
+        for l in range(L):
+            r3.record_topk(D, s_infer[l], record[l], buf.status)
+            y = r3.forward(buf, x, Wr[l], record[l], t["Wg"], t["Wu"], t["Wd"], bias=bias,
+                           agree_out=agree[l] if L > 1 else None)
+            if bwd:
+                r3.backward(buf, dy, x, Wr[l], record[l], t["Wg"], t["Wu"], t["Wd"])
+            if L > 1:
+                x = next_x(x, y)
 
     for _ in range(args.warmup):
         step()
@@ -115,10 +167,17 @@ def main():
     prof = r3.profile_read()
     r3.profile_enable(False)
     assert int(buf.status.item()) == 0, "device status word set"
+    if args.calib_copy:
+        src = torch.zeros(256 << 20, dtype=torch.uint8, device=dev)
+        dst = torch.empty_like(src)
+        r3.profile_copy(dst, src)
+        torch.cuda.synchronize()
+        del src, dst
     counts = buf.counts.cpu()
 
     ms_per_step = wall * 1e3 / args.steps
     work = kernel_work(sh, 1 if D.idx == r3.IDX_U8 else 2)
+    gbytes = gemm_bytes(sh, bwd)
     kernels = {}
     for name, (ms, n) in prof.items():
         kind, amount = work[name]
@@ -129,24 +188,36 @@ def main():
             ach, peak, unit = amount / avg_ms * 1e-6, PEAK_HBM_GBS, "GB/s"
         kernels[name] = {"bound": kind, "avg_ms": round(avg_ms, 4), "launches_per_step": n // args.steps,
                          "achieved": round(ach, 1), "unit": unit, "frac": round(ach / peak, 4)}
+        if name in gbytes:   # the expert GEMMs sit near the ridge: their share of HBM peak as well
+            kernels[name]["hbm_GBps"] = round(gbytes[name] / avg_ms * 1e-6, 1)
+            kernels[name]["hbm_frac"] = round(gbytes[name] / avg_ms * 1e-6 / PEAK_HBM_GBS, 4)
     mfma = {k: v for k, v in kernels.items() if v["bound"] == "mfma" and k.startswith("ffn")}
     dom = max(mfma, key=lambda k: mfma[k]["avg_ms"] * mfma[k]["launches_per_step"]) if mfma else None
     roofline = None
     if dom:
         kd = kernels[dom]
         roofline = {"kernel": dom, "bound": "mfma", "achieved": kd["achieved"], "peak": PEAK_BF16_TFLOPS,
-                    "unit": "TFLOP/s", "frac": kd["frac"], "traffic": None}
+                    "unit": "TFLOP/s", "frac": kd["frac"], "traffic": stored_traffic(args.workload, dom)}
     out = {
         "metric": "tokens/sec for R3 replayed MoE layer fwd+bwd at 1 GPU",
-        "value": round(sh.T / (ms_per_step * 1e-3), 1), "unit": "tokens/s", "n_gpus": 1,
+        "value": round(sh.T * L / (ms_per_step * 1e-3), 1), "unit": "tokens/s", "n_gpus": 1,
         "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": sh.act,
         "data": "synthetic (seeded; shape of a 128-expert top-8 MoE layer)",
-        "config": {"workload": "%s: T=%d d=%d E=%d K=%d F=%d %s, record+forward%s" % (
-            args.workload, sh.T, sh.d, sh.E, sh.K, sh.F, sh.act, "+backward" if bwd else ""),
+        "config": {"workload": "%s: T=%d d=%d E=%d K=%d F=%d %s%s, record+forward%s" % (
+            args.workload, sh.T, sh.d, sh.E, sh.K, sh.F, sh.act, " x %d layers" % L if L > 1 else "",
+            "+backward" if bwd else ""),
             "rows_per_expert_min_mean_max": [int(counts.min()), float(counts.float().mean()), int(counts.max())]},
         "roofline": roofline, "kernels": kernels,
     }
+    if L > 1:   # value counts token-layers per second; agreement = tokens whose own top-K is the replayed set
+        agree.zero_()
+        step()
+        rate = (agree[:, 0].double() / sh.T).cpu()
+        out["config"]["agreement_rate_per_layer_min_mean_max"] = [round(float(rate.min()), 4),
+                                                                  round(float(rate.mean()), 4),
+                                                                  round(float(rate.max()), 4)]
+        out["metric"] = "token-layers/sec for R3 record+replay forward over a %d-layer stack at 1 GPU" % L
     if args.cpu_tokens > 0:
         del buf
         torch.cuda.empty_cache()

@@ -171,6 +171,15 @@ int r3_profile_tags(void);
 const char *r3_profile_name(int tag);
 int r3_profile_read(int tag, double *total_ms, int *launches);
 
+/*
+ * Measurement aid: a plain device-to-device copy kernel (`calib_copy_kernel`)
+ * of `bytes` bytes (a multiple of 16; dst and src 16-byte aligned device
+ * pointers, not overlapping).  It reads `bytes` and writes `bytes` of HBM and
+ * nothing else, so hardware traffic counters read for it give the factor that
+ * converts those counters to bytes for the other kernels of the same run.
+ */
+int r3_profile_copy(void *dst, const void *src, size_t bytes, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -87,8 +87,13 @@ struct DmaKC {
         const int w = threadIdx.x >> 6, lane = threadIdx.x & 63;
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
+#ifdef R3_LAB_KC128  // timing probe only (wrong data): 8 rows x 128 B per instruction
+            const int row = 8 * ((w & 3) + kLoaderWaves * i) + (lane >> 3);
+            const int c = (lane & 7);
+#else
             const int row = 16 * ((w & 3) + kLoaderWaves * i) + (lane >> 2);
             const int c = (lane & 3) ^ ((row >> 2) & 3);
+#endif
             voff[i] = row * ld_bytes + c * 16;
         }
     }

@@ -39,6 +39,13 @@ ProfScope::~ProfScope() {
     std::lock_guard<std::mutex> lk(g_mu);
     (void)hipEventRecord(g_tags[tag].stop[slot], s);
 }
+
+// 16 bytes per thread per iteration, grid-stride: the reference point for traffic counters
+__global__ void __launch_bounds__(256) calib_copy_kernel(uint4 *__restrict__ dst, const uint4 *__restrict__ src,
+                                                         size_t n) {
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x)
+        dst[i] = src[i];
+}
 }  // namespace r3
 
 using namespace r3;
@@ -71,5 +78,15 @@ int r3_profile_read(int tag, double *total_ms, int *launches) {
     *total_ms = sum;
     *launches = t.used;
     return R3_OK;
+}
+
+int r3_profile_copy(void *dst, const void *src, size_t bytes, void *stream) {
+    if (!dst || !src || (bytes & 15) || ((uintptr_t)dst & 15) || ((uintptr_t)src & 15)) return R3_ERR_INVALID_ARG;
+    if (bytes == 0) return R3_OK;
+    size_t n = bytes / 16;
+    size_t blocks = (n + 255) / 256;
+    if (blocks > 256 * 32) blocks = 256 * 32;
+    calib_copy_kernel<<<dim3((unsigned)blocks), dim3(256), 0, (hipStream_t)stream>>>((uint4 *)dst, (const uint4 *)src, n);
+    return hipGetLastError() == hipSuccess ? R3_OK : R3_ERR_HIP;
 }
 }

@@ -20,7 +20,7 @@ _STATUS = {1: "R3_ERR_INVALID_ARG", 2: "R3_ERR_UNSUPPORTED", 3: "R3_ERR_WORKSPAC
 
 EXPORTS = ["r3_version", "r3_workspace_bytes", "r3_record_topk", "r3_replay_gate", "r3_permute",
            "r3_grouped_ffn", "r3_combine", "r3_moe_backward", "r3_profile_enable", "r3_profile_tags",
-           "r3_profile_name", "r3_profile_read"]
+           "r3_profile_name", "r3_profile_read", "r3_profile_copy"]
 
 
 class LayerDesc(C.Structure):
@@ -176,6 +176,13 @@ def backward(buf, dy, x, W_r, idx, W_gate, W_up, W_down, dbias=None, accumulate=
 
 def profile_enable(on=True):
     lib().r3_profile_enable(C.c_int(1 if on else 0))
+
+
+def profile_copy(dst, src):
+    """Plain copy of src into dst by the library's calibration kernel."""
+    assert dst.numel() * dst.element_size() == src.numel() * src.element_size()
+    _check(lib().r3_profile_copy(_p(dst), _p(src), C.c_size_t(src.numel() * src.element_size()), _stream()),
+           "r3_profile_copy")
 
 
 def profile_read():

@@ -1,0 +1,211 @@
+"""The benchmark configurations that are not the timed one, as parity cases at their full sizes:
+config 2 (T=4096 forward), config 4 (48-layer record+replay stack, T=131072, agreement per layer) and
+config 5 (Zipf-skewed load, T=65536, forward + backward).  Integer results are compared in full; floating
+point on samples the oracle can afford, using that every token's output depends on that token alone and
+that an upstream gradient which is zero outside a sample leaves only the sample in every weight gradient."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import sparse
+from paper_2510_11370_amd import r3, synth
+from util import Case, assert_close, assert_gates_close, host
+
+pytestmark = pytest.mark.gpu
+
+
+def _record_on_gpu(D, s_infer_np):
+    rec = torch.zeros(D.T, D.K, dtype=r3.idx_torch_dtype(D), device="cuda")
+    status = torch.zeros(1, dtype=torch.int32, device="cuda")
+    r3.record_topk(D, torch.from_numpy(s_infer_np).cuda(), rec, status)
+    torch.cuda.synchronize()
+    assert int(status.item()) == 0
+    return rec
+
+
+def _check_permutation(buf, idx, E):
+    counts, offsets, inv_perm, perm = sparse.permute(idx, E)
+    assert np.array_equal(buf.counts.cpu().numpy(), counts)
+    assert np.array_equal(buf.offsets.cpu().numpy(), offsets)
+    assert np.array_equal(buf.inv_perm.cpu().numpy(), inv_perm)
+    assert np.array_equal(buf.perm.cpu().numpy(), perm)
+    return counts, offsets, inv_perm, perm
+
+
+# ------------------------------------------------------------------ config 2: single layer forward, T=4096
+def test_config2_forward_4k_every_output():
+    c = Case(synth.CONFIGS["fwd_4k"], backward=False)
+    sh, D, n = c.shape, c.D, c.np
+    rec = _record_on_gpu(D, c.s_infer)
+    assert np.array_equal(rec.cpu().numpy().astype(np.int32), c.idx)
+    differs = int((sparse.topk_mask(c.s, sh.K) != c.idx).any(axis=1).sum())
+    print("config 2: %d of %d tokens replay a set that differs from the training top-%d" % (differs, sh.T, sh.K))
+    assert 0 < differs < sh.T // 4
+    buf = r3.LayerBuffers(D, backward=False)
+    r3.forward(buf, c.t["x"], c.t["Wr"], rec, c.t["Wg"], c.t["Wu"], c.t["Wd"])
+    torch.cuda.synchronize()
+    assert int(buf.status.item()) == 0
+    _check_permutation(buf, c.idx, sh.E)
+    ref = sparse.forward(n["x"], n["Wr"], c.idx, n["Wg"], n["Wu"], n["Wd"])   # all 4096 tokens
+    assert_gates_close(buf.gates.cpu().numpy(), ref["g"])
+    assert np.array_equal(host(buf.Xp), ref["Xp"])
+    assert_close(host(buf.H), ref["h"], "H", c.rel)
+    assert_close(host(buf.Yp), ref["o"], "Yp", c.rel)
+    assert_close(host(buf.y), ref["y"], "y", c.rel)
+
+
+# ------------------------------------------------------------------ config 5: Zipf-skewed load, T=65536
+@pytest.fixture(scope="module")
+def zipf():
+    c = Case(synth.CONFIGS["zipf_64k"], backward=True)
+    sh, D = c.shape, c.D
+    rec = _record_on_gpu(D, c.s_infer)
+    buf = r3.LayerBuffers(D, backward=True)
+    r3.forward(buf, c.t["x"], c.t["Wr"], rec, c.t["Wg"], c.t["Wu"], c.t["Wd"], bias=c.t["bias"])
+    torch.cuda.synchronize()
+    assert int(buf.status.item()) == 0
+    return c, rec, buf
+
+
+def test_config5_record_permutation_gates(zipf):
+    c, rec, buf = zipf
+    sh = c.shape
+    assert np.array_equal(rec.cpu().numpy().astype(np.int32), c.idx)
+    counts, _, _, _ = _check_permutation(buf, c.idx, sh.E)
+    srt = np.sort(counts)[::-1]
+    print("config 5 load: max %d (T=%d), top-8 %s, median %d, min %d, empty experts %d" % (
+        srt[0], sh.T, srt[:8].tolist(), int(np.median(counts)), srt[-1], int((counts == 0).sum())))
+    assert srt[0] > 8 * srt[len(srt) // 2]          # the bias really skews the load
+    assert_gates_close(buf.gates.cpu().numpy(), sparse.replay_gate(c.s, c.idx))
+
+
+def _zipf_sample(c, counts, n_random=160, n_rare=48):
+    """Random tokens plus tokens routed to the least-loaded non-empty expert."""
+    rng = np.random.default_rng(5)
+    tok = set(rng.choice(c.shape.T, n_random, replace=False).tolist())
+    rare = int(np.argmin(np.where(counts > 0, counts, np.iinfo(np.int32).max)))
+    has = np.nonzero((c.idx == rare).any(axis=1))[0]
+    tok.update(has[:n_rare].tolist())
+    return np.array(sorted(tok)), rare
+
+
+def test_config5_forward_and_backward_on_samples(zipf):
+    c, rec, buf = zipf
+    sh, n = c.shape, c.np
+    counts = buf.counts.cpu().numpy()
+    tok, rare = _zipf_sample(c, counts)
+    sel = torch.from_numpy(tok).cuda()
+    ref = sparse.forward(n["x"][tok], n["Wr"], c.idx[tok], n["Wg"], n["Wu"], n["Wd"], bias=n["bias"])
+    assert_close(host(buf.y[sel]), ref["y"], "y[sample]", c.rel)
+    # upstream gradient only on the sample: the oracle then needs only the sample for every weight gradient
+    dy = torch.zeros_like(c.t["dy"])
+    dy[sel] = c.t["dy"][sel]
+    dbias = torch.zeros(sh.E, dtype=torch.float32, device="cuda")
+    r3.backward(buf, dy, c.t["x"], c.t["Wr"], rec, c.t["Wg"], c.t["Wu"], c.t["Wd"], dbias=dbias)
+    torch.cuda.synchronize()
+    bwd = sparse.backward(n["dy"][tok], n["x"][tok], n["Wr"], c.idx[tok], n["Wg"], n["Wu"], n["Wd"], ref,
+                          want_dbias=True)
+    assert_close(host(buf.dx[sel]), bwd["dx"], "dx[sample]", c.rel)
+    rest = np.setdiff1d(np.arange(sh.T), tok)[:: max(1, sh.T // 4096)]
+    assert not buf.dx[torch.from_numpy(rest).cuda()].any()
+    assert_close(buf.dW_r.cpu().numpy(), bwd["dWr"], "dW_r", c.rel)
+    assert_close(dbias.cpu().numpy(), bwd["dbias"], "dbias", c.rel)
+    touched = np.unique(c.idx[tok])
+    rng = np.random.default_rng(6)
+    check = {int(np.argmax(counts)), rare, *rng.choice(touched, 2, replace=False).tolist()}
+    empty = np.nonzero(counts == 0)[0]
+    if len(empty):
+        check.add(int(empty[0]))
+    for e in sorted(check):
+        for got, want, name in ((buf.dW_gate, bwd["dWg"], "dW_gate"), (buf.dW_up, bwd["dWu"], "dW_up"),
+                                (buf.dW_down, bwd["dWd"], "dW_down")):
+            g = got[e].cpu().numpy()
+            if not want[e].any():
+                assert not g.any(), "%s[%d] must be exactly zero" % (name, e)
+            else:
+                assert_close(g, want[e], "%s[%d] (%d rows)" % (name, e, counts[e]), c.rel)
+
+
+def test_config5_down_projection_gradient_dense_dy(zipf):
+    """Full upstream gradient: every expert's dW_down (segments of 0 to T rows) against the defining sum
+    u^T dW_down[e] v = sum_rows (H[r].u)(g_r dy[t_r].v), evaluated in f64 from the layer's own H and gates."""
+    c, rec, buf = zipf
+    sh = c.shape
+    r3.backward(buf, c.t["dy"], c.t["x"], c.t["Wr"], rec, c.t["Wg"], c.t["Wu"], c.t["Wd"])
+    torch.cuda.synchronize()
+    gen = torch.Generator(device="cuda").manual_seed(11)
+    u = torch.randn(sh.F, generator=gen, device="cuda", dtype=torch.float64)
+    v = torch.randn(sh.d, generator=gen, device="cuda", dtype=torch.float64)
+    slot = buf.perm.long()
+    hu = buf.H.double() @ u                                             # [S]
+    dyv = (c.t["dy"].double() @ v)[slot // sh.K]                        # [S]
+    g = buf.gates.double().reshape(-1)[slot]
+    per_row = hu * g * dyv
+    seg = torch.repeat_interleave(torch.arange(sh.E, device="cuda"), buf.counts.long())
+    zero = torch.zeros(sh.E, dtype=torch.float64, device="cuda")
+    want = zero.clone().index_add_(0, seg, per_row)
+    l2 = zero.clone().index_add_(0, seg, per_row * per_row).sqrt()
+    l1 = zero.clone().index_add_(0, seg, per_row.abs())
+    got = torch.einsum("f,efd,d->e", u, buf.dW_down.double(), v)
+    # the kernel rounds g*dy to bf16 (2^-9 relative, independent per element) before the contraction and sums
+    # in f32: the error of a segment's sum grows like 2^-9 * l2, so a dropped 256-row tile of even the
+    # 65536-row segment (16 typical terms) stands far outside the bar
+    err = (got - want).abs()
+    bar = 6 * 2.0 ** -9 * l2 + 1e-5 * l1 + 1e-12
+    assert bool((err <= bar).all()), (err / bar).max().item()
+
+
+# ------------------------------------------------------------------ config 4: 48-layer record + replay stack
+CHECK_LAYERS = (0, 1, 23, 47)
+
+
+def test_config4_stack_record_replay_agreement():
+    """x_{l+1} = norm(x_l + y_l) on the GPU; per-layer router weights and noise; one shared set of expert weights.
+    Every layer: record and permutation bit-exact on all tokens, agreement counters equal to the oracle's on
+    the same logits bytes.  Checked layers: gates and y of a 2048-token sample, the oracle fed the GPU's
+    own x_l bytes, so that earlier layers' rounding cannot flip this layer's routing."""
+    sh = synth.CONFIGS["stack48_128k"]
+    L, T, K, E = sh.layers, sh.T, sh.K, sh.E
+    D = r3.desc(T, sh.d, E, K, sh.F, sh.act)
+    dev = "cuda"
+    W = {k: synth.draw(sh, k, dev).to(torch.bfloat16) for k in ("Wg", "Wu", "Wd")}
+    Wn = {k: v.float().cpu().numpy() for k, v in W.items()}
+    x = synth.draw(sh, "x", dev).to(torch.bfloat16)
+    record = torch.zeros(L, T, K, dtype=torch.uint8, device=dev)          # layer-major, 48 MiB
+    buf = r3.LayerBuffers(D, backward=False)
+    logits = torch.empty(T, E, dtype=torch.float32, device=dev)
+    agree = torch.zeros(L, 2, dtype=torch.int64, device=dev)
+    status = torch.zeros(1, dtype=torch.int32, device=dev)
+    sample = np.sort(np.random.default_rng(4).choice(T, 2048, replace=False))
+    sel = torch.from_numpy(sample).cuda()
+    rates = []
+    for l in range(L):
+        Wr = synth.draw(sh, "Wr", dev, layer=l).to(torch.bfloat16)
+        noise = synth.draw(sh, "noise", dev, layer=l)
+        # rollout side: inference logits = this layer's training logits + noise; record their top-K
+        r3.replay_gate(D, x, Wr, record[l], buf.gates, logits_out=logits, ws=buf.ws_gate)
+        s_infer = logits + noise
+        r3.record_topk(D, s_infer, record[l], status)
+        # training side: replay the record
+        r3.forward(buf, x, Wr, record[l], W["Wg"], W["Wu"], W["Wd"], logits_out=logits, agree_out=agree[l])
+        torch.cuda.synchronize()
+        assert int(status.item()) == 0 and int(buf.status.item()) == 0, l
+        idx = sparse.topk_mask(s_infer.cpu().numpy(), K)
+        assert np.array_equal(record[l].cpu().numpy().astype(np.int32), idx), "record of layer %d" % l
+        _check_permutation(buf, idx, E)
+        own = sparse.topk_mask(logits.cpu().numpy(), K)
+        same, shared = sparse.agreement(own, idx)
+        assert (int(agree[l, 0]), int(agree[l, 1])) == (same, shared), "agreement counters of layer %d" % l
+        rates.append(same / T)
+        if l in CHECK_LAYERS:
+            xs = x[sel].float().cpu().numpy()
+            ref = sparse.forward(xs, Wr.float().cpu().numpy(), idx[sample], Wn["Wg"], Wn["Wu"], Wn["Wd"])
+            assert_gates_close(buf.gates[sel].cpu().numpy(), ref["g"])
+            assert_close(host(buf.y[sel]), ref["y"], "y[sample] of layer %d" % l, 1e-2)
+        # residual, then unit RMS per token (the stand-in for a block's pre-MoE norm: SwiGLU is quadratic in
+        # its input, so a bare residual chain overflows after a few dozen layers)
+        r = x.float() + buf.y.float()
+        x = (r * torch.rsqrt(r.pow(2).mean(dim=1, keepdim=True) + 1e-6)).to(torch.bfloat16)
+    print("config 4: per-layer fraction of tokens whose training top-%d equals the replayed set: "
+          "min %.4f mean %.4f max %.4f" % (K, min(rates), sum(rates) / L, max(rates)))
+    assert 0.5 < min(rates) and max(rates) < 1.0
