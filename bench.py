@@ -197,7 +197,12 @@ def main():
     if dom:
         kd = kernels[dom]
         roofline = {"kernel": dom, "bound": "mfma", "achieved": kd["achieved"], "peak": PEAK_BF16_TFLOPS,
-                    "unit": "TFLOP/s", "frac": kd["frac"], "traffic": stored_traffic(args.workload, dom)}
+                    "unit": "TFLOP/s", "frac": kd["frac"], "traffic": None}
+        tr = stored_traffic(args.workload, dom)
+        if tr:   # HBM bytes per launch (fetch + write) from the committed counter summary
+            roofline.update(traffic=tr["bytes"], traffic_fetch_bytes=tr["fetch_bytes"],
+                            traffic_write_bytes=tr["write_bytes"], traffic_source=tr["source"],
+                            algorithmic_hbm_bytes=gbytes.get(dom))
     out = {
         "metric": "tokens/sec for R3 replayed MoE layer fwd+bwd at 1 GPU",
         "value": round(sh.T * L / (ms_per_step * 1e-3), 1), "unit": "tokens/s", "n_gpus": 1,
