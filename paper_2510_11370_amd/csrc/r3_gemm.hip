@@ -12,36 +12,15 @@
 
 namespace r3 {
 
-// Per-work-group time stamps, compiled in only for the kernel lab (-DR3_TIMELINE).
-#ifdef R3_TIMELINE
-__device__ long long *r3_timeline_buf = nullptr;
-#define R3_TL_DECL long long tl_[6] = {0, 0, 0, 0, 0, 0}
-#define R3_TL(i)                                  \
-    do {                                          \
-        tl_[i] = clock64();                       \
-        if ((i) == 0) tl_[4] = wall_clock64();    \
-    } while (0)
-#define R3_TL_FLUSH()                                                                   \
-    do {                                                                                \
-        __builtin_amdgcn_s_waitcnt(0);                                                  \
-        tl_[3] = clock64();                                                             \
-        tl_[5] = wall_clock64();                                                        \
-        if (r3_timeline_buf && threadIdx.x == 0) {                                      \
-            for (int i_ = 0; i_ < 6; ++i_) r3_timeline_buf[blockIdx.x * 8 + i_] = tl_[i_]; \
-            r3_timeline_buf[blockIdx.x * 8 + 6] = __builtin_amdgcn_s_getreg((4 << 0) | (0 << 6) | (31 << 11));  \
-            r3_timeline_buf[blockIdx.x * 8 + 7] = __builtin_amdgcn_s_getreg((20 << 0) | (0 << 6) | (31 << 11)); \
-        }                                                                               \
-    } while (0)
-#else
-#define R3_TL_DECL
-#define R3_TL(i)
-#define R3_TL_FLUSH()
-#endif
-
 // ---------------------------------------------------------------------------
-// Row-tile table: tiles[0] = number of tiles, then (expert, row0) pairs from
-// tiles[2].  One block; experts in ascending order, rows ascending.
+// Row-tile table: tiles[0] = number of tiles, tiles[2 .. 2+64) = the tile counters of up to
+// eight persistent launches (8 XCDs each, zeroed here), then (expert, row0) pairs from
+// tiles[kTileHdr].  One block; experts in ascending order, rows ascending.
 // ---------------------------------------------------------------------------
+constexpr int kTileHdr = 2 + 64;
+__device__ __forceinline__ int *tile_counters(const int32_t *tiles, int launch) {
+    return const_cast<int *>(tiles) + 2 + 8 * launch;
+}
 __global__ void __launch_bounds__(1024)
 build_row_tiles_kernel(int E, int BQ, const int32_t *__restrict__ offsets, int32_t *__restrict__ tiles) {
     __shared__ int32_t start[kMaxE + 1];
@@ -55,18 +34,34 @@ build_row_tiles_kernel(int E, int BQ, const int32_t *__restrict__ offsets, int32
         tiles[0] = run;
         tiles[1] = 0;
     }
+    if (threadIdx.x < 64) tiles[2 + threadIdx.x] = 0;
     __syncthreads();
     for (int e = threadIdx.x; e < E; e += blockDim.x) {
         const int n = start[e + 1] - start[e];
         for (int i = 0; i < n; ++i) {
-            tiles[2 + 2 * (start[e] + i)] = e;
-            tiles[3 + 2 * (start[e] + i)] = offsets[e] + i * BQ;
+            tiles[kTileHdr + 2 * (start[e] + i)] = e;
+            tiles[kTileHdr + 1 + 2 * (start[e] + i)] = offsets[e] + i * BQ;
         }
     }
 }
 
 static inline int max_row_tiles(int64_t S, int E, int BQ) { return (int)(S / BQ) + E; }
 static inline int grid_for(int64_t tiles) { return (int)((tiles + 7) / 8 * 8); }
+
+// Grid of a persistent launch: one work-group per compute unit of the current device (a
+// multiple of 8, so that every XCD gets the same number), fewer when there are fewer tiles.
+static int persistent_grid(int64_t max_tiles) {
+    static int cus[64] = {0};
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) dev = 0;
+    if (cus[dev] == 0) {
+        int n = 0;
+        if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n < 8) n = 256;
+        cus[dev] = n / 8 * 8;
+    }
+    const int64_t g = grid_for(max_tiles);
+    return (int)(g < cus[dev] ? g : cus[dev]);
+}
 
 __device__ __forceinline__ uint2 pack4(float a, float b, float c, float d) {
     return make_uint2(pack_bf16x2(a, b), pack_bf16x2(c, d));
@@ -87,19 +82,19 @@ __device__ __forceinline__ void unpack4(uint2 v, float *f) {
 __global__ void __launch_bounds__(kThreads2, 2)
 ffn1_kernel(int S, int d, int F, const bf16_t *__restrict__ Xp, const int32_t *__restrict__ offsets,
             const int32_t *__restrict__ tiles, const bf16_t *__restrict__ Wg, const bf16_t *__restrict__ Wu,
-            bf16_t *__restrict__ H, bf16_t *__restrict__ A, bf16_t *__restrict__ B) {
+            bf16_t *__restrict__ H, bf16_t *__restrict__ A, bf16_t *__restrict__ B, int launch) {
     __shared__ __attribute__((aligned(1024))) char s0[kStageBytes];
     __shared__ __attribute__((aligned(1024))) char s1[kStageBytes];
     __shared__ __attribute__((aligned(1024))) char s2[kStageBytes];
     __shared__ __attribute__((aligned(1024))) char s3[kStageBytes];
+    __shared__ int mailbox[2];
     constexpr int BF = 128;  // features per tile
-    R3_TL_DECL;
-    R3_TL(0);
     const int npt = F / BF;
-    const int id = xcd_tile_id(tiles[0] * npt);
-    if (id < 0) return;
+    TileLoop tl(tiles[0] * npt, tile_counters(tiles, launch));
+    for (int slot = tl.first(); tl.valid(slot); slot = tl.finish(mailbox)) {
+    const int id = tl.id(slot);
     const int tile = id / npt, pt = id - tile * npt;
-    const int e = tiles[2 + 2 * tile], row0 = tiles[3 + 2 * tile];
+    const int e = tiles[kTileHdr + 2 * tile], row0 = tiles[kTileHdr + 1 + 2 * tile];
     const int row_end = offsets[e + 1];
     const int f0 = pt * BF;
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
@@ -117,9 +112,8 @@ ffn1_kernel(int S, int d, int F, const bf16_t *__restrict__ Xp, const int32_t *_
 
     Acc2 acc;
     zero_acc2(acc);
-    R3_TL(1);
     mfma_mainloop2(acc, d / kBK2, P, Q, s0, s1, s2, s3, row_end - row0 > 128);
-    R3_TL(2);
+    tl.prefetch();
 
     // per wave: 64 rows x 64 features of H (and A, B), 32 rows at a time through LDS
     RowStage<128> st{wave_patch(s0, s1, s2, s3)};
@@ -148,7 +142,7 @@ ffn1_kernel(int S, int d, int F, const bf16_t *__restrict__ Xp, const int32_t *_
             st.flush((char *)dst + o, (int64_t)F * 2, valid);
         }
     }
-    R3_TL_FLUSH();
+    }
 }
 
 // ---------------------------------------------------------------------------
@@ -165,18 +159,20 @@ __global__ void __launch_bounds__(kThreads2, 2)
 rowgemm_kernel(int S, int d, int F, const bf16_t *__restrict__ Q0, const bf16_t *__restrict__ Q1,
                const int32_t *__restrict__ offsets, const int32_t *__restrict__ tiles,
                const bf16_t *__restrict__ W0, const bf16_t *__restrict__ W1, const bf16_t *__restrict__ A,
-               const bf16_t *__restrict__ B, bf16_t *__restrict__ out0, bf16_t *__restrict__ out1) {
+               const bf16_t *__restrict__ B, bf16_t *__restrict__ out0, bf16_t *__restrict__ out1, int launch) {
     __shared__ __attribute__((aligned(1024))) char s0[kStageBytes];
     __shared__ __attribute__((aligned(1024))) char s1[kStageBytes];
     __shared__ __attribute__((aligned(1024))) char s2[kStageBytes];
     __shared__ __attribute__((aligned(1024))) char s3[kStageBytes];
+    __shared__ int mailbox[2];
     const int NOUT = (MODE == 1) ? F : d;  // width of the output
     const int KQ = (MODE == 1) ? d : F;    // width of the Q source rows
     const int npt = NOUT / kTile;
-    const int id = xcd_tile_id(tiles[0] * npt);
-    if (id < 0) return;
+    TileLoop tl(tiles[0] * npt, tile_counters(tiles, launch));
+    for (int slot = tl.first(); tl.valid(slot); slot = tl.finish(mailbox)) {
+    const int id = tl.id(slot);
     const int tile = id / npt, pt = id - tile * npt;
-    const int e = tiles[2 + 2 * tile], row0 = tiles[3 + 2 * tile];
+    const int e = tiles[kTileHdr + 2 * tile], row0 = tiles[kTileHdr + 1 + 2 * tile];
     const int row_end = offsets[e + 1];
     const int p0 = pt * kTile;
     const int wave = threadIdx.x >> 6;
@@ -218,6 +214,7 @@ rowgemm_kernel(int S, int d, int F, const bf16_t *__restrict__ Q0, const bf16_t 
         P.init(F * 2, 128 * wp);
         mfma_mainloop2(acc, 2 * (F / kBK2), P, Q, s0, s1, s2, s3, row_end - row0 > 128);
     }
+    tl.prefetch();
 
     // per wave: 64 rows x 128 features, 32 rows at a time through LDS
     const int lane = threadIdx.x & 63;
@@ -271,6 +268,7 @@ rowgemm_kernel(int S, int d, int F, const bf16_t *__restrict__ Q0, const bf16_t 
             st.flush((char *)out0 + o, (int64_t)NOUT * 2, valid);
         }
     }
+    }
 }
 
 // ---------------------------------------------------------------------------
@@ -280,14 +278,16 @@ rowgemm_kernel(int S, int d, int F, const bf16_t *__restrict__ Q0, const bf16_t 
 // ---------------------------------------------------------------------------
 __global__ void __launch_bounds__(kThreads2, 2)
 wgrad_kernel(int E, int NQd, int NPd, const bf16_t *__restrict__ Qs, const bf16_t *__restrict__ Ps,
-             const int32_t *__restrict__ offsets, float *__restrict__ out, int accumulate) {
+             const int32_t *__restrict__ offsets, float *__restrict__ out, int accumulate, int *ctr) {
     __shared__ __attribute__((aligned(1024))) char s0[kStageBytes];
     __shared__ __attribute__((aligned(1024))) char s1[kStageBytes];
     __shared__ __attribute__((aligned(1024))) char s2[kStageBytes];
     __shared__ __attribute__((aligned(1024))) char s3[kStageBytes];
+    __shared__ int mailbox[2];
     const int nqt = NQd / kTile, npt = NPd / kTile;
-    const int id = xcd_tile_id(E * nqt * npt);
-    if (id < 0) return;
+    TileLoop tl(E * nqt * npt, ctr);
+    for (int slot = tl.first(); tl.valid(slot); slot = tl.finish(mailbox)) {
+    const int id = tl.id(slot);
     const int e = id / (nqt * npt);
     const int rem = id - e * nqt * npt;
     const int qt = rem / npt, pt = rem - qt * npt;
@@ -311,6 +311,7 @@ wgrad_kernel(int E, int NQd, int NPd, const bf16_t *__restrict__ Qs, const bf16_
     Acc2 acc;
     zero_acc2(acc);
     mfma_mainloop2(acc, (r1 - r0 + kBK2 - 1) / kBK2, P, Q, s0, s1, s2, s3);
+    tl.prefetch();
 
     // per wave: 64 rows (q) x 128 features (p) of f32, as 32-row x 64-feature blocks through LDS
     const int lane = threadIdx.x & 63;
@@ -333,6 +334,7 @@ wgrad_kernel(int E, int NQd, int NPd, const bf16_t *__restrict__ Qs, const bf16_
             const int64_t off = ((int64_t)(q0 + wq * 64 + tq * 32) * NPd + p0 + wp * 128 + half * 64) * 4;
             st.flush_f32(o + off, (int64_t)NPd * 4, 32, accumulate);
         }
+    }
 }
 
 // ---------------------------------------------------------------------------
@@ -434,7 +436,7 @@ bool mfma_ffn_supported(int d, int F) { return d % 256 == 0 && F % 256 == 0 && d
 bool mfma_router_supported(int d, int E) { return E % 128 == 0 && d % 128 == 0; }  // 2E % 128 for ds
 
 size_t mfma_tiles_bytes(int64_t S, int E) {
-    return align_up((size_t)(2 + 2 * (size_t)max_row_tiles(S, E, kTile)) * sizeof(int32_t), 256);
+    return align_up((size_t)(kTileHdr + 2 * (size_t)max_row_tiles(S, E, kTile)) * sizeof(int32_t), 256);
 }
 
 template <class K>
@@ -453,14 +455,14 @@ hipError_t mfma_ffn_forward(int64_t S, int d, int E, int F, const void *Xp, cons
     const int mt = max_row_tiles(S, E, kTile);
     {
         ProfScope ps(PROF_FFN1, s);
-        ffn1_kernel<<<grid_for((int64_t)mt * (F / 128)), kThreads2, 0, s>>>(
+        ffn1_kernel<<<persistent_grid((int64_t)mt * (F / 128)), kThreads2, 0, s>>>(
             (int)S, d, F, (const bf16_t *)Xp, offsets, tiles, (const bf16_t *)Wg, (const bf16_t *)Wu,
-            (bf16_t *)H, (bf16_t *)A, (bf16_t *)B);
+            (bf16_t *)H, (bf16_t *)A, (bf16_t *)B, 0);
     }
     ProfScope ps(PROF_FFN2, s);
-    rowgemm_kernel<0><<<grid_for((int64_t)mt * (d / kTile)), kThreads2, 0, s>>>(
+    rowgemm_kernel<0><<<persistent_grid((int64_t)mt * (d / kTile)), kThreads2, 0, s>>>(
         (int)S, d, F, (const bf16_t *)H, nullptr, offsets, tiles, (const bf16_t *)Wd, nullptr, nullptr, nullptr,
-        (bf16_t *)Yp, nullptr);
+        (bf16_t *)Yp, nullptr, 1);
     return hipGetLastError();
 }
 
@@ -469,9 +471,9 @@ hipError_t mfma_ffn_dh(int64_t S, int d, int E, int F, const void *dYp, const in
                        hipStream_t s) {
     const int mt = max_row_tiles(S, E, kTile);
     ProfScope ps(PROF_DH, s);
-    rowgemm_kernel<1><<<grid_for((int64_t)mt * (F / kTile)), kThreads2, 0, s>>>(
+    rowgemm_kernel<1><<<persistent_grid((int64_t)mt * (F / kTile)), kThreads2, 0, s>>>(
         (int)S, d, F, (const bf16_t *)dYp, nullptr, offsets, tiles, (const bf16_t *)Wd, nullptr,
-        (const bf16_t *)A, (const bf16_t *)B, (bf16_t *)dA, (bf16_t *)dB);
+        (const bf16_t *)A, (const bf16_t *)B, (bf16_t *)dA, (bf16_t *)dB, 0);
     return hipGetLastError();
 }
 
@@ -479,18 +481,19 @@ hipError_t mfma_ffn_dxp(int64_t S, int d, int E, int F, const void *dA, const vo
                         const int32_t *tiles, const void *Wg, const void *Wu, void *dXp, hipStream_t s) {
     const int mt = max_row_tiles(S, E, kTile);
     ProfScope ps(PROF_DXP, s);
-    rowgemm_kernel<2><<<grid_for((int64_t)mt * (d / kTile)), kThreads2, 0, s>>>(
+    rowgemm_kernel<2><<<persistent_grid((int64_t)mt * (d / kTile)), kThreads2, 0, s>>>(
         (int)S, d, F, (const bf16_t *)dA, (const bf16_t *)dB, offsets, tiles, (const bf16_t *)Wg,
-        (const bf16_t *)Wu, nullptr, nullptr, (bf16_t *)dXp, nullptr);
+        (const bf16_t *)Wu, nullptr, nullptr, (bf16_t *)dXp, nullptr, 1);
     return hipGetLastError();
 }
 
 hipError_t mfma_wgrad(int E, int NQd, int NPd, const void *Qs, const void *Ps, const int32_t *offsets,
-                      float *out, int accumulate, hipStream_t s) {
-    const int64_t tiles = (int64_t)E * (NQd / kTile) * (NPd / kTile);
+                      const int32_t *tiles, int launch, float *out, int accumulate, hipStream_t s) {
+    const int64_t ntiles = (int64_t)E * (NQd / kTile) * (NPd / kTile);
     ProfScope ps(PROF_WGRAD, s);
-    wgrad_kernel<<<grid_for(tiles), kThreads2, 0, s>>>(E, NQd, NPd, (const bf16_t *)Qs, (const bf16_t *)Ps,
-                                                      offsets, out, accumulate);
+    wgrad_kernel<<<persistent_grid(ntiles), kThreads2, 0, s>>>(E, NQd, NPd, (const bf16_t *)Qs, (const bf16_t *)Ps,
+                                                              offsets, out, accumulate,
+                                                              const_cast<int *>(tiles) + 2 + 8 * launch);
     return hipGetLastError();
 }
 

@@ -71,8 +71,10 @@ hipError_t mfma_ffn_dh(int64_t S, int d, int E, int F, const void *dYp, const in
                        hipStream_t s);
 hipError_t mfma_ffn_dxp(int64_t S, int d, int E, int F, const void *dA, const void *dB, const int32_t *offsets,
                         const int32_t *tiles, const void *Wg, const void *Wu, void *dXp, hipStream_t s);
+// `tiles` is the table mfma_build_tiles() filled in this call sequence; `launch` (2..7) picks the
+// tile counters of this launch: 0 and 1 belong to the forward pair and to dh / dxp
 hipError_t mfma_wgrad(int E, int NQd, int NPd, const void *Qs, const void *Ps, const int32_t *offsets,
-                      float *out, int accumulate, hipStream_t s);
+                      const int32_t *tiles, int launch, float *out, int accumulate, hipStream_t s);
 hipError_t mfma_router_logits(int T, int d, int E, const void *x, const void *Wr, const float *bias,
                               float *logits, hipStream_t s);
 hipError_t mfma_dwr(int T, int d, int E, const void *x, const void *ds, float *part, float *dWr, int accumulate,

@@ -87,13 +87,8 @@ struct DmaKC {
         const int w = threadIdx.x >> 6, lane = threadIdx.x & 63;
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-#ifdef R3_LAB_KC128  // timing probe only (wrong data): 8 rows x 128 B per instruction
-            const int row = 8 * ((w & 3) + kLoaderWaves * i) + (lane >> 3);
-            const int c = (lane & 7);
-#else
             const int row = 16 * ((w & 3) + kLoaderWaves * i) + (lane >> 2);
             const int c = (lane & 3) ^ ((row >> 2) & 3);
-#endif
             voff[i] = row * ld_bytes + c * 16;
         }
     }
@@ -264,16 +259,10 @@ __device__ __forceinline__ void stage_compute(Acc2 &acc, Frags &x, Frags &y, con
 // drains every outstanding load, including the ones just issued three stages ahead.
 __device__ __forceinline__ void stage_barrier(bool loader) {
     // s_waitcnt simm16: vmcnt[3:0] | expcnt[6:4] | lgkmcnt[11:8] | vmcnt_hi[15:14]
-#ifdef R3_LAB_D2
-    constexpr int vm = 1 * kLoadsPerStage;
-#else
     constexpr int vm = 2 * kLoadsPerStage;
-#endif
     if (loader) __builtin_amdgcn_s_waitcnt((vm & 15) | (7 << 4) | (0 << 8) | ((vm >> 4) << 14));
     else __builtin_amdgcn_s_waitcnt(15 | (7 << 4) | (0 << 8) | (3 << 14));
-#ifndef R3_LAB_SKIP_BARRIER
     __builtin_amdgcn_s_barrier();
-#endif
 }
 
 // nk k-tiles of 32.  st0..st3: the four 32 KB LDS stages (distinct arrays).
@@ -304,10 +293,8 @@ __device__ __forceinline__ void mfma_mainloop2(Acc2 &acc, int nk, const POp &P, 
         Q.issue(0, a0 + kOperandBytes);
         P.issue(1, a1);
         Q.issue(1, a1 + kOperandBytes);
-#ifndef R3_LAB_D2
         P.issue(2, a2);
         Q.issue(2, a2 + kOperandBytes);
-#endif
     }
     stage_barrier(loader);
     Frags x, y;
@@ -317,16 +304,6 @@ __device__ __forceinline__ void mfma_mainloop2(Acc2 &acc, int nk, const POp &P, 
     for (int j = 0; j < kTQ2; ++j) x.b[j] = bf16x8_t{};
     // single loop exit (no break) keeps the accumulators in place
     for (int kt = 0; kt < nk; kt += 4) {
-#ifdef R3_LAB_D2
-        stage_compute(acc, x, y, P, Q, st0, kt + 2, a2, loader);
-        stage_barrier(loader);
-        if (kt + 1 < nk) stage_compute(acc, x, y, P, Q, st1, kt + 3, a3, loader);
-        stage_barrier(loader);
-        if (kt + 2 < nk) stage_compute(acc, x, y, P, Q, st2, kt + 4, a0, loader);
-        stage_barrier(loader);
-        if (kt + 3 < nk) stage_compute(acc, x, y, P, Q, st3, kt + 5, a1, loader);
-        stage_barrier(loader);
-#else
         stage_compute(acc, x, y, P, Q, st0, kt + 3, a3, loader);
         stage_barrier(loader);
         if (kt + 1 < nk) stage_compute(acc, x, y, P, Q, st1, kt + 4, a0, loader);
@@ -335,7 +312,6 @@ __device__ __forceinline__ void mfma_mainloop2(Acc2 &acc, int nk, const POp &P, 
         stage_barrier(loader);
         if (kt + 3 < nk) stage_compute(acc, x, y, P, Q, st3, kt + 6, a2, loader);
         stage_barrier(loader);
-#endif
     }
     mfma_block(acc, x);
     // loads for stages past the end are still in flight: drain them, and meet, before anyone
@@ -343,6 +319,43 @@ __device__ __forceinline__ void mfma_mainloop2(Acc2 &acc, int nk, const POp &P, 
     __builtin_amdgcn_s_waitcnt(0 | (7 << 4) | (15 << 8));
     __builtin_amdgcn_s_barrier();
 }
+
+// Persistent work-groups.  A launch has one work-group per compute unit; each walks the tile
+// list instead of ending after one tile, so a tile's stores drain while the next tile's first
+// loads are in flight and no work-group launch sits between two tiles.  The XCD-aware order
+// of xcd_tile_id() is kept: XCD x owns tile ids [x*per, (x+1)*per).  The first tile of a
+// work-group is fixed by its index; later ones come from a per-XCD counter (zeroed before
+// the launch), so that slow and fast compute units even out.  The counter is fetched with a
+// vector atomic by one thread of a wave that issues no tile loads, between the tile loop and
+// the epilogue (whose duration hides the round trip, and where the fragment registers are
+// free to hold the answer); `mailbox` is two ints of LDS outside the stage buffers (alternating, so that a wave
+// that is still reading one tile's slot cannot see the next one's).
+constexpr int kQueueThread = kLoaderWaves * 64;
+
+struct TileLoop {
+    int total, per, xcd, stride, iter, nxt;
+    int *ctr;
+    __device__ __forceinline__ TileLoop(int total_, int *ctr_row)
+        : total(total_), per((total_ + 7) >> 3), xcd(blockIdx.x & 7), stride(gridDim.x >> 3), iter(0), nxt(0),
+          ctr(ctr_row + (blockIdx.x & 7)) {}
+    __device__ __forceinline__ int first() const { return blockIdx.x >> 3; }
+    __device__ __forceinline__ bool valid(int slot) const { return slot < per && xcd * per + slot < total; }
+    __device__ __forceinline__ int id(int slot) const { return xcd * per + slot; }
+    // ask for the slot after this one; call after the tile loop
+    __device__ __forceinline__ void prefetch() {
+        if (threadIdx.x == kQueueThread) nxt = stride + atomicAdd(ctr, 1);
+    }
+    // end of a tile: every wave's LDS traffic of the epilogue is complete and the waves have
+    // met before anyone loads the next tile into the stage buffers; returns the next slot
+    __device__ __forceinline__ int finish(volatile int *mailbox) {
+        volatile int *box = mailbox + (iter & 1);
+        if (threadIdx.x == kQueueThread) *box = nxt;
+        // not __syncthreads(): its fence would also wait for this tile's global stores
+        asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+        ++iter;
+        return *box;
+    }
+};
 
 // Epilogue staging.  The MFMA result layout gives a lane 4 consecutive features of ONE row
 // per register quad, so direct stores are 16-byte pieces scattered over 32 rows per
