@@ -40,7 +40,8 @@ def kernel_work(sh, idx_bytes=1):
         "ffn2_down": ("mfma", 2.0 * S * d * F),
         "ffn_dh": ("mfma", 2.0 * S * d * F),
         "ffn_dxp": ("mfma", 4.0 * S * d * F),
-        "ffn_wgrad": ("mfma", 2.0 * S * d * F),   # per launch; three launches per step
+        "ffn_wgrad_down": ("mfma", 2.0 * S * d * F),
+        "ffn_wgrad_gate_up": ("mfma", 4.0 * S * d * F),   # both products in one launch
     }
 
 
@@ -53,7 +54,8 @@ def gemm_bytes(sh, backward):
         "ffn1_swiglu": S * d * 2 + 2 * W + (3 if backward else 1) * S * F * 2,
         "ffn2_down": S * F * 2 + W + S * d * 2,
         "ffn_dh": S * d * 2 + W + 4 * S * F * 2,
-        "ffn_wgrad": (S * d + S * F) * 2 + 2 * W,          # f32 gradient out
+        "ffn_wgrad_down": (S * d + S * F) * 2 + 2 * W,          # f32 gradient out
+        "ffn_wgrad_gate_up": (S * d + 2 * S * F) * 2 + 4 * W,
         "ffn_dxp": 2 * S * F * 2 + 2 * W + S * d * 2,
     }
 

@@ -212,8 +212,8 @@ int r3_moe_backward(const r3_layer_desc *desc, const void *dy, const void *x, co
         if (mfma_ffn_dh(m.S, m.d, m.E, m.F, dYp, offsets, tiles, W_down, A, B, dA, dB, s) != hipSuccess)
             return R3_ERR_HIP;
         if (mfma_wgrad(m.E, m.F, m.d, H, dYp, offsets, tiles, 2, dW_down, accumulate, s) != hipSuccess) return R3_ERR_HIP;
-        if (mfma_wgrad(m.E, m.d, m.F, Xp, dA, offsets, tiles, 3, dW_gate, accumulate, s) != hipSuccess) return R3_ERR_HIP;
-        if (mfma_wgrad(m.E, m.d, m.F, Xp, dB, offsets, tiles, 4, dW_up, accumulate, s) != hipSuccess) return R3_ERR_HIP;
+        if (mfma_wgrad_pair(m.E, m.d, m.F, Xp, dA, dB, offsets, tiles, 3, dW_gate, dW_up, accumulate, s) != hipSuccess)
+            return R3_ERR_HIP;
         if (mfma_ffn_dxp(m.S, m.d, m.E, m.F, dA, dB, offsets, tiles, W_gate, W_up, dXp, s) != hipSuccess)
             return R3_ERR_HIP;
     } else {

@@ -338,6 +338,77 @@ wgrad_kernel(int E, int NQd, int NPd, const bf16_t *__restrict__ Qs, const bf16_
 }
 
 // ---------------------------------------------------------------------------
+// Two weight gradients with a common row operand in one pass:
+//   out0[e][q][p] (+)= sum_r Qs[r][q] * P0[r][p],   out1[e][q][p] (+)= sum_r Qs[r][q] * P1[r][p]
+// (dW_gate and dW_up: Qs = Xp, P0 = dA, P1 = dB).  The P tile is two 128-feature sub-tiles, one
+// of P0 and one of P1 at the same features, as in the forward SwiGLU kernel, so the Xp tile is
+// fetched once for both products.
+// ---------------------------------------------------------------------------
+__global__ void __launch_bounds__(kThreads2, 2)
+wgrad_pair_kernel(int E, int NQd, int NPd, const bf16_t *__restrict__ Qs, const bf16_t *__restrict__ P0,
+                  const bf16_t *__restrict__ P1, const int32_t *__restrict__ offsets, float *__restrict__ out0,
+                  float *__restrict__ out1, int accumulate, int *ctr) {
+    __shared__ __attribute__((aligned(1024))) char s0[kStageBytes];
+    __shared__ __attribute__((aligned(1024))) char s1[kStageBytes];
+    __shared__ __attribute__((aligned(1024))) char s2[kStageBytes];
+    __shared__ __attribute__((aligned(1024))) char s3[kStageBytes];
+    __shared__ int mailbox[2];
+    constexpr int BF = 128;  // features of P0 (and of P1) per tile
+    const int nqt = NQd / kTile, npt = NPd / BF;
+    TileLoop tl(E * nqt * npt, ctr);
+    for (int slot = tl.first(); tl.valid(slot); slot = tl.finish(mailbox)) {
+    const int id = tl.id(slot);
+    const int e = id / (nqt * npt);
+    const int rem = id - e * nqt * npt;
+    const int qt = rem / npt, pt = rem - qt * npt;
+    const int r0 = offsets[e], r1 = offsets[e + 1];
+    const int q0 = qt * kTile, p0 = pt * BF;
+    const int wave = threadIdx.x >> 6;
+    const int wp = wave % kWP2, wq = wave / kWP2;
+
+    OpTR128x2 P;
+    P.src[0] = Src{(const char *)(P0 + (int64_t)r0 * NPd), clamp_bytes((int64_t)(r1 - r0) * NPd * 2),
+                   (uint32_t)(kBK2 * NPd * 2)};
+    P.src[1] = Src{(const char *)(P1 + (int64_t)r0 * NPd), clamp_bytes((int64_t)(r1 - r0) * NPd * 2),
+                   (uint32_t)(kBK2 * NPd * 2)};
+    P.init(NPd * 2, p0 * 2, 64 * wp);
+    OpTR256 Q;
+    Q.src[0] = Src{(const char *)(Qs + (int64_t)r0 * NQd), clamp_bytes((int64_t)(r1 - r0) * NQd * 2),
+                   (uint32_t)(kBK2 * NQd * 2)};
+    Q.src[1] = Q.src[0];
+    Q.kswitch = 0x7fffffff;
+    Q.init(NQd * 2, q0 * 2, 64 * wq);
+
+    Acc2 acc;
+    zero_acc2(acc);
+    mfma_mainloop2(acc, (r1 - r0 + kBK2 - 1) / kBK2, P, Q, s0, s1, s2, s3);
+    tl.prefetch();
+
+    // per wave: 64 rows (q) x 64 features (p) of each product, 32-row blocks through LDS
+    const int lane = threadIdx.x & 63;
+    RowStage<256> st{wave_patch(s0, s1, s2, s3)};
+    const int q = lane & 31;
+#pragma unroll
+    for (int tq = 0; tq < kTQ2; ++tq)
+#pragma unroll
+        for (int half = 0; half < 2; ++half) {   // MFMA tiles 0,1: first product; 2,3: second
+#pragma unroll
+            for (int t = 0; t < 2; ++t)
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    const int tp = half * 2 + t;
+                    st.put16(q, (t * 32 + g * 8 + (lane >> 5) * 4) * 4,
+                             make_float4(acc[tp][tq][4 * g], acc[tp][tq][4 * g + 1], acc[tp][tq][4 * g + 2],
+                                         acc[tp][tq][4 * g + 3]));
+                }
+            char *o = (char *)((half ? out1 : out0) + (int64_t)e * NQd * NPd);
+            const int64_t off = ((int64_t)(q0 + wq * 64 + tq * 32) * NPd + p0 + wp * 64) * 4;
+            st.flush_f32(o + off, (int64_t)NPd * 4, 32, accumulate);
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------
 // Router logits  s[t][e] = sum_c x[t][c] Wr[c][e] (+ bias[e]), f32 out.
 // ---------------------------------------------------------------------------
 template <class TL>
@@ -494,6 +565,17 @@ hipError_t mfma_wgrad(int E, int NQd, int NPd, const void *Qs, const void *Ps, c
     wgrad_kernel<<<persistent_grid(ntiles), kThreads2, 0, s>>>(E, NQd, NPd, (const bf16_t *)Qs, (const bf16_t *)Ps,
                                                               offsets, out, accumulate,
                                                               const_cast<int *>(tiles) + 2 + 8 * launch);
+    return hipGetLastError();
+}
+
+hipError_t mfma_wgrad_pair(int E, int NQd, int NPd, const void *Qs, const void *P0, const void *P1,
+                           const int32_t *offsets, const int32_t *tiles, int launch, float *out0, float *out1,
+                           int accumulate, hipStream_t s) {
+    const int64_t ntiles = (int64_t)E * (NQd / kTile) * (NPd / 128);
+    ProfScope ps(PROF_WGRAD_PAIR, s);
+    wgrad_pair_kernel<<<persistent_grid(ntiles), kThreads2, 0, s>>>(
+        E, NQd, NPd, (const bf16_t *)Qs, (const bf16_t *)P0, (const bf16_t *)P1, offsets, out0, out1, accumulate,
+        const_cast<int *>(tiles) + 2 + 8 * launch);
     return hipGetLastError();
 }
 

@@ -8,7 +8,8 @@ namespace r3 {
 // A ProfScope brackets one kernel launch; r3_profile_read() sums what was recorded.
 enum ProfTag {
     PROF_RECORD = 0, PROF_LOGITS, PROF_GATE, PROF_PERMUTE_INDEX, PROF_GATHER_ROWS, PROF_FFN1, PROF_FFN2,
-    PROF_COMBINE, PROF_GATE_BWD, PROF_DWR, PROF_DH, PROF_WGRAD, PROF_DXP, PROF_DX_FINISH, PROF_NTAGS
+    PROF_COMBINE, PROF_GATE_BWD, PROF_DWR, PROF_DH, PROF_WGRAD, PROF_DXP, PROF_DX_FINISH, PROF_WGRAD_PAIR,
+    PROF_NTAGS
 };
 struct ProfScope {
     int tag, slot;
@@ -75,6 +76,10 @@ hipError_t mfma_ffn_dxp(int64_t S, int d, int E, int F, const void *dA, const vo
 // tile counters of this launch: 0 and 1 belong to the forward pair and to dh / dxp
 hipError_t mfma_wgrad(int E, int NQd, int NPd, const void *Qs, const void *Ps, const int32_t *offsets,
                       const int32_t *tiles, int launch, float *out, int accumulate, hipStream_t s);
+// out0 (+)= Qs^T P0 and out1 (+)= Qs^T P1 per expert in one pass over Qs
+hipError_t mfma_wgrad_pair(int E, int NQd, int NPd, const void *Qs, const void *P0, const void *P1,
+                           const int32_t *offsets, const int32_t *tiles, int launch, float *out0, float *out1,
+                           int accumulate, hipStream_t s);
 hipError_t mfma_router_logits(int T, int d, int E, const void *x, const void *Wr, const float *bias,
                               float *logits, hipStream_t s);
 hipError_t mfma_dwr(int T, int d, int E, const void *x, const void *ds, float *part, float *dWr, int accumulate,
