@@ -116,7 +116,8 @@ ffn1_kernel(int S, int d, int F, const bf16_t *__restrict__ Xp, const int32_t *_
     tl.prefetch();
 
     // per wave: 64 rows x 64 features of H (and A, B), 32 rows at a time through LDS
-    RowStage<128> st{wave_patch(s0, s1, s2, s3)};
+    // (three patches in turn, so that one block's stores and the next block's arithmetic overlap)
+    char *patch = wave_patch(s0, s1, s2, s3);
     const int q = lane & 31;
 #pragma unroll
     for (int tq = 0; tq < kTQ2; ++tq) {
@@ -127,6 +128,7 @@ ffn1_kernel(int S, int d, int F, const bf16_t *__restrict__ Xp, const int32_t *_
         for (int which = 0; which < 3; ++which) {              // 0: H, 1: A, 2: B
             bf16_t *dst = which == 0 ? H : which == 1 ? A : B;
             if (!dst) continue;
+            RowStage<128> st{patch + which * RowStage<128>::BYTES};
 #pragma unroll
             for (int tp = 0; tp < 2; ++tp)
 #pragma unroll
@@ -220,44 +222,61 @@ rowgemm_kernel(int S, int d, int F, const bf16_t *__restrict__ Q0, const bf16_t 
     const int lane = threadIdx.x & 63;
     RowStage<256> st{wave_patch(s0, s1, s2, s3)};
     const int q = lane & 31;
+    if constexpr (MODE == 1) {
+        // Four rounds of 32 rows x 64 features.  The saved pre-activations come in
+        // row-contiguously into two patches (A and B); each lane then replaces exactly the
+        // quads it read with dA (first patch) and dB (second patch), and the patches go out
+        // row-contiguously.  The next round's rows are fetched before this round's arithmetic.
+        RowStage<128> sa{st.base}, sb{st.base + RowStage<128>::BYTES};
+        auto where = [&](int r, int &valid) -> int64_t {
+            const int brow = row0 + wq * 64 + (r >> 1) * 32;
+            valid = min(32, row_end - brow);
+            return ((int64_t)brow * NOUT + p0 + wp * 128) * 2 + (r & 1) * 128;
+        };
+        int valid;
+        int64_t oh = where(0, valid);
+        RowStage<128>::Rows ra = sa.fetch((const char *)A + oh, (int64_t)NOUT * 2, valid);
+        RowStage<128>::Rows rb = sb.fetch((const char *)B + oh, (int64_t)NOUT * 2, valid);
 #pragma unroll
-    for (int tq = 0; tq < kTQ2; ++tq) {
-        const int brow = row0 + wq * 64 + tq * 32;
-        const int valid = min(32, row_end - brow);
-        const int64_t o = ((int64_t)brow * NOUT + p0 + wp * 128) * 2;
-        if constexpr (MODE == 1) {
-            // saved pre-activations come in row-contiguously into two patches (A and B), 64
-            // features at a time so that both fit the wave's 16 KB; each lane then replaces
-            // exactly the quads it read with dA (first patch) and dB (second patch)
-            RowStage<128> sa{st.base}, sb{st.base + RowStage<128>::BYTES};
-#pragma unroll
-            for (int half = 0; half < 2; ++half) {
-                const int64_t oh = o + half * 128;
-                sa.fill((const char *)A + oh, (int64_t)NOUT * 2, valid);
-                sb.fill((const char *)B + oh, (int64_t)NOUT * 2, valid);
-#pragma unroll
-                for (int t = 0; t < 2; ++t)
-#pragma unroll
-                    for (int g = 0; g < 4; ++g) {
-                        const int tp = half * 2 + t;
-                        const int bo = (t * 32 + g * 8 + (lane >> 5) * 4) * 2;
-                        float a[4], b[4], da[4], db[4];
-                        unpack4(sa.get8(q, bo), a);
-                        unpack4(sb.get8(q, bo), b);
-#pragma unroll
-                        for (int i = 0; i < 4; ++i) {
-                            const float dh = acc[tp][tq][4 * g + i];
-                            const float sg = sigmoid_fast(a[i]);
-                            da[i] = dh * b[i] * sg * (1.0f + a[i] * (1.0f - sg));
-                            db[i] = dh * a[i] * sg;
-                        }
-                        sa.put8(q, bo, pack4(da[0], da[1], da[2], da[3]));
-                        sb.put8(q, bo, pack4(db[0], db[1], db[2], db[3]));
-                    }
-                sa.flush((char *)out0 + oh, (int64_t)NOUT * 2, valid);
-                sb.flush((char *)out1 + oh, (int64_t)NOUT * 2, valid);
+        for (int r = 0; r < 4; ++r) {
+            const int tq = r >> 1, half = r & 1;
+            sa.deposit(ra);
+            sb.deposit(rb);
+            if (r + 1 < 4) {
+                int nvalid;
+                const int64_t noh = where(r + 1, nvalid);
+                ra = sa.fetch((const char *)A + noh, (int64_t)NOUT * 2, nvalid);
+                rb = sb.fetch((const char *)B + noh, (int64_t)NOUT * 2, nvalid);
             }
-        } else {
+#pragma unroll
+            for (int t = 0; t < 2; ++t)
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    const int tp = half * 2 + t;
+                    const int bo = (t * 32 + g * 8 + (lane >> 5) * 4) * 2;
+                    float a[4], b[4], da[4], db[4];
+                    unpack4(sa.get8(q, bo), a);
+                    unpack4(sb.get8(q, bo), b);
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        const float dh = acc[tp][tq][4 * g + i];
+                        const float sg = sigmoid_fast(a[i]);
+                        da[i] = dh * b[i] * sg * (1.0f + a[i] * (1.0f - sg));
+                        db[i] = dh * a[i] * sg;
+                    }
+                    sa.put8(q, bo, pack4(da[0], da[1], da[2], da[3]));
+                    sb.put8(q, bo, pack4(db[0], db[1], db[2], db[3]));
+                }
+            oh = where(r, valid);
+            sa.flush((char *)out0 + oh, (int64_t)NOUT * 2, valid);
+            sb.flush((char *)out1 + oh, (int64_t)NOUT * 2, valid);
+        }
+    } else {
+#pragma unroll
+        for (int tq = 0; tq < kTQ2; ++tq) {
+            const int brow = row0 + wq * 64 + tq * 32;
+            const int valid = min(32, row_end - brow);
+            const int64_t o = ((int64_t)brow * NOUT + p0 + wp * 128) * 2;
 #pragma unroll
             for (int tp = 0; tp < kTP2; ++tp)
 #pragma unroll

@@ -402,16 +402,29 @@ struct RowStage {
             }
         }
     }
-    // in (byte pointer at row 0) -> rows [0, valid) of the patch
-    __device__ __forceinline__ void fill(const char *in, int64_t ld_bytes, int valid) const {
+    // in (byte pointer at row 0) -> rows [0, valid) of the patch, in two halves so that a caller can
+    // have the next block's rows in flight while it works on this one
+    struct Rows {
+        uint4 v[32 / RPI];
+    };
+    __device__ __forceinline__ Rows fetch(const char *in, int64_t ld_bytes, int valid) const {
         const int lane = threadIdx.x & 63, r = lane / LPR, c = lane % LPR;
+        Rows x;
 #pragma unroll
         for (int i = 0; i < 32 / RPI; ++i) {
             const int row = i * RPI + r;
-            uint4 v = make_uint4(0u, 0u, 0u, 0u);
-            if (row < valid) v = *(const uint4 *)(in + row * ld_bytes + c * 16);
-            *(uint4 *)(base + row * PITCH + c * 16) = v;
+            x.v[i] = make_uint4(0u, 0u, 0u, 0u);
+            if (row < valid) x.v[i] = *(const uint4 *)(in + row * ld_bytes + c * 16);
         }
+        return x;
+    }
+    __device__ __forceinline__ void deposit(const Rows &x) const {
+        const int lane = threadIdx.x & 63, r = lane / LPR, c = lane % LPR;
+#pragma unroll
+        for (int i = 0; i < 32 / RPI; ++i) *(uint4 *)(base + (i * RPI + r) * PITCH + c * 16) = x.v[i];
+    }
+    __device__ __forceinline__ void fill(const char *in, int64_t ld_bytes, int valid) const {
+        deposit(fetch(in, ld_bytes, valid));
     }
 };
 
