@@ -547,12 +547,14 @@ template <> struct VecIO<float, 1> {
     static __device__ __forceinline__ V pack(const float *f) { return f[0]; }
 };
 
-template <typename T, int VEC>
+// KT > 0: K known at compile time, so that a thread's K row loads are all in flight together
+template <typename T, int VEC, int KT>
 __global__ void __launch_bounds__(256)
-combine_kernel(int K, int row_vecs, const typename VecIO<T, VEC>::V *__restrict__ Yp,
+combine_kernel(int Krt, int row_vecs, const typename VecIO<T, VEC>::V *__restrict__ Yp,
                const float *__restrict__ gates, const int32_t *__restrict__ inv_perm,
                typename VecIO<T, VEC>::V *__restrict__ y) {
     typedef VecIO<T, VEC> IO;
+    const int K = KT > 0 ? KT : Krt;
     const int t = blockIdx.x;
     __shared__ int32_t rows[kMaxK];
     __shared__ float g[kMaxK];
@@ -565,12 +567,26 @@ combine_kernel(int K, int row_vecs, const typename VecIO<T, VEC>::V *__restrict_
         float acc[VEC];
 #pragma unroll
         for (int i = 0; i < VEC; ++i) acc[i] = 0.0f;
-        for (int j = 0; j < K; ++j) {
-            float f[VEC];
-            IO::unpack(Yp[(int64_t)rows[j] * row_vecs + c], f);
-            const float gj = g[j];
+        if constexpr (KT > 0) {
+            typename IO::V v[KT];
 #pragma unroll
-            for (int i = 0; i < VEC; ++i) acc[i] = fmaf(gj, f[i], acc[i]);
+            for (int j = 0; j < KT; ++j) v[j] = Yp[(int64_t)rows[j] * row_vecs + c];
+#pragma unroll
+            for (int j = 0; j < KT; ++j) {   // fixed j order: the sum is the same for every launch shape
+                float f[VEC];
+                IO::unpack(v[j], f);
+                const float gj = g[j];
+#pragma unroll
+                for (int i = 0; i < VEC; ++i) acc[i] = fmaf(gj, f[i], acc[i]);
+            }
+        } else {
+            for (int j = 0; j < K; ++j) {
+                float f[VEC];
+                IO::unpack(Yp[(int64_t)rows[j] * row_vecs + c], f);
+                const float gj = g[j];
+#pragma unroll
+                for (int i = 0; i < VEC; ++i) acc[i] = fmaf(gj, f[i], acc[i]);
+            }
         }
         y[(int64_t)t * row_vecs + c] = IO::pack(acc);
     }
@@ -580,19 +596,22 @@ hipError_t launch_combine(int T, int d, int K, int act, const void *Yp, const fl
                           const int32_t *inv_perm, void *y, hipStream_t s) {
     ProfScope ps(PROF_COMBINE, s);
     if (act == R3_BF16) {
-        if (d % 8 == 0)
-            combine_kernel<bf16_t, 8><<<T, 256, 0, s>>>(K, d / 8, (const uint4 *)Yp, gates, inv_perm,
-                                                       (uint4 *)y);
+        if (d % 8 == 0 && K == 8)
+            combine_kernel<bf16_t, 8, 8><<<T, 256, 0, s>>>(K, d / 8, (const uint4 *)Yp, gates, inv_perm,
+                                                          (uint4 *)y);
+        else if (d % 8 == 0)
+            combine_kernel<bf16_t, 8, 0><<<T, 256, 0, s>>>(K, d / 8, (const uint4 *)Yp, gates, inv_perm,
+                                                          (uint4 *)y);
         else
-            combine_kernel<bf16_t, 1><<<T, 256, 0, s>>>(K, d, (const bf16_t *)Yp, gates, inv_perm,
-                                                       (bf16_t *)y);
+            combine_kernel<bf16_t, 1, 0><<<T, 256, 0, s>>>(K, d, (const bf16_t *)Yp, gates, inv_perm,
+                                                          (bf16_t *)y);
     } else {
         if (d % 4 == 0)
-            combine_kernel<float, 4><<<T, 256, 0, s>>>(K, d / 4, (const float4 *)Yp, gates, inv_perm,
-                                                      (float4 *)y);
+            combine_kernel<float, 4, 0><<<T, 256, 0, s>>>(K, d / 4, (const float4 *)Yp, gates, inv_perm,
+                                                         (float4 *)y);
         else
-            combine_kernel<float, 1><<<T, 256, 0, s>>>(K, d, (const float *)Yp, gates, inv_perm,
-                                                      (float *)y);
+            combine_kernel<float, 1, 0><<<T, 256, 0, s>>>(K, d, (const float *)Yp, gates, inv_perm,
+                                                         (float *)y);
     }
     return hipGetLastError();
 }
@@ -605,14 +624,15 @@ hipError_t launch_combine(int T, int d, int K, int act, const void *Yp, const fl
 // the recorded set) that the router weight gradient contracts: [T,E] f32, or for
 // bf16 activations [T,2E] holding dz as hi and lo bf16 halves.
 // ---------------------------------------------------------------------------
-template <typename T, int VEC, typename IdxT>
+template <typename T, int VEC, typename IdxT, int KT>
 __global__ void __launch_bounds__(256)
-gate_backward_kernel(int E, int K, int row_vecs, const typename VecIO<T, VEC>::V *__restrict__ dy,
+gate_backward_kernel(int E, int Krt, int row_vecs, const typename VecIO<T, VEC>::V *__restrict__ dy,
                      const typename VecIO<T, VEC>::V *__restrict__ Yp, const float *__restrict__ gates,
                      const int32_t *__restrict__ inv_perm, const IdxT *__restrict__ idx, int64_t stride,
                      typename VecIO<T, VEC>::V *__restrict__ dYp, float *__restrict__ dz,
                      T *__restrict__ ds_dense) {
     typedef VecIO<T, VEC> IO;
+    const int K = KT > 0 ? KT : Krt;
     const int t = blockIdx.x;
     const int nw = blockDim.x / kWave, w = threadIdx.x / kWave, lane = lane_id();
     __shared__ int32_t rows[kMaxK];
@@ -629,22 +649,54 @@ gate_backward_kernel(int E, int K, int row_vecs, const typename VecIO<T, VEC>::V
     if (ds_dense)
         for (int e = threadIdx.x; e < dsw; e += blockDim.x) Elem<T>::st(ds_dense + (int64_t)t * dsw + e, 0.0f);
     __syncthreads();
-    for (int j = 0; j < K; ++j) {
-        float dot = 0.0f;
-        const float gj = g[j];
-        for (int c = threadIdx.x; c < row_vecs; c += blockDim.x) {
-            float a[VEC], b[VEC], o[VEC];
-            IO::unpack(dy[(int64_t)t * row_vecs + c], a);
-            IO::unpack(Yp[(int64_t)rows[j] * row_vecs + c], b);
+    if constexpr (KT > 0) {
+        // dy is read once per column chunk and the K rows of Yp are all in flight together; per
+        // thread and per j the products are summed in the same order as in the loop below
+        float dot[KT];
 #pragma unroll
-            for (int i = 0; i < VEC; ++i) {
-                dot = fmaf(a[i], b[i], dot);
-                o[i] = gj * a[i];
+        for (int j = 0; j < KT; ++j) dot[j] = 0.0f;
+        for (int c = threadIdx.x; c < row_vecs; c += blockDim.x) {
+            float a[VEC];
+            IO::unpack(dy[(int64_t)t * row_vecs + c], a);
+            typename IO::V v[KT];
+#pragma unroll
+            for (int j = 0; j < KT; ++j) v[j] = Yp[(int64_t)rows[j] * row_vecs + c];
+#pragma unroll
+            for (int j = 0; j < KT; ++j) {
+                float b[VEC], o[VEC];
+                IO::unpack(v[j], b);
+                const float gj = g[j];
+#pragma unroll
+                for (int i = 0; i < VEC; ++i) {
+                    dot[j] = fmaf(a[i], b[i], dot[j]);
+                    o[i] = gj * a[i];
+                }
+                dYp[(int64_t)rows[j] * row_vecs + c] = IO::pack(o);
             }
-            dYp[(int64_t)rows[j] * row_vecs + c] = IO::pack(o);
         }
-        dot = wave_sum(dot);
-        if (lane == 0) part[w][j] = dot;
+#pragma unroll
+        for (int j = 0; j < KT; ++j) {
+            const float dsum = wave_sum(dot[j]);
+            if (lane == 0) part[w][j] = dsum;
+        }
+    } else {
+        for (int j = 0; j < K; ++j) {
+            float dot = 0.0f;
+            const float gj = g[j];
+            for (int c = threadIdx.x; c < row_vecs; c += blockDim.x) {
+                float a[VEC], b[VEC], o[VEC];
+                IO::unpack(dy[(int64_t)t * row_vecs + c], a);
+                IO::unpack(Yp[(int64_t)rows[j] * row_vecs + c], b);
+#pragma unroll
+                for (int i = 0; i < VEC; ++i) {
+                    dot = fmaf(a[i], b[i], dot);
+                    o[i] = gj * a[i];
+                }
+                dYp[(int64_t)rows[j] * row_vecs + c] = IO::pack(o);
+            }
+            dot = wave_sum(dot);
+            if (lane == 0) part[w][j] = dot;
+        }
     }
     __syncthreads();
     if (threadIdx.x < (unsigned)K) {
@@ -673,15 +725,19 @@ static hipError_t gate_backward_dispatch(int Tn, int E, int K, int row_vecs, con
                                          int idx_dtype, int64_t stride, void *dYp, float *dz,
                                          void *ds_dense, hipStream_t s) {
     typedef typename VecIO<T, VEC>::V V;
-    if (idx_dtype == R3_IDX_U8)
-        gate_backward_kernel<T, VEC, uint8_t><<<Tn, 256, 0, s>>>(E, K, row_vecs, (const V *)dy, (const V *)Yp,
-                                                               gates, inv_perm, (const uint8_t *)idx,
-                                                               stride, (V *)dYp, dz, (T *)ds_dense);
+    if (idx_dtype == R3_IDX_U8 && K == 8 && VEC > 1)
+        gate_backward_kernel<T, VEC, uint8_t, 8><<<Tn, 256, 0, s>>>(E, K, row_vecs, (const V *)dy, (const V *)Yp,
+                                                                  gates, inv_perm, (const uint8_t *)idx,
+                                                                  stride, (V *)dYp, dz, (T *)ds_dense);
+    else if (idx_dtype == R3_IDX_U8)
+        gate_backward_kernel<T, VEC, uint8_t, 0><<<Tn, 256, 0, s>>>(E, K, row_vecs, (const V *)dy, (const V *)Yp,
+                                                                  gates, inv_perm, (const uint8_t *)idx,
+                                                                  stride, (V *)dYp, dz, (T *)ds_dense);
     else
-        gate_backward_kernel<T, VEC, uint16_t><<<Tn, 256, 0, s>>>(E, K, row_vecs, (const V *)dy,
-                                                                (const V *)Yp, gates, inv_perm,
-                                                                (const uint16_t *)idx, stride, (V *)dYp,
-                                                                dz, (T *)ds_dense);
+        gate_backward_kernel<T, VEC, uint16_t, 0><<<Tn, 256, 0, s>>>(E, K, row_vecs, (const V *)dy,
+                                                                   (const V *)Yp, gates, inv_perm,
+                                                                   (const uint16_t *)idx, stride, (V *)dYp,
+                                                                   dz, (T *)ds_dense);
     return hipGetLastError();
 }
 
@@ -709,13 +765,14 @@ hipError_t launch_gate_backward(int T, int d, int E, int K, int act, const void 
 //   dx[t] = sum_j dXp[row_j]  +  sum_j dz[t,j] * W_r[:, idx_j]
 // WrT is W_r transposed ([E,d], act dtype) so that the router term reads rows.
 // ---------------------------------------------------------------------------
-template <typename T, int VEC, typename IdxT>
+template <typename T, int VEC, typename IdxT, int KT>
 __global__ void __launch_bounds__(256)
-dx_finish_kernel(int E, int K, int row_vecs, const typename VecIO<T, VEC>::V *__restrict__ dXp,
+dx_finish_kernel(int E, int Krt, int row_vecs, const typename VecIO<T, VEC>::V *__restrict__ dXp,
                  const typename VecIO<T, VEC>::V *__restrict__ WrT, const float *__restrict__ dz,
                  const int32_t *__restrict__ inv_perm, const IdxT *__restrict__ idx, int64_t stride,
                  typename VecIO<T, VEC>::V *__restrict__ dx) {
     typedef VecIO<T, VEC> IO;
+    const int K = KT > 0 ? KT : Krt;
     const int t = blockIdx.x;
     __shared__ int32_t rows[kMaxK];
     __shared__ int32_t ids[kMaxK];
@@ -730,18 +787,41 @@ dx_finish_kernel(int E, int K, int row_vecs, const typename VecIO<T, VEC>::V *__
         float acc[VEC];
 #pragma unroll
         for (int i = 0; i < VEC; ++i) acc[i] = 0.0f;
-        for (int j = 0; j < K; ++j) {
-            float f[VEC];
-            IO::unpack(dXp[(int64_t)rows[j] * row_vecs + c], f);
+        if constexpr (KT > 0) {   // all 2K row loads in flight together; same summation order as below
+            typename IO::V v[KT], w[KT];
 #pragma unroll
-            for (int i = 0; i < VEC; ++i) acc[i] += f[i];
-        }
-        for (int j = 0; j < K; ++j) {
-            float f[VEC];
-            IO::unpack(WrT[(int64_t)ids[j] * row_vecs + c], f);
-            const float zj = z[j];
+            for (int j = 0; j < KT; ++j) v[j] = dXp[(int64_t)rows[j] * row_vecs + c];
 #pragma unroll
-            for (int i = 0; i < VEC; ++i) acc[i] = fmaf(zj, f[i], acc[i]);
+            for (int j = 0; j < KT; ++j) w[j] = WrT[(int64_t)ids[j] * row_vecs + c];
+#pragma unroll
+            for (int j = 0; j < KT; ++j) {
+                float f[VEC];
+                IO::unpack(v[j], f);
+#pragma unroll
+                for (int i = 0; i < VEC; ++i) acc[i] += f[i];
+            }
+#pragma unroll
+            for (int j = 0; j < KT; ++j) {
+                float f[VEC];
+                IO::unpack(w[j], f);
+                const float zj = z[j];
+#pragma unroll
+                for (int i = 0; i < VEC; ++i) acc[i] = fmaf(zj, f[i], acc[i]);
+            }
+        } else {
+            for (int j = 0; j < K; ++j) {
+                float f[VEC];
+                IO::unpack(dXp[(int64_t)rows[j] * row_vecs + c], f);
+#pragma unroll
+                for (int i = 0; i < VEC; ++i) acc[i] += f[i];
+            }
+            for (int j = 0; j < K; ++j) {
+                float f[VEC];
+                IO::unpack(WrT[(int64_t)ids[j] * row_vecs + c], f);
+                const float zj = z[j];
+#pragma unroll
+                for (int i = 0; i < VEC; ++i) acc[i] = fmaf(zj, f[i], acc[i]);
+            }
         }
         dx[(int64_t)t * row_vecs + c] = IO::pack(acc);
     }
@@ -752,13 +832,16 @@ static hipError_t dx_finish_dispatch(int Tn, int E, int K, int row_vecs, const v
                                      const float *dz, const int32_t *inv_perm, const void *idx,
                                      int idx_dtype, int64_t stride, void *dx, hipStream_t s) {
     typedef typename VecIO<T, VEC>::V V;
-    if (idx_dtype == R3_IDX_U8)
-        dx_finish_kernel<T, VEC, uint8_t><<<Tn, 256, 0, s>>>(E, K, row_vecs, (const V *)dXp, (const V *)WrT, dz,
-                                                           inv_perm, (const uint8_t *)idx, stride, (V *)dx);
+    if (idx_dtype == R3_IDX_U8 && K == 8 && VEC > 1)
+        dx_finish_kernel<T, VEC, uint8_t, 8><<<Tn, 256, 0, s>>>(E, K, row_vecs, (const V *)dXp, (const V *)WrT, dz,
+                                                              inv_perm, (const uint8_t *)idx, stride, (V *)dx);
+    else if (idx_dtype == R3_IDX_U8)
+        dx_finish_kernel<T, VEC, uint8_t, 0><<<Tn, 256, 0, s>>>(E, K, row_vecs, (const V *)dXp, (const V *)WrT, dz,
+                                                              inv_perm, (const uint8_t *)idx, stride, (V *)dx);
     else
-        dx_finish_kernel<T, VEC, uint16_t><<<Tn, 256, 0, s>>>(E, K, row_vecs, (const V *)dXp, (const V *)WrT,
-                                                            dz, inv_perm, (const uint16_t *)idx, stride,
-                                                            (V *)dx);
+        dx_finish_kernel<T, VEC, uint16_t, 0><<<Tn, 256, 0, s>>>(E, K, row_vecs, (const V *)dXp, (const V *)WrT,
+                                                               dz, inv_perm, (const uint16_t *)idx, stride,
+                                                               (V *)dx);
     return hipGetLastError();
 }
 
