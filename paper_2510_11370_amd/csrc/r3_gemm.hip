@@ -79,7 +79,7 @@ __device__ __forceinline__ void unpack4(uint2 v, float *f) {
 // the same features, so a wave holds both pre-activations of a (row, feature)
 // pair in the same lane: MFMA tiles 0,1 are gate, tiles 2,3 the matching up.
 // ---------------------------------------------------------------------------
-__global__ void __launch_bounds__(kThreads2, 2)
+__global__ void __launch_bounds__(kThreads2, kMinWavesPerSimd)
 ffn1_kernel(int S, int d, int F, const bf16_t *__restrict__ Xp, const int32_t *__restrict__ offsets,
             const int32_t *__restrict__ tiles, const bf16_t *__restrict__ Wg, const bf16_t *__restrict__ Wu,
             bf16_t *__restrict__ H, bf16_t *__restrict__ A, bf16_t *__restrict__ B, int launch) {
@@ -108,7 +108,7 @@ ffn1_kernel(int S, int d, int F, const bf16_t *__restrict__ Xp, const int32_t *_
     Q.src[0] = Src{(const char *)(Xp + (int64_t)row0 * d), clamp_bytes((int64_t)(S - row0) * d * 2), kBK2 * 2};
     Q.src[1] = Q.src[0];
     Q.kswitch = 0x7fffffff;
-    Q.init(d * 2, 64 * wq);
+    Q.init(d * 2, kWaveRowsQ * wq);
 
     Acc2 acc;
     zero_acc2(acc);
@@ -121,7 +121,7 @@ ffn1_kernel(int S, int d, int F, const bf16_t *__restrict__ Xp, const int32_t *_
     const int q = lane & 31;
 #pragma unroll
     for (int tq = 0; tq < kTQ2; ++tq) {
-        const int brow = row0 + wq * 64 + tq * 32;            // first row of this block
+        const int brow = row0 + wq * kWaveRowsQ + tq * 32;            // first row of this block
         const int valid = min(32, row_end - brow);             // may be <= 0
         const int64_t o = ((int64_t)brow * F + f0 + wp * 64) * 2;  // byte offset of the block
 #pragma unroll
@@ -157,7 +157,7 @@ ffn1_kernel(int S, int d, int F, const bf16_t *__restrict__ Xp, const int32_t *_
 //         (two-phase reduction: first F over (dA, Wg), then F over (dB, Wu))
 // ---------------------------------------------------------------------------
 template <int MODE>
-__global__ void __launch_bounds__(kThreads2, 2)
+__global__ void __launch_bounds__(kThreads2, kMinWavesPerSimd)
 rowgemm_kernel(int S, int d, int F, const bf16_t *__restrict__ Q0, const bf16_t *__restrict__ Q1,
                const int32_t *__restrict__ offsets, const int32_t *__restrict__ tiles,
                const bf16_t *__restrict__ W0, const bf16_t *__restrict__ W1, const bf16_t *__restrict__ A,
@@ -189,7 +189,7 @@ rowgemm_kernel(int S, int d, int F, const bf16_t *__restrict__ Q0, const bf16_t 
         Q.src[1] = Src{(const char *)(Q1 + (int64_t)row0 * KQ), clamp_bytes((int64_t)(S - row0) * KQ * 2), kBK2 * 2};
         Q.kswitch = F / kBK2;
     }
-    Q.init(KQ * 2, 64 * wq);
+    Q.init(KQ * 2, kWaveRowsQ * wq);
 
     Acc2 acc;
     zero_acc2(acc);
@@ -223,13 +223,13 @@ rowgemm_kernel(int S, int d, int F, const bf16_t *__restrict__ Q0, const bf16_t 
     RowStage<256> st{wave_patch(s0, s1, s2, s3)};
     const int q = lane & 31;
     if constexpr (MODE == 1) {
-        // Four rounds of 32 rows x 64 features.  The saved pre-activations come in
+        // Rounds of 32 rows x 64 features.  The saved pre-activations come in
         // row-contiguously into two patches (A and B); each lane then replaces exactly the
         // quads it read with dA (first patch) and dB (second patch), and the patches go out
         // row-contiguously.  The next round's rows are fetched before this round's arithmetic.
         RowStage<128> sa{st.base}, sb{st.base + RowStage<128>::BYTES};
         auto where = [&](int r, int &valid) -> int64_t {
-            const int brow = row0 + wq * 64 + (r >> 1) * 32;
+            const int brow = row0 + wq * kWaveRowsQ + (r >> 1) * 32;
             valid = min(32, row_end - brow);
             return ((int64_t)brow * NOUT + p0 + wp * 128) * 2 + (r & 1) * 128;
         };
@@ -238,11 +238,11 @@ rowgemm_kernel(int S, int d, int F, const bf16_t *__restrict__ Q0, const bf16_t 
         RowStage<128>::Rows ra = sa.fetch((const char *)A + oh, (int64_t)NOUT * 2, valid);
         RowStage<128>::Rows rb = sb.fetch((const char *)B + oh, (int64_t)NOUT * 2, valid);
 #pragma unroll
-        for (int r = 0; r < 4; ++r) {
+        for (int r = 0; r < 2 * kTQ2; ++r) {
             const int tq = r >> 1, half = r & 1;
             sa.deposit(ra);
             sb.deposit(rb);
-            if (r + 1 < 4) {
+            if (r + 1 < 2 * kTQ2) {
                 int nvalid;
                 const int64_t noh = where(r + 1, nvalid);
                 ra = sa.fetch((const char *)A + noh, (int64_t)NOUT * 2, nvalid);
@@ -274,7 +274,7 @@ rowgemm_kernel(int S, int d, int F, const bf16_t *__restrict__ Q0, const bf16_t 
     } else {
 #pragma unroll
         for (int tq = 0; tq < kTQ2; ++tq) {
-            const int brow = row0 + wq * 64 + tq * 32;
+            const int brow = row0 + wq * kWaveRowsQ + tq * 32;
             const int valid = min(32, row_end - brow);
             const int64_t o = ((int64_t)brow * NOUT + p0 + wp * 128) * 2;
 #pragma unroll
@@ -295,7 +295,7 @@ rowgemm_kernel(int S, int d, int F, const bf16_t *__restrict__ Q0, const bf16_t 
 // Both operands are [row][feature] matrices, so both tiles are TR; the k loop
 // runs over the expert's rows and the buffer bound zero-fills the tail.
 // ---------------------------------------------------------------------------
-__global__ void __launch_bounds__(kThreads2, 2)
+__global__ void __launch_bounds__(kThreads2, kMinWavesPerSimd)
 wgrad_kernel(int E, int NQd, int NPd, const bf16_t *__restrict__ Qs, const bf16_t *__restrict__ Ps,
              const int32_t *__restrict__ offsets, float *__restrict__ out, int accumulate, int *ctr) {
     __shared__ __attribute__((aligned(1024))) char s0[kStageBytes];
@@ -325,7 +325,7 @@ wgrad_kernel(int E, int NQd, int NPd, const bf16_t *__restrict__ Qs, const bf16_
                    (uint32_t)(kBK2 * NQd * 2)};
     Q.src[1] = Q.src[0];
     Q.kswitch = 0x7fffffff;
-    Q.init(NQd * 2, q0 * 2, 64 * wq);
+    Q.init(NQd * 2, q0 * 2, kWaveRowsQ * wq);
 
     Acc2 acc;
     zero_acc2(acc);
@@ -350,7 +350,7 @@ wgrad_kernel(int E, int NQd, int NPd, const bf16_t *__restrict__ Qs, const bf16_
                              make_float4(acc[tp][tq][4 * g], acc[tp][tq][4 * g + 1], acc[tp][tq][4 * g + 2],
                                          acc[tp][tq][4 * g + 3]));
                 }
-            const int64_t off = ((int64_t)(q0 + wq * 64 + tq * 32) * NPd + p0 + wp * 128 + half * 64) * 4;
+            const int64_t off = ((int64_t)(q0 + wq * kWaveRowsQ + tq * 32) * NPd + p0 + wp * 128 + half * 64) * 4;
             st.flush_f32(o + off, (int64_t)NPd * 4, 32, accumulate);
         }
     }
@@ -363,7 +363,7 @@ wgrad_kernel(int E, int NQd, int NPd, const bf16_t *__restrict__ Qs, const bf16_
 // of P0 and one of P1 at the same features, as in the forward SwiGLU kernel, so the Xp tile is
 // fetched once for both products.
 // ---------------------------------------------------------------------------
-__global__ void __launch_bounds__(kThreads2, 2)
+__global__ void __launch_bounds__(kThreads2, kMinWavesPerSimd)
 wgrad_pair_kernel(int E, int NQd, int NPd, const bf16_t *__restrict__ Qs, const bf16_t *__restrict__ P0,
                   const bf16_t *__restrict__ P1, const int32_t *__restrict__ offsets, float *__restrict__ out0,
                   float *__restrict__ out1, int accumulate, int *ctr) {
@@ -396,7 +396,7 @@ wgrad_pair_kernel(int E, int NQd, int NPd, const bf16_t *__restrict__ Qs, const 
                    (uint32_t)(kBK2 * NQd * 2)};
     Q.src[1] = Q.src[0];
     Q.kswitch = 0x7fffffff;
-    Q.init(NQd * 2, q0 * 2, 64 * wq);
+    Q.init(NQd * 2, q0 * 2, kWaveRowsQ * wq);
 
     Acc2 acc;
     zero_acc2(acc);
@@ -421,7 +421,7 @@ wgrad_pair_kernel(int E, int NQd, int NPd, const bf16_t *__restrict__ Qs, const 
                                          acc[tp][tq][4 * g + 3]));
                 }
             char *o = (char *)((half ? out1 : out0) + (int64_t)e * NQd * NPd);
-            const int64_t off = ((int64_t)(q0 + wq * 64 + tq * 32) * NPd + p0 + wp * 64) * 4;
+            const int64_t off = ((int64_t)(q0 + wq * kWaveRowsQ + tq * 32) * NPd + p0 + wp * 64) * 4;
             st.flush_f32(o + off, (int64_t)NPd * 4, 32, accumulate);
         }
     }

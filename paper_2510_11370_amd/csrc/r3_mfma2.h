@@ -35,9 +35,25 @@ constexpr int kTile = 256;
 constexpr int kStages2 = 4;
 constexpr int kOperandBytes = kTile * kBK2 * 2;  // 16 KB
 constexpr int kStageBytes = 2 * kOperandBytes;   // 32 KB
-constexpr int kWaves2 = 8, kThreads2 = 512;
+#ifndef R3_GEMM_WAVES
+#define R3_GEMM_WAVES 8
+#endif
+#if R3_GEMM_WAVES == 8
+// 2 (P) x 4 (Q) waves of 128 x 64, two per SIMD; waves 0-3 also load
+constexpr int kWaves2 = 8, kThreads2 = 512, kMinWavesPerSimd = 2;
 constexpr int kWP2 = 2, kWQ2 = 4, kTP2 = 4, kTQ2 = 2;
+constexpr int kReadsPerMfma = 2;   // fragment reads threaded behind each MFMA of a sub-step
+#else
+// 2 x 2 waves of 128 x 128, one per SIMD (accumulators in the second half of the 512
+// registers a lone wave may use); every wave loads.  A third less LDS read traffic, but
+// measured 5 % (weight gradients) to 30 % (kernels with wide epilogues) slower than the
+// 8-wave form on the 16384-token layer: a lone wave has nobody to cover its stalls.
+constexpr int kWaves2 = 4, kThreads2 = 256, kMinWavesPerSimd = 1;
+constexpr int kWP2 = 2, kWQ2 = 2, kTP2 = 4, kTQ2 = 4;
+constexpr int kReadsPerMfma = 1;
+#endif
 constexpr int kLoaderWaves = 4;
+constexpr int kWaveRowsQ = 32 * kTQ2;            // output rows (Q) per wave
 constexpr int kLoadsPerStage = 8;                // buffer loads per loader wave per stage (4 per operand)
 constexpr uint32_t kRsrcFlags = 0x00020000u;
 
@@ -230,7 +246,7 @@ __device__ __forceinline__ void sub_step(Acc2 &acc, Frags &next, const Frags &cu
 #pragma unroll
     for (int i = 0; i < kTP2 * kTQ2; ++i) {
         __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);  // MFMA
-        __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);  // DS read
+        __builtin_amdgcn_sched_group_barrier(0x100, kReadsPerMfma, 0);  // DS read
     }
     __builtin_amdgcn_sched_barrier(0);
 }
@@ -267,26 +283,41 @@ __device__ __forceinline__ void stage_barrier(bool loader) {
 
 // nk k-tiles of 32.  st0..st3: the four 32 KB LDS stages (distinct arrays).
 // upper_half_live = false: output rows 128..255 of the tile are not needed (ragged tail of an
-// expert's segment); waves 4-7, which own them and load nothing, then only keep the barriers
-// company, and every SIMD is left with one multiplying wave instead of two.
+// expert's segment); the waves that own them skip fragment reads and MFMAs and only keep
+// their share of the loads and the barriers going.
 template <class POp, class QOp>
 __device__ __forceinline__ void mfma_mainloop2(Acc2 &acc, int nk, const POp &P, const QOp &Q, char *st0, char *st1,
                                                char *st2, char *st3, bool upper_half_live = true) {
     if (nk <= 0) return;
-    if (!upper_half_live && __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6)) >= kLoaderWaves) {
-        for (int kt = 0; kt < nk; kt += 4) {
-            stage_barrier(false);
-            stage_barrier(false);
-            stage_barrier(false);
-            stage_barrier(false);
+    const uint32_t a0 = lds_addr(st0), a1 = lds_addr(st1), a2 = lds_addr(st2), a3 = lds_addr(st3);
+    const int wave_ = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    // wave-uniform, and visibly so (scalar branch instead of exec masking)
+    const bool loader = wave_ < kLoaderWaves;
+    if (!upper_half_live && wave_ / kWP2 >= kWQ2 / 2) {
+        // this wave's rows are not needed: keep the loads (if it is a loader) and the barriers going
+        if (loader) {
+            P.issue(0, a0);
+            Q.issue(0, a0 + kOperandBytes);
+            P.issue(1, a1);
+            Q.issue(1, a1 + kOperandBytes);
+            P.issue(2, a2);
+            Q.issue(2, a2 + kOperandBytes);
         }
-        stage_barrier(false);  // the one after the prologue loads
+        stage_barrier(loader);
+        for (int kt = 0; kt < nk; kt += 4) {
+            if (loader) { P.issue(kt + 3, a3); Q.issue(kt + 3, a3 + kOperandBytes); }
+            stage_barrier(loader);
+            if (loader && kt + 1 < nk) { P.issue(kt + 4, a0); Q.issue(kt + 4, a0 + kOperandBytes); }
+            stage_barrier(loader);
+            if (loader && kt + 2 < nk) { P.issue(kt + 5, a1); Q.issue(kt + 5, a1 + kOperandBytes); }
+            stage_barrier(loader);
+            if (loader && kt + 3 < nk) { P.issue(kt + 6, a2); Q.issue(kt + 6, a2 + kOperandBytes); }
+            stage_barrier(loader);
+        }
+        __builtin_amdgcn_s_waitcnt(0 | (7 << 4) | (15 << 8));
         __builtin_amdgcn_s_barrier();
         return;
     }
-    const uint32_t a0 = lds_addr(st0), a1 = lds_addr(st1), a2 = lds_addr(st2), a3 = lds_addr(st3);
-    // wave-uniform, and visibly so (scalar branch instead of exec masking)
-    const bool loader = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6)) < kLoaderWaves;
     if (loader) {
         // stages 0, 1, 2 (a stage >= nk loads nothing useful but still counts)
         P.issue(0, a0);
@@ -326,11 +357,11 @@ __device__ __forceinline__ void mfma_mainloop2(Acc2 &acc, int nk, const POp &P, 
 // of xcd_tile_id() is kept: XCD x owns tile ids [x*per, (x+1)*per).  The first tile of a
 // work-group is fixed by its index; later ones come from a per-XCD counter (zeroed before
 // the launch), so that slow and fast compute units even out.  The counter is fetched with a
-// vector atomic by one thread of a wave that issues no tile loads, between the tile loop and
+// vector atomic by one thread, between the tile loop (all its loads drained) and
 // the epilogue (whose duration hides the round trip, and where the fragment registers are
 // free to hold the answer); `mailbox` is two ints of LDS outside the stage buffers (alternating, so that a wave
 // that is still reading one tile's slot cannot see the next one's).
-constexpr int kQueueThread = kLoaderWaves * 64;
+constexpr int kQueueThread = 0;
 
 struct TileLoop {
     int total, per, xcd, stride, iter, nxt;
@@ -428,11 +459,15 @@ struct RowStage {
     }
 };
 
-// the wave's private 16 KB of the (now idle) stage buffers
+// the wave's private share (128 KB / waves) of the (now idle) stage buffers
 __device__ __forceinline__ char *wave_patch(char *s0, char *s1, char *s2, char *s3) {
     const int w = threadIdx.x >> 6;
-    char *b = (w >> 1) == 0 ? s0 : (w >> 1) == 1 ? s1 : (w >> 1) == 2 ? s2 : s3;
-    return b + (w & 1) * 16384;
+    if constexpr (kWaves2 == 8) {
+        char *b = (w >> 1) == 0 ? s0 : (w >> 1) == 1 ? s1 : (w >> 1) == 2 ? s2 : s3;
+        return b + (w & 1) * 16384;
+    } else {
+        return w == 0 ? s0 : w == 1 ? s1 : w == 2 ? s2 : s3;
+    }
 }
 
 // Visit the wave's results as groups of 4 consecutive p for one q (tile-local p, q).
@@ -446,7 +481,7 @@ __device__ __forceinline__ void for_each_quad2(F f) {
         for (int tq = 0; tq < kTQ2; ++tq)
 #pragma unroll
             for (int g = 0; g < 4; ++g)
-                f(tp, tq, g, wp * 128 + tp * 32 + g * 8 + (lane >> 5) * 4, wq * 64 + tq * 32 + (lane & 31));
+                f(tp, tq, g, wp * 128 + tp * 32 + g * 8 + (lane >> 5) * 4, wq * kWaveRowsQ + tq * 32 + (lane & 31));
 }
 
 __device__ __forceinline__ uint32_t clamp_bytes(int64_t b) {
