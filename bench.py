@@ -78,6 +78,35 @@ def cpu_baseline(sh, tokens):
                       % (tokens, sh.E, dt)}
 
 
+def measured_ceilings(torch, r3, dev):
+    """What this machine sustains on the two resources the rooflines are drawn against, measured with the
+    library's calibration kernels outside the timed region: a register-only bf16 MFMA loop with constant and
+    with varied operand bits (the matrix rate is power-limited and depends on the data), and a plain copy."""
+    def timed(fn, reps=3):
+        best = None
+        for _ in range(reps):
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record()
+            work = fn()
+            b.record()
+            b.synchronize()
+            rate = work / (a.elapsed_time(b) * 1e-3)
+            best = rate if best is None else max(best, rate)
+        return best
+    sink = torch.zeros(1, dtype=torch.float32, device=dev)
+    src = torch.zeros(256 << 20, dtype=torch.uint8, device=dev)
+    dst = torch.empty_like(src)
+
+    def copy():
+        r3.profile_copy(dst, src)
+        return 2.0 * src.numel()
+    out = {"mfma_bf16_constant_operands_TFLOPs": round(timed(lambda: r3.profile_mfma(20000, False, sink)) * 1e-12, 1),
+           "mfma_bf16_varied_operands_TFLOPs": round(timed(lambda: r3.profile_mfma(20000, True, sink)) * 1e-12, 1),
+           "hbm_copy_GBs": round(timed(copy) * 1e-9, 1)}
+    del src, dst
+    return out
+
+
 def stored_traffic(workload, kernel):
     """HBM bytes per launch (fetch + write) of `kernel` from the committed counter summary of this workload
     (two rocprofv3 --pmc runs of this script, scaled by the calibration copy), or None if there is none."""
@@ -101,6 +130,7 @@ def main():
     ap.add_argument("--workload", default="fwdbwd_16k")
     ap.add_argument("--cpu-tokens", type=int, default=4096, help="tokens of the oracle's timed sample (0 = skip)")
     ap.add_argument("--forward-only", action="store_true")
+    ap.add_argument("--no-ceilings", action="store_true", help="skip the calibration kernels after the timed region")
     ap.add_argument("--calib-copy", action="store_true",
                     help="after the timed region, run one plain 256 MiB copy kernel (reference point for "
                          "hardware traffic counters collected around this command)")
@@ -225,6 +255,8 @@ def main():
                                                                   round(float(rate.mean()), 4),
                                                                   round(float(rate.max()), 4)]
         out["metric"] = "token-layers/sec for R3 record+replay forward over a %d-layer stack at 1 GPU" % L
+    if not args.no_ceilings:
+        out["ceilings"] = measured_ceilings(torch, r3, dev)
     if args.cpu_tokens > 0:
         del buf
         torch.cuda.empty_cache()

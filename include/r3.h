@@ -180,6 +180,19 @@ int r3_profile_read(int tag, double *total_ms, int *launches);
  */
 int r3_profile_copy(void *dst, const void *src, size_t bytes, void *stream);
 
+/*
+ * Measurement aid: a pure bf16 MFMA issue loop (`calib_mfma_kernel`, one
+ * work-group of 8 waves per compute unit, 8 independent 32x32x16 accumulator
+ * tiles per wave, operands in registers, no memory traffic) of `iters`
+ * iterations; random_operands != 0 fills the operand registers with varied bit
+ * patterns, 0 with one constant.  It does 2*32*32*16 * 8 * iters * 8 * grid
+ * FLOP (r3_profile_mfma_flops); timed by the caller it gives the matrix rate
+ * this machine sustains under its power limit, which depends on the operand
+ * data.  `sink` is a device float the kernel may write (never in practice).
+ */
+int r3_profile_mfma(int iters, int random_operands, float *sink, void *stream);
+double r3_profile_mfma_flops(int iters);
+
 #ifdef __cplusplus
 }
 #endif

@@ -47,6 +47,48 @@ __global__ void __launch_bounds__(256) calib_copy_kernel(uint4 *__restrict__ dst
     for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x)
         dst[i] = src[i];
 }
+
+typedef __bf16 cal_bf16x8_t __attribute__((ext_vector_type(8)));
+typedef float cal_f32x16_t __attribute__((ext_vector_type(16)));
+typedef unsigned short cal_u16x8_t __attribute__((ext_vector_type(8)));
+
+// the accumulator/fragment shape of the expert GEMMs' inner step, fed from registers only
+__global__ void __launch_bounds__(512, 2) calib_mfma_kernel(int iters, int rnd, float *sink) {
+    cal_bf16x8_t a[4], b[2];
+    uint32_t h = (threadIdx.x + blockIdx.x * 977u) * 2654435761u;
+    for (int i = 0; i < 6; ++i) {
+        cal_u16x8_t u;
+        for (int j = 0; j < 8; ++j) {
+            h = h * 1664525u + 1013904223u;
+            // finite bf16 values of either sign with varied mantissas, or the constant 1.0
+            u[j] = rnd ? (unsigned short)(0x3c00u + ((h >> 9) & 0x83ffu)) : (unsigned short)0x3f80u;
+        }
+        if (i < 4) a[i] = __builtin_bit_cast(cal_bf16x8_t, u);
+        else b[i - 4] = __builtin_bit_cast(cal_bf16x8_t, u);
+    }
+    cal_f32x16_t acc[4][2];
+    for (int i = 0; i < 4; ++i)
+        for (int j = 0; j < 2; ++j)
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+            for (int j = 0; j < 2; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
+    }
+    float s = 0.0f;
+    for (int i = 0; i < 4; ++i)
+        for (int j = 0; j < 2; ++j)
+            for (int v = 0; v < 16; ++v) s += acc[i][j][v];
+    if (s == 1.2345678f) *sink = s;  // keeps the loop alive
+}
+
+static int calib_grid() {
+    int dev = 0, n = 0;
+    if (hipGetDevice(&dev) != hipSuccess) dev = 0;
+    if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n < 1) n = 256;
+    return n;
+}
 }  // namespace r3
 
 using namespace r3;
@@ -89,5 +131,15 @@ int r3_profile_copy(void *dst, const void *src, size_t bytes, void *stream) {
     if (blocks > 256 * 32) blocks = 256 * 32;
     calib_copy_kernel<<<dim3((unsigned)blocks), dim3(256), 0, (hipStream_t)stream>>>((uint4 *)dst, (const uint4 *)src, n);
     return hipGetLastError() == hipSuccess ? R3_OK : R3_ERR_HIP;
+}
+
+int r3_profile_mfma(int iters, int random_operands, float *sink, void *stream) {
+    if (iters < 1 || iters > (1 << 24) || !sink) return R3_ERR_INVALID_ARG;
+    calib_mfma_kernel<<<dim3(calib_grid()), dim3(512), 0, (hipStream_t)stream>>>(iters, random_operands, sink);
+    return hipGetLastError() == hipSuccess ? R3_OK : R3_ERR_HIP;
+}
+
+double r3_profile_mfma_flops(int iters) {
+    return 2.0 * 32 * 32 * 16 * 8.0 * (double)iters * 8.0 * (double)calib_grid();
 }
 }

@@ -20,7 +20,8 @@ _STATUS = {1: "R3_ERR_INVALID_ARG", 2: "R3_ERR_UNSUPPORTED", 3: "R3_ERR_WORKSPAC
 
 EXPORTS = ["r3_version", "r3_workspace_bytes", "r3_record_topk", "r3_replay_gate", "r3_permute",
            "r3_grouped_ffn", "r3_combine", "r3_moe_backward", "r3_profile_enable", "r3_profile_tags",
-           "r3_profile_name", "r3_profile_read", "r3_profile_copy"]
+           "r3_profile_name", "r3_profile_read", "r3_profile_copy",
+           "r3_profile_mfma", "r3_profile_mfma_flops"]
 
 
 class LayerDesc(C.Structure):
@@ -50,6 +51,7 @@ def lib():
         for name in EXPORTS[2:]:
             getattr(L, name).restype = C.c_int
         L.r3_profile_name.restype = C.c_char_p
+        L.r3_profile_mfma_flops.restype = C.c_double
         _lib = L
     return _lib
 
@@ -183,6 +185,13 @@ def profile_copy(dst, src):
     assert dst.numel() * dst.element_size() == src.numel() * src.element_size()
     _check(lib().r3_profile_copy(_p(dst), _p(src), C.c_size_t(src.numel() * src.element_size()), _stream()),
            "r3_profile_copy")
+
+
+def profile_mfma(iters, random_operands, sink):
+    """Launch the register-only MFMA loop; returns the FLOP it performs (the caller times it)."""
+    _check(lib().r3_profile_mfma(C.c_int(iters), C.c_int(1 if random_operands else 0), _p(sink), _stream()),
+           "r3_profile_mfma")
+    return float(lib().r3_profile_mfma_flops(C.c_int(iters)))
 
 
 def profile_read():
