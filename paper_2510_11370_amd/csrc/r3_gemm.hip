@@ -14,10 +14,16 @@ namespace r3 {
 
 // ---------------------------------------------------------------------------
 // Row-tile table: tiles[0] = number of tiles, tiles[2 .. 2+64) = the tile counters of up to
-// eight persistent launches (8 XCDs each, zeroed here), then (expert, row0) pairs from
-// tiles[kTileHdr].  One block; experts in ascending order, rows ascending.
+// eight persistent launches (8 XCDs each, zeroed here), tiles[66 .. 66+kMaxE) = the experts in
+// descending order of row count (ties by id), then (expert, row0) pairs from tiles[kTileHdr].
+// One block; row tiles list experts in ascending order, rows ascending.
+// The weight-gradient kernels, whose tiles last as long as their expert has rows, take experts in
+// that order (dealt out evenly to the 8 XCD shares of the tile list): with the shared tile
+// counter that is longest-first scheduling, and a heavily loaded expert no longer starts late
+// and finishes alone.
 // ---------------------------------------------------------------------------
-constexpr int kTileHdr = 2 + 64;
+constexpr int kTileOrder = 2 + 64;
+constexpr int kTileHdr = kTileOrder + kMaxE;
 __device__ __forceinline__ int *tile_counters(const int32_t *tiles, int launch) {
     return const_cast<int *>(tiles) + 2 + 8 * launch;
 }
@@ -35,6 +41,22 @@ build_row_tiles_kernel(int E, int BQ, const int32_t *__restrict__ offsets, int32
         tiles[1] = 0;
     }
     if (threadIdx.x < 64) tiles[2 + threadIdx.x] = 0;
+    for (int e = threadIdx.x; e < E; e += blockDim.x) {
+        const int n = offsets[e + 1] - offsets[e];
+        int rank = 0;
+        for (int o = 0; o < E; ++o) {
+            const int m = offsets[o + 1] - offsets[o];
+            rank += (m > n) || (m == n && o < e);
+        }
+        // the tile list is cut into 8 contiguous XCD shares: deal the ranked experts out to the
+        // shares in serpentine order, so that every share holds an equal mix, heaviest first
+        int pos = rank;
+        if (E % 8 == 0) {
+            const int j = rank >> 3, c = rank & 7;
+            pos = ((j & 1) ? 7 - c : c) * (E >> 3) + j;
+        }
+        tiles[kTileOrder + pos] = e;
+    }
     __syncthreads();
     for (int e = threadIdx.x; e < E; e += blockDim.x) {
         const int n = start[e + 1] - start[e];
@@ -297,7 +319,8 @@ rowgemm_kernel(int S, int d, int F, const bf16_t *__restrict__ Q0, const bf16_t 
 // ---------------------------------------------------------------------------
 __global__ void __launch_bounds__(kThreads2, kMinWavesPerSimd)
 wgrad_kernel(int E, int NQd, int NPd, const bf16_t *__restrict__ Qs, const bf16_t *__restrict__ Ps,
-             const int32_t *__restrict__ offsets, float *__restrict__ out, int accumulate, int *ctr) {
+             const int32_t *__restrict__ offsets, float *__restrict__ out, int accumulate, int *ctr,
+             const int32_t *__restrict__ order) {
     __shared__ __attribute__((aligned(1024))) char s0[kStageBytes];
     __shared__ __attribute__((aligned(1024))) char s1[kStageBytes];
     __shared__ __attribute__((aligned(1024))) char s2[kStageBytes];
@@ -307,8 +330,9 @@ wgrad_kernel(int E, int NQd, int NPd, const bf16_t *__restrict__ Qs, const bf16_
     TileLoop tl(E * nqt * npt, ctr);
     for (int slot = tl.first(); tl.valid(slot); slot = tl.finish(mailbox)) {
     const int id = tl.id(slot);
-    const int e = id / (nqt * npt);
-    const int rem = id - e * nqt * npt;
+    const int eo = id / (nqt * npt);
+    const int rem = id - eo * nqt * npt;
+    const int e = order[eo];
     const int qt = rem / npt, pt = rem - qt * npt;
     const int r0 = offsets[e], r1 = offsets[e + 1];
     const int q0 = qt * kTile, p0 = pt * kTile;
@@ -366,7 +390,7 @@ wgrad_kernel(int E, int NQd, int NPd, const bf16_t *__restrict__ Qs, const bf16_
 __global__ void __launch_bounds__(kThreads2, kMinWavesPerSimd)
 wgrad_pair_kernel(int E, int NQd, int NPd, const bf16_t *__restrict__ Qs, const bf16_t *__restrict__ P0,
                   const bf16_t *__restrict__ P1, const int32_t *__restrict__ offsets, float *__restrict__ out0,
-                  float *__restrict__ out1, int accumulate, int *ctr) {
+                  float *__restrict__ out1, int accumulate, int *ctr, const int32_t *__restrict__ order) {
     __shared__ __attribute__((aligned(1024))) char s0[kStageBytes];
     __shared__ __attribute__((aligned(1024))) char s1[kStageBytes];
     __shared__ __attribute__((aligned(1024))) char s2[kStageBytes];
@@ -377,8 +401,9 @@ wgrad_pair_kernel(int E, int NQd, int NPd, const bf16_t *__restrict__ Qs, const 
     TileLoop tl(E * nqt * npt, ctr);
     for (int slot = tl.first(); tl.valid(slot); slot = tl.finish(mailbox)) {
     const int id = tl.id(slot);
-    const int e = id / (nqt * npt);
-    const int rem = id - e * nqt * npt;
+    const int eo = id / (nqt * npt);
+    const int rem = id - eo * nqt * npt;
+    const int e = order[eo];
     const int qt = rem / npt, pt = rem - qt * npt;
     const int r0 = offsets[e], r1 = offsets[e + 1];
     const int q0 = qt * kTile, p0 = pt * BF;
@@ -583,7 +608,8 @@ hipError_t mfma_wgrad(int E, int NQd, int NPd, const void *Qs, const void *Ps, c
     ProfScope ps(PROF_WGRAD, s);
     wgrad_kernel<<<persistent_grid(ntiles), kThreads2, 0, s>>>(E, NQd, NPd, (const bf16_t *)Qs, (const bf16_t *)Ps,
                                                               offsets, out, accumulate,
-                                                              const_cast<int *>(tiles) + 2 + 8 * launch);
+                                                              const_cast<int *>(tiles) + 2 + 8 * launch,
+                                                              tiles + kTileOrder);
     return hipGetLastError();
 }
 
@@ -594,7 +620,7 @@ hipError_t mfma_wgrad_pair(int E, int NQd, int NPd, const void *Qs, const void *
     ProfScope ps(PROF_WGRAD_PAIR, s);
     wgrad_pair_kernel<<<persistent_grid(ntiles), kThreads2, 0, s>>>(
         E, NQd, NPd, (const bf16_t *)Qs, (const bf16_t *)P0, (const bf16_t *)P1, offsets, out0, out1, accumulate,
-        const_cast<int *>(tiles) + 2 + 8 * launch);
+        const_cast<int *>(tiles) + 2 + 8 * launch, tiles + kTileOrder);
     return hipGetLastError();
 }
 
