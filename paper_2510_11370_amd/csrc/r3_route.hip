@@ -170,9 +170,160 @@ record_topk_wave_kernel(int T, int E, int K, const float *__restrict__ logits, i
     if (__ballot(bad) && lane == 0 && status) atomicOr(status, R3_DATA_NONFINITE);
 }
 
+// The same selection for E = 32 NV with vector loads and one pass over the row: the 8 lanes of a
+// token read consecutive float4 pieces (lane `sub` holds ids 32 i + 4 sub + c, i < NV, c < 4: one
+// 128-byte segment per token per load instruction), keep the keys in registers, and after the
+// merges express "above the threshold" and "equal to it" as E-bit masks, OR-ed over the 8 lanes.
+// The recorded set is the first mask plus the lowest-id bits of the second up to K; lane `sub`
+// writes its sub-th set bit, so the K ids land ascending in one 8-byte segment.
+// Value of lane `partner(lane)` inside each group of 8 lanes, through DPP (a VALU move, no LDS
+// round trip): STEP 0: lane^1, STEP 1: lane^2 (quad permutes), STEP 2: 7 - lane%8 (half-row
+// mirror).  After the three steps every lane of a group has met every other one.
+template <int STEP>
+__device__ __forceinline__ uint32_t group8_exchange(uint32_t v) {
+    constexpr int ctrl = STEP == 0 ? 0xB1 : STEP == 1 ? 0x4E : 0x141;
+    return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, ctrl, 0xf, 0xf, false);
+}
+
+__device__ __forceinline__ uint32_t umed3(uint32_t a, uint32_t b, uint32_t c) {
+    return max(min(a, b), min(max(a, b), c));
+}
+
+template <int STEP>
+__device__ __forceinline__ void merge_top8(uint32_t (&top)[8]) {
+    uint32_t other[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) other[j] = group8_exchange<STEP>(top[j]);
+#pragma unroll
+    for (int j = 0; j < 8; ++j) top[j] = max(top[j], other[7 - j]);
+    cmpx_desc(top[0], top[4]); cmpx_desc(top[1], top[5]); cmpx_desc(top[2], top[6]); cmpx_desc(top[3], top[7]);
+    cmpx_desc(top[0], top[2]); cmpx_desc(top[1], top[3]); cmpx_desc(top[4], top[6]); cmpx_desc(top[5], top[7]);
+    cmpx_desc(top[0], top[1]); cmpx_desc(top[2], top[3]); cmpx_desc(top[4], top[5]); cmpx_desc(top[6], top[7]);
+}
+
+template <typename IdxT, int NV>
+__global__ void __launch_bounds__(256)
+record_topk_vec_kernel(int T, int K, const float *__restrict__ logits, int64_t ld, IdxT *__restrict__ idx,
+                       int64_t stride, int32_t *status) {
+    const int t = blockIdx.x * 32 + (int)(threadIdx.x >> 3);
+    const int sub = threadIdx.x & 7;
+    const bool live = t < T;
+    const float4 *row = (const float4 *)(logits + (int64_t)(live ? t : 0) * ld);
+    uint32_t key[NV][4];
+    bool bad = false;
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+        const float4 v = row[i * 8 + sub];
+        bool nf;
+        key[i][0] = order_key(v.x, nf); bad |= nf;
+        key[i][1] = order_key(v.y, nf); bad |= nf;
+        key[i][2] = order_key(v.z, nf); bad |= nf;
+        key[i][3] = order_key(v.w, nf); bad |= nf;
+    }
+    uint32_t top[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) top[j] = 0u;
+    // insertion into the descending list: new top[j] = median(top[j-1], top[j], v), one v_med3_u32
+#pragma unroll
+    for (int i = 0; i < NV; ++i)
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            const uint32_t v = key[i][c];
+            uint32_t nt[8];
+            nt[0] = max(top[0], v);
+#pragma unroll
+            for (int j = 1; j < 8; ++j) nt[j] = umed3(top[j - 1], top[j], v);
+#pragma unroll
+            for (int j = 0; j < 8; ++j) top[j] = nt[j];
+        }
+    merge_top8<0>(top);
+    merge_top8<1>(top);
+    merge_top8<2>(top);
+    uint32_t thr = 0u;
+#pragma unroll
+    for (int j = 0; j < 8; ++j)
+        if (j == K - 1) thr = top[j];
+    uint32_t gt[NV], eq[NV];
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+        uint32_t g = 0u, q = 0u;
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            g |= (uint32_t)(key[i][c] > thr) << c;
+            q |= (uint32_t)(key[i][c] == thr) << c;
+        }
+        gt[i] = g << (4 * sub);
+        eq[i] = q << (4 * sub);
+    }
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+        gt[i] |= group8_exchange<0>(gt[i]);
+        eq[i] |= group8_exchange<0>(eq[i]);
+        gt[i] |= group8_exchange<1>(gt[i]);
+        eq[i] |= group8_exchange<1>(eq[i]);
+        gt[i] |= group8_exchange<2>(gt[i]);
+        eq[i] |= group8_exchange<2>(eq[i]);
+    }
+    int quota = K;
+#pragma unroll
+    for (int i = 0; i < NV; ++i) quota -= __popc(gt[i]);
+    // equal keys: lowest ids first, `quota` of them
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+        uint32_t w = eq[i];
+        const int c = __popc(w);
+        if (c <= quota) {
+            gt[i] |= w;
+            quota -= c;
+        } else {
+            while (quota > 0) {
+                const uint32_t b = w & (0u - w);
+                gt[i] |= b;
+                w ^= b;
+                --quota;
+            }
+        }
+    }
+    // lane `sub` emits the sub-th selected id
+    int want = sub, id = -1;
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+        uint32_t w = gt[i];
+        const int c = __popc(w);
+        if (id < 0) {
+            if (want < c) {
+                for (int j = 0; j < want; ++j) w &= w - 1u;
+                id = 32 * i + __ffs((int)w) - 1;
+            } else {
+                want -= c;
+            }
+        }
+    }
+    if (live) {
+        if (sub < K && id >= 0) idx[(int64_t)t * stride + sub] = (IdxT)id;
+        if (bad && status) atomicOr(status, R3_DATA_NONFINITE);
+    }
+}
+
+template <typename IdxT>
+static bool launch_record_vec(int T, int E, int K, const float *logits, int64_t ld, IdxT *idx, int64_t stride,
+                              int32_t *status, hipStream_t s) {
+    if (K > 8 || E % 32 != 0 || ld % 4 != 0 || ((uintptr_t)logits & 15)) return false;
+    const int grid = (T + 31) / 32;
+    switch (E / 32) {
+        case 2: record_topk_vec_kernel<IdxT, 2><<<grid, 256, 0, s>>>(T, K, logits, ld, idx, stride, status); return true;
+        case 4: record_topk_vec_kernel<IdxT, 4><<<grid, 256, 0, s>>>(T, K, logits, ld, idx, stride, status); return true;
+        case 8: record_topk_vec_kernel<IdxT, 8><<<grid, 256, 0, s>>>(T, K, logits, ld, idx, stride, status); return true;
+        default: return false;
+    }
+}
+
 hipError_t launch_record_topk(int T, int E, int K, const float *logits, int64_t ld, void *idx,
                               int idx_dtype, int64_t stride, int32_t *status, hipStream_t s) {
     ProfScope ps(PROF_RECORD, s);
+    if (idx_dtype == R3_IDX_U8 ? launch_record_vec(T, E, K, logits, ld, (uint8_t *)idx, stride, status, s)
+                               : launch_record_vec(T, E, K, logits, ld, (uint16_t *)idx, stride, status, s))
+        return hipGetLastError();
     if (K <= 8 && E <= 512) {
         const int EPL = (E + 7) / 8;
         const int grid = (T + 31) / 32;

@@ -45,7 +45,8 @@ def sync():
 @pytest.mark.parametrize("T,E,K,kind", [
     (256, 8, 2, "normal"), (4096, 128, 8, "normal"), (1000, 128, 8, "ties"), (333, 300, 4, "normal"),
     (100, 1024, 16, "normal"), (77, 128, 8, "nan"), (64, 64, 64, "normal"), (1, 128, 8, "normal"),
-    (129, 512, 8, "ties"), (200, 40, 9, "ties"),
+    (129, 512, 8, "ties"), (200, 40, 9, "ties"), (500, 256, 8, "ties"), (300, 64, 3, "ties"),
+    (1000, 128, 5, "ties"), (77, 256, 8, "nan"), (4099, 128, 1, "normal"), (2048, 64, 8, "normal"),
 ])
 def test_record_topk_bit_exact(T, E, K, kind):
     rng = np.random.default_rng(T * 1000 + E)
