@@ -171,6 +171,32 @@ def test_replay_gate_and_logits(name):
     assert torch.equal(gates, gates2)
 
 
+def test_recompute_routing_replay_is_plain_topk_gating():
+    """The variant that records from the training engine's own logits (Related Works, "Routing Replay"):
+    r3_record_topk on the layer's training logits, replayed into the same layer.  With an unchanged model
+    (mini step 1) the replay changes nothing: every token agrees, and the gates are the standard
+    top-K softmax gates (third equation of Section 4.1 = its replay-gate equation with I_infer = I_train)."""
+    c = Case(SHAPES["mfma_small"], backward=False)
+    sh, D = c.shape, c.D
+    gates = torch.empty(sh.T, sh.K, dtype=torch.float32, device="cuda")
+    logits = torch.empty(sh.T, sh.E, dtype=torch.float32, device="cuda")
+    rec = torch.zeros(sh.T, sh.K, dtype=r3.idx_torch_dtype(D), device="cuda")
+    ws = r3.workspace(D, r3.OP_REPLAY_GATE)
+    r3.replay_gate(D, c.t["x"], c.t["Wr"], rec, gates, logits_out=logits, ws=ws)       # training logits
+    r3.record_topk(D, logits, rec, None)                                               # recompute-stage record
+    agree = torch.zeros(2, dtype=torch.int64, device="cuda")
+    r3.replay_gate(D, c.t["x"], c.t["Wr"], rec, gates, agree_out=agree, ws=ws)         # update-stage replay
+    sync()
+    assert (int(agree[0]), int(agree[1])) == (sh.T, sh.T * sh.K)
+    lg = logits.cpu().numpy()
+    own = sparse.topk_mask(lg, sh.K)
+    assert np.array_equal(rec.cpu().numpy().astype(np.int32), own)
+    # standard gating from a library softmax over all experts, renormalised over the top-K set
+    p = torch.softmax(torch.from_numpy(lg.astype(np.float64)), dim=1).numpy()
+    sel = np.take_along_axis(p, own, axis=1)
+    assert_gates_close(gates.cpu().numpy(), sel / sel.sum(axis=1, keepdims=True))
+
+
 # ------------------------------------------------------------------ expert FFN and combine, step by step
 @pytest.mark.parametrize("name,simt", [("config1_f32", False), ("odd_bf16", False), ("mfma_small", False),
                                        ("mfma_ragged", False), ("mfma_fewexperts", False),
