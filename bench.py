@@ -257,6 +257,9 @@ def main():
         out["metric"] = "token-layers/sec for R3 record+replay forward over a %d-layer stack at 1 GPU" % L
     if not args.no_ceilings:
         out["ceilings"] = measured_ceilings(torch, r3, dev)
+        if roofline:   # context only: the same achieved rate against what this machine sustains on such data
+            roofline["frac_of_measured_ceiling"] = round(
+                roofline["achieved"] / out["ceilings"]["mfma_bf16_varied_operands_TFLOPs"], 4)
     if args.cpu_tokens > 0:
         del buf
         torch.cuda.empty_cache()
