@@ -6,6 +6,8 @@
 // operand addressing and epilogue.  Expert segments are ragged: a small kernel
 // turns `offsets` into a list of (expert, first row) row tiles on the device, so
 // nothing returns to the host between the permutation and the contractions.
+#include <type_traits>
+
 #include "r3_kernels.h"
 #include "r3_mfma.h"
 #include "r3_mfma2.h"
@@ -112,25 +114,42 @@ ffn1_kernel(int S, int d, int F, const bf16_t *__restrict__ Xp, const int32_t *_
     __shared__ int mailbox[2];
     constexpr int BF = 128;  // features per tile
     const int npt = F / BF;
-    TileLoop tl(tiles[0] * npt, tile_counters(tiles, launch));
-    for (int slot = tl.first(); tl.valid(slot); slot = tl.finish(mailbox)) {
-    const int id = tl.id(slot);
-    const int tile = id / npt, pt = id - tile * npt;
-    const int e = tiles[kTileHdr + 2 * tile], row0 = tiles[kTileHdr + 1 + 2 * tile];
-    const int row_end = offsets[e + 1];
-    const int f0 = pt * BF;
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int wp = wave % kWP2, wq = wave / kWP2;
-
     OpTR128x2 P;
-    P.src[0] = Src{(const char *)(Wg + (int64_t)e * d * F), clamp_bytes((int64_t)d * F * 2), (uint32_t)(kBK2 * F * 2)};
-    P.src[1] = Src{(const char *)(Wu + (int64_t)e * d * F), clamp_bytes((int64_t)d * F * 2), (uint32_t)(kBK2 * F * 2)};
-    P.init(F * 2, f0 * 2, 64 * wp);
+    P.init(F * 2, 0, 64 * wp);
     OpKC256 Q;
-    Q.src[0] = Src{(const char *)(Xp + (int64_t)row0 * d), clamp_bytes((int64_t)(S - row0) * d * 2), kBK2 * 2};
-    Q.src[1] = Q.src[0];
     Q.kswitch = 0x7fffffff;
     Q.init(d * 2, kWaveRowsQ * wq);
+    TileLoopStatic tl(tiles[0] * npt, tile_counters(tiles, launch));
+    struct Tile {
+        int e, row0, row_end, f0;
+    };
+    auto decode = [&](int slot_) {
+        const int id = tl.id(slot_);
+        const int tile = id / npt, pt = id - tile * npt;
+        Tile t;
+        t.e = tiles[kTileHdr + 2 * tile];
+        t.row0 = tiles[kTileHdr + 1 + 2 * tile];
+        t.row_end = offsets[t.e + 1];
+        t.f0 = pt * BF;
+        return t;
+    };
+    auto aim = [&](const Tile &t) {   // point the operands at a tile
+        const int64_t wb = ((int64_t)d * F - t.f0) * 2;
+        P.src[0] = Src{(const char *)(Wg + (int64_t)t.e * d * F + t.f0), clamp_bytes(wb), (uint32_t)(kBK2 * F * 2)};
+        P.src[1] = Src{(const char *)(Wu + (int64_t)t.e * d * F + t.f0), clamp_bytes(wb), (uint32_t)(kBK2 * F * 2)};
+        Q.src[0] = Src{(const char *)(Xp + (int64_t)t.row0 * d), clamp_bytes((int64_t)(S - t.row0) * d * 2), kBK2 * 2};
+        Q.src[1] = Q.src[0];
+    };
+    if (!tl.valid(tl.first())) return;
+    Tile cur = decode(tl.first());
+    for (int slot = tl.first(), next = tl.second(); tl.valid(slot);) {
+    // the next tile's coordinates are fetched now (scalar loads), a whole tile before their use
+    const bool more = tl.valid(next);
+    const Tile nxt = more ? decode(next) : cur;
+    const int e = cur.e, row0 = cur.row0, row_end = cur.row_end, f0 = cur.f0;
+    aim(cur);
 
     Acc2 acc;
     zero_acc2(acc);
@@ -166,6 +185,10 @@ ffn1_kernel(int S, int d, int F, const bf16_t *__restrict__ Xp, const int32_t *_
             st.flush((char *)dst + o, (int64_t)F * 2, valid);
         }
     }
+    const int after = tl.finish(mailbox);
+    slot = next;
+    next = after;
+    cur = nxt;
     }
 }
 
@@ -192,52 +215,61 @@ rowgemm_kernel(int S, int d, int F, const bf16_t *__restrict__ Q0, const bf16_t 
     const int NOUT = (MODE == 1) ? F : d;  // width of the output
     const int KQ = (MODE == 1) ? d : F;    // width of the Q source rows
     const int npt = NOUT / kTile;
-    TileLoop tl(tiles[0] * npt, tile_counters(tiles, launch));
-    for (int slot = tl.first(); tl.valid(slot); slot = tl.finish(mailbox)) {
-    const int id = tl.id(slot);
-    const int tile = id / npt, pt = id - tile * npt;
-    const int e = tiles[kTileHdr + 2 * tile], row0 = tiles[kTileHdr + 1 + 2 * tile];
-    const int row_end = offsets[e + 1];
-    const int p0 = pt * kTile;
+    const int nk = (MODE == 0) ? F / kBK2 : (MODE == 1) ? d / kBK2 : 2 * (F / kBK2);
     const int wave = threadIdx.x >> 6;
     const int wp = wave % kWP2, wq = wave / kWP2;
-    const bf16_t *w0 = W0 + (int64_t)e * d * F;
-
+    // operand forms: the weights are feature-contiguous (TR) for MODE 0, K-contiguous otherwise
+    typedef typename std::conditional<MODE == 0, OpTR256, OpKC256>::type POp;
+    POp P;
     OpKC256 Q;
-    Q.src[0] = Src{(const char *)(Q0 + (int64_t)row0 * KQ), clamp_bytes((int64_t)(S - row0) * KQ * 2), kBK2 * 2};
-    Q.src[1] = Q.src[0];
-    Q.kswitch = 0x7fffffff;
-    if constexpr (MODE == 2) {
-        Q.src[1] = Src{(const char *)(Q1 + (int64_t)row0 * KQ), clamp_bytes((int64_t)(S - row0) * KQ * 2), kBK2 * 2};
-        Q.kswitch = F / kBK2;
-    }
+    P.kswitch = Q.kswitch = (MODE == 2) ? F / kBK2 : 0x7fffffff;
+    if constexpr (MODE == 0) P.init(d * 2, 0, 128 * wp);
+    else P.init((MODE == 1 ? d : F) * 2, 128 * wp);
     Q.init(KQ * 2, kWaveRowsQ * wq);
+    TileLoopStatic tl(tiles[0] * npt, tile_counters(tiles, launch));
+    struct Tile {
+        int e, row0, row_end, p0;
+    };
+    auto decode = [&](int slot_) {
+        const int id = tl.id(slot_);
+        const int tile = id / npt, pt = id - tile * npt;
+        Tile t;
+        t.e = tiles[kTileHdr + 2 * tile];
+        t.row0 = tiles[kTileHdr + 1 + 2 * tile];
+        t.row_end = offsets[t.e + 1];
+        t.p0 = pt * kTile;
+        return t;
+    };
+    auto aim = [&](const Tile &t) {   // point the operands at a tile
+        const bf16_t *w0 = W0 + (int64_t)t.e * d * F;
+        Q.src[0] = Src{(const char *)(Q0 + (int64_t)t.row0 * KQ), clamp_bytes((int64_t)(S - t.row0) * KQ * 2), kBK2 * 2};
+        Q.src[1] = Q.src[0];
+        if constexpr (MODE == 2)
+            Q.src[1] = Src{(const char *)(Q1 + (int64_t)t.row0 * KQ), clamp_bytes((int64_t)(S - t.row0) * KQ * 2), kBK2 * 2};
+        if constexpr (MODE == 0) {
+            P.src[0] = Src{(const char *)(w0 + t.p0), clamp_bytes(((int64_t)d * F - t.p0) * 2), (uint32_t)(kBK2 * d * 2)};
+            P.src[1] = P.src[0];
+        } else if constexpr (MODE == 1) {
+            P.src[0] = Src{(const char *)(w0 + (int64_t)t.p0 * d), clamp_bytes((int64_t)(F - t.p0) * d * 2), kBK2 * 2};
+            P.src[1] = P.src[0];
+        } else {
+            const bf16_t *w1 = W1 + (int64_t)t.e * d * F;
+            P.src[0] = Src{(const char *)(w0 + (int64_t)t.p0 * F), clamp_bytes((int64_t)(d - t.p0) * F * 2), kBK2 * 2};
+            P.src[1] = Src{(const char *)(w1 + (int64_t)t.p0 * F), clamp_bytes((int64_t)(d - t.p0) * F * 2), kBK2 * 2};
+        }
+    };
+    if (!tl.valid(tl.first())) return;
+    Tile cur = decode(tl.first());
+    for (int slot = tl.first(), next = tl.second(); tl.valid(slot);) {
+    // the next tile's coordinates are fetched now (scalar loads), a whole tile before their use
+    const bool more = tl.valid(next);
+    const Tile nxt = more ? decode(next) : cur;
+    const int row0 = cur.row0, row_end = cur.row_end, p0 = cur.p0;
+    aim(cur);
 
     Acc2 acc;
     zero_acc2(acc);
-    if constexpr (MODE == 0) {
-        OpTR256 P;
-        P.src[0] = Src{(const char *)w0, clamp_bytes((int64_t)d * F * 2), (uint32_t)(kBK2 * d * 2)};
-        P.src[1] = P.src[0];
-        P.kswitch = 0x7fffffff;
-        P.init(d * 2, p0 * 2, 128 * wp);
-        mfma_mainloop2(acc, F / kBK2, P, Q, s0, s1, s2, s3, row_end - row0 > 128);
-    } else if constexpr (MODE == 1) {
-        OpKC256 P;
-        P.src[0] = Src{(const char *)(w0 + (int64_t)p0 * d), clamp_bytes((int64_t)(F - p0) * d * 2), kBK2 * 2};
-        P.src[1] = P.src[0];
-        P.kswitch = 0x7fffffff;
-        P.init(d * 2, 128 * wp);
-        mfma_mainloop2(acc, d / kBK2, P, Q, s0, s1, s2, s3, row_end - row0 > 128);
-    } else {
-        const bf16_t *w1 = W1 + (int64_t)e * d * F;
-        OpKC256 P;
-        P.src[0] = Src{(const char *)(w0 + (int64_t)p0 * F), clamp_bytes((int64_t)(d - p0) * F * 2), kBK2 * 2};
-        P.src[1] = Src{(const char *)(w1 + (int64_t)p0 * F), clamp_bytes((int64_t)(d - p0) * F * 2), kBK2 * 2};
-        P.kswitch = F / kBK2;
-        P.init(F * 2, 128 * wp);
-        mfma_mainloop2(acc, 2 * (F / kBK2), P, Q, s0, s1, s2, s3, row_end - row0 > 128);
-    }
+    mfma_mainloop2(acc, nk, P, Q, s0, s1, s2, s3, row_end - row0 > 128);
     tl.prefetch();
 
     // per wave: 64 rows x 128 features, 32 rows at a time through LDS
@@ -264,6 +296,7 @@ rowgemm_kernel(int S, int d, int F, const bf16_t *__restrict__ Q0, const bf16_t 
             const int tq = r >> 1, half = r & 1;
             sa.deposit(ra);
             sb.deposit(rb);
+
             if (r + 1 < 2 * kTQ2) {
                 int nvalid;
                 const int64_t noh = where(r + 1, nvalid);
@@ -309,6 +342,10 @@ rowgemm_kernel(int S, int d, int F, const bf16_t *__restrict__ Q0, const bf16_t 
             st.flush((char *)out0 + o, (int64_t)NOUT * 2, valid);
         }
     }
+    const int after = tl.finish(mailbox);
+    slot = next;
+    next = after;
+    cur = nxt;
     }
 }
 
@@ -328,7 +365,7 @@ wgrad_kernel(int E, int NQd, int NPd, const bf16_t *__restrict__ Qs, const bf16_
     __shared__ int mailbox[2];
     const int nqt = NQd / kTile, npt = NPd / kTile;
     TileLoop tl(E * nqt * npt, ctr);
-    for (int slot = tl.first(); tl.valid(slot); slot = tl.finish(mailbox)) {
+    for (int slot = tl.first(), next = tl.second(); tl.valid(slot);) {
     const int id = tl.id(slot);
     const int eo = id / (nqt * npt);
     const int rem = id - eo * nqt * npt;
@@ -377,6 +414,9 @@ wgrad_kernel(int E, int NQd, int NPd, const bf16_t *__restrict__ Qs, const bf16_
             const int64_t off = ((int64_t)(q0 + wq * kWaveRowsQ + tq * 32) * NPd + p0 + wp * 128 + half * 64) * 4;
             st.flush_f32(o + off, (int64_t)NPd * 4, 32, accumulate);
         }
+    const int after = tl.finish(mailbox);
+    slot = next;
+    next = after;
     }
 }
 
@@ -399,7 +439,7 @@ wgrad_pair_kernel(int E, int NQd, int NPd, const bf16_t *__restrict__ Qs, const 
     constexpr int BF = 128;  // features of P0 (and of P1) per tile
     const int nqt = NQd / kTile, npt = NPd / BF;
     TileLoop tl(E * nqt * npt, ctr);
-    for (int slot = tl.first(); tl.valid(slot); slot = tl.finish(mailbox)) {
+    for (int slot = tl.first(), next = tl.second(); tl.valid(slot);) {
     const int id = tl.id(slot);
     const int eo = id / (nqt * npt);
     const int rem = id - eo * nqt * npt;
@@ -449,6 +489,9 @@ wgrad_pair_kernel(int E, int NQd, int NPd, const bf16_t *__restrict__ Qs, const 
             const int64_t off = ((int64_t)(q0 + wq * kWaveRowsQ + tq * 32) * NPd + p0 + wp * 64) * 4;
             st.flush_f32(o + off, (int64_t)NPd * 4, 32, accumulate);
         }
+    const int after = tl.finish(mailbox);
+    slot = next;
+    next = after;
     }
 }
 

@@ -354,39 +354,57 @@ __device__ __forceinline__ void mfma_mainloop2(Acc2 &acc, int nk, const POp &P, 
 // Persistent work-groups.  A launch has one work-group per compute unit; each walks the tile
 // list instead of ending after one tile, so a tile's stores drain while the next tile's first
 // loads are in flight and no work-group launch sits between two tiles.  The XCD-aware order
-// of xcd_tile_id() is kept: XCD x owns tile ids [x*per, (x+1)*per).  The first tile of a
-// work-group is fixed by its index; later ones come from a per-XCD counter (zeroed before
-// the launch), so that slow and fast compute units even out.  The counter is fetched with a
-// vector atomic by one thread, between the tile loop (all its loads drained) and
-// the epilogue (whose duration hides the round trip, and where the fragment registers are
-// free to hold the answer); `mailbox` is two ints of LDS outside the stage buffers (alternating, so that a wave
-// that is still reading one tile's slot cannot see the next one's).
+// of xcd_tile_id() is kept: XCD x owns tile ids [x*per, (x+1)*per).  The first two tiles of a
+// work-group are fixed by its index; later ones come from a per-XCD counter (zeroed before
+// the launch), so that slow and fast compute units even out, or, where all tiles take about
+// the same time, simply follow round-robin.  The queue runs two tiles ahead:
+// while tile i is worked on, tile i+1 is already known (its coordinates are fetched a whole
+// tile before they are needed), and tile i+2 is asked for between tile i's loop (all its loads
+// drained) and its epilogue (whose duration hides most of the round trip of the vector atomic,
+// and where the fragment registers are free to hold the answer).  (Pulling the next tile's
+// first stages into L2 during the epilogue, with loads into an LDS sink, was measured: no gain.)
+// `mailbox` is two ints of LDS outside the stage buffers (alternating, so that a wave that is
+// still reading one tile's slot cannot see the next one's).
 constexpr int kQueueThread = 0;
 
-struct TileLoop {
+// DYNAMIC = false: plain round-robin (slot, slot + stride, ...), for kernels whose tiles all
+// take about the same time; nothing is fetched, so no wave waits for an atomic's round trip.
+template <bool DYNAMIC>
+struct TileLoopT {
     int total, per, xcd, stride, iter, nxt;
     int *ctr;
-    __device__ __forceinline__ TileLoop(int total_, int *ctr_row)
+    __device__ __forceinline__ TileLoopT(int total_, int *ctr_row)
         : total(total_), per((total_ + 7) >> 3), xcd(blockIdx.x & 7), stride(gridDim.x >> 3), iter(0), nxt(0),
           ctr(ctr_row + (blockIdx.x & 7)) {}
     __device__ __forceinline__ int first() const { return blockIdx.x >> 3; }
+    __device__ __forceinline__ int second() const { return (blockIdx.x >> 3) + stride; }
     __device__ __forceinline__ bool valid(int slot) const { return slot < per && xcd * per + slot < total; }
     __device__ __forceinline__ int id(int slot) const { return xcd * per + slot; }
-    // ask for the slot after this one; call after the tile loop
+    // ask for the slot two after the current one; call after the tile loop
     __device__ __forceinline__ void prefetch() {
-        if (threadIdx.x == kQueueThread) nxt = stride + atomicAdd(ctr, 1);
+        if constexpr (DYNAMIC)
+            if (threadIdx.x == kQueueThread) nxt = 2 * stride + atomicAdd(ctr, 1);
     }
     // end of a tile: every wave's LDS traffic of the epilogue is complete and the waves have
-    // met before anyone loads the next tile into the stage buffers; returns the next slot
+    // met before anyone loads the next tile into the stage buffers; returns the slot two after
+    // the current one
     __device__ __forceinline__ int finish(volatile int *mailbox) {
-        volatile int *box = mailbox + (iter & 1);
-        if (threadIdx.x == kQueueThread) *box = nxt;
-        // not __syncthreads(): its fence would also wait for this tile's global stores
-        asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
-        ++iter;
-        return *box;
+        if constexpr (DYNAMIC) {
+            volatile int *box = mailbox + (iter & 1);
+            if (threadIdx.x == kQueueThread) *box = nxt;
+            // not __syncthreads(): its fence would also wait for this tile's global stores
+            asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+            ++iter;
+            return *box;
+        } else {
+            asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+            ++iter;
+            return first() + (iter + 1) * stride;
+        }
     }
 };
+typedef TileLoopT<true> TileLoop;          // tiles of uneven length (weight gradients)
+typedef TileLoopT<false> TileLoopStatic;   // tiles of even length (row tiles)
 
 // Epilogue staging.  The MFMA result layout gives a lane 4 consecutive features of ONE row
 // per register quad, so direct stores are 16-byte pieces scattered over 32 rows per
