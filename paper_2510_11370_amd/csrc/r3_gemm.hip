@@ -364,6 +364,13 @@ wgrad_kernel(int E, int NQd, int NPd, const bf16_t *__restrict__ Qs, const bf16_
     __shared__ __attribute__((aligned(1024))) char s3[kStageBytes];
     __shared__ int mailbox[2];
     const int nqt = NQd / kTile, npt = NPd / kTile;
+    const int wave = threadIdx.x >> 6;
+    const int wp = wave % kWP2, wq = wave / kWP2;
+    // operands are set up once; a tile only moves their source windows (column offset included)
+    OpTR256 P, Q;
+    P.kswitch = Q.kswitch = 0x7fffffff;
+    P.init(NPd * 2, 0, 128 * wp);
+    Q.init(NQd * 2, 0, kWaveRowsQ * wq);
     TileLoop tl(E * nqt * npt, ctr);
     for (int slot = tl.first(), next = tl.second(); tl.valid(slot);) {
     const int id = tl.id(slot);
@@ -373,20 +380,12 @@ wgrad_kernel(int E, int NQd, int NPd, const bf16_t *__restrict__ Qs, const bf16_
     const int qt = rem / npt, pt = rem - qt * npt;
     const int r0 = offsets[e], r1 = offsets[e + 1];
     const int q0 = qt * kTile, p0 = pt * kTile;
-    const int wave = threadIdx.x >> 6;
-    const int wp = wave % kWP2, wq = wave / kWP2;
-
-    OpTR256 P, Q;
-    P.src[0] = Src{(const char *)(Ps + (int64_t)r0 * NPd), clamp_bytes((int64_t)(r1 - r0) * NPd * 2),
+    P.src[0] = Src{(const char *)(Ps + (int64_t)r0 * NPd + p0), clamp_bytes(((int64_t)(r1 - r0) * NPd - p0) * 2),
                    (uint32_t)(kBK2 * NPd * 2)};
     P.src[1] = P.src[0];
-    P.kswitch = 0x7fffffff;
-    P.init(NPd * 2, p0 * 2, 128 * wp);
-    Q.src[0] = Src{(const char *)(Qs + (int64_t)r0 * NQd), clamp_bytes((int64_t)(r1 - r0) * NQd * 2),
+    Q.src[0] = Src{(const char *)(Qs + (int64_t)r0 * NQd + q0), clamp_bytes(((int64_t)(r1 - r0) * NQd - q0) * 2),
                    (uint32_t)(kBK2 * NQd * 2)};
     Q.src[1] = Q.src[0];
-    Q.kswitch = 0x7fffffff;
-    Q.init(NQd * 2, q0 * 2, kWaveRowsQ * wq);
 
     Acc2 acc;
     zero_acc2(acc);
@@ -438,6 +437,13 @@ wgrad_pair_kernel(int E, int NQd, int NPd, const bf16_t *__restrict__ Qs, const 
     __shared__ int mailbox[2];
     constexpr int BF = 128;  // features of P0 (and of P1) per tile
     const int nqt = NQd / kTile, npt = NPd / BF;
+    const int wave = threadIdx.x >> 6;
+    const int wp = wave % kWP2, wq = wave / kWP2;
+    OpTR128x2 P;
+    P.init(NPd * 2, 0, 64 * wp);
+    OpTR256 Q;
+    Q.kswitch = 0x7fffffff;
+    Q.init(NQd * 2, 0, kWaveRowsQ * wq);
     TileLoop tl(E * nqt * npt, ctr);
     for (int slot = tl.first(), next = tl.second(); tl.valid(slot);) {
     const int id = tl.id(slot);
@@ -447,21 +453,12 @@ wgrad_pair_kernel(int E, int NQd, int NPd, const bf16_t *__restrict__ Qs, const 
     const int qt = rem / npt, pt = rem - qt * npt;
     const int r0 = offsets[e], r1 = offsets[e + 1];
     const int q0 = qt * kTile, p0 = pt * BF;
-    const int wave = threadIdx.x >> 6;
-    const int wp = wave % kWP2, wq = wave / kWP2;
-
-    OpTR128x2 P;
-    P.src[0] = Src{(const char *)(P0 + (int64_t)r0 * NPd), clamp_bytes((int64_t)(r1 - r0) * NPd * 2),
-                   (uint32_t)(kBK2 * NPd * 2)};
-    P.src[1] = Src{(const char *)(P1 + (int64_t)r0 * NPd), clamp_bytes((int64_t)(r1 - r0) * NPd * 2),
-                   (uint32_t)(kBK2 * NPd * 2)};
-    P.init(NPd * 2, p0 * 2, 64 * wp);
-    OpTR256 Q;
-    Q.src[0] = Src{(const char *)(Qs + (int64_t)r0 * NQd), clamp_bytes((int64_t)(r1 - r0) * NQd * 2),
+    const uint64_t pbytes = clamp_bytes(((int64_t)(r1 - r0) * NPd - p0) * 2);
+    P.src[0] = Src{(const char *)(P0 + (int64_t)r0 * NPd + p0), pbytes, (uint32_t)(kBK2 * NPd * 2)};
+    P.src[1] = Src{(const char *)(P1 + (int64_t)r0 * NPd + p0), pbytes, (uint32_t)(kBK2 * NPd * 2)};
+    Q.src[0] = Src{(const char *)(Qs + (int64_t)r0 * NQd + q0), clamp_bytes(((int64_t)(r1 - r0) * NQd - q0) * 2),
                    (uint32_t)(kBK2 * NQd * 2)};
     Q.src[1] = Q.src[0];
-    Q.kswitch = 0x7fffffff;
-    Q.init(NQd * 2, q0 * 2, kWaveRowsQ * wq);
 
     Acc2 acc;
     zero_acc2(acc);

@@ -64,7 +64,7 @@ typedef __attribute__((address_space(3))) void *lds_void_ptr;
 // `step` is how far one k-tile advances.
 struct Src {
     const char *base;
-    uint32_t nbytes;
+    uint64_t nbytes;   // a segment may exceed 4 GB; each descriptor sees at most 2 GB of what is left
     uint32_t step;
 };
 
@@ -72,7 +72,8 @@ typedef int rsrc_t __attribute__((ext_vector_type(4)));  // buffer descriptor wo
 
 __device__ __forceinline__ rsrc_t src_rsrc(const Src &s, int kt) {
     const uint64_t adv = (uint64_t)kt * s.step;
-    const uint32_t left = adv < s.nbytes ? (uint32_t)(s.nbytes - adv) : 0u;
+    const uint64_t rest = adv < s.nbytes ? s.nbytes - adv : 0u;
+    const uint32_t left = rest > 0x7fffffffu ? 0x7fffffffu : (uint32_t)rest;
     const uint64_t b = (uint64_t)(s.base + adv);
     // the words are wave-uniform by construction; readfirstlane makes that visible to the
     // compiler so that they live in SGPRs
@@ -502,8 +503,6 @@ __device__ __forceinline__ void for_each_quad2(F f) {
                 f(tp, tq, g, wp * 128 + tp * 32 + g * 8 + (lane >> 5) * 4, wq * kWaveRowsQ + tq * 32 + (lane & 31));
 }
 
-__device__ __forceinline__ uint32_t clamp_bytes(int64_t b) {
-    return b <= 0 ? 0u : (b > 0x7fffffffLL ? 0x7fffffffu : (uint32_t)b);
-}
+__device__ __forceinline__ uint64_t clamp_bytes(int64_t b) { return b <= 0 ? 0u : (uint64_t)b; }
 
 }  // namespace r3
