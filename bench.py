@@ -107,6 +107,63 @@ def measured_ceilings(torch, r3, dev):
     return out
 
 
+def bench_diagnostics(args, torch, r3, dev):
+    """Secondary workload: the Section 3 diagnostics on a record pair of the 48-layer configuration's size and
+    on 10 M token log-probabilities (the sample size of the paper's scatter plot)."""
+    L, T, K, E, n = 48, 131072, 8, 128, 10_000_000
+    g = torch.Generator(device=dev).manual_seed(1)
+    a = torch.rand(L, T, E, generator=g, device=dev).argsort(dim=2)[:, :, :K].sort(dim=2).values.to(torch.uint8)
+    b = a.clone()
+    hit = torch.rand(L, T, generator=g, device=dev) < 0.1
+    b[hit] = torch.rand(int(hit.sum()), E, generator=g, device=dev).argsort(dim=1)[:, :K].to(torch.uint8)
+    D = r3.desc(T, 16, E, K, 16)
+    hist = torch.zeros(K + 1, dtype=torch.int64, device=dev)
+    tc = torch.empty(T, dtype=torch.int32, device=dev)
+    tr = torch.empty(T, dtype=torch.int32, device=dev)
+    so = torch.arange(0, T + 1, 2048, dtype=torch.int32, device=dev)
+    sm = torch.empty(so.numel() - 1, dtype=torch.float64, device=dev)
+    li = torch.log(torch.rand(n, generator=g, device=dev).clamp_min(1e-4))
+    lt = li + 0.05 * torch.randn(n, generator=g, device=dev)
+    kl = torch.zeros(1, dtype=torch.float64, device=dev)
+    taus = [1.0, 1.5, 2.0, 4.0, 10.0]
+    frac = torch.zeros(len(taus), dtype=torch.float64, device=dev)
+    ws = torch.empty(256 << 10, dtype=torch.uint8, device=dev)
+
+    def step():
+        r3.routing_diff(D, L, a, b, T * K, hist, tc, tr, so, sm)
+        r3.policy_discrepancy(lt, li, taus, kl, frac, ws)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    r3.profile_enable(True)
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    prof = r3.profile_read()
+    r3.profile_enable(False)
+    work = {"routing_diff": 2 * L * T * K + 8 * T, "policy_discrepancy": 8 * n}
+    kernels = {}
+    for name, (ms, cnt) in prof.items():
+        gbs = work[name] / (ms / cnt) * 1e-6
+        kernels[name] = {"bound": "hbm", "avg_ms": round(ms / cnt, 4), "launches_per_step": cnt // args.steps,
+                         "achieved": round(gbs, 1), "unit": "GB/s", "frac": round(gbs / PEAK_HBM_GBS, 4)}
+    ms_per_step = wall * 1e3 / args.steps
+    dom = max(kernels, key=lambda k: kernels[k]["avg_ms"])
+    print(json.dumps({
+        "metric": "routers compared/sec (two 48x131072x8 records) with a 10M-token policy discrepancy, 1 GPU",
+        "value": round(L * T / (ms_per_step * 1e-3), 1), "unit": "routers/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "u8", "data": "synthetic (seeded)",
+        "config": {"workload": "diagnostics: routing_diff L=48 T=131072 K=8 E=128 uint8 + policy_discrepancy n=1e7",
+                   "kl_k3": kl.item(), "F_tau": dict(zip(map(str, taus), frac.cpu().tolist()))},
+        "roofline": {"kernel": dom, "bound": "hbm", "achieved": kernels[dom]["achieved"], "peak": PEAK_HBM_GBS,
+                     "unit": "GB/s", "frac": kernels[dom]["frac"], "traffic": None},
+        "kernels": kernels}))
+
+
 def stored_traffic(workload, kernel):
     """HBM bytes per launch (fetch + write) of `kernel` from the committed counter summary of this workload
     (two rocprofv3 --pmc runs of this script, scaled by the calibration copy), or None if there is none."""
@@ -142,6 +199,9 @@ def main():
     from paper_2510_11370_amd import r3, synth
     if not torch.cuda.is_available():
         sys.exit("bench.py: no GPU visible")
+    if args.workload == "diagnostics":
+        torch.cuda.set_device(0)
+        return bench_diagnostics(args, torch, r3, "cuda")
     sh = synth.CONFIGS[args.workload]
     dev = "cuda"
     torch.cuda.set_device(0)

@@ -159,6 +159,45 @@ int r3_moe_backward(const r3_layer_desc *desc, const void *dy, const void *x,
                     int accumulate, void *ws, size_t ws_bytes, void *stream);
 
 /*
+ * Routing differences between two records of the same tokens (Section 3.2:
+ * router-level, token-level and sequence-level comparison).  idx_a, idx_b:
+ * device records of L layers, dtype desc->idx, K ids per router in any order;
+ * the ids of token t in layer l start at element l*layer_stride +
+ * t*token_stride (token_stride = desc->idx_token_stride, K if 0; layer-major
+ * [L][T][K]: layer_stride = T*K; token-major [T][L][K]: token stride L*K,
+ * layer_stride = K).  d = K - |A n B| is the number of differing choices of
+ * one router.  Outputs (device): router_hist [K+1] int64, ADDED to (clear it
+ * first): routers with d = 0..K;  token_choices [T] int32: d summed over the
+ * layers;  token_routers [T] int32: layers with d > 0;  seq_mean [nseq] f64
+ * or NULL: mean of token_routers over tokens seq_offsets[s]..seq_offsets[s+1]
+ * (device int32 [nseq+1], ascending, within [0,T]).  Only T, K, E, idx and
+ * idx_token_stride of desc are used.  All counts are exact.
+ */
+int r3_routing_diff(const r3_layer_desc *desc, int L, const void *idx_a, const void *idx_b,
+                    int64_t layer_stride, const int32_t *seq_offsets, int nseq,
+                    int64_t *router_hist, int32_t *token_choices, int32_t *token_routers,
+                    double *seq_mean, void *stream);
+
+/*
+ * Policy discrepancy over n response tokens (Section 3.1): from the float32
+ * log-probabilities of the sampled tokens under the training engine
+ * (logp_train) and the inference engine (logp_infer), both device [n],
+ *   *kl_out   = mean of r - 1 - log r,  r = exp(logp_train - logp_infer)
+ *               (the k3 estimate of KL(pi_train || pi_infer), "KL Divergence
+ *               Estimation"; evaluated in f64, fixed summation order),
+ *   frac_out[i] = share of tokens with max(r, 1/r) > tau[i] (the extreme token
+ *               distribution function F(tau)); the test |log r| > log tau is
+ *               taken in float32 on the float32 difference, with
+ *               log tau = float32(log(float64(tau))).
+ * tau: HOST pointer, ntau <= 8 values >= 1 (read during the call); kl_out,
+ * frac_out: device f64.  ws: device workspace of r3_policy_workspace_bytes().
+ */
+int r3_policy_discrepancy(int64_t n, const float *logp_train, const float *logp_infer, int ntau,
+                          const float *tau, double *kl_out, double *frac_out, void *ws,
+                          size_t ws_bytes, void *stream);
+size_t r3_policy_workspace_bytes(void);
+
+/*
  * Measurement aid (not part of the method): per-kernel timing with HIP events
  * recorded on the launch stream.  r3_profile_enable(1) clears the counters and
  * starts recording (at most 512 launches per kernel are kept), (0) stops.

@@ -228,4 +228,38 @@ int r3_moe_backward(const r3_layer_desc *desc, const void *dy, const void *x, co
                                    s));
 }
 
+int r3_routing_diff(const r3_layer_desc *desc, int L, const void *idx_a, const void *idx_b, int64_t layer_stride,
+                    const int32_t *seq_offsets, int nseq, int64_t *router_hist, int32_t *token_choices,
+                    int32_t *token_routers, double *seq_mean, void *stream) {
+    Dims m;
+    int rc = check_desc(desc, m);
+    if (rc) return rc;
+    if (L <= 0 || !idx_a || !idx_b || layer_stride < m.K || !router_hist || !token_choices || !token_routers ||
+        nseq < 0 || (seq_mean && (!seq_offsets || nseq == 0)))
+        return R3_ERR_INVALID_ARG;
+    if (!aligned(router_hist, 8) || !aligned(token_choices, 4) || !aligned(token_routers, 4) ||
+        (seq_mean && (!aligned(seq_mean, 8) || !aligned(seq_offsets, 4))) ||
+        (m.idx == R3_IDX_U16 && (!aligned(idx_a, 2) || !aligned(idx_b, 2))))
+        return R3_ERR_INVALID_ARG;
+    return hip_rc(launch_routing_diff(m.T, m.K, L, idx_a, idx_b, m.idx, m.stride, layer_stride, seq_offsets,
+                                      seq_mean ? nseq : 0, router_hist, token_choices, token_routers, seq_mean,
+                                      (hipStream_t)stream));
+}
+
+size_t r3_policy_workspace_bytes(void) { return policy_ws_bytes(); }
+
+int r3_policy_discrepancy(int64_t n, const float *logp_train, const float *logp_infer, int ntau, const float *tau,
+                          double *kl_out, double *frac_out, void *ws, size_t ws_bytes, void *stream) {
+    if (n < 0 || ntau < 0 || ntau > policy_max_tau() || !kl_out || (ntau > 0 && (!tau || !frac_out)) ||
+        (n > 0 && (!logp_train || !logp_infer)))
+        return R3_ERR_INVALID_ARG;
+    for (int i = 0; i < ntau; ++i)
+        if (!(tau[i] >= 1.0f)) return R3_ERR_INVALID_ARG;
+    if (!aligned(logp_train, 4) || !aligned(logp_infer, 4) || !aligned(kl_out, 8) || (frac_out && !aligned(frac_out, 8)))
+        return R3_ERR_INVALID_ARG;
+    if (!ws || ws_bytes < policy_ws_bytes() || !aligned(ws, 256)) return R3_ERR_WORKSPACE;
+    return hip_rc(launch_policy_discrepancy(n, logp_train, logp_infer, ntau, tau, kl_out, frac_out, ws,
+                                            (hipStream_t)stream));
+}
+
 }  // extern "C"

@@ -9,7 +9,7 @@ namespace r3 {
 enum ProfTag {
     PROF_RECORD = 0, PROF_LOGITS, PROF_GATE, PROF_PERMUTE_INDEX, PROF_GATHER_ROWS, PROF_FFN1, PROF_FFN2,
     PROF_COMBINE, PROF_GATE_BWD, PROF_DWR, PROF_DH, PROF_WGRAD, PROF_DXP, PROF_DX_FINISH, PROF_WGRAD_PAIR,
-    PROF_NTAGS
+    PROF_ROUTING_DIFF, PROF_POLICY, PROF_NTAGS
 };
 struct ProfScope {
     int tag, slot;
@@ -41,6 +41,15 @@ hipError_t launch_dx_finish(int T, int d, int E, int K, int act, const void *dXp
                             int64_t stride, void *dx, hipStream_t s);
 hipError_t launch_transpose(int R, int C, int act, const void *in, void *out, hipStream_t s);
 hipError_t launch_colsum(int T, int E, int act, const void *ds, float *out, int accumulate, hipStream_t s);
+
+// r3_diag.hip
+size_t policy_ws_bytes();
+int policy_max_tau();
+hipError_t launch_routing_diff(int T, int K, int L, const void *a, const void *b, int idx_dtype, int64_t token_stride,
+                               int64_t layer_stride, const int32_t *seq_offsets, int nseq, int64_t *router_hist,
+                               int32_t *token_choices, int32_t *token_routers, double *seq_mean, hipStream_t s);
+hipError_t launch_policy_discrepancy(int64_t n, const float *lt, const float *li, int ntau, const float *tau_host,
+                                     double *kl, double *frac, void *ws, hipStream_t s);
 
 // r3_simt.hip
 hipError_t simt_router_logits(int T, int d, int E, int act, const void *x, const void *Wr, const float *bias,

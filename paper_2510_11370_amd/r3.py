@@ -21,7 +21,8 @@ _STATUS = {1: "R3_ERR_INVALID_ARG", 2: "R3_ERR_UNSUPPORTED", 3: "R3_ERR_WORKSPAC
 EXPORTS = ["r3_version", "r3_workspace_bytes", "r3_record_topk", "r3_replay_gate", "r3_permute",
            "r3_grouped_ffn", "r3_combine", "r3_moe_backward", "r3_profile_enable", "r3_profile_tags",
            "r3_profile_name", "r3_profile_read", "r3_profile_copy",
-           "r3_profile_mfma", "r3_profile_mfma_flops"]
+           "r3_profile_mfma", "r3_profile_mfma_flops", "r3_routing_diff", "r3_policy_discrepancy",
+           "r3_policy_workspace_bytes"]
 
 
 class LayerDesc(C.Structure):
@@ -52,6 +53,7 @@ def lib():
             getattr(L, name).restype = C.c_int
         L.r3_profile_name.restype = C.c_char_p
         L.r3_profile_mfma_flops.restype = C.c_double
+        L.r3_policy_workspace_bytes.restype = C.c_size_t
         _lib = L
     return _lib
 
@@ -126,6 +128,24 @@ def moe_backward(D, dy, x, W_r, idx, gates, inv_perm, perm, offsets, Xp, A, B, H
                                  _p(W_up), _p(W_down), _p(dx), _p(dW_r), _p(dW_gate), _p(dW_up), _p(dW_down),
                                  _p(dbias), C.c_int(1 if accumulate else 0), _p(ws), C.c_size_t(ws.numel()),
                                  _stream()), "r3_moe_backward")
+
+
+def routing_diff(D, L, idx_a, idx_b, layer_stride, router_hist, token_choices, token_routers, seq_offsets=None,
+                 seq_mean=None):
+    nseq = 0 if seq_offsets is None else seq_offsets.numel() - 1
+    _check(lib().r3_routing_diff(C.byref(D), C.c_int(L), _p(idx_a), _p(idx_b), C.c_int64(layer_stride),
+                                 _p(seq_offsets), C.c_int(nseq), _p(router_hist), _p(token_choices),
+                                 _p(token_routers), _p(seq_mean), _stream()), "r3_routing_diff")
+
+
+def policy_discrepancy(logp_train, logp_infer, taus, kl_out, frac_out, ws=None):
+    """taus: host floats (>= 1); kl_out [1], frac_out [len(taus)]: device float64."""
+    if ws is None:
+        ws = torch.empty(lib().r3_policy_workspace_bytes(), dtype=torch.uint8, device=logp_train.device)
+    tau = (C.c_float * max(len(taus), 1))(*taus)
+    _check(lib().r3_policy_discrepancy(C.c_int64(logp_train.numel()), _p(logp_train), _p(logp_infer),
+                                       C.c_int(len(taus)), tau, _p(kl_out), _p(frac_out), _p(ws),
+                                       C.c_size_t(ws.numel()), _stream()), "r3_policy_discrepancy")
 
 
 class LayerBuffers:
