@@ -213,7 +213,7 @@ def main():
     Wr = [synth.draw(sh, "Wr", dev, layer=l).to(adt) for l in range(L)]
     dy = synth.draw(sh, "dy", dev).to(adt) if bwd else None
     bias = synth.draw(sh, "bias", dev)
-    buf = r3.LayerBuffers(D, backward=bwd)
+    buf = r3.LayerBuffers(D, backward=bwd, gathered_copy=bwd)   # forward only: rows gathered inside the GEMM
     record = torch.zeros(L, sh.T, sh.K, dtype=r3.idx_torch_dtype(D), device=dev)   # layer-major record
     agree = torch.zeros(L, 2, dtype=torch.int64, device=dev)
 

@@ -127,9 +127,14 @@ int r3_permute(const r3_layer_desc *desc, const void *x, const void *idx,
  * (required: it is the second GEMM's input and the backward's saved value);
  * A_save, B_save [T*K,F] or both NULL (forward only).  All act dtype; f32
  * accumulation; `offsets` is read on the device.
+ * Xp may be NULL when x [T,d] and perm [T*K] (from r3_permute) are given: row
+ * r is then read as x[perm[r] / K] inside the first contraction's tile loads
+ * and no gathered copy of the tokens is needed (r3_permute may be called with
+ * Xp = NULL as well); needs T*d*sizeof(act) < 2^31.  x and perm are ignored
+ * when Xp is given.  The backward needs Xp.
  */
-int r3_grouped_ffn(const r3_layer_desc *desc, const void *Xp, const int32_t *offsets,
-                   const void *W_gate, const void *W_up, const void *W_down,
+int r3_grouped_ffn(const r3_layer_desc *desc, const void *Xp, const void *x, const int32_t *perm,
+                   const int32_t *offsets, const void *W_gate, const void *W_up, const void *W_down,
                    void *Yp, void *H, void *A_save, void *B_save, void *ws,
                    size_t ws_bytes, void *stream);
 

@@ -132,26 +132,31 @@ int r3_permute(const r3_layer_desc *desc, const void *x, const void *idx, int32_
                                  perm, Xp, status_word, ws, (hipStream_t)stream));
 }
 
-int r3_grouped_ffn(const r3_layer_desc *desc, const void *Xp, const int32_t *offsets, const void *W_gate,
-                   const void *W_up, const void *W_down, void *Yp, void *H, void *A_save, void *B_save,
-                   void *ws, size_t ws_bytes, void *stream) {
+int r3_grouped_ffn(const r3_layer_desc *desc, const void *Xp, const void *x, const int32_t *perm,
+                   const int32_t *offsets, const void *W_gate, const void *W_up, const void *W_down, void *Yp,
+                   void *H, void *A_save, void *B_save, void *ws, size_t ws_bytes, void *stream) {
     Dims m;
     int rc = check_desc(desc, m);
     if (rc) return rc;
-    if (!Xp || !offsets || !W_gate || !W_up || !W_down || !Yp || !H || ((A_save == nullptr) != (B_save == nullptr)))
+    if (!offsets || !W_gate || !W_up || !W_down || !Yp || !H || ((A_save == nullptr) != (B_save == nullptr)))
         return R3_ERR_INVALID_ARG;
-    if (!aligned(Xp, 16) || !aligned(W_gate, 16) || !aligned(W_up, 16) || !aligned(W_down, 16) ||
-        !aligned(Yp, 16) || !aligned(H, 16) || !aligned(A_save, 16) || !aligned(B_save, 16))
+    if (!Xp && (!x || !perm)) return R3_ERR_INVALID_ARG;   // rows come from Xp, or from x through perm
+    if (!aligned(Xp, 16) || !aligned(x, 16) || !aligned(perm, 4) || !aligned(W_gate, 16) || !aligned(W_up, 16) ||
+        !aligned(W_down, 16) || !aligned(Yp, 16) || !aligned(H, 16) || !aligned(A_save, 16) || !aligned(B_save, 16))
         return R3_ERR_INVALID_ARG;
+    const void *rows = Xp ? Xp : x;
+    const int32_t *via = Xp ? nullptr : perm;
+    if (via && (int64_t)m.T * m.d * m.eb > 0x7fffffffLL) return R3_ERR_UNSUPPORTED;   // 32-bit row offsets
     hipStream_t s = (hipStream_t)stream;
     if (use_mfma_ffn(m)) {
         if (!ws || ws_bytes < mfma_tiles_bytes(m.S, m.E) || !aligned(ws, 256)) return R3_ERR_WORKSPACE;
         int32_t *tiles = (int32_t *)ws;
         if (mfma_build_tiles(m.E, offsets, tiles, s) != hipSuccess) return R3_ERR_HIP;
-        return hip_rc(mfma_ffn_forward(m.S, m.d, m.E, m.F, Xp, offsets, tiles, W_gate, W_up, W_down, Yp, H,
-                                       A_save, B_save, s));
+        return hip_rc(mfma_ffn_forward(m.S, m.d, m.E, m.F, rows, via, m.K, m.T, offsets, tiles, W_gate, W_up, W_down,
+                                       Yp, H, A_save, B_save, s));
     }
-    if (simt_ffn1((int)m.S, m.d, m.E, m.F, m.act, Xp, offsets, W_gate, W_up, H, A_save, B_save, s) != hipSuccess)
+    if (simt_ffn1((int)m.S, m.d, m.E, m.F, m.act, rows, via, m.K, offsets, W_gate, W_up, H, A_save, B_save, s) !=
+        hipSuccess)
         return R3_ERR_HIP;
     return hip_rc(simt_ffn2((int)m.S, m.d, m.E, m.F, m.act, H, offsets, W_down, Yp, s));
 }

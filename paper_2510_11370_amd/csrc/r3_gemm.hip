@@ -104,9 +104,10 @@ __device__ __forceinline__ void unpack4(uint2 v, float *f) {
 // pair in the same lane: MFMA tiles 0,1 are gate, tiles 2,3 the matching up.
 // ---------------------------------------------------------------------------
 __global__ void __launch_bounds__(kThreads2, kMinWavesPerSimd)
-ffn1_kernel(int S, int d, int F, const bf16_t *__restrict__ Xp, const int32_t *__restrict__ offsets,
-            const int32_t *__restrict__ tiles, const bf16_t *__restrict__ Wg, const bf16_t *__restrict__ Wu,
-            bf16_t *__restrict__ H, bf16_t *__restrict__ A, bf16_t *__restrict__ B, int launch) {
+ffn1_kernel(int S, int d, int F, const bf16_t *__restrict__ Xp, const int32_t *__restrict__ perm, int K, int T,
+            const int32_t *__restrict__ offsets, const int32_t *__restrict__ tiles, const bf16_t *__restrict__ Wg,
+            const bf16_t *__restrict__ Wu, bf16_t *__restrict__ H, bf16_t *__restrict__ A, bf16_t *__restrict__ B,
+            int launch) {
     __shared__ __attribute__((aligned(1024))) char s0[kStageBytes];
     __shared__ __attribute__((aligned(1024))) char s1[kStageBytes];
     __shared__ __attribute__((aligned(1024))) char s2[kStageBytes];
@@ -139,22 +140,36 @@ ffn1_kernel(int S, int d, int F, const bf16_t *__restrict__ Xp, const int32_t *_
         const int64_t wb = ((int64_t)d * F - t.f0) * 2;
         P.src[0] = Src{(const char *)(Wg + (int64_t)t.e * d * F + t.f0), clamp_bytes(wb), (uint32_t)(kBK2 * F * 2)};
         P.src[1] = Src{(const char *)(Wu + (int64_t)t.e * d * F + t.f0), clamp_bytes(wb), (uint32_t)(kBK2 * F * 2)};
-        Q.src[0] = Src{(const char *)(Xp + (int64_t)t.row0 * d), clamp_bytes((int64_t)(S - t.row0) * d * 2), kBK2 * 2};
+        if (perm) {
+            // dispatch folded into the tile load: `Xp` is x [T,d]; each lane's four rows of the tile
+            // are read from their tokens' rows (rows past the end of the permutation repeat the last
+            // one; they are never stored)
+            Q.src[0] = Src{(const char *)Xp, clamp_bytes((int64_t)T * d * 2), kBK2 * 2};
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int local = 16 * ((wave & 3) + kLoaderWaves * i) + (lane >> 2);
+                const int tok = perm[min(t.row0 + local, S - 1)] / K;
+                Q.dma.voff[i] = tok * (d * 2) + (((lane & 3) ^ ((local >> 2) & 3)) << 4);
+            }
+        } else {
+            Q.src[0] = Src{(const char *)(Xp + (int64_t)t.row0 * d), clamp_bytes((int64_t)(S - t.row0) * d * 2), kBK2 * 2};
+        }
         Q.src[1] = Q.src[0];
     };
     if (!tl.valid(tl.first())) return;
     Tile cur = decode(tl.first());
+    aim(cur);
     for (int slot = tl.first(), next = tl.second(); tl.valid(slot);) {
     // the next tile's coordinates are fetched now (scalar loads), a whole tile before their use
     const bool more = tl.valid(next);
     const Tile nxt = more ? decode(next) : cur;
     const int e = cur.e, row0 = cur.row0, row_end = cur.row_end, f0 = cur.f0;
-    aim(cur);
 
     Acc2 acc;
     zero_acc2(acc);
     mfma_mainloop2(acc, d / kBK2, P, Q, s0, s1, s2, s3, row_end - row0 > 128);
     tl.prefetch();
+    if (more) aim(nxt);   // here, so that the row-index loads of a gathered tile hide behind the epilogue
 
     // per wave: 64 rows x 64 features of H (and A, B), 32 rows at a time through LDS
     // (three patches in turn, so that one block's stores and the next block's arithmetic overlap)
@@ -604,14 +619,14 @@ hipError_t mfma_build_tiles(int E, const int32_t *offsets, int32_t *tiles, hipSt
     return hipGetLastError();
 }
 
-hipError_t mfma_ffn_forward(int64_t S, int d, int E, int F, const void *Xp, const int32_t *offsets,
-                            const int32_t *tiles, const void *Wg, const void *Wu, const void *Wd, void *Yp,
-                            void *H, void *A, void *B, hipStream_t s) {
+hipError_t mfma_ffn_forward(int64_t S, int d, int E, int F, const void *Xp, const int32_t *perm, int K, int T,
+                            const int32_t *offsets, const int32_t *tiles, const void *Wg, const void *Wu,
+                            const void *Wd, void *Yp, void *H, void *A, void *B, hipStream_t s) {
     const int mt = max_row_tiles(S, E, kTile);
     {
         ProfScope ps(PROF_FFN1, s);
         ffn1_kernel<<<persistent_grid((int64_t)mt * (F / 128)), kThreads2, 0, s>>>(
-            (int)S, d, F, (const bf16_t *)Xp, offsets, tiles, (const bf16_t *)Wg, (const bf16_t *)Wu,
+            (int)S, d, F, (const bf16_t *)Xp, perm, K, T, offsets, tiles, (const bf16_t *)Wg, (const bf16_t *)Wu,
             (bf16_t *)H, (bf16_t *)A, (bf16_t *)B, 0);
     }
     ProfScope ps(PROF_FFN2, s);

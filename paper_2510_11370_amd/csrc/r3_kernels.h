@@ -54,8 +54,10 @@ hipError_t launch_policy_discrepancy(int64_t n, const float *lt, const float *li
 // r3_simt.hip
 hipError_t simt_router_logits(int T, int d, int E, int act, const void *x, const void *Wr, const float *bias,
                               float *logits, hipStream_t s);
-hipError_t simt_ffn1(int S, int d, int E, int F, int act, const void *Xp, const int32_t *offsets, const void *Wg,
-                     const void *Wu, void *H, void *A, void *B, hipStream_t s);
+// perm != NULL: `Xp` is x [T,d] and row r of the grouped operand is x[perm[r] / K] (no gathered copy)
+hipError_t simt_ffn1(int S, int d, int E, int F, int act, const void *Xp, const int32_t *perm, int K,
+                     const int32_t *offsets, const void *Wg, const void *Wu, void *H, void *A, void *B,
+                     hipStream_t s);
 hipError_t simt_ffn2(int S, int d, int E, int F, int act, const void *H, const int32_t *offsets, const void *Wd,
                      void *Yp, hipStream_t s);
 hipError_t simt_dh(int S, int d, int E, int F, int act, const void *dYp, const int32_t *offsets, const void *Wd,
@@ -73,9 +75,11 @@ bool mfma_router_supported(int d, int E);
 size_t mfma_tiles_bytes(int64_t S, int E);
 size_t mfma_dwr_ws_bytes(int T, int d, int E);
 hipError_t mfma_build_tiles(int E, const int32_t *offsets, int32_t *tiles, hipStream_t s);
-hipError_t mfma_ffn_forward(int64_t S, int d, int E, int F, const void *Xp, const int32_t *offsets,
-                            const int32_t *tiles, const void *Wg, const void *Wu, const void *Wd, void *Yp,
-                            void *H, void *A, void *B, hipStream_t s);
+// perm != NULL: `Xp` is x [T,d] (T*d*2 bytes readable) and the first contraction gathers its rows
+// through perm in the tile loads
+hipError_t mfma_ffn_forward(int64_t S, int d, int E, int F, const void *Xp, const int32_t *perm, int K, int T,
+                            const int32_t *offsets, const int32_t *tiles, const void *Wg, const void *Wu,
+                            const void *Wd, void *Yp, void *H, void *A, void *B, hipStream_t s);
 hipError_t mfma_ffn_dh(int64_t S, int d, int E, int F, const void *dYp, const int32_t *offsets,
                        const int32_t *tiles, const void *Wd, const void *A, const void *B, void *dA, void *dB,
                        hipStream_t s);

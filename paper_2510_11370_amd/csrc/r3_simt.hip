@@ -33,17 +33,18 @@ simt_logits_kernel(int Tn, int d, int E, const T *__restrict__ x, const T *__res
 // A = Xp Wg[e], B = Xp Wu[e], H = silu(A) * B
 template <typename T>
 __global__ void __launch_bounds__(256)
-simt_ffn1_kernel(int S, int d, int E, int F, const T *__restrict__ Xp, const int32_t *__restrict__ offsets,
-                 const T *__restrict__ Wg, const T *__restrict__ Wu, T *__restrict__ H, T *__restrict__ A,
-                 T *__restrict__ B) {
+simt_ffn1_kernel(int S, int d, int E, int F, const T *__restrict__ Xp, const int32_t *__restrict__ perm, int K,
+                 const int32_t *__restrict__ offsets, const T *__restrict__ Wg, const T *__restrict__ Wu,
+                 T *__restrict__ H, T *__restrict__ A, T *__restrict__ B) {
     int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (i >= (int64_t)S * F) return;
     int r = (int)(i / F), f = (int)(i - (int64_t)r * F);
     int e = expert_of_row(offsets, E, r);
     const T *wg = Wg + (int64_t)e * d * F + f, *wu = Wu + (int64_t)e * d * F + f;
+    const int src = perm ? perm[r] / K : r;   // perm given: Xp is x [T,d], row r reads its token
     float a = 0.0f, b = 0.0f;
     for (int c = 0; c < d; ++c) {
-        float xv = Elem<T>::ld(Xp + (int64_t)r * d + c);
+        float xv = Elem<T>::ld(Xp + (int64_t)src * d + c);
         a = fmaf(xv, Elem<T>::ld(wg + (int64_t)c * F), a);
         b = fmaf(xv, Elem<T>::ld(wu + (int64_t)c * F), b);
     }
@@ -150,11 +151,12 @@ hipError_t simt_router_logits(int T, int d, int E, int act, const void *x, const
     return hipGetLastError();
 }
 
-hipError_t simt_ffn1(int S, int d, int E, int F, int act, const void *Xp, const int32_t *offsets, const void *Wg,
-                     const void *Wu, void *H, void *A, void *B, hipStream_t s) {
+hipError_t simt_ffn1(int S, int d, int E, int F, int act, const void *Xp, const int32_t *perm, int K,
+                     const int32_t *offsets, const void *Wg, const void *Wu, void *H, void *A, void *B,
+                     hipStream_t s) {
     int g = blocks_for((int64_t)S * F);
-    R3_BY_ACT(act, (simt_ffn1_kernel<bf16_t><<<g, 256, 0, s>>>(S, d, E, F, (const bf16_t *)Xp, offsets, (const bf16_t *)Wg, (const bf16_t *)Wu, (bf16_t *)H, (bf16_t *)A, (bf16_t *)B)),
-              (simt_ffn1_kernel<float><<<g, 256, 0, s>>>(S, d, E, F, (const float *)Xp, offsets, (const float *)Wg, (const float *)Wu, (float *)H, (float *)A, (float *)B)));
+    R3_BY_ACT(act, (simt_ffn1_kernel<bf16_t><<<g, 256, 0, s>>>(S, d, E, F, (const bf16_t *)Xp, perm, K, offsets, (const bf16_t *)Wg, (const bf16_t *)Wu, (bf16_t *)H, (bf16_t *)A, (bf16_t *)B)),
+              (simt_ffn1_kernel<float><<<g, 256, 0, s>>>(S, d, E, F, (const float *)Xp, perm, K, offsets, (const float *)Wg, (const float *)Wu, (float *)H, (float *)A, (float *)B)));
     return hipGetLastError();
 }
 

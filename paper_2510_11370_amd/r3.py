@@ -111,8 +111,9 @@ def permute(D, x, idx, counts, offsets, inv_perm, perm, Xp, ws, status=None):
                             _p(Xp), _p(status), _p(ws), C.c_size_t(ws.numel()), _stream()), "r3_permute")
 
 
-def grouped_ffn(D, Xp, offsets, W_gate, W_up, W_down, Yp, H, A_save=None, B_save=None, ws=None):
-    _check(lib().r3_grouped_ffn(C.byref(D), _p(Xp), _p(offsets), _p(W_gate), _p(W_up), _p(W_down), _p(Yp),
+def grouped_ffn(D, Xp, offsets, W_gate, W_up, W_down, Yp, H, A_save=None, B_save=None, ws=None, x=None, perm=None):
+    """Xp=None with x and perm: the token rows are gathered inside the first contraction."""
+    _check(lib().r3_grouped_ffn(C.byref(D), _p(Xp), _p(x), _p(perm), _p(offsets), _p(W_gate), _p(W_up), _p(W_down), _p(Yp),
                                 _p(H), _p(A_save), _p(B_save), _p(ws),
                                 C.c_size_t(0 if ws is None else ws.numel()), _stream()), "r3_grouped_ffn")
 
@@ -151,7 +152,8 @@ def policy_discrepancy(logp_train, logp_infer, taus, kl_out, frac_out, ws=None):
 class LayerBuffers:
     """Caller-owned buffers of one layer (everything the C ABI reads or writes)."""
 
-    def __init__(self, D, device="cuda", backward=True):
+    def __init__(self, D, device="cuda", backward=True, gathered_copy=True):
+        """gathered_copy=False (forward only): no Xp; the expert FFN reads token rows through perm."""
         T, d, E, K, F = D.T, D.d, D.E, D.K, D.F
         S = T * K
         a = act_dtype(D)
@@ -162,7 +164,9 @@ class LayerBuffers:
         self.offsets = e(E + 1, dt=torch.int32)
         self.inv_perm = e(S, dt=torch.int32)
         self.perm = e(S, dt=torch.int32)
-        self.Xp, self.Yp, self.H, self.y = e(S, d), e(S, d), e(S, F), e(T, d)
+        assert gathered_copy or not backward, "the backward needs the gathered rows"
+        self.Xp = e(S, d) if gathered_copy else None
+        self.Yp, self.H, self.y = e(S, d), e(S, F), e(T, d)
         self.status = torch.zeros(1, dtype=torch.int32, device=device)
         self.ws_gate = workspace(D, OP_REPLAY_GATE, device)
         self.ws_perm = workspace(D, OP_PERMUTE, device)
@@ -184,7 +188,8 @@ def forward(buf, x, W_r, idx, W_gate, W_up, W_down, bias=None, logits_out=None, 
     replay_gate(D, x, W_r, idx, buf.gates, bias=bias, logits_out=logits_out, agree_out=agree_out,
                 status=buf.status, ws=buf.ws_gate)
     permute(D, x, idx, buf.counts, buf.offsets, buf.inv_perm, buf.perm, buf.Xp, buf.ws_perm, status=buf.status)
-    grouped_ffn(D, buf.Xp, buf.offsets, W_gate, W_up, W_down, buf.Yp, buf.H, buf.A, buf.B, ws=buf.ws_ffn)
+    grouped_ffn(D, buf.Xp, buf.offsets, W_gate, W_up, W_down, buf.Yp, buf.H, buf.A, buf.B, ws=buf.ws_ffn,
+                x=x, perm=buf.perm)
     combine(D, buf.Yp, buf.gates, buf.inv_perm, buf.y)
     return buf.y
 

@@ -52,6 +52,11 @@ def test_config2_forward_4k_every_output():
     assert_close(host(buf.H), ref["h"], "H", c.rel)
     assert_close(host(buf.Yp), ref["o"], "Yp", c.rel)
     assert_close(host(buf.y), ref["y"], "y", c.rel)
+    # the forward-only configuration needs no gathered copy of the tokens: same bits without it
+    buf2 = r3.LayerBuffers(D, backward=False, gathered_copy=False)
+    r3.forward(buf2, c.t["x"], c.t["Wr"], rec, c.t["Wg"], c.t["Wu"], c.t["Wd"])
+    torch.cuda.synchronize()
+    assert torch.equal(buf.y, buf2.y) and torch.equal(buf.H, buf2.H)
 
 
 # ------------------------------------------------------------------ config 5: Zipf-skewed load, T=65536
@@ -172,7 +177,7 @@ def test_config4_stack_record_replay_agreement():
     Wn = {k: v.float().cpu().numpy() for k, v in W.items()}
     x = synth.draw(sh, "x", dev).to(torch.bfloat16)
     record = torch.zeros(L, T, K, dtype=torch.uint8, device=dev)          # layer-major, 48 MiB
-    buf = r3.LayerBuffers(D, backward=False)
+    buf = r3.LayerBuffers(D, backward=False, gathered_copy=False)   # rows are gathered inside the expert GEMM
     logits = torch.empty(T, E, dtype=torch.float32, device=dev)
     agree = torch.zeros(L, 2, dtype=torch.int64, device=dev)
     status = torch.zeros(1, dtype=torch.int32, device=dev)

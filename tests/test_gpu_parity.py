@@ -221,6 +221,14 @@ def test_grouped_ffn_and_combine_steps(name, simt):
     assert_close(host(B), b, "B", c.rel)
     assert_close(host(H), h, "H", c.rel)
     assert_close(host(Yp), o, "Yp", c.rel)
+    # the same call reading the token rows through perm instead of a gathered copy: the gather moves
+    # bytes, so every output must be bit-identical
+    Yp2, H2, A2, B2 = (torch.zeros(S, w, dtype=adt, device="cuda") for w in (sh.d, sh.F, sh.F, sh.F))
+    r3.grouped_ffn(D, None, dev(offsets, torch.int32), c.t["Wg"], c.t["Wu"], c.t["Wd"], Yp2, H2, A2, B2,
+                   ws=r3.workspace(D, r3.OP_GROUPED_FFN), x=c.t["x"], perm=dev(perm, torch.int32))
+    sync()
+    for got, want, nm in ((Yp2, Yp, "Yp"), (H2, H, "H"), (A2, A, "A"), (B2, B, "B")):
+        assert torch.equal(got, want), nm
     # combine on oracle-made inputs: o rounded to the activation dtype, oracle gates as f32
     g = sparse.replay_gate(c.s, c.idx)
     o_act = synth._round(torch.from_numpy(o).float(), sh.act).numpy()
@@ -258,6 +266,11 @@ def test_forward_chain(name, simt):
     # recompute stage and update stage run the same kernels: bit-identical forward, twice
     buf2 = _run_forward(c, backward=True)
     assert torch.equal(buf.y, buf2.y) and torch.equal(buf.gates, buf2.gates)
+    # forward without the gathered copy of the tokens (rows read through perm in the expert GEMM)
+    buf3 = r3.LayerBuffers(c.D, backward=False, gathered_copy=False)
+    r3.forward(buf3, c.t["x"], c.t["Wr"], c.t["idx"], c.t["Wg"], c.t["Wu"], c.t["Wd"], bias=c.t["bias"])
+    sync()
+    assert buf3.Xp is None and torch.equal(buf.y, buf3.y) and torch.equal(buf.Yp, buf3.Yp)
 
 
 @pytest.mark.parametrize("name,simt", [("config1_f32", False), ("odd_f32", False), ("odd_bf16", False),
@@ -334,3 +347,5 @@ def test_host_errors_are_returned_before_launch():
         r3.permute(D, x, x, x, x, x, x, x, torch.empty(0, dtype=torch.uint8, device="cuda"))
     with pytest.raises(r3.R3Error, match="INVALID_ARG"):
         r3.combine(D, x.view(-1)[1:], x, x, x)  # misaligned
+    with pytest.raises(r3.R3Error, match="INVALID_ARG"):
+        r3.grouped_ffn(D, None, x, x, x, x, x, x, x=x)  # neither Xp nor (x, perm)
