@@ -52,7 +52,7 @@ enum { R3_BF16 = 0, R3_F32 = 1 };     /* desc->act   */
 enum { R3_IDX_U8 = 0, R3_IDX_U16 = 1 }; /* desc->idx   */
 
 /* bits of the device status word */
-enum { R3_DATA_IDX_RANGE = 1, R3_DATA_IDX_DUP = 2, R3_DATA_NONFINITE = 4 };
+enum { R3_DATA_IDX_RANGE = 1, R3_DATA_IDX_DUP = 2, R3_DATA_NONFINITE = 4, R3_DATA_CACHE_ADDR = 8 };
 
 typedef enum r3_op {
     R3_OP_REPLAY_GATE = 0,
@@ -201,6 +201,44 @@ int r3_policy_discrepancy(int64_t n, const float *logp_train, const float *logp_
                           const float *tau, double *kl_out, double *frac_out, void *ws,
                           size_t ws_bytes, void *stream);
 size_t r3_policy_workspace_bytes(void);
+
+/*
+ * Router-mask cache (Section 4.2: routing masks stored with the KV cache per
+ * layer and token prefix, so that a prefix that hits the cache brings its masks
+ * and is not prefilled again).  Masks live in `pages`, a device pool
+ * [num_pages][P][L][K] of ids (idx_dtype R3_IDX_U8 / R3_IDX_U16): P tokens per
+ * page, one token's L*K ids contiguous.  block_table: device int32
+ * [nseq][max_blocks]; entry b of sequence s is the page that holds its tokens
+ * b*P .. b*P+P-1 (negative: none).  A prefix shared by several sequences is the
+ * same page ids in their rows; the library never allocates or frees pages.
+ *
+ * r3_mask_cache_append: ids of n new tokens (device; element (l, i, k) at
+ * idx_new[l*layer_stride + i*token_stride + k], so both [n][L][K] and the
+ * [L][n][K] that L calls of r3_record_topk leave are accepted) go to the slot of
+ * token position[i] (0-based) of sequence seq_id[i] (device int32 [n]).  Two
+ * entries that name the same slot race.
+ *
+ * r3_mask_cache_gather: the layer-major record out[L][T][K] of a packed batch:
+ * sequence s owns tokens seq_start[s] .. seq_start[s+1]-1 (device int32
+ * [nseq+1], ascending from 0 to T) and its j-th token is read from page
+ * block_table[s][j / P], slot j % P.  The result is what r3_replay_gate,
+ * r3_permute and r3_moe_backward take as idx, layer by layer.
+ *
+ * A token whose sequence, position or page is out of range is skipped by
+ * append and zero-filled by gather, and R3_DATA_CACHE_ADDR is set in
+ * *status_word (device, may be NULL); nothing is accessed out of bounds.
+ * Pure copies: results are bit-exact.  pages, idx_new, out: aligned to the id
+ * size.  n = 0 / T = 0 are no-ops.
+ */
+int r3_mask_cache_append(int idx_dtype, int L, int K, int P, void *pages, int64_t num_pages,
+                         const int32_t *block_table, int nseq, int max_blocks, int64_t n,
+                         const int32_t *seq_id, const int32_t *position, const void *idx_new,
+                         int64_t layer_stride, int64_t token_stride, int32_t *status_word,
+                         void *stream);
+int r3_mask_cache_gather(int idx_dtype, int L, int K, int P, const void *pages, int64_t num_pages,
+                         const int32_t *block_table, int nseq, int max_blocks,
+                         const int32_t *seq_start, int64_t T, void *out, int32_t *status_word,
+                         void *stream);
 
 /*
  * Measurement aid (not part of the method): per-kernel timing with HIP events

@@ -8,7 +8,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libr3.so")
-SOURCES = ["r3_api.hip", "r3_route.hip", "r3_simt.hip", "r3_gemm.hip", "r3_diag.hip", "r3_prof.hip"]
+SOURCES = ["r3_api.hip", "r3_route.hip", "r3_simt.hip", "r3_gemm.hip", "r3_diag.hip", "r3_cache.hip", "r3_prof.hip"]
 HEADERS = ["r3_common.h", "r3_kernels.h", "r3_mfma.h", "r3_mfma2.h"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",

@@ -267,4 +267,45 @@ int r3_policy_discrepancy(int64_t n, const float *logp_train, const float *logp_
                                             (hipStream_t)stream));
 }
 
+static int check_cache(int idx_dtype, int L, int K, int P, const void *pages, int64_t num_pages,
+                       const int32_t *block_table, int nseq, int max_blocks, int &idx_bytes) {
+    if (idx_dtype != R3_IDX_U8 && idx_dtype != R3_IDX_U16) return R3_ERR_INVALID_ARG;
+    idx_bytes = idx_dtype == R3_IDX_U8 ? 1 : 2;
+    if (L <= 0 || K <= 0 || P <= 0 || !pages || num_pages <= 0 || !block_table || nseq <= 0 || max_blocks <= 0)
+        return R3_ERR_INVALID_ARG;
+    if (!aligned(pages, idx_bytes) || !aligned(block_table, 4)) return R3_ERR_INVALID_ARG;
+    // rows of the pool are addressed as page*P + slot in 64 bits; positions as int32
+    if ((int64_t)max_blocks * P > 0x7fffffffll || (int64_t)L * K > (1 << 20)) return R3_ERR_UNSUPPORTED;
+    return R3_OK;
+}
+
+int r3_mask_cache_append(int idx_dtype, int L, int K, int P, void *pages, int64_t num_pages,
+                         const int32_t *block_table, int nseq, int max_blocks, int64_t n, const int32_t *seq_id,
+                         const int32_t *position, const void *idx_new, int64_t layer_stride, int64_t token_stride,
+                         int32_t *status_word, void *stream) {
+    int ib = 0;
+    int rc = check_cache(idx_dtype, L, K, P, pages, num_pages, block_table, nseq, max_blocks, ib);
+    if (rc) return rc;
+    if (n < 0 || (n > 0 && (!seq_id || !position || !idx_new)) || layer_stride < 0 || token_stride < 0)
+        return R3_ERR_INVALID_ARG;
+    if (!aligned(seq_id, 4) || !aligned(position, 4) || !aligned(idx_new, ib) || (status_word && !aligned(status_word, 4)))
+        return R3_ERR_INVALID_ARG;
+    return hip_rc(launch_cache_append(ib, L, K, P, pages, num_pages, block_table, nseq, max_blocks, n, seq_id,
+                                      position, idx_new, layer_stride, token_stride, status_word,
+                                      (hipStream_t)stream));
+}
+
+int r3_mask_cache_gather(int idx_dtype, int L, int K, int P, const void *pages, int64_t num_pages,
+                         const int32_t *block_table, int nseq, int max_blocks, const int32_t *seq_start, int64_t T,
+                         void *out, int32_t *status_word, void *stream) {
+    int ib = 0;
+    int rc = check_cache(idx_dtype, L, K, P, pages, num_pages, block_table, nseq, max_blocks, ib);
+    if (rc) return rc;
+    if (T < 0 || T > 0x7fffffffll - 64 || !seq_start || (T > 0 && !out)) return R3_ERR_INVALID_ARG;
+    if (!aligned(seq_start, 4) || !aligned(out, ib) || (status_word && !aligned(status_word, 4)))
+        return R3_ERR_INVALID_ARG;
+    return hip_rc(launch_cache_gather(ib, L, K, P, pages, num_pages, block_table, nseq, max_blocks, seq_start,
+                                      (int)T, out, status_word, (hipStream_t)stream));
+}
+
 }  // extern "C"

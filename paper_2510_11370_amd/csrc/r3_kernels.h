@@ -9,7 +9,7 @@ namespace r3 {
 enum ProfTag {
     PROF_RECORD = 0, PROF_LOGITS, PROF_GATE, PROF_PERMUTE_INDEX, PROF_GATHER_ROWS, PROF_FFN1, PROF_FFN2,
     PROF_COMBINE, PROF_GATE_BWD, PROF_DWR, PROF_DH, PROF_WGRAD, PROF_DXP, PROF_DX_FINISH, PROF_WGRAD_PAIR,
-    PROF_ROUTING_DIFF, PROF_POLICY, PROF_NTAGS
+    PROF_ROUTING_DIFF, PROF_POLICY, PROF_CACHE_APPEND, PROF_CACHE_GATHER, PROF_NTAGS
 };
 struct ProfScope {
     int tag, slot;
@@ -50,6 +50,15 @@ hipError_t launch_routing_diff(int T, int K, int L, const void *a, const void *b
                                int32_t *token_choices, int32_t *token_routers, double *seq_mean, hipStream_t s);
 hipError_t launch_policy_discrepancy(int64_t n, const float *lt, const float *li, int ntau, const float *tau_host,
                                      double *kl, double *frac, void *ws, hipStream_t s);
+
+// r3_cache.hip
+hipError_t launch_cache_append(int idx_bytes, int L, int K, int P, void *pages, int64_t num_pages,
+                               const int32_t *block_table, int nseq, int max_blocks, int64_t n,
+                               const int32_t *seq_id, const int32_t *position, const void *idx_new,
+                               int64_t layer_stride, int64_t token_stride, int32_t *status, hipStream_t s);
+hipError_t launch_cache_gather(int idx_bytes, int L, int K, int P, const void *pages, int64_t num_pages,
+                               const int32_t *block_table, int nseq, int max_blocks, const int32_t *seq_start,
+                               int T, void *out, int32_t *status, hipStream_t s);
 
 // r3_simt.hip
 hipError_t simt_router_logits(int T, int d, int E, int act, const void *x, const void *Wr, const float *bias,

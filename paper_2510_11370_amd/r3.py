@@ -22,7 +22,7 @@ EXPORTS = ["r3_version", "r3_workspace_bytes", "r3_record_topk", "r3_replay_gate
            "r3_grouped_ffn", "r3_combine", "r3_moe_backward", "r3_profile_enable", "r3_profile_tags",
            "r3_profile_name", "r3_profile_read", "r3_profile_copy",
            "r3_profile_mfma", "r3_profile_mfma_flops", "r3_routing_diff", "r3_policy_discrepancy",
-           "r3_policy_workspace_bytes"]
+           "r3_policy_workspace_bytes", "r3_mask_cache_append", "r3_mask_cache_gather"]
 
 
 class LayerDesc(C.Structure):
@@ -147,6 +147,30 @@ def policy_discrepancy(logp_train, logp_infer, taus, kl_out, frac_out, ws=None):
     _check(lib().r3_policy_discrepancy(C.c_int64(logp_train.numel()), _p(logp_train), _p(logp_infer),
                                        C.c_int(len(taus)), tau, _p(kl_out), _p(frac_out), _p(ws),
                                        C.c_size_t(ws.numel()), _stream()), "r3_policy_discrepancy")
+
+
+def _idx_code(t):
+    return IDX_U8 if t.dtype == torch.uint8 else IDX_U16
+
+
+def mask_cache_append(pages, block_table, seq_id, position, idx_new, layer_stride, token_stride, status=None):
+    """pages [num_pages,P,L,K]; block_table int32 [nseq,max_blocks]; idx_new: element (l,i,k) at
+    l*layer_stride + i*token_stride + k."""
+    num_pages, P, L, K = pages.shape
+    _check(lib().r3_mask_cache_append(C.c_int(_idx_code(pages)), C.c_int(L), C.c_int(K), C.c_int(P), _p(pages),
+                                      C.c_int64(num_pages), _p(block_table), C.c_int(block_table.shape[0]),
+                                      C.c_int(block_table.shape[1]), C.c_int64(seq_id.numel()), _p(seq_id),
+                                      _p(position), _p(idx_new), C.c_int64(layer_stride), C.c_int64(token_stride),
+                                      _p(status), _stream()), "r3_mask_cache_append")
+
+
+def mask_cache_gather(pages, block_table, seq_start, out, status=None):
+    """out [L,T,K]: the layer-major record of the packed batch described by seq_start (int32 [nseq+1])."""
+    num_pages, P, L, K = pages.shape
+    _check(lib().r3_mask_cache_gather(C.c_int(_idx_code(pages)), C.c_int(L), C.c_int(K), C.c_int(P), _p(pages),
+                                      C.c_int64(num_pages), _p(block_table), C.c_int(block_table.shape[0]),
+                                      C.c_int(block_table.shape[1]), _p(seq_start), C.c_int64(out.shape[1]),
+                                      _p(out), _p(status), _stream()), "r3_mask_cache_gather")
 
 
 class LayerBuffers:

@@ -89,3 +89,49 @@ def make_layer(shape: LayerShape, device="cpu", layer: int = 0, backward: bool =
     """All tensors of one layer as a dict of float32 tensors."""
     names = ["x", "Wr", "Wg", "Wu", "Wd", "noise", "bias"] + (["dy"] if backward else [])
     return {n: draw(shape, n, device, layer) for n in names}
+
+
+def rollout_batch(T: int, P: int, group: int = 4, prompt_share: float = 0.3, seed: int = 0):
+    """Layout of a packed batch of rollouts for the mask cache: sequences in groups of `group` that share
+    a prompt (several responses are sampled per prompt), T tokens in all.  Returns numpy arrays
+        lens [nseq], shared [nseq] (leading tokens that sit in pages owned by the group's first sequence:
+        whole pages of the prompt, 0 for the owner), block_table int32 [nseq, max_blocks] (-1 unused) with
+        physical pages dealt in a seeded shuffled order, num_pages.
+    Lengths are log-uniform between 1/8 and 8/8 of twice the mean, like a mix of short and long responses.
+    Layout only: no ids are drawn here."""
+    import numpy as np
+    rng = np.random.default_rng(seed)
+    mean = max(P * 4, min(2048, T // 8 if T >= 64 else T))
+    lens, owner_prompt = [], []
+    left = T
+    while left > 0:
+        prompt = int(mean * prompt_share * rng.uniform(0.5, 1.5))
+        for g in range(group):
+            if left <= 0:
+                break
+            n = int(np.exp(rng.uniform(np.log(mean / 4), np.log(mean * 2))))
+            n = max(1, min(n, left))
+            lens.append(n)
+            owner_prompt.append((g, prompt))
+            left -= n
+    nseq = len(lens)
+    lens = np.array(lens, np.int64)
+    shared = np.zeros(nseq, np.int64)
+    blocks = (lens + P - 1) // P
+    max_blocks = int(blocks.max())
+    table = -np.ones((nseq, max_blocks), np.int32)
+    logical, owner = 0, 0
+    for s in range(nseq):
+        g, prompt = owner_prompt[s]
+        if g == 0:
+            owner = s
+        else:
+            full = min(prompt, int(lens[owner]), int(lens[s])) // P          # whole pages of the common prompt
+            shared[s] = full * P
+            table[s, :full] = table[owner, :full]
+        first = int(shared[s]) // P
+        table[s, first:blocks[s]] = np.arange(logical, logical + blocks[s] - first)
+        logical += int(blocks[s]) - first
+    deal = rng.permutation(logical).astype(np.int32)
+    table = np.where(table >= 0, deal[np.maximum(table, 0)], -1).astype(np.int32)
+    return lens, shared, table, logical
