@@ -164,6 +164,62 @@ def bench_diagnostics(args, torch, r3, dev):
         "kernels": kernels}))
 
 
+def bench_mask_cache(args, torch, r3, synth, dev):
+    """Secondary workload: the Section 4.2 mask cache at the 48-layer configuration's size.  One step stores the
+    masks of every token the batch's sequences own (a rollout's worth, handed over layer-major as the per-layer
+    recording leaves them) and gathers the packed batch's layer-major record back through the block table."""
+    import numpy as np
+    L, T, K, E, P = 48, 131072, 8, 128, 16
+    lens, shared, table_np, num_pages = synth.rollout_batch(T, P, group=4, seed=3)
+    start = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+    seq_id = np.concatenate([np.full(int(n - sh), s, np.int32) for s, (n, sh) in enumerate(zip(lens, shared))])
+    pos = np.concatenate([np.arange(sh, n, dtype=np.int32) for n, sh in zip(lens, shared)])
+    n = len(seq_id)
+    g = torch.Generator(device=dev).manual_seed(2)
+    new = torch.randint(0, E, (L, n, K), generator=g, device=dev).to(torch.uint8)
+    pages = torch.zeros((num_pages, P, L, K), dtype=torch.uint8, device=dev)
+    table = torch.from_numpy(table_np).to(dev)
+    d_seq, d_pos, d_start = (torch.from_numpy(a).to(dev) for a in (seq_id, pos, start))
+    out = torch.empty((L, T, K), dtype=torch.uint8, device=dev)
+    status = torch.zeros(1, dtype=torch.int32, device=dev)
+
+    def step():
+        r3.mask_cache_append(pages, table, d_seq, d_pos, new, n * K, K, status)
+        r3.mask_cache_gather(pages, table, d_start, out, status)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    r3.profile_enable(True)
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    prof = r3.profile_read()
+    r3.profile_enable(False)
+    assert int(status.item()) == 0
+    work = {"mask_cache_append": 2 * n * L * K + 8 * n, "mask_cache_gather": 2 * T * L * K}
+    kernels = {}
+    for name, (ms, cnt) in prof.items():
+        gbs = work[name] / (ms / cnt) * 1e-6
+        kernels[name] = {"bound": "hbm", "avg_ms": round(ms / cnt, 4), "launches_per_step": cnt // args.steps,
+                         "achieved": round(gbs, 1), "unit": "GB/s", "frac": round(gbs / PEAK_HBM_GBS, 4)}
+    ms_per_step = wall * 1e3 / args.steps
+    dom = max(kernels, key=lambda k: kernels[k]["avg_ms"])
+    print(json.dumps({
+        "metric": "tokens' masks stored and gathered/sec (48 layers x top-8 uint8, paged, 1 GPU)",
+        "value": round(T / (ms_per_step * 1e-3), 1), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "u8", "data": "synthetic (seeded)",
+        "config": {"workload": "mask_cache: L=48 T=131072 K=8 uint8, page 16 tokens, %d sequences in groups of 4 "
+                               "with shared prompts (%d tokens come from shared pages), %d pages"
+                               % (len(lens), int(shared.sum()), num_pages)},
+        "roofline": {"kernel": dom, "bound": "hbm", "achieved": kernels[dom]["achieved"], "peak": PEAK_HBM_GBS,
+                     "unit": "GB/s", "frac": kernels[dom]["frac"], "traffic": None},
+        "kernels": kernels}))
+
+
 def stored_traffic(workload, kernel):
     """HBM bytes per launch (fetch + write) of `kernel` from the committed counter summary of this workload
     (two rocprofv3 --pmc runs of this script, scaled by the calibration copy), or None if there is none."""
@@ -202,6 +258,9 @@ def main():
     if args.workload == "diagnostics":
         torch.cuda.set_device(0)
         return bench_diagnostics(args, torch, r3, "cuda")
+    if args.workload == "mask_cache":
+        torch.cuda.set_device(0)
+        return bench_mask_cache(args, torch, r3, synth, "cuda")
     sh = synth.CONFIGS[args.workload]
     dev = "cuda"
     torch.cuda.set_device(0)

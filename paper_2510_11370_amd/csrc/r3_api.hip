@@ -288,6 +288,7 @@ int r3_mask_cache_append(int idx_dtype, int L, int K, int P, void *pages, int64_
     if (rc) return rc;
     if (n < 0 || (n > 0 && (!seq_id || !position || !idx_new)) || layer_stride < 0 || token_stride < 0)
         return R3_ERR_INVALID_ARG;
+    if (n > 0x7fffffffll) return R3_ERR_UNSUPPORTED;
     if (!aligned(seq_id, 4) || !aligned(position, 4) || !aligned(idx_new, ib) || (status_word && !aligned(status_word, 4)))
         return R3_ERR_INVALID_ARG;
     return hip_rc(launch_cache_append(ib, L, K, P, pages, num_pages, block_table, nseq, max_blocks, n, seq_id,

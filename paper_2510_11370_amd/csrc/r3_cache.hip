@@ -66,6 +66,51 @@ cache_append_kernel(int64_t n, int L, int S, int P, char *pages, int64_t num_pag
     }
 }
 
+// Layer-major sources (token stride below the layer stride, e.g. the [L][n][K] that per-layer recording
+// leaves): the transposition runs through LDS like the gather's, in the other direction.  Work-group =
+// kTokTile consecutive new tokens x a chunk of LC layers; phase 1 reads, per layer, the tile's tokens
+// (consecutive threads, consecutive source addresses when the source is packed), phase 2 writes each
+// token's LC*S units into its page row as one run.
+template <int U>
+__global__ void __launch_bounds__(256)
+cache_append_tiled_kernel(int64_t n, int L, int S, int LC, int P, char *pages, int64_t num_pages,
+                          const int32_t *block_table, int nseq, int max_blocks, const int32_t *seq_id,
+                          const int32_t *position, const char *src, int64_t layer_bytes, int64_t token_bytes,
+                          int32_t *status) {
+    typedef typename UnitOf<U>::type unit_t;
+    extern __shared__ __align__(16) char smem[];
+    __shared__ int64_t row_of[kTokTile];
+    unit_t *tile = (unit_t *)smem;
+    const int64_t i0 = (int64_t)blockIdx.x * kTokTile;
+    const int l0 = blockIdx.y * LC;
+    const int nl = min(LC, L - l0);
+    const int nt = (int)min((int64_t)kTokTile, n - i0);
+    const int pitch = (LC * S) | 1;
+    if (threadIdx.x < kTokTile) {
+        int64_t row = -1;
+        if ((int)threadIdx.x < nt) {
+            row = page_row(block_table, nseq, max_blocks, P, num_pages, seq_id[i0 + threadIdx.x],
+                           position[i0 + threadIdx.x]);
+            if (row < 0 && blockIdx.y == 0 && status) atomicOr(status, R3_DATA_CACHE_ADDR);
+        }
+        row_of[threadIdx.x] = row;
+    }
+    const int span = nt * S;
+    for (int v = threadIdx.x; v < nl * span; v += 256) {
+        const int l = v / span, ts = v - l * span;
+        const int tok = ts / S, sub = ts - tok * S;
+        tile[tok * pitch + l * S + sub] =
+            *(const unit_t *)(src + (l0 + l) * layer_bytes + (i0 + tok) * token_bytes + (int64_t)sub * U);
+    }
+    __syncthreads();
+    const int run = nl * S;
+    for (int v = threadIdx.x; v < nt * run; v += 256) {
+        const int tok = v / run, c = v - tok * run;
+        const int64_t row = row_of[tok];
+        if (row >= 0) *(unit_t *)(pages + ((row * L + l0) * S + c) * U) = tile[tok * pitch + c];
+    }
+}
+
 // Work-group = kTokTile tokens x a chunk of LC layers.  Phase 1 reads each token's LC*S units from its
 // page row (consecutive threads, consecutive units); phase 2 writes, per layer, the kTokTile*S units of
 // the tile's tokens (consecutive threads, consecutive addresses of the record).  LDS row pitch is odd
@@ -112,6 +157,12 @@ cache_gather_kernel(int T, int L, int S, int LC, int P, const char *pages, int64
     }
 }
 
+// layers per chunk: the LDS tile of kTokTile tokens stays within 48 KiB
+int layers_per_chunk(int L, int S, int U) {
+    const int lc = (int)std::min<int64_t>(L, (48 * 1024 / (kTokTile * U) - 1) / S);
+    return lc < 1 ? 1 : lc;
+}
+
 int pick_unit(int64_t router_bytes, std::initializer_list<int64_t> others) {
     int u = 16;
     while (u > 1) {
@@ -134,9 +185,28 @@ hipError_t launch_cache_append(int idx_bytes, int L, int K, int P, void *pages, 
     const int U = pick_unit(rb, {layer_stride * idx_bytes, token_stride * idx_bytes, (int64_t)(uintptr_t)pages,
                                  (int64_t)(uintptr_t)idx_new});
     const int S = (int)(rb / U);
+    ProfScope ps(PROF_CACHE_APPEND, s);
+    if (token_stride < layer_stride && L > 1) {
+        const int LC = layers_per_chunk(L, S, U);
+        const size_t lds = (size_t)kTokTile * ((LC * S) | 1) * U;
+        dim3 grid((unsigned)((n + kTokTile - 1) / kTokTile), (L + LC - 1) / LC);
+#define R3_APPEND_T(UU)                                                                                        \
+    cache_append_tiled_kernel<UU><<<grid, 256, lds, s>>>(n, L, S, LC, P, (char *)pages, num_pages, block_table, \
+                                                         nseq, max_blocks, seq_id, position,                   \
+                                                         (const char *)idx_new, layer_stride * idx_bytes,      \
+                                                         token_stride * idx_bytes, status)
+        switch (U) {
+            case 16: R3_APPEND_T(16); break;
+            case 8: R3_APPEND_T(8); break;
+            case 4: R3_APPEND_T(4); break;
+            case 2: R3_APPEND_T(2); break;
+            default: R3_APPEND_T(1); break;
+        }
+#undef R3_APPEND_T
+        return hipGetLastError();
+    }
     const int64_t total = n * L * S;
     const int grid = (int)std::min<int64_t>((total + 255) / 256, 1 << 16);
-    ProfScope ps(PROF_CACHE_APPEND, s);
 #define R3_APPEND(UU)                                                                                          \
     cache_append_kernel<UU><<<grid, 256, 0, s>>>(n, L, S, P, (char *)pages, num_pages, block_table, nseq,      \
                                                  max_blocks, seq_id, position, (const char *)idx_new,          \
@@ -159,9 +229,7 @@ hipError_t launch_cache_gather(int idx_bytes, int L, int K, int P, const void *p
     const int64_t rb = (int64_t)K * idx_bytes;
     const int U = pick_unit(rb, {(int64_t)(uintptr_t)pages, (int64_t)(uintptr_t)out});
     const int S = (int)(rb / U);
-    // layers per chunk: the LDS tile of kTokTile tokens stays within 48 KiB
-    int LC = (int)std::min<int64_t>(L, (48 * 1024 / (kTokTile * U) - 1) / S);
-    if (LC < 1) LC = 1;
+    const int LC = layers_per_chunk(L, S, U);
     const size_t lds = (size_t)kTokTile * ((LC * S) | 1) * U;
     dim3 grid((T + kTokTile - 1) / kTokTile, (L + LC - 1) / LC);
     ProfScope ps(PROF_CACHE_GATHER, s);
