@@ -81,7 +81,9 @@ def cpu_baseline(sh, tokens):
 def measured_ceilings(torch, r3, dev):
     """What this machine sustains on the two resources the rooflines are drawn against, measured with the
     library's calibration kernels outside the timed region: a register-only bf16 MFMA loop with constant and
-    with varied operand bits (the matrix rate is power-limited and depends on the data), and a plain copy."""
+    with varied operand bits (the matrix rate is power-limited and depends on the data), the same loop fed with the
+    expert GEMMs' mix of LDS fragment reads and global->LDS loads (no barriers, epilogues or HBM misses: what a
+    perfect schedule of that mix would reach), and a plain copy."""
     def timed(fn, reps=3):
         best = None
         for _ in range(reps):
@@ -97,11 +99,14 @@ def measured_ceilings(torch, r3, dev):
     src = torch.zeros(256 << 20, dtype=torch.uint8, device=dev)
     dst = torch.empty_like(src)
 
+    mix_src = torch.randn(1 << 19, device=dev).to(torch.bfloat16)
+
     def copy():
         r3.profile_copy(dst, src)
         return 2.0 * src.numel()
     out = {"mfma_bf16_constant_operands_TFLOPs": round(timed(lambda: r3.profile_mfma(20000, False, sink)) * 1e-12, 1),
            "mfma_bf16_varied_operands_TFLOPs": round(timed(lambda: r3.profile_mfma(20000, True, sink)) * 1e-12, 1),
+           "gemm_instruction_mix_TFLOPs": round(timed(lambda: r3.profile_gemm_mix(20000, mix_src, sink)) * 1e-12, 1),
            "hbm_copy_GBs": round(timed(copy) * 1e-9, 1)}
     del src, dst
     return out
@@ -379,6 +384,8 @@ def main():
         if roofline:   # context only: the same achieved rate against what this machine sustains on such data
             roofline["frac_of_measured_ceiling"] = round(
                 roofline["achieved"] / out["ceilings"]["mfma_bf16_varied_operands_TFLOPs"], 4)
+            roofline["frac_of_instruction_mix_ceiling"] = round(
+                roofline["achieved"] / out["ceilings"]["gemm_instruction_mix_TFLOPs"], 4)
     if args.cpu_tokens > 0:
         del buf
         torch.cuda.empty_cache()

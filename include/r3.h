@@ -275,6 +275,17 @@ int r3_profile_copy(void *dst, const void *src, size_t bytes, void *stream);
 int r3_profile_mfma(int iters, int random_operands, float *sink, void *stream);
 double r3_profile_mfma_flops(int iters);
 
+/*
+ * Measurement aid: the same MFMA loop fed the way the expert GEMMs feed theirs
+ * (`calib_mix_kernel`): per 8 MFMAs a wave reads 6 fragments from LDS, and per
+ * 16 MFMAs of each wave the work-group brings 32 KB into LDS with direct
+ * global->LDS loads from `src_1mib` (device, 1 MiB, 16-byte aligned, finite
+ * bf16 values; stays cache-resident).  No barriers, epilogues or HBM misses:
+ * the rate a perfect schedule of that instruction mix reaches under the power
+ * limit.  Same FLOP count as r3_profile_mfma (r3_profile_mfma_flops).
+ */
+int r3_profile_gemm_mix(int iters, const void *src_1mib, float *sink, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -21,7 +21,7 @@ _STATUS = {1: "R3_ERR_INVALID_ARG", 2: "R3_ERR_UNSUPPORTED", 3: "R3_ERR_WORKSPAC
 EXPORTS = ["r3_version", "r3_workspace_bytes", "r3_record_topk", "r3_replay_gate", "r3_permute",
            "r3_grouped_ffn", "r3_combine", "r3_moe_backward", "r3_profile_enable", "r3_profile_tags",
            "r3_profile_name", "r3_profile_read", "r3_profile_copy",
-           "r3_profile_mfma", "r3_profile_mfma_flops", "r3_routing_diff", "r3_policy_discrepancy",
+           "r3_profile_mfma", "r3_profile_mfma_flops", "r3_profile_gemm_mix", "r3_routing_diff", "r3_policy_discrepancy",
            "r3_policy_workspace_bytes", "r3_mask_cache_append", "r3_mask_cache_gather"]
 
 
@@ -240,6 +240,13 @@ def profile_mfma(iters, random_operands, sink):
     """Launch the register-only MFMA loop; returns the FLOP it performs (the caller times it)."""
     _check(lib().r3_profile_mfma(C.c_int(iters), C.c_int(1 if random_operands else 0), _p(sink), _stream()),
            "r3_profile_mfma")
+    return float(lib().r3_profile_mfma_flops(C.c_int(iters)))
+
+
+def profile_gemm_mix(iters, src, sink):
+    """Launch the MFMA + LDS-read + global->LDS loop; src: 1 MiB of finite bf16 values on the device."""
+    assert src.numel() * src.element_size() >= 1 << 20
+    _check(lib().r3_profile_gemm_mix(C.c_int(iters), _p(src), _p(sink), _stream()), "r3_profile_gemm_mix")
     return float(lib().r3_profile_mfma_flops(C.c_int(iters)))
 
 
