@@ -464,7 +464,11 @@ struct RowStage {
         for (int i = 0; i < 32 / RPI; ++i) {
             const int row = i * RPI + r;
             x.v[i] = make_uint4(0u, 0u, 0u, 0u);
-            if (row < valid) x.v[i] = *(const uint4 *)(in + row * ld_bytes + c * 16);
+            if (row < valid) {
+                // read once per launch: non-temporal, so the rows do not displace operand tiles in L2
+                typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+                x.v[i] = __builtin_bit_cast(uint4, __builtin_nontemporal_load((const u32x4 *)(in + row * ld_bytes + c * 16)));
+            }
         }
         return x;
     }

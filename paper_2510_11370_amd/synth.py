@@ -36,7 +36,7 @@ class LayerShape:
         return replace(self, **kw)
 
 
-# The five benchmark configurations (BASELINE.json "configs", in order).
+# The five benchmark configurations, smallest first (the second and third are the ones throughput is quoted on).
 CONFIGS = {
     "tiny_f32": LayerShape(T=256, d=128, E=8, K=2, F=256, act="f32", sigma=0.05, seed=0),
     "fwd_4k": LayerShape(T=4096, d=2048, E=128, K=8, F=768, sigma=0.01, seed=1),
