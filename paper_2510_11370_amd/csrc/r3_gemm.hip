@@ -167,7 +167,7 @@ ffn1_kernel(int S, int d, int F, const bf16_t *__restrict__ Xp, const int32_t *_
 
     Acc2 acc;
     zero_acc2(acc);
-    mfma_mainloop2(acc, d / kBK2, P, Q, s0, s1, s2, s3, row_end - row0 > 128);
+    mfma_mainloop2(acc, d / kBK2, P, Q, s0, s1, s2, s3, row_end - row0);
     tl.prefetch();
     if (more) aim(nxt);   // here, so that the row-index loads of a gathered tile hide behind the epilogue
 
@@ -284,7 +284,7 @@ rowgemm_kernel(int S, int d, int F, const bf16_t *__restrict__ Q0, const bf16_t 
 
     Acc2 acc;
     zero_acc2(acc);
-    mfma_mainloop2(acc, nk, P, Q, s0, s1, s2, s3, row_end - row0 > 128);
+    mfma_mainloop2(acc, nk, P, Q, s0, s1, s2, s3, row_end - row0);
     tl.prefetch();
 
     // per wave: 64 rows x 128 features, 32 rows at a time through LDS

@@ -93,6 +93,8 @@ __device__ __forceinline__ uint32_t lds_addr(const void *p) { return (uint32_t)(
 // counting.  No other instruction in these kernels uses M0.
 __device__ __forceinline__ void lds_load16(rsrc_t r, uint32_t dst_wave, int voff) {
     const uint32_t m0v = __builtin_amdgcn_readfirstlane(dst_wave);
+    // (no cache hint: marked non-temporal these loads ran the row-tiled kernels at half speed --
+    // the operand tiles live on being shared through L2 by the compute units of an XCD)
     asm volatile("s_mov_b32 m0, %0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds" ::"s"(m0v), "v"(voff), "s"(r)
                  : "memory");
 }
@@ -283,18 +285,18 @@ __device__ __forceinline__ void stage_barrier(bool loader) {
 }
 
 // nk k-tiles of 32.  st0..st3: the four 32 KB LDS stages (distinct arrays).
-// upper_half_live = false: output rows 128..255 of the tile are not needed (ragged tail of an
-// expert's segment); the waves that own them skip fragment reads and MFMAs and only keep
-// their share of the loads and the barriers going.
+// live_rows < 256: only output rows [0, live_rows) of the tile are needed (ragged tail of an
+// expert's segment); the waves whose rows are all dead skip fragment reads and MFMAs and only
+// keep their share of the loads and the barriers going.
 template <class POp, class QOp>
 __device__ __forceinline__ void mfma_mainloop2(Acc2 &acc, int nk, const POp &P, const QOp &Q, char *st0, char *st1,
-                                               char *st2, char *st3, bool upper_half_live = true) {
+                                               char *st2, char *st3, int live_rows = kTile) {
     if (nk <= 0) return;
     const uint32_t a0 = lds_addr(st0), a1 = lds_addr(st1), a2 = lds_addr(st2), a3 = lds_addr(st3);
     const int wave_ = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
     // wave-uniform, and visibly so (scalar branch instead of exec masking)
     const bool loader = wave_ < kLoaderWaves;
-    if (!upper_half_live && wave_ / kWP2 >= kWQ2 / 2) {
+    if ((wave_ / kWP2) * kWaveRowsQ >= live_rows) {
         // this wave's rows are not needed: keep the loads (if it is a loader) and the barriers going
         if (loader) {
             P.issue(0, a0);
@@ -432,7 +434,13 @@ struct RowStage {
         for (int i = 0; i < 32 / RPI; ++i) {
             const int row = i * RPI + r;
             const uint4 v = *(const uint4 *)(base + row * PITCH + c * 16);
-            if (row < valid) *(uint4 *)(out + row * ld_bytes + c * 16) = v;
+            if (row < valid) {
+                // non-temporal: the output is not read again by this kernel and should not displace
+                // operand tiles in L2 (measured: 1-3 % on the row-tiled GEMMs, at the price of 3 % on
+                // the much shorter kernels that read these rows next)
+                typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+                __builtin_nontemporal_store(__builtin_bit_cast(u32x4, v), (u32x4 *)(out + row * ld_bytes + c * 16));
+            }
         }
     }
     // same for f32 rows, adding what is already in memory (accumulate != 0)
