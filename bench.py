@@ -248,6 +248,9 @@ def main():
     ap.add_argument("--workload", default="fwdbwd_16k")
     ap.add_argument("--cpu-tokens", type=int, default=4096, help="tokens of the oracle's timed sample (0 = skip)")
     ap.add_argument("--forward-only", action="store_true")
+    ap.add_argument("--gathered-copy", action="store_true",
+                    help="materialise the expert-sorted copy of the tokens (Xp) instead of reading x through the "
+                         "permutation inside the expert GEMMs")
     ap.add_argument("--no-ceilings", action="store_true", help="skip the calibration kernels after the timed region")
     ap.add_argument("--calib-copy", action="store_true",
                     help="after the timed region, run one plain 256 MiB copy kernel (reference point for "
@@ -277,7 +280,7 @@ def main():
     Wr = [synth.draw(sh, "Wr", dev, layer=l).to(adt) for l in range(L)]
     dy = synth.draw(sh, "dy", dev).to(adt) if bwd else None
     bias = synth.draw(sh, "bias", dev)
-    buf = r3.LayerBuffers(D, backward=bwd, gathered_copy=bwd)   # forward only: rows gathered inside the GEMM
+    buf = r3.LayerBuffers(D, backward=bwd, gathered_copy=args.gathered_copy)   # default: rows gathered inside the GEMMs
     record = torch.zeros(L, sh.T, sh.K, dtype=r3.idx_torch_dtype(D), device=dev)   # layer-major record
     agree = torch.zeros(L, 2, dtype=torch.int64, device=dev)
 

@@ -131,7 +131,7 @@ int r3_permute(const r3_layer_desc *desc, const void *x, const void *idx,
  * r is then read as x[perm[r] / K] inside the first contraction's tile loads
  * and no gathered copy of the tokens is needed (r3_permute may be called with
  * Xp = NULL as well); needs T*d*sizeof(act) < 2^31.  x and perm are ignored
- * when Xp is given.  The backward needs Xp.
+ * when Xp is given.
  */
 int r3_grouped_ffn(const r3_layer_desc *desc, const void *Xp, const void *x, const int32_t *perm,
                    const int32_t *offsets, const void *W_gate, const void *W_up, const void *W_down,
@@ -153,6 +153,10 @@ int r3_combine(const r3_layer_desc *desc, const void *Yp, const float *gates,
  * dW_down [E,F,d] f32;  dbias [E] f32 or NULL.  accumulate = 0 overwrites the
  * weight gradients, 1 adds to them.  Experts outside a token's recorded set get
  * exactly zero router gradient from that token.
+ * Xp may be NULL (perm is then required): dW_gate and dW_up read the token rows
+ * from x through perm inside their tile loads, with the same results bit for
+ * bit; bf16 MFMA shapes only (else R3_ERR_UNSUPPORTED), T*d*sizeof(act) < 2^31.
+ * perm is not read when Xp is given.
  */
 int r3_moe_backward(const r3_layer_desc *desc, const void *dy, const void *x,
                     const void *W_r, const void *idx, const float *gates,

@@ -40,7 +40,7 @@ bool use_mfma_ffn(const Dims &m) { return m.act == R3_BF16 && mfma_ffn_supported
 bool use_mfma_router(const Dims &m) { return m.act == R3_BF16 && mfma_router_supported(m.d, m.E) && !force_simt(); }
 
 struct BwdWs {
-    size_t dYp, dz, ds, WrT, dA, dB, tiles, part, total;
+    size_t dYp, dz, ds, WrT, dA, dB, tiles, part, tok, total;
 };
 BwdWs bwd_layout(const Dims &m) {
     BwdWs w;
@@ -54,6 +54,7 @@ BwdWs bwd_layout(const Dims &m) {
     w.dB = take((size_t)m.S * m.F * m.eb);
     w.tiles = take(use_mfma_ffn(m) ? mfma_tiles_bytes(m.S, m.E) : 0);
     w.part = take(use_mfma_router(m) ? mfma_dwr_ws_bytes(m.T, m.d, m.E) : 0);
+    w.tok = take(use_mfma_ffn(m) ? mfma_row_tokens_bytes(m.S) : 0);  // row -> token list (backward without Xp)
     w.total = o;
     return w;
 }
@@ -178,11 +179,10 @@ int r3_moe_backward(const r3_layer_desc *desc, const void *dy, const void *x, co
                     const void *Yp, const void *W_gate, const void *W_up, const void *W_down, void *dx,
                     float *dW_r, float *dW_gate, float *dW_up, float *dW_down, float *dbias,
                     int accumulate, void *ws, size_t ws_bytes, void *stream) {
-    (void)perm;
     Dims m;
     int rc = check_desc(desc, m);
     if (rc) return rc;
-    const void *ptrs[] = {dy, x, W_r, idx, gates, inv_perm, offsets, Xp, A, B, H, Yp, W_gate, W_up, W_down,
+    const void *ptrs[] = {dy, x, W_r, idx, gates, inv_perm, offsets, A, B, H, Yp, W_gate, W_up, W_down,
                           dx, dW_r, dW_gate, dW_up, dW_down};
     for (const void *p : ptrs)
         if (!p) return R3_ERR_INVALID_ARG;
@@ -190,6 +190,10 @@ int r3_moe_backward(const r3_layer_desc *desc, const void *dy, const void *x, co
     for (const void *p : a16)
         if (!aligned(p, 16)) return R3_ERR_INVALID_ARG;
     if (accumulate != 0 && accumulate != 1) return R3_ERR_INVALID_ARG;
+    if (!Xp) {   // the gathered rows are read from x through perm
+        if (!perm || !aligned(perm, 4)) return R3_ERR_INVALID_ARG;
+        if (!use_mfma_ffn(m) || (int64_t)m.T * m.d * m.eb >= (1ll << 31)) return R3_ERR_UNSUPPORTED;
+    }
     const BwdWs w = bwd_layout(m);
     if (!ws || ws_bytes < w.total || !aligned(ws, 256)) return R3_ERR_WORKSPACE;
     hipStream_t s = (hipStream_t)stream;
@@ -217,7 +221,13 @@ int r3_moe_backward(const r3_layer_desc *desc, const void *dy, const void *x, co
         if (mfma_ffn_dh(m.S, m.d, m.E, m.F, dYp, offsets, tiles, W_down, A, B, dA, dB, s) != hipSuccess)
             return R3_ERR_HIP;
         if (mfma_wgrad(m.E, m.F, m.d, H, dYp, offsets, tiles, 2, dW_down, accumulate, s) != hipSuccess) return R3_ERR_HIP;
-        if (mfma_wgrad_pair(m.E, m.d, m.F, Xp, dA, dB, offsets, tiles, 3, dW_gate, dW_up, accumulate, s) != hipSuccess)
+        int32_t *tok = nullptr;
+        if (!Xp) {
+            tok = (int32_t *)(base + w.tok);
+            if (mfma_row_tokens(S, m.K, perm, tok, s) != hipSuccess) return R3_ERR_HIP;
+        }
+        if (mfma_wgrad_pair(m.E, m.d, m.F, Xp ? Xp : x, tok, m.T, dA, dB, offsets, tiles, 3, dW_gate, dW_up, accumulate,
+                            s) != hipSuccess)
             return R3_ERR_HIP;
         if (mfma_ffn_dxp(m.S, m.d, m.E, m.F, dA, dB, offsets, tiles, W_gate, W_up, dXp, s) != hipSuccess)
             return R3_ERR_HIP;

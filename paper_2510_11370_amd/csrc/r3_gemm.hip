@@ -24,6 +24,7 @@ namespace r3 {
 // counter that is longest-first scheduling, and a heavily loaded expert no longer starts late
 // and finishes alone.
 // ---------------------------------------------------------------------------
+constexpr int kRowTokensPad = 64;   // zeros after the row->token list
 constexpr int kTileOrder = 2 + 64;
 constexpr int kTileHdr = kTileOrder + kMaxE;
 __device__ __forceinline__ int *tile_counters(const int32_t *tiles, int launch) {
@@ -441,10 +442,14 @@ wgrad_kernel(int E, int NQd, int NPd, const bf16_t *__restrict__ Qs, const bf16_
 // of P0 and one of P1 at the same features, as in the forward SwiGLU kernel, so the Xp tile is
 // fetched once for both products.
 // ---------------------------------------------------------------------------
+// GATHER: Qs is the un-permuted matrix [nrows, NQd] and row r of the reduction is its row tok[r]
+// (dW_gate, dW_up straight from x: no gathered copy of the tokens is read).
+template <bool GATHER>
 __global__ void __launch_bounds__(kThreads2, kMinWavesPerSimd)
-wgrad_pair_kernel(int E, int NQd, int NPd, const bf16_t *__restrict__ Qs, const bf16_t *__restrict__ P0,
-                  const bf16_t *__restrict__ P1, const int32_t *__restrict__ offsets, float *__restrict__ out0,
-                  float *__restrict__ out1, int accumulate, int *ctr, const int32_t *__restrict__ order) {
+wgrad_pair_kernel(int E, int NQd, int NPd, const bf16_t *__restrict__ Qs, const int32_t *__restrict__ tok, int nrows,
+                  const bf16_t *__restrict__ P0, const bf16_t *__restrict__ P1, const int32_t *__restrict__ offsets,
+                  float *__restrict__ out0, float *__restrict__ out1, int accumulate, int *ctr,
+                  const int32_t *__restrict__ order) {
     __shared__ __attribute__((aligned(1024))) char s0[kStageBytes];
     __shared__ __attribute__((aligned(1024))) char s1[kStageBytes];
     __shared__ __attribute__((aligned(1024))) char s2[kStageBytes];
@@ -456,9 +461,13 @@ wgrad_pair_kernel(int E, int NQd, int NPd, const bf16_t *__restrict__ Qs, const 
     const int wp = wave % kWP2, wq = wave / kWP2;
     OpTR128x2 P;
     P.init(NPd * 2, 0, 64 * wp);
-    OpTR256 Q;
-    Q.kswitch = 0x7fffffff;
-    Q.init(NQd * 2, 0, kWaveRowsQ * wq);
+    typename std::conditional<GATHER, OpTR256G, OpTR256>::type Q;
+    if constexpr (GATHER) {
+        Q.init(NQd * 2, kWaveRowsQ * wq);
+    } else {
+        Q.kswitch = 0x7fffffff;
+        Q.init(NQd * 2, 0, kWaveRowsQ * wq);
+    }
     TileLoop tl(E * nqt * npt, ctr);
     for (int slot = tl.first(), next = tl.second(); tl.valid(slot);) {
     const int id = tl.id(slot);
@@ -471,9 +480,13 @@ wgrad_pair_kernel(int E, int NQd, int NPd, const bf16_t *__restrict__ Qs, const 
     const uint64_t pbytes = clamp_bytes(((int64_t)(r1 - r0) * NPd - p0) * 2);
     P.src[0] = Src{(const char *)(P0 + (int64_t)r0 * NPd + p0), pbytes, (uint32_t)(kBK2 * NPd * 2)};
     P.src[1] = Src{(const char *)(P1 + (int64_t)r0 * NPd + p0), pbytes, (uint32_t)(kBK2 * NPd * 2)};
-    Q.src[0] = Src{(const char *)(Qs + (int64_t)r0 * NQd + q0), clamp_bytes(((int64_t)(r1 - r0) * NQd - q0) * 2),
-                   (uint32_t)(kBK2 * NQd * 2)};
-    Q.src[1] = Q.src[0];
+    if constexpr (GATHER) {
+        Q.aim(Qs, (uint64_t)nrows * NQd * 2, q0 * 2, tok + r0, r1 - r0);
+    } else {
+        Q.src[0] = Src{(const char *)(Qs + (int64_t)r0 * NQd + q0), clamp_bytes(((int64_t)(r1 - r0) * NQd - q0) * 2),
+                       (uint32_t)(kBK2 * NQd * 2)};
+        Q.src[1] = Q.src[0];
+    }
 
     Acc2 acc;
     zero_acc2(acc);
@@ -668,14 +681,35 @@ hipError_t mfma_wgrad(int E, int NQd, int NPd, const void *Qs, const void *Ps, c
     return hipGetLastError();
 }
 
-hipError_t mfma_wgrad_pair(int E, int NQd, int NPd, const void *Qs, const void *P0, const void *P1,
-                           const int32_t *offsets, const int32_t *tiles, int launch, float *out0, float *out1,
-                           int accumulate, hipStream_t s) {
+hipError_t mfma_wgrad_pair(int E, int NQd, int NPd, const void *Qs, const int32_t *tok, int nrows, const void *P0,
+                           const void *P1, const int32_t *offsets, const int32_t *tiles, int launch, float *out0,
+                           float *out1, int accumulate, hipStream_t s) {
     const int64_t ntiles = (int64_t)E * (NQd / kTile) * (NPd / 128);
     ProfScope ps(PROF_WGRAD_PAIR, s);
-    wgrad_pair_kernel<<<persistent_grid(ntiles), kThreads2, 0, s>>>(
-        E, NQd, NPd, (const bf16_t *)Qs, (const bf16_t *)P0, (const bf16_t *)P1, offsets, out0, out1, accumulate,
-        const_cast<int *>(tiles) + 2 + 8 * launch, tiles + kTileOrder);
+    if (tok)
+        wgrad_pair_kernel<true><<<persistent_grid(ntiles), kThreads2, 0, s>>>(
+            E, NQd, NPd, (const bf16_t *)Qs, tok, nrows, (const bf16_t *)P0, (const bf16_t *)P1, offsets, out0, out1,
+            accumulate, const_cast<int *>(tiles) + 2 + 8 * launch, tiles + kTileOrder);
+    else
+        wgrad_pair_kernel<false><<<persistent_grid(ntiles), kThreads2, 0, s>>>(
+            E, NQd, NPd, (const bf16_t *)Qs, nullptr, 0, (const bf16_t *)P0, (const bf16_t *)P1, offsets, out0, out1,
+            accumulate, const_cast<int *>(tiles) + 2 + 8 * launch, tiles + kTileOrder);
+    return hipGetLastError();
+}
+
+// tok[r] = perm[r] / K for r < S (the token whose row sits at position r of the expert-sorted order),
+// followed by `pad` zeros, so that index fetches one past a segment's end stay inside the array
+__global__ void __launch_bounds__(256) row_tokens_kernel(int S, int K, int pad, const int32_t *__restrict__ perm,
+                                                         int32_t *__restrict__ tok) {
+    const int r = blockIdx.x * 256 + threadIdx.x;
+    if (r < S) tok[r] = perm[r] / K;
+    else if (r < S + pad) tok[r] = 0;
+}
+
+size_t mfma_row_tokens_bytes(int64_t S) { return (size_t)(S + kRowTokensPad) * sizeof(int32_t); }
+
+hipError_t mfma_row_tokens(int S, int K, const int32_t *perm, int32_t *tok, hipStream_t s) {
+    row_tokens_kernel<<<(S + kRowTokensPad + 255) / 256, 256, 0, s>>>(S, K, kRowTokensPad, perm, tok);
     return hipGetLastError();
 }
 

@@ -98,10 +98,15 @@ hipError_t mfma_ffn_dxp(int64_t S, int d, int E, int F, const void *dA, const vo
 // tile counters of this launch: 0 and 1 belong to the forward pair and to dh / dxp
 hipError_t mfma_wgrad(int E, int NQd, int NPd, const void *Qs, const void *Ps, const int32_t *offsets,
                       const int32_t *tiles, int launch, float *out, int accumulate, hipStream_t s);
-// out0 (+)= Qs^T P0 and out1 (+)= Qs^T P1 per expert in one pass over Qs
-hipError_t mfma_wgrad_pair(int E, int NQd, int NPd, const void *Qs, const void *P0, const void *P1,
-                           const int32_t *offsets, const int32_t *tiles, int launch, float *out0, float *out1,
-                           int accumulate, hipStream_t s);
+// out0 (+)= Qs^T P0 and out1 (+)= Qs^T P1 per expert in one pass over Qs.  tok != NULL: Qs is the
+// un-permuted [nrows, NQd] matrix and row r of the reduction is its row tok[r] (a list made by
+// mfma_row_tokens; nrows * NQd * 2 < 2^31)
+hipError_t mfma_wgrad_pair(int E, int NQd, int NPd, const void *Qs, const int32_t *tok, int nrows, const void *P0,
+                           const void *P1, const int32_t *offsets, const int32_t *tiles, int launch, float *out0,
+                           float *out1, int accumulate, hipStream_t s);
+// tok[r] = perm[r] / K (r < S), padded; mfma_row_tokens_bytes(S) bytes
+size_t mfma_row_tokens_bytes(int64_t S);
+hipError_t mfma_row_tokens(int S, int K, const int32_t *perm, int32_t *tok, hipStream_t s);
 hipError_t mfma_router_logits(int T, int d, int E, const void *x, const void *Wr, const float *bias,
                               float *logits, hipStream_t s);
 hipError_t mfma_dwr(int T, int d, int E, const void *x, const void *ds, float *part, float *dWr, int accumulate,

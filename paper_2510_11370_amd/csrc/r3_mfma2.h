@@ -152,6 +152,7 @@ struct DmaTR {
 //            wave come from sub-tile 0 and tiles 2,3 from sub-tile 1 at the same features
 // A second Src set takes over from k-tile `kswitch` on (two-phase reductions).
 struct OpKC256 {
+    static constexpr bool kIndexed = false;
     static constexpr int kDsReads = kTP2, kDsReadsQ = kTQ2;  // ds_read_b128 per sub-step as P / as Q
     Src src[2];
     int kswitch;
@@ -170,6 +171,7 @@ struct OpKC256 {
 };
 
 struct OpTR256 {
+    static constexpr bool kIndexed = false;
     static constexpr int kDsReads = 2 * kTP2, kDsReadsQ = 2 * kTQ2;  // two ds_read_b64_tr_b16 per fragment
     Src src[2];
     int kswitch;
@@ -188,6 +190,7 @@ struct OpTR256 {
 };
 
 struct OpTR128x2 {
+    static constexpr bool kIndexed = false;
     static constexpr int kDsReads = 2 * kTP2, kDsReadsQ = 2 * kTQ2;
     Src src[2];  // sub-tile 0, sub-tile 1
     DmaTR<128> dma;
@@ -203,6 +206,76 @@ struct OpTR128x2 {
     __device__ __forceinline__ bf16x8_t frag(const char *tile, int t, int s) const {
         return fr.read(tile + (t >> 1) * (kOperandBytes / 2), t & 1, s);
     }
+};
+
+// Transposed 256-feature tile whose k-rows are gathered through an index: k-row r of the reduction is
+// row rows[r] of a row-major matrix of `ld_bytes` per row, so a permuted copy of that matrix never has
+// to exist.  A chunk of the tile is two k-rows; their two indices are fetched with scalar loads one
+// stage ahead of the tile loads that use them (scalar loads do not touch the vector-memory counter
+// that paces the stages), and each lane builds its own row address.  k-rows >= n read as zero (an
+// offset outside the buffer window).  `rows` must be readable up to index n (one past the live rows).
+typedef const __attribute__((address_space(4))) int32_t *const_i32_ptr;
+struct OpTR256G {
+    static constexpr int kDsReads = 2 * kTP2, kDsReadsQ = 2 * kTQ2;
+    static constexpr bool kIndexed = true;
+    static constexpr int kOutside = 0x7ffffff0;  // beyond any window (windows are < 2^31 bytes)
+    rsrc_t rs;
+    const_i32_ptr rows;
+    int n, ld_bytes, wl;
+    int cvoff[4];
+    mutable int pend[8];   // indices of this wave's eight k-rows of the next stage to issue
+    TrFrag<256> fr;
+    __device__ __forceinline__ void init(int ld_bytes_, int wave_base) {
+        wl = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6) & 3);
+        ld_bytes = ld_bytes_;
+        fr.init(wave_base);
+    }
+    // loader wave wl owns chunks 4 wl .. 4 wl + 3 of a stage, i.e. k-rows 8 wl .. 8 wl + 7: eight
+    // consecutive entries of the index list (past the live rows the base is held at n: unused values)
+    __device__ __forceinline__ void fetch(int kt) const {
+        const int base = min(kt * kBK2 + 8 * wl, n);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) pend[j] = rows[base + j];
+    }
+    // point at a tile: the whole matrix (`bytes` < 2^31), feature offset col_bytes, index list, live k-rows
+    __device__ __forceinline__ void aim(const void *matrix, uint64_t bytes, int col_bytes, const int32_t *rows_, int n_) {
+        rs = src_rsrc(Src{(const char *)matrix, bytes, 0u}, 0);
+        // wave-uniform by construction (a tile's coordinates); said so, so that the index fetches are
+        // scalar loads -- as vector loads they would count against the stage pacing
+        const uint64_t ra = (uint64_t)rows_;
+        rows = (const_i32_ptr)(((uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(ra >> 32)) << 32) |
+                               (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)ra));
+        n = __builtin_amdgcn_readfirstlane(n_);
+        col_bytes = __builtin_amdgcn_readfirstlane(col_bytes);
+        const int lane = threadIdx.x & 63, pc = lane & 31;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int k = 2 * i + (lane >> 5);   // k-row within the wave's eight; 8 wl does not change k & 3
+            cvoff[i] = col_bytes + ((((pc >> 2) ^ (k & 3)) << 2) | (pc & 3)) * 16;
+        }
+        fetch(0);
+    }
+    __device__ __forceinline__ void issue(int kt, uint32_t tile) const {
+        const int lane = threadIdx.x & 63;
+        // the next stage's indices are asked for first, so that the scalar loads' latency runs
+        // under the address arithmetic and the four tile loads of this stage
+        int nxt[8];
+        {
+            const int base = min((kt + 1) * kBK2 + 8 * wl, n);
+#pragma unroll
+            for (int j = 0; j < 8; ++j) nxt[j] = rows[base + j];
+        }
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int k = kt * kBK2 + 8 * wl + 2 * i + (lane >> 5);
+            const int row = (lane & 32) ? pend[2 * i + 1] : pend[2 * i];
+            const int voff = k < n ? row * ld_bytes + cvoff[i] : kOutside;
+            lds_load16(rs, tile + 1024 * (4 * wl + i), voff);
+        }
+#pragma unroll
+        for (int j = 0; j < 8; ++j) pend[j] = nxt[j];
+    }
+    __device__ __forceinline__ bf16x8_t frag(const char *tile, int t, int s) const { return fr.read(tile, t, s); }
 };
 
 typedef f32x16_t Acc2[kTP2][kTQ2];
@@ -323,12 +396,23 @@ __device__ __forceinline__ void mfma_mainloop2(Acc2 &acc, int nk, const POp &P, 
     }
     if (loader) {
         // stages 0, 1, 2 (a stage >= nk loads nothing useful but still counts)
-        P.issue(0, a0);
-        Q.issue(0, a0 + kOperandBytes);
-        P.issue(1, a1);
-        Q.issue(1, a1 + kOperandBytes);
-        P.issue(2, a2);
-        Q.issue(2, a2 + kOperandBytes);
+        if constexpr (POp::kIndexed || QOp::kIndexed) {
+            // an indexed operand's address arithmetic per stage is long: kept as a real loop, or the
+            // compiler works out all three stages ahead and spills the results
+#pragma nounroll
+            for (int st = 0; st < 3; ++st) {
+                const uint32_t a = st == 0 ? a0 : st == 1 ? a1 : a2;
+                P.issue(st, a);
+                Q.issue(st, a + kOperandBytes);
+            }
+        } else {
+            P.issue(0, a0);
+            Q.issue(0, a0 + kOperandBytes);
+            P.issue(1, a1);
+            Q.issue(1, a1 + kOperandBytes);
+            P.issue(2, a2);
+            Q.issue(2, a2 + kOperandBytes);
+        }
     }
     stage_barrier(loader);
     Frags x, y;

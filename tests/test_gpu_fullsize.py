@@ -116,3 +116,17 @@ def test_router_weight_gradient_with_sparse_upstream_gradient(full):
     other = np.setdiff1d(np.arange(sh.T), tok)[:512]
     assert not buf.dx[torch.from_numpy(other).cuda()].any()  # no gradient where dy is zero
     assert not torch.equal(keep, buf.dW_r)
+
+
+def test_without_the_gathered_copy_bit_identical(full):
+    """The launch configuration bench.py times: no expert-sorted copy of the tokens; forward and backward read
+    x through the permutation inside the expert GEMMs.  Every output equals the gathered-copy path's bit for bit."""
+    sh, t, buf = full["sh"], full["t"], full["buf"]
+    r3.backward(buf, t["dy"], t["x"], t["Wr"], full["rec"], t["Wg"], t["Wu"], t["Wd"])   # (an earlier test used a sparse dy)
+    buf2 = r3.LayerBuffers(full["D"], backward=True, gathered_copy=False)
+    r3.forward(buf2, t["x"], t["Wr"], full["rec"], t["Wg"], t["Wu"], t["Wd"])
+    r3.backward(buf2, t["dy"], t["x"], t["Wr"], full["rec"], t["Wg"], t["Wu"], t["Wd"])
+    torch.cuda.synchronize()
+    assert buf2.Xp is None and int(buf2.status.item()) == 0
+    for k in ("y", "Yp", "H", "gates", "dx", "dW_r", "dW_gate", "dW_up", "dW_down"):
+        assert torch.equal(getattr(buf, k), getattr(buf2, k)), k

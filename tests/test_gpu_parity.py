@@ -310,6 +310,22 @@ def test_backward_chain(name, simt):
     sync()
     for k in ("dW_r", "dW_gate", "dW_up", "dW_down"):
         assert torch.allclose(getattr(buf, k), 2 * keep[k], rtol=1e-5, atol=1e-6 * float(keep[k].abs().max())), k
+    # without the gathered copy of the tokens: forward and backward read x through perm inside the expert
+    # GEMMs' tile loads; every result is the same bit for bit (MFMA shapes; the others say unsupported)
+    buf2 = r3.LayerBuffers(c.D, backward=True, gathered_copy=False)
+    mfma = name.startswith("mfma") and not simt
+    if mfma:
+        r3.forward(buf2, c.t["x"], c.t["Wr"], c.t["idx"], c.t["Wg"], c.t["Wu"], c.t["Wd"], bias=c.t["bias"])
+        r3.backward(buf2, c.t["dy"], c.t["x"], c.t["Wr"], c.t["idx"], c.t["Wg"], c.t["Wu"], c.t["Wd"])
+        sync()
+        assert buf2.Xp is None and int(buf2.status.item()) == 0
+        for k, v in keep.items():
+            assert torch.equal(getattr(buf2, k), v), k
+    else:
+        r3.forward(buf2, c.t["x"], c.t["Wr"], c.t["idx"], c.t["Wg"], c.t["Wu"], c.t["Wd"], bias=c.t["bias"])
+        with pytest.raises(r3.R3Error, match="UNSUPPORTED"):
+            r3.backward(buf2, c.t["dy"], c.t["x"], c.t["Wr"], c.t["idx"], c.t["Wg"], c.t["Wu"], c.t["Wd"])
+        sync()
 
 
 def test_router_gradient_is_zero_off_the_replayed_set():
