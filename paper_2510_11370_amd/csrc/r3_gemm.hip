@@ -104,24 +104,23 @@ __device__ __forceinline__ void unpack4(uint2 v, float *f) {
 // the same features, so a wave holds both pre-activations of a (row, feature)
 // pair in the same lane: MFMA tiles 0,1 are gate, tiles 2,3 the matching up.
 // ---------------------------------------------------------------------------
+template <bool GATHER>
 __global__ void __launch_bounds__(kThreads2, kMinWavesPerSimd)
 ffn1_kernel(int S, int d, int F, const bf16_t *__restrict__ Xp, const int32_t *__restrict__ perm, int K, int T,
             const int32_t *__restrict__ offsets, const int32_t *__restrict__ tiles, const bf16_t *__restrict__ Wg,
             const bf16_t *__restrict__ Wu, bf16_t *__restrict__ H, bf16_t *__restrict__ A, bf16_t *__restrict__ B,
             int launch) {
-    __shared__ __attribute__((aligned(1024))) char s0[kStageBytes];
-    __shared__ __attribute__((aligned(1024))) char s1[kStageBytes];
-    __shared__ __attribute__((aligned(1024))) char s2[kStageBytes];
-    __shared__ __attribute__((aligned(1024))) char s3[kStageBytes];
+    __shared__ __attribute__((aligned(1024))) char bufA[kSuperBytes];
+    __shared__ __attribute__((aligned(1024))) char bufB[kSuperBytes];
     __shared__ int mailbox[2];
+    char *const s0 = bufA, *const s1 = bufA + kStageBytes, *const s2 = bufB, *const s3 = bufB + kStageBytes;
     constexpr int BF = 128;  // features per tile
     const int npt = F / BF;
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int wp = wave % kWP2, wq = wave / kWP2;
     OpTR128x2 P;
     P.init(F * 2, 0, 64 * wp);
-    OpKC256 Q;
-    Q.kswitch = 0x7fffffff;
+    OpKC64<GATHER> Q;
     Q.init(d * 2, kWaveRowsQ * wq);
     TileLoopStatic tl(tiles[0] * npt, tile_counters(tiles, launch));
     struct Tile {
@@ -141,19 +140,19 @@ ffn1_kernel(int S, int d, int F, const bf16_t *__restrict__ Xp, const int32_t *_
         const int64_t wb = ((int64_t)d * F - t.f0) * 2;
         P.src[0] = Src{(const char *)(Wg + (int64_t)t.e * d * F + t.f0), clamp_bytes(wb), (uint32_t)(kBK2 * F * 2)};
         P.src[1] = Src{(const char *)(Wu + (int64_t)t.e * d * F + t.f0), clamp_bytes(wb), (uint32_t)(kBK2 * F * 2)};
-        if (perm) {
-            // dispatch folded into the tile load: `Xp` is x [T,d]; each lane's four rows of the tile
+        if constexpr (GATHER) {
+            // dispatch folded into the tile load: `Xp` is x [T,d]; each lane's eight rows of the tile
             // are read from their tokens' rows (rows past the end of the permutation repeat the last
             // one; they are never stored)
-            Q.src[0] = Src{(const char *)Xp, clamp_bytes((int64_t)T * d * 2), kBK2 * 2};
+            Q.src[0] = Src{(const char *)Xp, clamp_bytes((int64_t)T * d * 2), kBK3 * 2};
+            const int chunk = Q.lane_chunk();
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const int local = 16 * ((wave & 3) + kLoaderWaves * i) + (lane >> 2);
-                const int tok = perm[min(t.row0 + local, S - 1)] / K;
-                Q.dma.voff[i] = tok * (d * 2) + (((lane & 3) ^ ((local >> 2) & 3)) << 4);
+            for (int i = 0; i < 8; ++i) {
+                const int tok = perm[min(t.row0 + Q.lane_row(i), S - 1)] / K;
+                Q.voff[i] = tok * (d * 2) + chunk;
             }
         } else {
-            Q.src[0] = Src{(const char *)(Xp + (int64_t)t.row0 * d), clamp_bytes((int64_t)(S - t.row0) * d * 2), kBK2 * 2};
+            Q.src[0] = Src{(const char *)(Xp + (int64_t)t.row0 * d), clamp_bytes((int64_t)(S - t.row0) * d * 2), kBK3 * 2};
         }
         Q.src[1] = Q.src[0];
     };
@@ -168,7 +167,7 @@ ffn1_kernel(int S, int d, int F, const bf16_t *__restrict__ Xp, const int32_t *_
 
     Acc2 acc;
     zero_acc2(acc);
-    mfma_mainloop2(acc, d / kBK2, P, Q, s0, s1, s2, s3, row_end - row0);
+    mfma_mainloop3(acc, d / kBK3, P, Q, bufA, bufB, row_end - row0);
     tl.prefetch();
     if (more) aim(nxt);   // here, so that the row-index loads of a gathered tile hide behind the epilogue
 
@@ -223,25 +222,29 @@ rowgemm_kernel(int S, int d, int F, const bf16_t *__restrict__ Q0, const bf16_t 
                const int32_t *__restrict__ offsets, const int32_t *__restrict__ tiles,
                const bf16_t *__restrict__ W0, const bf16_t *__restrict__ W1, const bf16_t *__restrict__ A,
                const bf16_t *__restrict__ B, bf16_t *__restrict__ out0, bf16_t *__restrict__ out1, int launch) {
-    __shared__ __attribute__((aligned(1024))) char s0[kStageBytes];
-    __shared__ __attribute__((aligned(1024))) char s1[kStageBytes];
-    __shared__ __attribute__((aligned(1024))) char s2[kStageBytes];
-    __shared__ __attribute__((aligned(1024))) char s3[kStageBytes];
+    __shared__ __attribute__((aligned(1024))) char bufA[kSuperBytes];
+    __shared__ __attribute__((aligned(1024))) char bufB[kSuperBytes];
     __shared__ int mailbox[2];
+    char *const s0 = bufA, *const s1 = bufA + kStageBytes, *const s2 = bufB, *const s3 = bufB + kStageBytes;
     const int NOUT = (MODE == 1) ? F : d;  // width of the output
     const int KQ = (MODE == 1) ? d : F;    // width of the Q source rows
     const int npt = NOUT / kTile;
-    const int nk = (MODE == 0) ? F / kBK2 : (MODE == 1) ? d / kBK2 : 2 * (F / kBK2);
+    const int nw = (MODE == 0) ? F / kBK3 : (MODE == 1) ? d / kBK3 : 2 * (F / kBK3);   // windows of 64 k
     const int wave = threadIdx.x >> 6;
     const int wp = wave % kWP2, wq = wave / kWP2;
     // operand forms: the weights are feature-contiguous (TR) for MODE 0, K-contiguous otherwise
-    typedef typename std::conditional<MODE == 0, OpTR256, OpKC256>::type POp;
+    typedef typename std::conditional<MODE == 0, OpTR256, OpKC64<false>>::type POp;
     POp P;
-    OpKC256 Q;
-    P.kswitch = Q.kswitch = (MODE == 2) ? F / kBK2 : 0x7fffffff;
-    if constexpr (MODE == 0) P.init(d * 2, 0, 128 * wp);
-    else P.init((MODE == 1 ? d : F) * 2, 128 * wp);
+    OpKC64<false> Q;
+    if constexpr (MODE == 0) {
+        P.kswitch = 0x7fffffff;
+        P.init(d * 2, 0, 128 * wp);
+    } else {
+        P.init((MODE == 1 ? d : F) * 2, 128 * wp);
+        if constexpr (MODE == 2) P.wswitch = F / kBK3;
+    }
     Q.init(KQ * 2, kWaveRowsQ * wq);
+    if constexpr (MODE == 2) Q.wswitch = F / kBK3;
     TileLoopStatic tl(tiles[0] * npt, tile_counters(tiles, launch));
     struct Tile {
         int e, row0, row_end, p0;
@@ -258,20 +261,20 @@ rowgemm_kernel(int S, int d, int F, const bf16_t *__restrict__ Q0, const bf16_t 
     };
     auto aim = [&](const Tile &t) {   // point the operands at a tile
         const bf16_t *w0 = W0 + (int64_t)t.e * d * F;
-        Q.src[0] = Src{(const char *)(Q0 + (int64_t)t.row0 * KQ), clamp_bytes((int64_t)(S - t.row0) * KQ * 2), kBK2 * 2};
+        Q.src[0] = Src{(const char *)(Q0 + (int64_t)t.row0 * KQ), clamp_bytes((int64_t)(S - t.row0) * KQ * 2), kBK3 * 2};
         Q.src[1] = Q.src[0];
         if constexpr (MODE == 2)
-            Q.src[1] = Src{(const char *)(Q1 + (int64_t)t.row0 * KQ), clamp_bytes((int64_t)(S - t.row0) * KQ * 2), kBK2 * 2};
+            Q.src[1] = Src{(const char *)(Q1 + (int64_t)t.row0 * KQ), clamp_bytes((int64_t)(S - t.row0) * KQ * 2), kBK3 * 2};
         if constexpr (MODE == 0) {
             P.src[0] = Src{(const char *)(w0 + t.p0), clamp_bytes(((int64_t)d * F - t.p0) * 2), (uint32_t)(kBK2 * d * 2)};
             P.src[1] = P.src[0];
         } else if constexpr (MODE == 1) {
-            P.src[0] = Src{(const char *)(w0 + (int64_t)t.p0 * d), clamp_bytes((int64_t)(F - t.p0) * d * 2), kBK2 * 2};
+            P.src[0] = Src{(const char *)(w0 + (int64_t)t.p0 * d), clamp_bytes((int64_t)(F - t.p0) * d * 2), kBK3 * 2};
             P.src[1] = P.src[0];
         } else {
             const bf16_t *w1 = W1 + (int64_t)t.e * d * F;
-            P.src[0] = Src{(const char *)(w0 + (int64_t)t.p0 * F), clamp_bytes((int64_t)(d - t.p0) * F * 2), kBK2 * 2};
-            P.src[1] = Src{(const char *)(w1 + (int64_t)t.p0 * F), clamp_bytes((int64_t)(d - t.p0) * F * 2), kBK2 * 2};
+            P.src[0] = Src{(const char *)(w0 + (int64_t)t.p0 * F), clamp_bytes((int64_t)(d - t.p0) * F * 2), kBK3 * 2};
+            P.src[1] = Src{(const char *)(w1 + (int64_t)t.p0 * F), clamp_bytes((int64_t)(d - t.p0) * F * 2), kBK3 * 2};
         }
     };
     if (!tl.valid(tl.first())) return;
@@ -285,7 +288,7 @@ rowgemm_kernel(int S, int d, int F, const bf16_t *__restrict__ Q0, const bf16_t 
 
     Acc2 acc;
     zero_acc2(acc);
-    mfma_mainloop2(acc, nk, P, Q, s0, s1, s2, s3, row_end - row0);
+    mfma_mainloop3(acc, nw, P, Q, bufA, bufB, row_end - row0);
     tl.prefetch();
 
     // per wave: 64 rows x 128 features, 32 rows at a time through LDS
@@ -638,9 +641,14 @@ hipError_t mfma_ffn_forward(int64_t S, int d, int E, int F, const void *Xp, cons
     const int mt = max_row_tiles(S, E, kTile);
     {
         ProfScope ps(PROF_FFN1, s);
-        ffn1_kernel<<<persistent_grid((int64_t)mt * (F / 128)), kThreads2, 0, s>>>(
-            (int)S, d, F, (const bf16_t *)Xp, perm, K, T, offsets, tiles, (const bf16_t *)Wg, (const bf16_t *)Wu,
-            (bf16_t *)H, (bf16_t *)A, (bf16_t *)B, 0);
+        if (perm)
+            ffn1_kernel<true><<<persistent_grid((int64_t)mt * (F / 128)), kThreads2, 0, s>>>(
+                (int)S, d, F, (const bf16_t *)Xp, perm, K, T, offsets, tiles, (const bf16_t *)Wg, (const bf16_t *)Wu,
+                (bf16_t *)H, (bf16_t *)A, (bf16_t *)B, 0);
+        else
+            ffn1_kernel<false><<<persistent_grid((int64_t)mt * (F / 128)), kThreads2, 0, s>>>(
+                (int)S, d, F, (const bf16_t *)Xp, perm, K, T, offsets, tiles, (const bf16_t *)Wg, (const bf16_t *)Wu,
+                (bf16_t *)H, (bf16_t *)A, (bf16_t *)B, 0);
     }
     ProfScope ps(PROF_FFN2, s);
     rowgemm_kernel<0><<<persistent_grid((int64_t)mt * (d / kTile)), kThreads2, 0, s>>>(

@@ -1,5 +1,6 @@
-// 256x256 bf16 MFMA tile loop for gfx950 with direct global->LDS loads and a four-stage
-// LDS ring (32 k per stage, loads issued three stages ahead).
+// 256x256 bf16 MFMA tile loops for gfx950 with direct global->LDS loads: a ring of 32-k stages
+// (loads issued two stages ahead; used where both operands are transposed tiles) and, further
+// down, a two-buffer loop over 64-k windows (used where an operand is K-contiguous).
 //
 // D[p][q] = sum_k P[p][k] * Q[q][k], f32 accumulation; P feeds the MFMA A operand
 // (output's contiguous dimension), Q the B operand (output rows).  8 waves, arranged
@@ -21,8 +22,8 @@
 // flight never alias the stage being read (no vmcnt wait in front of the fragment reads).
 // Wave roles.  All 8 waves multiply.  Waves 0-3 ("loaders") also issue every tile load and
 // count them: each issues the same number of loads per stage (a stage past the end of the
-// reduction gets a zero-length descriptor), so "s_waitcnt vmcnt(2 stages' worth)" at the end
-// of stage kt is exactly "stage kt+1 has landed".  (Having waves 4-7 touch the lines of
+// reduction gets a zero-length descriptor), so "s_waitcnt vmcnt(one stage's worth)" at the end
+// of stage kt is exactly "stage kt+1 has landed" (a third stage of prefetch was measured: no gain).  (Having waves 4-7 touch the lines of
 // later stages to warm L2 was tried and measured slower: the extra requests cost more in the
 // vector memory path than the shorter load latency gave back.)
 #pragma once
@@ -89,7 +90,7 @@ __device__ __forceinline__ uint32_t lds_addr(const void *p) { return (uint32_t)(
 // buffer_load_dwordx4 ... lds: lane i's 16 bytes go to LDS address dst_wave + 16 i.
 // Written as inline asm on purpose: the compiler then neither tracks these loads nor puts
 // conservative vmcnt waits in front of later LDS reads (it cannot tell that a read of the
-// resident stage does not alias a load three stages ahead); stage_barrier() does the
+// resident stage does not alias a load two stages ahead); stage_barrier() does the
 // counting.  No other instruction in these kernels uses M0.
 __device__ __forceinline__ void lds_load16(rsrc_t r, uint32_t dst_wave, int voff) {
     const uint32_t m0v = __builtin_amdgcn_readfirstlane(dst_wave);
@@ -152,7 +153,7 @@ struct DmaTR {
 //            wave come from sub-tile 0 and tiles 2,3 from sub-tile 1 at the same features
 // A second Src set takes over from k-tile `kswitch` on (two-phase reductions).
 struct OpKC256 {
-    static constexpr bool kIndexed = false;
+    static constexpr bool kIndexed = false, kWindowed = false;
     static constexpr int kDsReads = kTP2, kDsReadsQ = kTQ2;  // ds_read_b128 per sub-step as P / as Q
     Src src[2];
     int kswitch;
@@ -171,7 +172,7 @@ struct OpKC256 {
 };
 
 struct OpTR256 {
-    static constexpr bool kIndexed = false;
+    static constexpr bool kIndexed = false, kWindowed = false;
     static constexpr int kDsReads = 2 * kTP2, kDsReadsQ = 2 * kTQ2;  // two ds_read_b64_tr_b16 per fragment
     Src src[2];
     int kswitch;
@@ -190,7 +191,7 @@ struct OpTR256 {
 };
 
 struct OpTR128x2 {
-    static constexpr bool kIndexed = false;
+    static constexpr bool kIndexed = false, kWindowed = false;
     static constexpr int kDsReads = 2 * kTP2, kDsReadsQ = 2 * kTQ2;
     Src src[2];  // sub-tile 0, sub-tile 1
     DmaTR<128> dma;
@@ -217,7 +218,7 @@ struct OpTR128x2 {
 typedef const __attribute__((address_space(4))) int32_t *const_i32_ptr;
 struct OpTR256G {
     static constexpr int kDsReads = 2 * kTP2, kDsReadsQ = 2 * kTQ2;
-    static constexpr bool kIndexed = true;
+    static constexpr bool kIndexed = true, kWindowed = false;
     static constexpr int kOutside = 0x7ffffff0;  // beyond any window (windows are < 2^31 bytes)
     rsrc_t rs;
     const_i32_ptr rows;
@@ -330,7 +331,7 @@ __device__ __forceinline__ void sub_step(Acc2 &acc, Frags &next, const Frags &cu
 // One resident stage (two 16-k sub-steps).  On entry `x` holds the last fragment set of the
 // previous stage (zeros before the first): its MFMAs open this stage, so the matrix pipe has
 // work while this stage's first fragment reads are in flight.  On exit `x` holds this
-// stage's last fragment set, not yet multiplied.  The loads of the stage three ahead are
+// stage's last fragment set, not yet multiplied.  The loads of the stage two ahead are
 // issued between the two sub-steps (inline asm, stays where it is written).  At most two
 // fragment sets are live next to the 128 accumulator registers.
 template <class POp, class QOp>
@@ -345,13 +346,13 @@ __device__ __forceinline__ void stage_compute(Acc2 &acc, Frags &x, Frags &y, con
     sub_step(acc, x, y, P, Q, stage, 1);
 }
 
-// End of a stage.  Loaders wait until at most two stages' loads are outstanding (their share
+// End of a stage.  Loaders wait until at most one stage's loads are outstanding (their share
 // of the next stage has landed); everyone waits for its LDS reads; then the waves meet.  A
 // bare s_barrier is used on purpose: __syncthreads() carries a fence for which the compiler
-// drains every outstanding load, including the ones just issued three stages ahead.
+// drains every outstanding load, including the ones just issued two stages ahead.
 __device__ __forceinline__ void stage_barrier(bool loader) {
     // s_waitcnt simm16: vmcnt[3:0] | expcnt[6:4] | lgkmcnt[11:8] | vmcnt_hi[15:14]
-    constexpr int vm = 2 * kLoadsPerStage;
+    constexpr int vm = kLoadsPerStage;
     if (loader) __builtin_amdgcn_s_waitcnt((vm & 15) | (7 << 4) | (0 << 8) | ((vm >> 4) << 14));
     else __builtin_amdgcn_s_waitcnt(15 | (7 << 4) | (0 << 8) | (3 << 14));
     __builtin_amdgcn_s_barrier();
@@ -376,18 +377,16 @@ __device__ __forceinline__ void mfma_mainloop2(Acc2 &acc, int nk, const POp &P, 
             Q.issue(0, a0 + kOperandBytes);
             P.issue(1, a1);
             Q.issue(1, a1 + kOperandBytes);
-            P.issue(2, a2);
-            Q.issue(2, a2 + kOperandBytes);
         }
         stage_barrier(loader);
         for (int kt = 0; kt < nk; kt += 4) {
-            if (loader) { P.issue(kt + 3, a3); Q.issue(kt + 3, a3 + kOperandBytes); }
+            if (loader) { P.issue(kt + 2, a2); Q.issue(kt + 2, a2 + kOperandBytes); }
             stage_barrier(loader);
-            if (loader && kt + 1 < nk) { P.issue(kt + 4, a0); Q.issue(kt + 4, a0 + kOperandBytes); }
+            if (loader && kt + 1 < nk) { P.issue(kt + 3, a3); Q.issue(kt + 3, a3 + kOperandBytes); }
             stage_barrier(loader);
-            if (loader && kt + 2 < nk) { P.issue(kt + 5, a1); Q.issue(kt + 5, a1 + kOperandBytes); }
+            if (loader && kt + 2 < nk) { P.issue(kt + 4, a0); Q.issue(kt + 4, a0 + kOperandBytes); }
             stage_barrier(loader);
-            if (loader && kt + 3 < nk) { P.issue(kt + 6, a2); Q.issue(kt + 6, a2 + kOperandBytes); }
+            if (loader && kt + 3 < nk) { P.issue(kt + 5, a1); Q.issue(kt + 5, a1 + kOperandBytes); }
             stage_barrier(loader);
         }
         __builtin_amdgcn_s_waitcnt(0 | (7 << 4) | (15 << 8));
@@ -395,13 +394,13 @@ __device__ __forceinline__ void mfma_mainloop2(Acc2 &acc, int nk, const POp &P, 
         return;
     }
     if (loader) {
-        // stages 0, 1, 2 (a stage >= nk loads nothing useful but still counts)
+        // stages 0 and 1 (a stage >= nk loads nothing useful but still counts)
         if constexpr (POp::kIndexed || QOp::kIndexed) {
             // an indexed operand's address arithmetic per stage is long: kept as a real loop, or the
-            // compiler works out all three stages ahead and spills the results
+            // compiler works out both stages ahead and spills the results
 #pragma nounroll
-            for (int st = 0; st < 3; ++st) {
-                const uint32_t a = st == 0 ? a0 : st == 1 ? a1 : a2;
+            for (int st = 0; st < 2; ++st) {
+                const uint32_t a = st == 0 ? a0 : a1;
                 P.issue(st, a);
                 Q.issue(st, a + kOperandBytes);
             }
@@ -410,8 +409,6 @@ __device__ __forceinline__ void mfma_mainloop2(Acc2 &acc, int nk, const POp &P, 
             Q.issue(0, a0 + kOperandBytes);
             P.issue(1, a1);
             Q.issue(1, a1 + kOperandBytes);
-            P.issue(2, a2);
-            Q.issue(2, a2 + kOperandBytes);
         }
     }
     stage_barrier(loader);
@@ -422,13 +419,13 @@ __device__ __forceinline__ void mfma_mainloop2(Acc2 &acc, int nk, const POp &P, 
     for (int j = 0; j < kTQ2; ++j) x.b[j] = bf16x8_t{};
     // single loop exit (no break) keeps the accumulators in place
     for (int kt = 0; kt < nk; kt += 4) {
-        stage_compute(acc, x, y, P, Q, st0, kt + 3, a3, loader);
+        stage_compute(acc, x, y, P, Q, st0, kt + 2, a2, loader);
         stage_barrier(loader);
-        if (kt + 1 < nk) stage_compute(acc, x, y, P, Q, st1, kt + 4, a0, loader);
+        if (kt + 1 < nk) stage_compute(acc, x, y, P, Q, st1, kt + 3, a3, loader);
         stage_barrier(loader);
-        if (kt + 2 < nk) stage_compute(acc, x, y, P, Q, st2, kt + 5, a1, loader);
+        if (kt + 2 < nk) stage_compute(acc, x, y, P, Q, st2, kt + 4, a0, loader);
         stage_barrier(loader);
-        if (kt + 3 < nk) stage_compute(acc, x, y, P, Q, st3, kt + 6, a2, loader);
+        if (kt + 3 < nk) stage_compute(acc, x, y, P, Q, st3, kt + 5, a1, loader);
         stage_barrier(loader);
     }
     mfma_block(acc, x);
@@ -436,6 +433,184 @@ __device__ __forceinline__ void mfma_mainloop2(Acc2 &acc, int nk, const POp &P, 
     // reuses the stage buffers (the epilogues stage their stores through them)
     __builtin_amdgcn_s_waitcnt(0 | (7 << 4) | (15 << 8));
     __builtin_amdgcn_s_barrier();
+}
+
+// ---------------------------------------------------------------------------
+// Windowed form of the main loop: the reduction advances in windows of 64 k, held in two 64 KB
+// buffers (P window 32 KB, Q window 32 KB).  Its reason is the K-contiguous operands: with 64 k
+// per window a row of such an operand is 128 B, one whole cache line, and eight lanes of a tile
+// load cover it with one request; with 32-k stages every line was asked for twice, half each
+// time, one stage apart, and the kernels whose two operands are both of this kind ran into the
+// request rate of the L2 (measured on the 16384-token layer: -16 % / -12 % on the two such
+// kernels with whole-line requests and the same bytes).  The window after the current one is
+// loaded while the current one is multiplied (measured: a shallower prefetch costs nothing),
+// so every wait is "all my loads have landed" and nothing has to be counted.
+// Transposed operands keep their 32-k tile form: a window is two such tiles back to back.
+// ---------------------------------------------------------------------------
+constexpr int kBK3 = 64;
+constexpr int kWinBytes = kTile * kBK3 * 2;   // 32 KB: one operand's window
+constexpr int kSuperBytes = 2 * kWinBytes;    // 64 KB: both operands
+constexpr int kLoadsPerWindow = 16;           // tile loads per loader wave per window (8 per operand)
+
+// K-contiguous 256-row window [256 rows][128 B]: 32 chunks of 1 KB (8 rows x 128 B), eight per
+// loader wave; the 16-byte chunk c of row r sits at slot c ^ ((r >> 1) & 7) (KcFrag<64>'s
+// conflict-free order), applied on the global side.  Chunk i of a wave is 32 rows below chunk
+// i - 1 and has the same swizzle, so one per-lane offset and a stride describe all eight --
+// unless the rows are gathered (ROWS = true): then each lane keeps the offsets of its eight rows.
+template <bool ROWS>
+struct OpKC64 {
+    static constexpr bool kIndexed = false, kWindowed = true;
+    Src src[2];
+    int wswitch;           // window from which src[1] takes over (two-phase reductions)
+    int voff[ROWS ? 8 : 1];
+    int step;              // bytes between a lane's consecutive chunks (32 rows)
+    KcFrag<kBK3> fr;
+    __device__ __forceinline__ int lane_chunk() const {
+        const int w = threadIdx.x >> 6, lane = threadIdx.x & 63;
+        const int row0 = 8 * (w & 3) + (lane >> 3);
+        return ((lane & 7) ^ ((row0 >> 1) & 7)) * 16;
+    }
+    __device__ __forceinline__ int lane_row(int i) const {   // row of this lane in its chunk i
+        const int w = threadIdx.x >> 6, lane = threadIdx.x & 63;
+        return 8 * (w & 3) + (lane >> 3) + 32 * i;
+    }
+    __device__ __forceinline__ void init(int ld_bytes, int wave_base) {
+        wswitch = 0x7fffffff;
+        step = 32 * ld_bytes;
+        voff[0] = lane_row(0) * ld_bytes + lane_chunk();
+        fr.init(wave_base);
+    }
+    __device__ __forceinline__ void issue_window(int J, uint32_t win) const {
+        const bool second = J >= wswitch;
+        const Src &s = second ? src[1] : src[0];
+        const rsrc_t r = src_rsrc(s, second ? J - wswitch : J);
+        const int w = threadIdx.x >> 6;
+#pragma unroll
+        for (int i = 0; i < 8; ++i)
+            lds_load16(r, win + 1024 * ((w & 3) + kLoaderWaves * i), ROWS ? voff[ROWS ? i : 0] : voff[0] + i * step);
+    }
+    __device__ __forceinline__ bf16x8_t frag_window(const char *win, int t, int u) const { return fr.read(win, t, u); }
+};
+
+// a 32-k tile operand as a window: tiles 2J and 2J+1 back to back
+template <class Op>
+__device__ __forceinline__ void win_issue(const Op &op, int J, uint32_t win) {
+    if constexpr (Op::kWindowed) {
+        op.issue_window(J, win);
+    } else {
+        op.issue(2 * J, win);
+        op.issue(2 * J + 1, win + kOperandBytes);
+    }
+}
+template <class Op>
+__device__ __forceinline__ bf16x8_t win_frag(const Op &op, const char *win, int t, int u) {
+    if constexpr (Op::kWindowed) return op.frag_window(win, t, u);
+    else return op.frag(win + (u >> 1) * kOperandBytes, t, u & 1);
+}
+
+template <class POp, class QOp>
+__device__ __forceinline__ void sub_step3(Acc2 &acc, Frags &next, const Frags &cur, const POp &P, const QOp &Q,
+                                          const char *buf, int u) {
+#pragma unroll
+    for (int i = 0; i < kTP2; ++i) next.a[i] = win_frag(P, buf, i, u);
+#pragma unroll
+    for (int j = 0; j < kTQ2; ++j) next.b[j] = win_frag(Q, buf + kWinBytes, j, u);
+    mfma_block(acc, cur);
+#pragma unroll
+    for (int i = 0; i < kTP2 * kTQ2; ++i) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);  // MFMA
+        __builtin_amdgcn_sched_group_barrier(0x100, kReadsPerMfma, 0);  // DS read
+    }
+    __builtin_amdgcn_sched_barrier(0);
+}
+
+// End of a window: a loader's loads (the next window) have all landed, everyone's fragment reads
+// are done, then the waves meet.  Bare s_barrier, as in stage_barrier().
+__device__ __forceinline__ void window_barrier(bool loader) {
+    if (loader) __builtin_amdgcn_s_waitcnt(0 | (7 << 4) | (0 << 8) | (0 << 14));
+    else __builtin_amdgcn_s_waitcnt(15 | (7 << 4) | (0 << 8) | (3 << 14));
+    __builtin_amdgcn_s_barrier();
+}
+
+// One resident window (four 16-k sub-steps).  `x` carries the last fragment set of the previous
+// window in and this window's last one out, as in stage_compute(); the next window's loads go out
+// into the buffer the previous window has just left, one operand before the first sub-step and
+// the other after it (measured: all sixteen at once makes the loader waves late for the window's
+// barrier; later than this shortens the time the loads have).
+template <class POp, class QOp>
+__device__ __forceinline__ void window_compute(Acc2 &acc, Frags &x, Frags &y, const POp &P, const QOp &Q,
+                                               const char *buf, int Jnext, uint32_t bnext, bool load_next) {
+    if (load_next) win_issue(P, Jnext, bnext);
+    __builtin_amdgcn_sched_barrier(0);
+    sub_step3(acc, y, x, P, Q, buf, 0);
+    if (load_next) win_issue(Q, Jnext, bnext + kWinBytes);
+    __builtin_amdgcn_sched_barrier(0);
+    sub_step3(acc, x, y, P, Q, buf, 1);
+    sub_step3(acc, y, x, P, Q, buf, 2);
+    sub_step3(acc, x, y, P, Q, buf, 3);
+}
+
+// nw windows of 64 k.  bufA, bufB: the two 64 KB LDS buffers (distinct arrays).  live_rows as in
+// mfma_mainloop2().  Every wave passes the same barriers whatever its role: one after the first
+// window's loads and one per window.
+template <class POp, class QOp>
+__device__ __forceinline__ void mfma_mainloop3(Acc2 &acc, int nw, const POp &P, const QOp &Q, char *bufA, char *bufB,
+                                               int live_rows = kTile) {
+    if (nw <= 0) return;
+    const uint32_t aA = lds_addr(bufA), aB = lds_addr(bufB);
+    const int wave_ = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    const bool loader = wave_ < kLoaderWaves;
+    if (loader) {
+        // windows 0 and 1 go out together; only window 0 is waited for (each loader wave issues
+        // kLoadsPerWindow loads per window, so "at most that many outstanding" is "window 0 is in")
+        if constexpr (POp::kIndexed || QOp::kIndexed) {
+            // an indexed operand's address arithmetic per tile load is long: kept as a real loop, or the
+            // compiler works it all out ahead and spills the results (reloads that wait on the loads)
+#pragma nounroll
+            for (int w = 0; w < 2; ++w)
+                if (w < nw) {
+                    const uint32_t a = w ? aB : aA;
+                    win_issue(P, w, a);
+                    win_issue(Q, w, a + kWinBytes);
+                }
+        } else {
+            win_issue(P, 0, aA);
+            win_issue(Q, 0, aA + kWinBytes);
+            if (nw > 1) {
+                win_issue(P, 1, aB);
+                win_issue(Q, 1, aB + kWinBytes);
+            }
+        }
+        if (nw > 1) __builtin_amdgcn_s_waitcnt((kLoadsPerWindow & 15) | (7 << 4) | (0 << 8) | ((kLoadsPerWindow >> 4) << 14));
+        else __builtin_amdgcn_s_waitcnt(0 | (7 << 4) | (0 << 8) | (0 << 14));
+    }
+    __builtin_amdgcn_s_barrier();
+    if ((wave_ / kWP2) * kWaveRowsQ >= live_rows) {
+        // this wave's rows are not needed: keep the loads (if it is a loader) and the barriers going
+        for (int J = 0; J < nw; J += 2) {
+            if (loader && J > 0 && J + 1 < nw) { win_issue(P, J + 1, aB); win_issue(Q, J + 1, aB + kWinBytes); }
+            window_barrier(loader);
+            if (J + 1 < nw) {
+                if (loader && J + 2 < nw) { win_issue(P, J + 2, aA); win_issue(Q, J + 2, aA + kWinBytes); }
+                window_barrier(loader);
+            }
+        }
+        return;
+    }
+    Frags x, y;
+#pragma unroll
+    for (int i = 0; i < kTP2; ++i) x.a[i] = bf16x8_t{};
+#pragma unroll
+    for (int j = 0; j < kTQ2; ++j) x.b[j] = bf16x8_t{};
+    for (int J = 0; J < nw; J += 2) {
+        window_compute(acc, x, y, P, Q, bufA, J + 1, aB, loader && J > 0 && J + 1 < nw);
+        window_barrier(loader);
+        if (J + 1 < nw) {
+            window_compute(acc, x, y, P, Q, bufB, J + 2, aA, loader && J + 2 < nw);
+            window_barrier(loader);
+        }
+    }
+    mfma_block(acc, x);
 }
 
 // Persistent work-groups.  A launch has one work-group per compute unit; each walks the tile
