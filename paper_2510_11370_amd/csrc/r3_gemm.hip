@@ -33,22 +33,30 @@ __device__ __forceinline__ int *tile_counters(const int32_t *tiles, int launch) 
 __global__ void __launch_bounds__(1024)
 build_row_tiles_kernel(int E, int BQ, const int32_t *__restrict__ offsets, int32_t *__restrict__ tiles) {
     __shared__ int32_t start[kMaxE + 1];
+    __shared__ int32_t off[kMaxE + 1];
+    // the offsets come in once, in parallel (read one by one by a single thread they cost a memory
+    // round trip each, and this kernel sits between two others on every pass)
+    for (int e = threadIdx.x; e <= E; e += blockDim.x) off[e] = offsets[e];
+    __syncthreads();
+    // row tiles per expert (the division in parallel), then one thread adds them up
+    for (int e = threadIdx.x; e < E; e += blockDim.x) start[e + 1] = (off[e + 1] - off[e] + BQ - 1) / BQ;
+    __syncthreads();
     if (threadIdx.x == 0) {
         int run = 0;
-        for (int e = 0; e < E; ++e) {
+        start[0] = 0;
+        for (int e = 1; e <= E; ++e) {
+            run += start[e];
             start[e] = run;
-            run += (offsets[e + 1] - offsets[e] + BQ - 1) / BQ;
         }
-        start[E] = run;
         tiles[0] = run;
         tiles[1] = 0;
     }
     if (threadIdx.x < 64) tiles[2 + threadIdx.x] = 0;
     for (int e = threadIdx.x; e < E; e += blockDim.x) {
-        const int n = offsets[e + 1] - offsets[e];
+        const int n = off[e + 1] - off[e];
         int rank = 0;
         for (int o = 0; o < E; ++o) {
-            const int m = offsets[o + 1] - offsets[o];
+            const int m = off[o + 1] - off[o];
             rank += (m > n) || (m == n && o < e);
         }
         // the tile list is cut into 8 contiguous XCD shares: deal the ranked experts out to the
@@ -65,7 +73,7 @@ build_row_tiles_kernel(int E, int BQ, const int32_t *__restrict__ offsets, int32
         const int n = start[e + 1] - start[e];
         for (int i = 0; i < n; ++i) {
             tiles[kTileHdr + 2 * (start[e] + i)] = e;
-            tiles[kTileHdr + 1 + 2 * (start[e] + i)] = offsets[e] + i * BQ;
+            tiles[kTileHdr + 1 + 2 * (start[e] + i)] = off[e] + i * BQ;
         }
     }
 }
