@@ -29,6 +29,9 @@ SHAPES = {
     "mfma_fewexperts": SH(T=700, d=256, E=128, K=2, F=256, act="bf16", sigma=0.02, zipf_s=2.0, seed=25),
     # more than 256 experts: the record is uint16
     "mfma_u16": SH(T=900, d=256, E=384, K=4, F=256, act="bf16", sigma=0.02, zipf_s=1.0, seed=26),
+    # other widths: 12 / 8 and 16 / 20 windows of 64 k in the row-tiled GEMMs, 3 / 4 and 2 / 5 column tiles
+    "mfma_wide": SH(T=900, d=768, E=128, K=4, F=512, act="bf16", sigma=0.02, zipf_s=0.8, seed=27),
+    "mfma_tall": SH(T=1500, d=1024, E=128, K=2, F=1280, act="bf16", sigma=0.02, seed=28),
 }
 
 
@@ -275,7 +278,8 @@ def test_forward_chain(name, simt):
 
 @pytest.mark.parametrize("name,simt", [("config1_f32", False), ("odd_f32", False), ("odd_bf16", False),
                                        ("mfma_small", False), ("mfma_ragged", False),
-                                       ("mfma_fewexperts", False), ("mfma_small", True), ("mfma_u16", False), ("mfma_u16", True)])
+                                       ("mfma_fewexperts", False), ("mfma_small", True), ("mfma_u16", False), ("mfma_u16", True),
+                                       ("mfma_wide", False), ("mfma_tall", False)])
 def test_backward_chain(name, simt):
     if simt:
         os.environ["R3_FORCE_SIMT"] = "1"
