@@ -28,6 +28,7 @@ def kernel_work(sh, idx_bytes=1):
     eb = 2  # bf16
     return {
         "record_topk": ("hbm", T * (E * 4 + K * idx_bytes)),
+        "agreement": ("hbm", T * (E * 4 + K * idx_bytes)),
         "router_logits": ("hbm", T * (d * eb + E * 4) + d * E * eb),
         "replay_gate": ("hbm", T * (K * idx_bytes + K * 4 + K * 4)),
         "permute_index": ("hbm", T * K * (2 * idx_bytes + 8)),
@@ -287,6 +288,8 @@ def main():
     def next_x(x, y):
         """Harness glue between stacked layers: residual, then unit RMS per token (stands in for the rest
         of a transformer block; the expert FFN is quadratic in its input, a bare residual chain overflows)."""
+        if adt == torch.bfloat16:   # two passes over the activations instead of eight: this is glue, not the method
+            return torch.nn.functional.rms_norm(x + y, (x.shape[1],), None, 1e-6)
         r = x.float() + y.float()
         return (r * torch.rsqrt(r.pow(2).mean(dim=1, keepdim=True) + 1e-6)).to(adt)
 

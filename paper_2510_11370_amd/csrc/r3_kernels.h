@@ -9,7 +9,7 @@ namespace r3 {
 enum ProfTag {
     PROF_RECORD = 0, PROF_LOGITS, PROF_GATE, PROF_PERMUTE_INDEX, PROF_GATHER_ROWS, PROF_FFN1, PROF_FFN2,
     PROF_COMBINE, PROF_GATE_BWD, PROF_DWR, PROF_DH, PROF_WGRAD, PROF_DXP, PROF_DX_FINISH, PROF_WGRAD_PAIR,
-    PROF_ROUTING_DIFF, PROF_POLICY, PROF_CACHE_APPEND, PROF_CACHE_GATHER, PROF_NTAGS
+    PROF_ROUTING_DIFF, PROF_POLICY, PROF_CACHE_APPEND, PROF_CACHE_GATHER, PROF_AGREEMENT, PROF_NTAGS
 };
 struct ProfScope {
     int tag, slot;

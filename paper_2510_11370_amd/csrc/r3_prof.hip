@@ -18,7 +18,7 @@ const char *kNames[PROF_NTAGS] = {"record_topk", "router_logits", "replay_gate",
                                   "gather_rows", "ffn1_swiglu", "ffn2_down", "combine", "gate_backward",
                                   "router_wgrad", "ffn_dh", "ffn_wgrad_down", "ffn_dxp", "dx_finish",
                                   "ffn_wgrad_gate_up", "routing_diff", "policy_discrepancy",
-                                  "mask_cache_append", "mask_cache_gather"};
+                                  "mask_cache_append", "mask_cache_gather", "agreement"};
 }  // namespace
 
 ProfScope::ProfScope(int tag_, hipStream_t s_) : tag(tag_), slot(-1), s(s_) {

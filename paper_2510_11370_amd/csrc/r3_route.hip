@@ -386,50 +386,67 @@ hipError_t launch_gate(int T, int E, int K, const float *logits, const void *idx
 }
 
 // Routing agreement (Section 3.2, router level): per token compare the top-K
-// set of the training logits with the recorded set.  One wave per token, rank
-// counting as in the general record kernel.  agree[0] += tokens with equal
-// sets, agree[1] += shared experts.  Integer atomics only.
+// set of the training logits with the recorded set.  A wave takes a token at a
+// time: its E order keys sit in the wave's LDS strip, and for each recorded
+// expert all 64 lanes count the keys ahead of it (one ballot per 64 experts).
+// A wave walks many tokens and a block adds its totals once: agree[0] += tokens
+// with equal sets, agree[1] += shared experts.  Integer atomics only.
 template <typename IdxT>
 __global__ void __launch_bounds__(256)
 agreement_kernel(int T, int E, int K, const float *__restrict__ logits, const IdxT *__restrict__ idx,
                  int64_t stride, unsigned long long *agree) {
     extern __shared__ uint32_t keys_all[];
+    __shared__ unsigned long long part[4][2];
     const int w = threadIdx.x / kWave, lane = lane_id();
-    const int t = blockIdx.x * 4 + w;
     uint32_t *keys = keys_all + w * E;
-    if (t < T)
+    unsigned long long equal = 0, common = 0;
+    for (int t = blockIdx.x * 4 + w; t < T; t += gridDim.x * 4) {
         for (int e = lane; e < E; e += kWave) {
             bool nf;
             keys[e] = order_key(logits[(int64_t)t * E + e], nf);
         }
-    __syncthreads();
-    if (t >= T) return;
-    int shared = 0;
-    for (int base = 0; base < K; base += kWave) {
-        int j = base + lane;
-        bool sel = false;
-        if (j < K) {
-            int e = min((int)idx[(int64_t)t * stride + j], E - 1);
-            uint32_t mine = keys[e];
+        // one wave's LDS writes are complete before its later LDS reads
+        __builtin_amdgcn_s_waitcnt(0);
+        __builtin_amdgcn_wave_barrier();
+        int shared = 0;
+        for (int j = 0; j < K; ++j) {
+            const int e = min((int)idx[(int64_t)t * stride + j], E - 1);
+            const uint32_t mine = keys[e];
             int ahead = 0;
-            for (int f = 0; f < E; ++f) {
-                uint32_t kf = keys[f];
-                ahead += (kf > mine || (kf == mine && f < e)) ? 1 : 0;
+            for (int f0 = 0; f0 < E; f0 += kWave) {
+                const int f = f0 + lane;
+                const uint32_t kf = f < E ? keys[f] : 0u;
+                const bool before = f < E && (kf > mine || (kf == mine && f < e));
+                ahead += __popcll(__ballot(before));
             }
-            sel = ahead < K;
+            shared += ahead < K;
         }
-        shared += __popcll(__ballot(sel));
+        common += (unsigned long long)shared;
+        equal += shared == K;
+        __builtin_amdgcn_wave_barrier();   // the strip is rewritten for the next token
     }
     if (lane == 0) {
-        atomicAdd(agree + 1, (unsigned long long)shared);
-        if (shared == K) atomicAdd(agree, 1ull);
+        part[w][0] = equal;
+        part[w][1] = common;
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        unsigned long long a0 = 0, a1 = 0;
+        for (int i = 0; i < 4; ++i) {
+            a0 += part[i][0];
+            a1 += part[i][1];
+        }
+        if (a1) atomicAdd(agree + 1, a1);
+        if (a0) atomicAdd(agree, a0);
     }
 }
 
 hipError_t launch_agreement(int T, int E, int K, const float *logits, const void *idx, int idx_dtype,
                             int64_t stride, int64_t *agree, hipStream_t s) {
+    ProfScope ps(PROF_AGREEMENT, s);
     size_t lds = (size_t)4 * E * sizeof(uint32_t);
     int grid = (T + 3) / 4;
+    if (grid > 2048) grid = 2048;
     if (idx_dtype == R3_IDX_U8)
         agreement_kernel<uint8_t><<<grid, 256, lds, s>>>(T, E, K, logits, (const uint8_t *)idx, stride,
                                                         (unsigned long long *)agree);
