@@ -480,23 +480,31 @@ struct OpKC64 {
         voff[0] = lane_row(0) * ld_bytes + lane_chunk();
         fr.init(wave_base);
     }
-    __device__ __forceinline__ void issue_window(int J, uint32_t win) const {
+    // rows: only rows [0, rows) of the window are wanted (a multiple of 64; the rest is left as it is)
+    __device__ __forceinline__ void issue_window(int J, uint32_t win, int rows = kTile) const {
         const bool second = J >= wswitch;
         const Src &s = second ? src[1] : src[0];
         const rsrc_t r = src_rsrc(s, second ? J - wswitch : J);
         const int w = threadIdx.x >> 6;
+        if (rows == kTile) {   // the common case as straight-line code
 #pragma unroll
-        for (int i = 0; i < 8; ++i)
-            lds_load16(r, win + 1024 * ((w & 3) + kLoaderWaves * i), ROWS ? voff[ROWS ? i : 0] : voff[0] + i * step);
+            for (int i = 0; i < 8; ++i)
+                lds_load16(r, win + 1024 * ((w & 3) + kLoaderWaves * i), ROWS ? voff[ROWS ? i : 0] : voff[0] + i * step);
+        } else {
+#pragma unroll
+            for (int i = 0; i < 6; ++i)
+                if (32 * i < rows)   // chunk i of a wave holds rows 32 i + 8 (w & 3) ..+7
+                    lds_load16(r, win + 1024 * ((w & 3) + kLoaderWaves * i), ROWS ? voff[ROWS ? i : 0] : voff[0] + i * step);
+        }
     }
     __device__ __forceinline__ bf16x8_t frag_window(const char *win, int t, int u) const { return fr.read(win, t, u); }
 };
 
 // a 32-k tile operand as a window: tiles 2J and 2J+1 back to back
 template <class Op>
-__device__ __forceinline__ void win_issue(const Op &op, int J, uint32_t win) {
+__device__ __forceinline__ void win_issue(const Op &op, int J, uint32_t win, int rows = kTile) {
     if constexpr (Op::kWindowed) {
-        op.issue_window(J, win);
+        op.issue_window(J, win, rows);
     } else {
         op.issue(2 * J, win);
         op.issue(2 * J + 1, win + kOperandBytes);
@@ -539,11 +547,11 @@ __device__ __forceinline__ void window_barrier(bool loader) {
 // barrier; later than this shortens the time the loads have).
 template <class POp, class QOp>
 __device__ __forceinline__ void window_compute(Acc2 &acc, Frags &x, Frags &y, const POp &P, const QOp &Q,
-                                               const char *buf, int Jnext, uint32_t bnext, bool load_next) {
+                                               const char *buf, int Jnext, uint32_t bnext, bool load_next, int qrows) {
     if (load_next) win_issue(P, Jnext, bnext);
     __builtin_amdgcn_sched_barrier(0);
     sub_step3(acc, y, x, P, Q, buf, 0);
-    if (load_next) win_issue(Q, Jnext, bnext + kWinBytes);
+    if (load_next) win_issue(Q, Jnext, bnext + kWinBytes, qrows);
     __builtin_amdgcn_sched_barrier(0);
     sub_step3(acc, x, y, P, Q, buf, 1);
     sub_step3(acc, y, x, P, Q, buf, 2);
@@ -560,9 +568,14 @@ __device__ __forceinline__ void mfma_mainloop3(Acc2 &acc, int nw, const POp &P, 
     const uint32_t aA = lds_addr(bufA), aB = lds_addr(bufB);
     const int wave_ = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
     const bool loader = wave_ < kLoaderWaves;
+    // rows of the Q window that some wave reads: whole 64-row blocks (a tail tile's dead rows are
+    // not fetched at all: their loads, though out of range, would still take their turn in the
+    // vector memory path, and a tail tile is bound by that path and its latency)
+    const int qrows = min(kTile, (live_rows + kWaveRowsQ - 1) / kWaveRowsQ * kWaveRowsQ);
     if (loader) {
-        // windows 0 and 1 go out together; only window 0 is waited for (each loader wave issues
-        // kLoadsPerWindow loads per window, so "at most that many outstanding" is "window 0 is in")
+        // windows 0 and 1 go out together; only window 0 is waited for: it is in when at most window
+        // 1's loads are outstanding, 16 per loader wave for a full window; a tail tile issues fewer
+        // for Q, so there only window 1's P share (8) may remain
         if constexpr (POp::kIndexed || QOp::kIndexed) {
             // an indexed operand's address arithmetic per tile load is long: kept as a real loop, or the
             // compiler works it all out ahead and spills the results (reloads that wait on the loads)
@@ -571,27 +584,29 @@ __device__ __forceinline__ void mfma_mainloop3(Acc2 &acc, int nw, const POp &P, 
                 if (w < nw) {
                     const uint32_t a = w ? aB : aA;
                     win_issue(P, w, a);
-                    win_issue(Q, w, a + kWinBytes);
+                    win_issue(Q, w, a + kWinBytes, qrows);
                 }
         } else {
             win_issue(P, 0, aA);
-            win_issue(Q, 0, aA + kWinBytes);
+            win_issue(Q, 0, aA + kWinBytes, qrows);
             if (nw > 1) {
                 win_issue(P, 1, aB);
-                win_issue(Q, 1, aB + kWinBytes);
+                win_issue(Q, 1, aB + kWinBytes, qrows);
             }
         }
-        if (nw > 1) __builtin_amdgcn_s_waitcnt((kLoadsPerWindow & 15) | (7 << 4) | (0 << 8) | ((kLoadsPerWindow >> 4) << 14));
+        if (nw > 1 && qrows == kTile)
+            __builtin_amdgcn_s_waitcnt((kLoadsPerWindow & 15) | (7 << 4) | (0 << 8) | ((kLoadsPerWindow >> 4) << 14));
+        else if (nw > 1) __builtin_amdgcn_s_waitcnt((kLoadsPerWindow / 2) | (7 << 4) | (0 << 8) | (0 << 14));
         else __builtin_amdgcn_s_waitcnt(0 | (7 << 4) | (0 << 8) | (0 << 14));
     }
     __builtin_amdgcn_s_barrier();
     if ((wave_ / kWP2) * kWaveRowsQ >= live_rows) {
         // this wave's rows are not needed: keep the loads (if it is a loader) and the barriers going
         for (int J = 0; J < nw; J += 2) {
-            if (loader && J > 0 && J + 1 < nw) { win_issue(P, J + 1, aB); win_issue(Q, J + 1, aB + kWinBytes); }
+            if (loader && J > 0 && J + 1 < nw) { win_issue(P, J + 1, aB); win_issue(Q, J + 1, aB + kWinBytes, qrows); }
             window_barrier(loader);
             if (J + 1 < nw) {
-                if (loader && J + 2 < nw) { win_issue(P, J + 2, aA); win_issue(Q, J + 2, aA + kWinBytes); }
+                if (loader && J + 2 < nw) { win_issue(P, J + 2, aA); win_issue(Q, J + 2, aA + kWinBytes, qrows); }
                 window_barrier(loader);
             }
         }
@@ -603,10 +618,10 @@ __device__ __forceinline__ void mfma_mainloop3(Acc2 &acc, int nw, const POp &P, 
 #pragma unroll
     for (int j = 0; j < kTQ2; ++j) x.b[j] = bf16x8_t{};
     for (int J = 0; J < nw; J += 2) {
-        window_compute(acc, x, y, P, Q, bufA, J + 1, aB, loader && J > 0 && J + 1 < nw);
+        window_compute(acc, x, y, P, Q, bufA, J + 1, aB, loader && J > 0 && J + 1 < nw, qrows);
         window_barrier(loader);
         if (J + 1 < nw) {
-            window_compute(acc, x, y, P, Q, bufB, J + 2, aA, loader && J + 2 < nw);
+            window_compute(acc, x, y, P, Q, bufB, J + 2, aA, loader && J + 2 < nw, qrows);
             window_barrier(loader);
         }
     }
