@@ -118,9 +118,9 @@ ffn1_kernel(int S, int d, int F, const bf16_t *__restrict__ Xp, const int32_t *_
             const int32_t *__restrict__ offsets, const int32_t *__restrict__ tiles, const bf16_t *__restrict__ Wg,
             const bf16_t *__restrict__ Wu, bf16_t *__restrict__ H, bf16_t *__restrict__ A, bf16_t *__restrict__ B,
             int launch) {
-    __shared__ __attribute__((aligned(1024))) char bufA[kSuperBytes];
-    __shared__ __attribute__((aligned(1024))) char bufB[kSuperBytes];
+    __shared__ __attribute__((aligned(1024))) char lds[2 * kSuperBytes];   // one piece: a tail tile lays it out differently
     __shared__ int mailbox[2];
+    char *const bufA = lds, *const bufB = lds + kSuperBytes;
     char *const s0 = bufA, *const s1 = bufA + kStageBytes, *const s2 = bufB, *const s3 = bufB + kStageBytes;
     constexpr int BF = 128;  // features per tile
     const int npt = F / BF;
@@ -175,7 +175,8 @@ ffn1_kernel(int S, int d, int F, const bf16_t *__restrict__ Xp, const int32_t *_
 
     Acc2 acc;
     zero_acc2(acc);
-    mfma_mainloop3(acc, d / kBK3, P, Q, bufA, bufB, row_end - row0);
+    if (row_end - row0 <= kWaveRowsQ) mfma_tail_loop3(acc, d / kBK3, P, Q, lds);
+    else mfma_mainloop3(acc, d / kBK3, P, Q, bufA, bufB, row_end - row0);
     tl.prefetch();
     if (more) aim(nxt);   // here, so that the row-index loads of a gathered tile hide behind the epilogue
 
@@ -230,9 +231,9 @@ rowgemm_kernel(int S, int d, int F, const bf16_t *__restrict__ Q0, const bf16_t 
                const int32_t *__restrict__ offsets, const int32_t *__restrict__ tiles,
                const bf16_t *__restrict__ W0, const bf16_t *__restrict__ W1, const bf16_t *__restrict__ A,
                const bf16_t *__restrict__ B, bf16_t *__restrict__ out0, bf16_t *__restrict__ out1, int launch) {
-    __shared__ __attribute__((aligned(1024))) char bufA[kSuperBytes];
-    __shared__ __attribute__((aligned(1024))) char bufB[kSuperBytes];
+    __shared__ __attribute__((aligned(1024))) char lds[2 * kSuperBytes];   // one piece: a tail tile lays it out differently
     __shared__ int mailbox[2];
+    char *const bufA = lds, *const bufB = lds + kSuperBytes;
     char *const s0 = bufA, *const s1 = bufA + kStageBytes, *const s2 = bufB, *const s3 = bufB + kStageBytes;
     const int NOUT = (MODE == 1) ? F : d;  // width of the output
     const int KQ = (MODE == 1) ? d : F;    // width of the Q source rows
@@ -296,7 +297,8 @@ rowgemm_kernel(int S, int d, int F, const bf16_t *__restrict__ Q0, const bf16_t 
 
     Acc2 acc;
     zero_acc2(acc);
-    mfma_mainloop3(acc, nw, P, Q, bufA, bufB, row_end - row0);
+    if (row_end - row0 <= kWaveRowsQ) mfma_tail_loop3(acc, nw, P, Q, lds);
+    else mfma_mainloop3(acc, nw, P, Q, bufA, bufB, row_end - row0);
     tl.prefetch();
 
     // per wave: 64 rows x 128 features, 32 rows at a time through LDS

@@ -518,11 +518,11 @@ __device__ __forceinline__ bf16x8_t win_frag(const Op &op, const char *win, int 
 
 template <class POp, class QOp>
 __device__ __forceinline__ void sub_step3(Acc2 &acc, Frags &next, const Frags &cur, const POp &P, const QOp &Q,
-                                          const char *buf, int u) {
+                                          const char *pwin, const char *qwin, int u) {
 #pragma unroll
-    for (int i = 0; i < kTP2; ++i) next.a[i] = win_frag(P, buf, i, u);
+    for (int i = 0; i < kTP2; ++i) next.a[i] = win_frag(P, pwin, i, u);
 #pragma unroll
-    for (int j = 0; j < kTQ2; ++j) next.b[j] = win_frag(Q, buf + kWinBytes, j, u);
+    for (int j = 0; j < kTQ2; ++j) next.b[j] = win_frag(Q, qwin, j, u);
     mfma_block(acc, cur);
 #pragma unroll
     for (int i = 0; i < kTP2 * kTQ2; ++i) {
@@ -550,12 +550,12 @@ __device__ __forceinline__ void window_compute(Acc2 &acc, Frags &x, Frags &y, co
                                                const char *buf, int Jnext, uint32_t bnext, bool load_next, int qrows) {
     if (load_next) win_issue(P, Jnext, bnext);
     __builtin_amdgcn_sched_barrier(0);
-    sub_step3(acc, y, x, P, Q, buf, 0);
+    sub_step3(acc, y, x, P, Q, buf, buf + kWinBytes, 0);
     if (load_next) win_issue(Q, Jnext, bnext + kWinBytes, qrows);
     __builtin_amdgcn_sched_barrier(0);
-    sub_step3(acc, x, y, P, Q, buf, 1);
-    sub_step3(acc, y, x, P, Q, buf, 2);
-    sub_step3(acc, x, y, P, Q, buf, 3);
+    sub_step3(acc, x, y, P, Q, buf, buf + kWinBytes, 1);
+    sub_step3(acc, y, x, P, Q, buf, buf + kWinBytes, 2);
+    sub_step3(acc, x, y, P, Q, buf, buf + kWinBytes, 3);
 }
 
 // nw windows of 64 k.  bufA, bufB: the two 64 KB LDS buffers (distinct arrays).  live_rows as in
@@ -626,6 +626,75 @@ __device__ __forceinline__ void mfma_mainloop3(Acc2 &acc, int nw, const POp &P, 
         }
     }
     mfma_block(acc, x);
+}
+
+// ---------------------------------------------------------------------------
+// The same loop for a tail tile: at most 64 live rows (the last few rows of an expert's segment).
+// Such a tile multiplies little and is bound by the latency of its weight windows, so the space the
+// dead 192 rows of the Q windows would take holds a third window instead and the loads run two
+// windows ahead.  `lds` is the work-group's whole 128 KB: P windows at 0, 32, 64 KB; Q windows (rows
+// 0..63 only, 8 KB each) from 96 KB.  Only waves 0 and 1 hold live rows; waves 0-3 load.
+// A loader wave issues kTailLoads per window, so "at most that many outstanding" is "the next
+// window is in" as long as the one after it has been issued.
+// ---------------------------------------------------------------------------
+constexpr int kTailQBytes = kWaveRowsQ * kBK3 * 2;                       // 8 KB: 64 rows of a Q window
+constexpr int kTailLoads = 8 + 8 * kWaveRowsQ / kTile;                   // 8 for P + 2 for Q
+constexpr int kTailQBase = 3 * kWinBytes;
+
+__device__ __forceinline__ void tail_barrier(bool loader, bool one_ahead) {
+    if (!loader) __builtin_amdgcn_s_waitcnt(15 | (7 << 4) | (0 << 8) | (3 << 14));
+    else if (one_ahead) __builtin_amdgcn_s_waitcnt((kTailLoads & 15) | (7 << 4) | (0 << 8) | ((kTailLoads >> 4) << 14));
+    else __builtin_amdgcn_s_waitcnt(0 | (7 << 4) | (0 << 8) | (0 << 14));
+    __builtin_amdgcn_s_barrier();
+}
+
+template <class POp, class QOp>
+__device__ __forceinline__ void mfma_tail_loop3(Acc2 &acc, int nw, const POp &P, const QOp &Q, char *lds) {
+    if (nw <= 0) return;
+    const uint32_t a0 = lds_addr(lds);
+    const int wave_ = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    const bool loader = wave_ < kLoaderWaves;
+    const bool live = wave_ / kWP2 == 0;
+    auto issue = [&](int J, int slot) {
+        win_issue(P, J, a0 + slot * kWinBytes);
+        win_issue(Q, J, a0 + kTailQBase + slot * kTailQBytes, kWaveRowsQ);
+    };
+    if (loader) {
+        if constexpr (POp::kIndexed || QOp::kIndexed) {
+#pragma nounroll
+            for (int w = 0; w < 2; ++w)
+                if (w < nw) issue(w, w);
+        } else {
+            issue(0, 0);
+            if (nw > 1) issue(1, 1);
+        }
+    }
+    tail_barrier(loader, nw > 1);
+    Frags x, y;
+#pragma unroll
+    for (int i = 0; i < kTP2; ++i) x.a[i] = bf16x8_t{};
+#pragma unroll
+    for (int j = 0; j < kTQ2; ++j) x.b[j] = bf16x8_t{};
+    // window J sits in slot J % 3; window J + 2 goes into the slot window J - 1 has just left
+    auto window = [&](int J, int slot) {
+        const int nslot = slot == 0 ? 2 : slot - 1;   // (slot + 2) % 3
+        if (loader && J + 2 < nw) issue(J + 2, nslot);
+        __builtin_amdgcn_sched_barrier(0);
+        if (live) {
+            const char *pw = lds + slot * kWinBytes, *qw = lds + kTailQBase + slot * kTailQBytes;
+            sub_step3(acc, y, x, P, Q, pw, qw, 0);
+            sub_step3(acc, x, y, P, Q, pw, qw, 1);
+            sub_step3(acc, y, x, P, Q, pw, qw, 2);
+            sub_step3(acc, x, y, P, Q, pw, qw, 3);
+        }
+        tail_barrier(loader, J + 2 < nw);
+    };
+    for (int J = 0; J < nw; J += 3) {
+        window(J, 0);
+        if (J + 1 < nw) window(J + 1, 1);
+        if (J + 2 < nw) window(J + 2, 2);
+    }
+    if (live) mfma_block(acc, x);
 }
 
 // Persistent work-groups.  A launch has one work-group per compute unit; each walks the tile
