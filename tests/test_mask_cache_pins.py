@@ -60,3 +60,24 @@ def test_page_size_one_and_empty_sequences():
     mc.append(pages, P, [[2, 0, 1]], [0, 0, 0], [0, 1, 2], ids)
     got = mc.gather(pages, P, [[-1, -1, -1], [2, 0, 1], [-1, -1, -1]], [0, 0, 3, 3])
     assert np.array_equal(got, ids.transpose(1, 0, 2))
+
+
+def test_rollout_batch_layout_is_consistent():
+    """The seeded batch layout the GPU tests and the bench use: lengths add up, every position has a page, a
+    shared prefix is whole pages of the group's first sequence, and no page is owned twice."""
+    from paper_2510_11370_amd import synth
+    for T, P, group in ((1000, 16, 4), (131072, 16, 4), (65, 1, 4), (300, 8, 1), (5, 4, 4)):
+        lens, shared, table, num_pages = synth.rollout_batch(T, P, group=group, seed=T)
+        assert lens.sum() == T and (lens > 0).all() and (shared % P == 0).all() and (shared <= lens).all()
+        owned = []
+        owner = 0
+        for s in range(len(lens)):
+            nb = (lens[s] + P - 1) // P
+            assert (table[s, :nb] >= 0).all() and (table[s, :nb] < num_pages).all() and (table[s, nb:] == -1).all()
+            if shared[s] == 0:
+                owner = s
+            else:
+                k = shared[s] // P
+                assert np.array_equal(table[s, :k], table[owner, :k])
+            owned.extend(table[s, shared[s] // P:nb].tolist())
+        assert len(owned) == len(set(owned)) == num_pages
