@@ -252,6 +252,9 @@ def main():
     ap.add_argument("--gathered-copy", action="store_true",
                     help="materialise the expert-sorted copy of the tokens (Xp) instead of reading x through the "
                          "permutation inside the expert GEMMs")
+    ap.add_argument("--graph", action="store_true",
+                    help="time replays of the step captured in a HIP graph (single-layer workloads) instead of "
+                         "eager launches")
     ap.add_argument("--no-ceilings", action="store_true", help="skip the calibration kernels after the timed region")
     ap.add_argument("--calib-copy", action="store_true",
                     help="after the timed region, run one plain 256 MiB copy kernel (reference point for "
@@ -319,13 +322,37 @@ def main():
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
-    # timed region: exactly --steps steps, per-kernel HIP events recorded inside the library
-    r3.profile_enable(True)
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        step()
-    torch.cuda.synchronize()
-    wall = time.perf_counter() - t0
+    if args.graph:
+        # the step captured once in a HIP graph and replayed: the timed region is --steps replays; the per-kernel
+        # events come from a second, eager pass of the same length that is not part of `value`
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.stream(side):
+            step()
+            side.synchronize()
+            with torch.cuda.graph(graph, stream=side):
+                step()
+        torch.cuda.current_stream().wait_stream(side)
+        graph.replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            graph.replay()
+        torch.cuda.synchronize()
+        wall = time.perf_counter() - t0
+        r3.profile_enable(True)
+        for _ in range(args.steps):
+            step()
+        torch.cuda.synchronize()
+    else:
+        # timed region: exactly --steps steps, per-kernel HIP events recorded inside the library
+        r3.profile_enable(True)
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            step()
+        torch.cuda.synchronize()
+        wall = time.perf_counter() - t0
     prof = r3.profile_read()
     r3.profile_enable(False)
     assert int(buf.status.item()) == 0, "device status word set"
@@ -373,7 +400,7 @@ def main():
         "data": "synthetic (seeded; shape of a 128-expert top-8 MoE layer)",
         "config": {"workload": "%s: T=%d d=%d E=%d K=%d F=%d %s%s, record+forward%s" % (
             args.workload, sh.T, sh.d, sh.E, sh.K, sh.F, sh.act, " x %d layers" % L if L > 1 else "",
-            "+backward" if bwd else ""),
+            "+backward" if bwd else "") + (", launched as a HIP graph" if args.graph else ""),
             "rows_per_expert_min_mean_max": [int(counts.min()), float(counts.float().mean()), int(counts.max())]},
         "roofline": roofline, "kernels": kernels,
     }
