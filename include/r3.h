@@ -120,6 +120,27 @@ int r3_permute(const r3_layer_desc *desc, const void *x, const void *idx,
                void *stream);
 
 /*
+ * r3_permute for callers that cannot allocate or carry a workspace: code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.
+ * Same arguments, results and status bits as r3_permute, without `ws`: the
+ * scratch (per-chunk expert histograms and their running sums) is a fixed
+ * array of R3_STATIC_SCRATCH_BYTES inside the library's device code, one copy
+ * per GPU, held until the process ends; nothing is allocated or freed, by
+ * this call or by anything it uses.  Its device address is looked up on the
+ * first call on each device (with that device current) and kept.
+ * Returns R3_ERR_UNSUPPORTED when r3_workspace_bytes(desc, R3_OP_PERMUTE)
+ * exceeds R3_STATIC_SCRATCH_BYTES (that is (T*K/1024 rounded up, at most 512)
+ * * E * 8 bytes: E <= 1024 always fits), R3_ERR_HIP when the address lookup
+ * fails.  All calls on one GPU share the one array, on every stream: two calls
+ * that overlap in time on a GPU race; calls ordered by a stream or an event
+ * are fine (every word that is read is written first by the same call).
+ */
+#define R3_STATIC_SCRATCH_BYTES (4u << 20)
+int r3_permute_static(const r3_layer_desc *desc, const void *x, const void *idx,
+                      int32_t *counts, int32_t *offsets, int32_t *inv_perm, int32_t *perm,
+                      void *Xp, int32_t *status_word, void *stream);
+
+/*
  * The expert networks E_i of the replay-output equation, as bias-free SwiGLU:
  * for expert e and its rows r in [offsets[e], offsets[e+1]):
  *   A = Xp W_gate[e], B = Xp W_up[e], H = silu(A) * B, Yp = H W_down[e].

@@ -1,7 +1,9 @@
 // C ABI of the replayed MoE layer: argument checks, workspace carving and the
 // launch sequence of each call.  See include/r3.h for the contract.
+#include <atomic>
 #include <cstdlib>
 #include <cstring>
+#include <mutex>
 
 #include "r3_kernels.h"
 
@@ -60,6 +62,31 @@ BwdWs bwd_layout(const Dims &m) {
 }
 
 int hip_rc(hipError_t e) { return e == hipSuccess ? R3_OK : R3_ERR_HIP; }
+
+// Scratch of r3_permute_static: a fixed array in every device's copy of this code object, held until
+// the process ends.  `scratch` is a host-side stand-in for the symbol, not a device address; the
+// device address is looked up once per device (static_scratch) and only that pointer is ever handed
+// to a kernel.
+constexpr int kMaxDevices = 64;
+static __device__ __align__(256) __attribute__((used)) unsigned char scratch[R3_STATIC_SCRATCH_BYTES];
+std::atomic<void *> g_scratch_ptr[kMaxDevices];
+std::mutex g_scratch_mu;
+
+int static_scratch(void **out) {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return R3_ERR_HIP;
+    void *p = g_scratch_ptr[dev].load(std::memory_order_acquire);
+    if (!p) {
+        std::lock_guard<std::mutex> lk(g_scratch_mu);
+        p = g_scratch_ptr[dev].load(std::memory_order_relaxed);
+        if (!p) {
+            if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return R3_ERR_HIP;
+            g_scratch_ptr[dev].store(p, std::memory_order_release);
+        }
+    }
+    *out = p;
+    return R3_OK;
+}
 
 }  // namespace
 
@@ -131,6 +158,20 @@ int r3_permute(const r3_layer_desc *desc, const void *x, const void *idx, int32_
     if (!ws || ws_bytes < permute_ws_bytes(m.T, m.E, m.K) || !aligned(ws, 256)) return R3_ERR_WORKSPACE;
     return hip_rc(launch_permute(m.T, m.d, m.E, m.K, m.eb, x, idx, m.idx, m.stride, counts, offsets, inv_perm,
                                  perm, Xp, status_word, ws, (hipStream_t)stream));
+}
+
+int r3_permute_static(const r3_layer_desc *desc, const void *x, const void *idx, int32_t *counts,
+                      int32_t *offsets, int32_t *inv_perm, int32_t *perm, void *Xp, int32_t *status_word,
+                      void *stream) {
+    Dims m;
+    int rc = check_desc(desc, m);
+    if (rc) return rc;
+    if (permute_ws_bytes(m.T, m.E, m.K) > (size_t)R3_STATIC_SCRATCH_BYTES) return R3_ERR_UNSUPPORTED;
+    void *ws = nullptr;
+    rc = static_scratch(&ws);
+    if (rc) return rc;
+    return r3_permute(desc, x, idx, counts, offsets, inv_perm, perm, Xp, status_word, ws,
+                      (size_t)R3_STATIC_SCRATCH_BYTES, stream);
 }
 
 int r3_grouped_ffn(const r3_layer_desc *desc, const void *Xp, const void *x, const int32_t *perm,

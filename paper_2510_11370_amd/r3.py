@@ -19,7 +19,7 @@ DATA_IDX_RANGE, DATA_IDX_DUP, DATA_NONFINITE = 1, 2, 4
 _STATUS = {1: "R3_ERR_INVALID_ARG", 2: "R3_ERR_UNSUPPORTED", 3: "R3_ERR_WORKSPACE", 4: "R3_ERR_HIP"}
 
 EXPORTS = ["r3_version", "r3_workspace_bytes", "r3_record_topk", "r3_replay_gate", "r3_permute",
-           "r3_grouped_ffn", "r3_combine", "r3_moe_backward", "r3_profile_enable", "r3_profile_tags",
+           "r3_permute_static", "r3_grouped_ffn", "r3_combine", "r3_moe_backward", "r3_profile_enable", "r3_profile_tags",
            "r3_profile_name", "r3_profile_read", "r3_profile_copy",
            "r3_profile_mfma", "r3_profile_mfma_flops", "r3_profile_gemm_mix", "r3_routing_diff", "r3_policy_discrepancy",
            "r3_policy_workspace_bytes", "r3_mask_cache_append", "r3_mask_cache_gather"]
@@ -109,6 +109,12 @@ def replay_gate(D, x, W_r, idx, gates, bias=None, logits_out=None, agree_out=Non
 def permute(D, x, idx, counts, offsets, inv_perm, perm, Xp, ws, status=None):
     _check(lib().r3_permute(C.byref(D), _p(x), _p(idx), _p(counts), _p(offsets), _p(inv_perm), _p(perm),
                             _p(Xp), _p(status), _p(ws), C.c_size_t(ws.numel()), _stream()), "r3_permute")
+
+
+def permute_static(D, x, idx, counts, offsets, inv_perm, perm, Xp, status=None):
+    """r3_permute with the library's own fixed scratch array (allocates nothing, takes no workspace)."""
+    _check(lib().r3_permute_static(C.byref(D), _p(x), _p(idx), _p(counts), _p(offsets), _p(inv_perm), _p(perm),
+                                   _p(Xp), _p(status), _stream()), "r3_permute_static")
 
 
 def grouped_ffn(D, Xp, offsets, W_gate, W_up, W_down, Yp, H, A_save=None, B_save=None, ws=None, x=None, perm=None):
