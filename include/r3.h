@@ -145,9 +145,12 @@ int r3_permute_static(const r3_layer_desc *desc, const void *x, const void *idx,
  * for expert e and its rows r in [offsets[e], offsets[e+1]):
  *   A = Xp W_gate[e], B = Xp W_up[e], H = silu(A) * B, Yp = H W_down[e].
  * Xp [T*K,d]; W_gate, W_up [E,d,F]; W_down [E,F,d]; Yp [T*K,d]; H [T*K,F]
- * (required: it is the second GEMM's input and the backward's saved value);
- * A_save, B_save [T*K,F] or both NULL (forward only).  All act dtype; f32
- * accumulation; `offsets` is read on the device.
+ * (required: it is the second GEMM's input and the backward's saved value).
+ * FA_save, FB_save [T*K,F] or both NULL (forward only): what the backward
+ * needs of the pre-activations, as the two factors its SwiGLU step multiplies
+ * with: FA = B * silu'(A) (so that dA = dh * FA) and FB = silu(A) (dB = dh * FB),
+ * silu'(a) = s (1 + a (1 - s)), s = sigmoid(a).  A and B themselves are not
+ * stored.  All act dtype; f32 accumulation; `offsets` is read on the device.
  * Xp may be NULL when x [T,d] and perm [T*K] (from r3_permute) are given: row
  * r is then read as x[perm[r] / K] inside the first contraction's tile loads
  * and no gathered copy of the tokens is needed (r3_permute may be called with
@@ -156,7 +159,7 @@ int r3_permute_static(const r3_layer_desc *desc, const void *x, const void *idx,
  */
 int r3_grouped_ffn(const r3_layer_desc *desc, const void *Xp, const void *x, const int32_t *perm,
                    const int32_t *offsets, const void *W_gate, const void *W_up, const void *W_down,
-                   void *Yp, void *H, void *A_save, void *B_save, void *ws,
+                   void *Yp, void *H, void *FA_save, void *FB_save, void *ws,
                    size_t ws_bytes, void *stream);
 
 /*
@@ -169,21 +172,26 @@ int r3_combine(const r3_layer_desc *desc, const void *Yp, const float *gates,
 /*
  * Backward of the replayed layer (Section 4.1, purpose (b): the gradient still
  * reaches the router logits through the softmax; the recorded mask is a
- * constant).  Given dy [T,d] act and the forward's tensors, writes the
- * gradient of sum(dy*y):  dx [T,d] act;  dW_r [d,E], dW_gate, dW_up [E,d,F],
- * dW_down [E,F,d] f32;  dbias [E] f32 or NULL.  accumulate = 0 overwrites the
- * weight gradients, 1 adds to them.  Experts outside a token's recorded set get
- * exactly zero router gradient from that token.
- * Xp may be NULL (perm is then required): dW_gate and dW_up read the token rows
- * from x through perm inside their tile loads, with the same results bit for
- * bit; bf16 MFMA shapes only (else R3_ERR_UNSUPPORTED), T*d*sizeof(act) < 2^31.
- * perm is not read when Xp is given.
+ * constant).  Given dy [T,d] act and the forward's tensors (FA, FB, H as
+ * r3_grouped_ffn saved them), writes the gradient of sum(dy*y):  dx [T,d] act;
+ * dW_r [d,E], dW_gate, dW_up [E,d,F], dW_down [E,F,d] f32;  dbias [E] f32 or
+ * NULL.  accumulate = 0 overwrites the weight gradients, 1 adds to them.
+ * Experts outside a token's recorded set get exactly zero router gradient from
+ * that token.
+ * bf16 shapes the MFMA kernels tile (d and F multiples of 256): perm is
+ * required and T*d*sizeof(act) < 2^31 (else R3_ERR_UNSUPPORTED).  The expert
+ * gradients read the rows of dy (and of x when Xp is NULL) through perm inside
+ * their tile loads, and the softmax backward takes its dot products
+ * <dy_t, o_j> from the down projection's gradient GEMM (<dy, H W_down> =
+ * <dy W_down^T, H>), so no per-slot copy of dy is made and Yp is not read: Yp
+ * and Xp may be NULL.  Other shapes and f32 run plain kernels, which need Xp
+ * and Yp and do not read perm.
  */
 int r3_moe_backward(const r3_layer_desc *desc, const void *dy, const void *x,
                     const void *W_r, const void *idx, const float *gates,
                     const int32_t *inv_perm, const int32_t *perm,
-                    const int32_t *offsets, const void *Xp, const void *A,
-                    const void *B, const void *H, const void *Yp, const void *W_gate,
+                    const int32_t *offsets, const void *Xp, const void *FA,
+                    const void *FB, const void *H, const void *Yp, const void *W_gate,
                     const void *W_up, const void *W_down, void *dx, float *dW_r,
                     float *dW_gate, float *dW_up, float *dW_down, float *dbias,
                     int accumulate, void *ws, size_t ws_bytes, void *stream);

@@ -21,18 +21,13 @@ def k3_kl(logp_train, logp_infer):
 
 
 def extreme_fraction(logp_train, logp_infer, taus):
-    """F(tau) for each tau: share of tokens with max(r, 1/r) > tau.
+    """F(tau) for each tau: share of tokens with max(r, 1/r) > tau, r = pi_train(t) / pi_infer(t).
 
-    max(r, 1/r) > tau  <=>  |log r| > log tau.  The comparison is taken in float32 (the precision the
-    kernel decides it in): log r is the float32 difference of the two float32 log-probs, log tau the
-    float32 rounding of the float64 logarithm."""
-    lt, li = np.asarray(logp_train, np.float32), np.asarray(logp_infer, np.float32)
-    d = np.abs(lt - li)                                   # float32 arithmetic
-    out = []
-    for tau in taus:
-        thr = np.float32(np.log(np.float64(tau)))
-        out.append(float(np.count_nonzero(d > thr)) / max(d.size, 1))
-    return out
+    max(r, 1/r) > tau  <=>  |log r| > log tau, evaluated in float64: log r is the exact difference of the
+    two float32 log-probabilities (exact in float64 unless their exponents are far apart), log tau the
+    float64 logarithm."""
+    d = np.abs(np.asarray(logp_train, np.float32).astype(np.float64) - np.asarray(logp_infer, np.float32).astype(np.float64))
+    return [float(np.count_nonzero(d > np.log(np.float64(tau)))) / max(d.size, 1) for tau in taus]
 
 
 def differing_choices(a, b):

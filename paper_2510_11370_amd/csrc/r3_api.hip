@@ -42,21 +42,26 @@ bool use_mfma_ffn(const Dims &m) { return m.act == R3_BF16 && mfma_ffn_supported
 bool use_mfma_router(const Dims &m) { return m.act == R3_BF16 && mfma_router_supported(m.d, m.E) && !force_simt(); }
 
 struct BwdWs {
-    size_t dYp, dz, ds, WrT, dA, dB, tiles, part, tok, total;
+    size_t dXp, dz, ds, WrT, dA, dB, tiles, part, tok, Hg, grow, wpart, total;
 };
+int row_parts(const Dims &m) { return 2 * (m.F / 256); }   // partial dot products per row (MFMA path)
 BwdWs bwd_layout(const Dims &m) {
     BwdWs w;
     size_t o = 0;
     auto take = [&](size_t bytes) { size_t at = o; o += align_up(bytes, 256); return at; };
-    w.dYp = take((size_t)m.S * m.d * m.eb);  // later reused for dXp
+    const bool mf = use_mfma_ffn(m);
+    w.dXp = take((size_t)m.S * m.d * m.eb);  // the plain kernels keep g*dy here first
     w.dz = take((size_t)m.T * m.K * sizeof(float));
     w.ds = take((size_t)m.T * m.E * (m.act == R3_BF16 ? 2 : 1) * m.eb);  // bf16: (hi, lo) halves
     w.WrT = take((size_t)m.E * m.d * m.eb);
     w.dA = take((size_t)m.S * m.F * m.eb);
     w.dB = take((size_t)m.S * m.F * m.eb);
-    w.tiles = take(use_mfma_ffn(m) ? mfma_tiles_bytes(m.S, m.E) : 0);
+    w.tiles = take(mf ? mfma_tiles_bytes(m.S, m.E) : 0);
     w.part = take(use_mfma_router(m) ? mfma_dwr_ws_bytes(m.T, m.d, m.E) : 0);
-    w.tok = take(use_mfma_ffn(m) ? mfma_row_tokens_bytes(m.S) : 0);  // row -> token list (backward without Xp)
+    w.tok = take(mf ? mfma_row_tokens_bytes(m.S) : 0);           // row -> token list
+    w.Hg = take(mf ? (size_t)m.S * m.F * m.eb : 0);              // gate-scaled H rows
+    w.grow = take(mf ? (size_t)m.S * sizeof(float) : 0);         // row -> gate list
+    w.wpart = take(mf ? (size_t)m.S * row_parts(m) * sizeof(float) : 0);
     w.total = o;
     return w;
 }
@@ -176,15 +181,15 @@ int r3_permute_static(const r3_layer_desc *desc, const void *x, const void *idx,
 
 int r3_grouped_ffn(const r3_layer_desc *desc, const void *Xp, const void *x, const int32_t *perm,
                    const int32_t *offsets, const void *W_gate, const void *W_up, const void *W_down, void *Yp,
-                   void *H, void *A_save, void *B_save, void *ws, size_t ws_bytes, void *stream) {
+                   void *H, void *FA_save, void *FB_save, void *ws, size_t ws_bytes, void *stream) {
     Dims m;
     int rc = check_desc(desc, m);
     if (rc) return rc;
-    if (!offsets || !W_gate || !W_up || !W_down || !Yp || !H || ((A_save == nullptr) != (B_save == nullptr)))
+    if (!offsets || !W_gate || !W_up || !W_down || !Yp || !H || ((FA_save == nullptr) != (FB_save == nullptr)))
         return R3_ERR_INVALID_ARG;
     if (!Xp && (!x || !perm)) return R3_ERR_INVALID_ARG;   // rows come from Xp, or from x through perm
     if (!aligned(Xp, 16) || !aligned(x, 16) || !aligned(perm, 4) || !aligned(W_gate, 16) || !aligned(W_up, 16) ||
-        !aligned(W_down, 16) || !aligned(Yp, 16) || !aligned(H, 16) || !aligned(A_save, 16) || !aligned(B_save, 16))
+        !aligned(W_down, 16) || !aligned(Yp, 16) || !aligned(H, 16) || !aligned(FA_save, 16) || !aligned(FB_save, 16))
         return R3_ERR_INVALID_ARG;
     const void *rows = Xp ? Xp : x;
     const int32_t *via = Xp ? nullptr : perm;
@@ -195,9 +200,9 @@ int r3_grouped_ffn(const r3_layer_desc *desc, const void *Xp, const void *x, con
         int32_t *tiles = (int32_t *)ws;
         if (mfma_build_tiles(m.E, offsets, tiles, s) != hipSuccess) return R3_ERR_HIP;
         return hip_rc(mfma_ffn_forward(m.S, m.d, m.E, m.F, rows, via, m.K, m.T, offsets, tiles, W_gate, W_up, W_down,
-                                       Yp, H, A_save, B_save, s));
+                                       Yp, H, FA_save, FB_save, s));
     }
-    if (simt_ffn1((int)m.S, m.d, m.E, m.F, m.act, rows, via, m.K, offsets, W_gate, W_up, H, A_save, B_save, s) !=
+    if (simt_ffn1((int)m.S, m.d, m.E, m.F, m.act, rows, via, m.K, offsets, W_gate, W_up, H, FA_save, FB_save, s) !=
         hipSuccess)
         return R3_ERR_HIP;
     return hip_rc(simt_ffn2((int)m.S, m.d, m.E, m.F, m.act, H, offsets, W_down, Yp, s));
@@ -216,69 +221,77 @@ int r3_combine(const r3_layer_desc *desc, const void *Yp, const float *gates, co
 
 int r3_moe_backward(const r3_layer_desc *desc, const void *dy, const void *x, const void *W_r,
                     const void *idx, const float *gates, const int32_t *inv_perm, const int32_t *perm,
-                    const int32_t *offsets, const void *Xp, const void *A, const void *B, const void *H,
+                    const int32_t *offsets, const void *Xp, const void *FA, const void *FB, const void *H,
                     const void *Yp, const void *W_gate, const void *W_up, const void *W_down, void *dx,
                     float *dW_r, float *dW_gate, float *dW_up, float *dW_down, float *dbias,
                     int accumulate, void *ws, size_t ws_bytes, void *stream) {
     Dims m;
     int rc = check_desc(desc, m);
     if (rc) return rc;
-    const void *ptrs[] = {dy, x, W_r, idx, gates, inv_perm, offsets, A, B, H, Yp, W_gate, W_up, W_down,
+    const bool mf = use_mfma_ffn(m);
+    const void *ptrs[] = {dy, x, W_r, idx, gates, inv_perm, offsets, FA, FB, H, W_gate, W_up, W_down,
                           dx, dW_r, dW_gate, dW_up, dW_down};
     for (const void *p : ptrs)
         if (!p) return R3_ERR_INVALID_ARG;
-    const void *a16[] = {dy, x, W_r, Xp, A, B, H, Yp, W_gate, W_up, W_down, dx, dW_r, dW_gate, dW_up, dW_down};
+    const void *a16[] = {dy, x, W_r, Xp, FA, FB, H, Yp, W_gate, W_up, W_down, dx, dW_r, dW_gate, dW_up, dW_down};
     for (const void *p : a16)
         if (!aligned(p, 16)) return R3_ERR_INVALID_ARG;
     if (accumulate != 0 && accumulate != 1) return R3_ERR_INVALID_ARG;
-    if (!Xp) {   // the gathered rows are read from x through perm
+    if (mf) {
+        // rows of dy (and of x when there is no Xp) are read through perm inside the tile loads
         if (!perm || !aligned(perm, 4)) return R3_ERR_INVALID_ARG;
-        if (!use_mfma_ffn(m) || (int64_t)m.T * m.d * m.eb >= (1ll << 31)) return R3_ERR_UNSUPPORTED;
+        if ((int64_t)m.T * m.d * m.eb >= (1ll << 31)) return R3_ERR_UNSUPPORTED;   // 32-bit row offsets
+    } else if (!Yp || !Xp) {
+        return Xp ? R3_ERR_INVALID_ARG : R3_ERR_UNSUPPORTED;   // the plain kernels need both copies
     }
     const BwdWs w = bwd_layout(m);
     if (!ws || ws_bytes < w.total || !aligned(ws, 256)) return R3_ERR_WORKSPACE;
     hipStream_t s = (hipStream_t)stream;
     char *base = (char *)ws;
-    void *dYp = base + w.dYp, *ds = base + w.ds, *WrT = base + w.WrT, *dA = base + w.dA, *dB = base + w.dB;
-    void *dXp = dYp;  // dYp is dead once dW_down and dH are done
+    void *dXp = base + w.dXp, *ds = base + w.ds, *WrT = base + w.WrT, *dA = base + w.dA, *dB = base + w.dB;
     float *dz = (float *)(base + w.dz);
     const int S = (int)m.S;
-
-    // combine and masked softmax:  dYp, dz, dense ds
-    if (launch_gate_backward(m.T, m.d, m.E, m.K, m.act, dy, Yp, gates, inv_perm, idx, m.idx, m.stride, dYp, dz,
-                             ds, s) != hipSuccess)
-        return R3_ERR_HIP;
-    // router:  dW_r = x^T ds, dbias = column sums
     hipError_t e;
-    if (use_mfma_router(m)) e = mfma_dwr(m.T, m.d, m.E, x, ds, (float *)(base + w.part), dW_r, accumulate, s);
-    else e = simt_dwr(m.T, m.d, m.E, m.act, x, ds, dW_r, accumulate, s);
-    if (e != hipSuccess) return R3_ERR_HIP;
-    if (dbias && launch_colsum(m.T, m.E, m.act, ds, dbias, accumulate, s) != hipSuccess) return R3_ERR_HIP;
-    if (launch_transpose(m.d, m.E, m.act, W_r, WrT, s) != hipSuccess) return R3_ERR_HIP;
-    // experts
-    if (use_mfma_ffn(m)) {
-        int32_t *tiles = (int32_t *)(base + w.tiles);
+
+    if (mf) {
+        // experts first: the gradient GEMM of the down projection reads dy through the row -> token
+        // list and leaves the dot products the masked softmax needs (no g*dy copy, no read of Yp)
+        int32_t *tiles = (int32_t *)(base + w.tiles), *tok = (int32_t *)(base + w.tok);
+        float *grow = (float *)(base + w.grow), *wpart = (float *)(base + w.wpart);
+        void *Hg = base + w.Hg;
+        if (mfma_row_tokens(S, m.K, perm, gates, tok, grow, s) != hipSuccess) return R3_ERR_HIP;
         if (mfma_build_tiles(m.E, offsets, tiles, s) != hipSuccess) return R3_ERR_HIP;
-        if (mfma_ffn_dh(m.S, m.d, m.E, m.F, dYp, offsets, tiles, W_down, A, B, dA, dB, s) != hipSuccess)
+        if (mfma_ffn_dh(m.S, m.d, m.E, m.F, dy, tok, m.T, grow, offsets, tiles, W_down, FA, FB, H, dA, dB, Hg, wpart,
+                        s) != hipSuccess)
             return R3_ERR_HIP;
-        if (mfma_wgrad(m.E, m.F, m.d, H, dYp, offsets, tiles, 2, dW_down, accumulate, s) != hipSuccess) return R3_ERR_HIP;
-        int32_t *tok = nullptr;
-        if (!Xp) {
-            tok = (int32_t *)(base + w.tok);
-            if (mfma_row_tokens(S, m.K, perm, tok, s) != hipSuccess) return R3_ERR_HIP;
-        }
-        if (mfma_wgrad_pair(m.E, m.d, m.F, Xp ? Xp : x, tok, m.T, dA, dB, offsets, tiles, 3, dW_gate, dW_up, accumulate,
-                            s) != hipSuccess)
+        if (launch_gate_backward_parts(m.T, m.E, m.K, row_parts(m), wpart, gates, inv_perm, idx, m.idx, m.stride, dz,
+                                       ds, s) != hipSuccess)
+            return R3_ERR_HIP;
+        if (mfma_wgrad(m.E, m.F, m.d, Hg, dy, tok, m.T, offsets, tiles, 2, dW_down, accumulate, s) != hipSuccess)
+            return R3_ERR_HIP;
+        if (mfma_wgrad_pair(m.E, m.d, m.F, Xp ? Xp : x, Xp ? nullptr : tok, m.T, dA, dB, offsets, tiles, 3, dW_gate,
+                            dW_up, accumulate, s) != hipSuccess)
             return R3_ERR_HIP;
         if (mfma_ffn_dxp(m.S, m.d, m.E, m.F, dA, dB, offsets, tiles, W_gate, W_up, dXp, s) != hipSuccess)
             return R3_ERR_HIP;
     } else {
-        if (simt_dh(S, m.d, m.E, m.F, m.act, dYp, offsets, W_down, A, B, dA, dB, s) != hipSuccess) return R3_ERR_HIP;
+        // combine and masked softmax:  dYp = g*dy per slot, dz, dense ds
+        void *dYp = dXp;  // dYp is dead once dW_down and dH are done
+        if (launch_gate_backward(m.T, m.d, m.E, m.K, m.act, dy, Yp, gates, inv_perm, idx, m.idx, m.stride, dYp, dz,
+                                 ds, s) != hipSuccess)
+            return R3_ERR_HIP;
+        if (simt_dh(S, m.d, m.E, m.F, m.act, dYp, offsets, W_down, FA, FB, dA, dB, s) != hipSuccess) return R3_ERR_HIP;
         if (simt_wgrad(m.E, m.F, m.d, m.act, H, dYp, offsets, dW_down, accumulate, s) != hipSuccess) return R3_ERR_HIP;
         if (simt_wgrad(m.E, m.d, m.F, m.act, Xp, dA, offsets, dW_gate, accumulate, s) != hipSuccess) return R3_ERR_HIP;
         if (simt_wgrad(m.E, m.d, m.F, m.act, Xp, dB, offsets, dW_up, accumulate, s) != hipSuccess) return R3_ERR_HIP;
         if (simt_dxp(S, m.d, m.E, m.F, m.act, dA, dB, offsets, W_gate, W_up, dXp, s) != hipSuccess) return R3_ERR_HIP;
     }
+    // router:  dW_r = x^T ds, dbias = column sums
+    if (use_mfma_router(m)) e = mfma_dwr(m.T, m.d, m.E, x, ds, (float *)(base + w.part), dW_r, accumulate, s);
+    else e = simt_dwr(m.T, m.d, m.E, m.act, x, ds, dW_r, accumulate, s);
+    if (e != hipSuccess) return R3_ERR_HIP;
+    if (dbias && launch_colsum(m.T, m.E, m.act, ds, dbias, accumulate, s) != hipSuccess) return R3_ERR_HIP;
+    if (launch_transpose(m.d, m.E, m.act, W_r, WrT, s) != hipSuccess) return R3_ERR_HIP;
     // dx = un-permuted expert gradients + router term
     return hip_rc(launch_dx_finish(m.T, m.d, m.E, m.K, m.act, dXp, WrT, dz, inv_perm, idx, m.idx, m.stride, dx,
                                    s));

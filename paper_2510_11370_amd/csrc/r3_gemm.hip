@@ -111,26 +111,26 @@ __device__ __forceinline__ void unpack4(uint2 v, float *f) {
 // The P operand is two 128-feature sub-tiles, one of W_gate and one of W_up, at
 // the same features, so a wave holds both pre-activations of a (row, feature)
 // pair in the same lane: MFMA tiles 0,1 are gate, tiles 2,3 the matching up.
+// What is saved for the backward are not A and B but the two factors its SwiGLU
+// step multiplies dh with: FA = B silu'(A) (dA = dh FA) and FB = silu(A)
+// (dB = dh FB); the sigmoid is in registers here anyway, and the backward's
+// epilogue is left with two multiplications per element.
 // ---------------------------------------------------------------------------
 template <bool GATHER>
 __global__ void __launch_bounds__(kThreads2, kMinWavesPerSimd)
 ffn1_kernel(int S, int d, int F, const bf16_t *__restrict__ Xp, const int32_t *__restrict__ perm, int K, int T,
             const int32_t *__restrict__ offsets, const int32_t *__restrict__ tiles, const bf16_t *__restrict__ Wg,
-            const bf16_t *__restrict__ Wu, bf16_t *__restrict__ H, bf16_t *__restrict__ A, bf16_t *__restrict__ B,
-            int launch) {
+            const bf16_t *__restrict__ Wu, bf16_t *__restrict__ H, bf16_t *__restrict__ FA, bf16_t *__restrict__ FB) {
     __shared__ __attribute__((aligned(1024))) char lds[2 * kSuperBytes];   // one piece: a tail tile lays it out differently
-    __shared__ int mailbox[2];
     char *const bufA = lds, *const bufB = lds + kSuperBytes;
     char *const s0 = bufA, *const s1 = bufA + kStageBytes, *const s2 = bufB, *const s3 = bufB + kStageBytes;
     constexpr int BF = 128;  // features per tile
     const int npt = F / BF;
-    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-    const int wp = wave % kWP2, wq = wave / kWP2;
     OpTR128x2 P;
-    P.init(F * 2, 0, 64 * wp);
+    P.init(F * 2, 0, 64 * ((threadIdx.x >> 6) % kWP2));
     OpKC64<GATHER> Q;
-    Q.init(d * 2, kWaveRowsQ * wq);
-    TileLoopStatic tl(tiles[0] * npt, tile_counters(tiles, launch));
+    Q.init(d * 2, kWaveRowsQ * ((threadIdx.x >> 6) / kWP2));
+    RowTileLoop tl(tiles[0] * npt);
     struct Tile {
         int e, row0, row_end, f0;
     };
@@ -154,11 +154,10 @@ ffn1_kernel(int S, int d, int F, const bf16_t *__restrict__ Xp, const int32_t *_
             // one; they are never stored)
             Q.src[0] = Src{(const char *)Xp, clamp_bytes((int64_t)T * d * 2), kBK3 * 2};
             const int chunk = Q.lane_chunk();
+            int v[8];
 #pragma unroll
-            for (int i = 0; i < 8; ++i) {
-                const int tok = perm[min(t.row0 + Q.lane_row(i), S - 1)] / K;
-                Q.voff[i] = tok * (d * 2) + chunk;
-            }
+            for (int i = 0; i < 8; ++i) v[i] = (perm[min(t.row0 + Q.lane_row(i), S - 1)] / K) * (d * 2) + chunk;
+            Q.set_rows(v);
         } else {
             Q.src[0] = Src{(const char *)(Xp + (int64_t)t.row0 * d), clamp_bytes((int64_t)(S - t.row0) * d * 2), kBK3 * 2};
         }
@@ -176,40 +175,49 @@ ffn1_kernel(int S, int d, int F, const bf16_t *__restrict__ Xp, const int32_t *_
     Acc2 acc;
     zero_acc2(acc);
     if (row_end - row0 <= kWaveRowsQ) mfma_tail_loop3(acc, d / kBK3, P, Q, lds);
-    else mfma_mainloop3(acc, d / kBK3, P, Q, bufA, bufB, row_end - row0);
-    tl.prefetch();
+    else mfma_mainloop3(acc, d / kBK3, P, Q, lds, row_end - row0);
     if (more) aim(nxt);   // here, so that the row-index loads of a gathered tile hide behind the epilogue
 
-    // per wave: 64 rows x 64 features of H (and A, B), 32 rows at a time through LDS
-    // (three patches in turn, so that one block's stores and the next block's arithmetic overlap)
-    char *patch = wave_patch(s0, s1, s2, s3);
+    // per wave: 64 rows x 64 features of H (and FA, FB), 32 rows at a time through LDS
+    // (three patches, so that one tensor's stores and the next one's deposits overlap)
+    const int tid = opaque_tid();
+    const int lane = tid & 63, wq = (tid >> 6) / kWP2, wp = (tid >> 6) % kWP2;
+    char *patch = wave_patch(s0, s1, s2, s3, tid);
     const int q = lane & 31;
+    const bool save = FA != nullptr;
 #pragma unroll
     for (int tq = 0; tq < kTQ2; ++tq) {
         const int brow = row0 + wq * kWaveRowsQ + tq * 32;            // first row of this block
         const int valid = min(32, row_end - brow);             // may be <= 0
         const int64_t o = ((int64_t)brow * F + f0 + wp * 64) * 2;  // byte offset of the block
+        RowStage<128> sh{patch, tid}, sa{patch + RowStage<128>::BYTES, tid}, sb{patch + 2 * RowStage<128>::BYTES, tid};
 #pragma unroll
-        for (int which = 0; which < 3; ++which) {              // 0: H, 1: A, 2: B
-            bf16_t *dst = which == 0 ? H : which == 1 ? A : B;
-            if (!dst) continue;
-            RowStage<128> st{patch + which * RowStage<128>::BYTES};
+        for (int tp = 0; tp < 2; ++tp)
 #pragma unroll
-            for (int tp = 0; tp < 2; ++tp)
+            for (int g = 0; g < 4; ++g) {
+                float h[4], fa[4], fb[4];
 #pragma unroll
-                for (int g = 0; g < 4; ++g) {
-                    float v[4];
-#pragma unroll
-                    for (int i = 0; i < 4; ++i) {
-                        const float a = acc[tp][tq][4 * g + i], b = acc[tp + 2][tq][4 * g + i];
-                        v[i] = which == 0 ? a * sigmoid_fast(a) * b : which == 1 ? a : b;
-                    }
-                    st.put8(q, (tp * 32 + g * 8 + (lane >> 5) * 4) * 2, pack4(v[0], v[1], v[2], v[3]));
+                for (int i = 0; i < 4; ++i) {
+                    const float a = acc[tp][tq][4 * g + i], b = acc[tp + 2][tq][4 * g + i];
+                    const float sg = sigmoid_fast(a);
+                    fb[i] = a * sg;                                  // silu(a)
+                    h[i] = fb[i] * b;
+                    fa[i] = b * fmaf(fb[i], 1.0f - sg, sg);          // b silu'(a), silu'(a) = sg (1 + a (1 - sg))
                 }
-            st.flush((char *)dst + o, (int64_t)F * 2, valid);
+                const int bo = (tp * 32 + g * 8 + (lane >> 5) * 4) * 2;
+                sh.put8(q, bo, pack4(h[0], h[1], h[2], h[3]));
+                if (save) {
+                    sa.put8(q, bo, pack4(fa[0], fa[1], fa[2], fa[3]));
+                    sb.put8(q, bo, pack4(fb[0], fb[1], fb[2], fb[3]));
+                }
+            }
+        sh.flush((char *)H + o, (int64_t)F * 2, valid);
+        if (save) {
+            sa.flush((char *)FA + o, (int64_t)F * 2, valid);
+            sb.flush((char *)FB + o, (int64_t)F * 2, valid);
         }
     }
-    const int after = tl.finish(mailbox);
+    const int after = tl.finish();
     slot = next;
     next = after;
     cur = nxt;
@@ -220,8 +228,14 @@ ffn1_kernel(int S, int d, int F, const bf16_t *__restrict__ Xp, const int32_t *_
 // Row-ragged contraction with a plain or SwiGLU-backward epilogue:
 //   out[row][p0+p] = sum_k Q[row][k] * Pmat[e](p, k)
 // MODE 0: Yp = H Wd          P from Wd[e] [F,d]  (TR: k rows, features c), K = F
-// MODE 1: dH = dYp Wd^T      P from Wd[e] [F,d]  (KC: feature rows f),      K = d
-//         epilogue dA = dh*B*silu'(A), dB = dh*silu(A)
+// MODE 1: u = dy Wd^T        P from Wd[e] [F,d]  (KC: feature rows f),      K = d
+//         The Q rows are the upstream gradient's rows read through the row -> token list (row r is
+//         dy[tok[r]]): the gated copy g*dy of every slot is never written.  Epilogue, with g the
+//         row's gate, FA = B silu'(A) and FB = silu(A) saved by the forward:
+//           dA = g u FA,  dB = g u FB,  Hg = g H  (the row operand of dW_down = Hg^T dy),
+//           wpart[row][2 pt + wp] = g * sum over this wave's 128 features of u H
+//         The parts of a row add up to g <dy, o> = g dg (o = H Wd: <dy, H Wd> = <dy Wd^T, H>), which is
+//         all the masked-softmax backward needs, so the expert outputs are not read again either.
 // MODE 2: dXp = dA Wg^T + dB Wu^T   P from Wg[e], Wu[e] [d,F] (KC: rows c), K = 2F
 //         (two-phase reduction: first F over (dA, Wg), then F over (dB, Wu))
 // ---------------------------------------------------------------------------
@@ -229,32 +243,37 @@ template <int MODE>
 __global__ void __launch_bounds__(kThreads2, kMinWavesPerSimd)
 rowgemm_kernel(int S, int d, int F, const bf16_t *__restrict__ Q0, const bf16_t *__restrict__ Q1,
                const int32_t *__restrict__ offsets, const int32_t *__restrict__ tiles,
-               const bf16_t *__restrict__ W0, const bf16_t *__restrict__ W1, const bf16_t *__restrict__ A,
-               const bf16_t *__restrict__ B, bf16_t *__restrict__ out0, bf16_t *__restrict__ out1, int launch) {
+               const bf16_t *__restrict__ W0, const bf16_t *__restrict__ W1, const bf16_t *__restrict__ FA,
+               const bf16_t *__restrict__ FB, bf16_t *__restrict__ out0, bf16_t *__restrict__ out1,
+               const int32_t *__restrict__ tok, int T, const float *__restrict__ grow,
+               const bf16_t *__restrict__ Hs, bf16_t *__restrict__ out2, float *__restrict__ wpart) {
     __shared__ __attribute__((aligned(1024))) char lds[2 * kSuperBytes];   // one piece: a tail tile lays it out differently
-    __shared__ int mailbox[2];
     char *const bufA = lds, *const bufB = lds + kSuperBytes;
     char *const s0 = bufA, *const s1 = bufA + kStageBytes, *const s2 = bufB, *const s3 = bufB + kStageBytes;
     const int NOUT = (MODE == 1) ? F : d;  // width of the output
     const int KQ = (MODE == 1) ? d : F;    // width of the Q source rows
     const int npt = NOUT / kTile;
     const int nw = (MODE == 0) ? F / kBK3 : (MODE == 1) ? d / kBK3 : 2 * (F / kBK3);   // windows of 64 k
-    const int wave = threadIdx.x >> 6;
-    const int wp = wave % kWP2, wq = wave / kWP2;
+    const int wp0 = (threadIdx.x >> 6) % kWP2, wq0 = (threadIdx.x >> 6) / kWP2;
     // operand forms: the weights are feature-contiguous (TR) for MODE 0, K-contiguous otherwise
-    typedef typename std::conditional<MODE == 0, OpTR256, OpKC64<false>>::type POp;
+    typedef typename std::conditional<MODE == 0, OpTR256, OpKC64<false, false, true>>::type POp;
+    constexpr bool GATHER = MODE == 1;     // Q rows through the row -> token list
+    __shared__ int4 qstash[GATHER ? 2 * 256 : 1];   // the gathered rows' offsets (no registers to spare for them)
     POp P;
-    OpKC64<false> Q;
+#ifndef R3_DH_STASH
+#define R3_DH_STASH 1
+#endif
+    OpKC64<GATHER, GATHER && R3_DH_STASH> Q;
     if constexpr (MODE == 0) {
         P.kswitch = 0x7fffffff;
-        P.init(d * 2, 0, 128 * wp);
+        P.init(d * 2, 0, 128 * wp0);
     } else {
-        P.init((MODE == 1 ? d : F) * 2, 128 * wp);
+        P.init((MODE == 1 ? d : F) * 2, 128 * wp0);
         if constexpr (MODE == 2) P.wswitch = F / kBK3;
     }
-    Q.init(KQ * 2, kWaveRowsQ * wq);
+    Q.init(KQ * 2, kWaveRowsQ * wq0, qstash);
     if constexpr (MODE == 2) Q.wswitch = F / kBK3;
-    TileLoopStatic tl(tiles[0] * npt, tile_counters(tiles, launch));
+    RowTileLoop tl(tiles[0] * npt);
     struct Tile {
         int e, row0, row_end, p0;
     };
@@ -270,7 +289,18 @@ rowgemm_kernel(int S, int d, int F, const bf16_t *__restrict__ Q0, const bf16_t 
     };
     auto aim = [&](const Tile &t) {   // point the operands at a tile
         const bf16_t *w0 = W0 + (int64_t)t.e * d * F;
-        Q.src[0] = Src{(const char *)(Q0 + (int64_t)t.row0 * KQ), clamp_bytes((int64_t)(S - t.row0) * KQ * 2), kBK3 * 2};
+        if constexpr (GATHER) {
+            // each lane's eight rows of the tile come from their tokens' rows of Q0 [T, KQ] (rows past the
+            // end of the list read token 0: the list is padded with zeros; they are never stored)
+            Q.src[0] = Src{(const char *)Q0, clamp_bytes((int64_t)T * KQ * 2), kBK3 * 2};
+            const int chunk = Q.lane_chunk();
+            int v[8];
+#pragma unroll
+            for (int i = 0; i < 8; ++i) v[i] = tok[min(t.row0 + Q.lane_row(i), S)] * (KQ * 2) + chunk;
+            Q.set_rows(v);
+        } else {
+            Q.src[0] = Src{(const char *)(Q0 + (int64_t)t.row0 * KQ), clamp_bytes((int64_t)(S - t.row0) * KQ * 2), kBK3 * 2};
+        }
         Q.src[1] = Q.src[0];
         if constexpr (MODE == 2)
             Q.src[1] = Src{(const char *)(Q1 + (int64_t)t.row0 * KQ), clamp_bytes((int64_t)(S - t.row0) * KQ * 2), kBK3 * 2};
@@ -288,49 +318,74 @@ rowgemm_kernel(int S, int d, int F, const bf16_t *__restrict__ Q0, const bf16_t 
     };
     if (!tl.valid(tl.first())) return;
     Tile cur = decode(tl.first());
+    if constexpr (GATHER) aim(cur);
     for (int slot = tl.first(), next = tl.second(); tl.valid(slot);) {
     // the next tile's coordinates are fetched now (scalar loads), a whole tile before their use
     const bool more = tl.valid(next);
     const Tile nxt = more ? decode(next) : cur;
     const int row0 = cur.row0, row_end = cur.row_end, p0 = cur.p0;
-    aim(cur);
+    if constexpr (!GATHER) aim(cur);
+    if constexpr (MODE == 1) {
+        // the operands' lane constants are made anew for every tile, from a thread index the compiler
+        // cannot trace: kept across tiles they are live through the epilogue, the fullest part of this
+        // kernel, and are then spilled, with reloads in the tile loop that wait on the tile loads
+        const int t0 = opaque_tid();
+        P.set_lane(d * 2, 128 * ((t0 >> 6) % kWP2), t0);
+        Q.set_lane(KQ * 2, kWaveRowsQ * ((t0 >> 6) / kWP2), t0, qstash);
+    }
 
     Acc2 acc;
     zero_acc2(acc);
     if (row_end - row0 <= kWaveRowsQ) mfma_tail_loop3(acc, nw, P, Q, lds);
-    else mfma_mainloop3(acc, nw, P, Q, bufA, bufB, row_end - row0);
-    tl.prefetch();
+    else mfma_mainloop3(acc, nw, P, Q, lds, row_end - row0);
+    if constexpr (GATHER)
+        if (more) aim(nxt);   // here, so that the row-index loads of the next tile hide behind the epilogue
 
     // per wave: 64 rows x 128 features, 32 rows at a time through LDS
-    const int lane = threadIdx.x & 63;
-    RowStage<256> st{wave_patch(s0, s1, s2, s3)};
+    const int tid = opaque_tid();
+    const int lane = tid & 63, wq = (tid >> 6) / kWP2, wp = (tid >> 6) % kWP2;
+    RowStage<256> st{wave_patch(s0, s1, s2, s3, tid), tid};
     const int q = lane & 31;
     if constexpr (MODE == 1) {
-        // Rounds of 32 rows x 64 features.  The saved pre-activations come in
-        // row-contiguously into two patches (A and B); each lane then replaces exactly the
-        // quads it read with dA (first patch) and dB (second patch), and the patches go out
-        // row-contiguously.  The next round's rows are fetched before this round's arithmetic.
-        RowStage<128> sa{st.base}, sb{st.base + RowStage<128>::BYTES};
-        auto where = [&](int r, int &valid) -> int64_t {
+        // Four rounds of 32 rows x 64 features, each in three phases: FA -> dA, FB -> dB, H -> g H and the
+        // row's dot product.  A phase's rows come in row-contiguously into a patch, each lane replaces
+        // exactly the quads it read, and the patch goes out row-contiguously.  The rows of the phase
+        // after next are asked for while this one is worked on: two 4 KB blocks in flight per wave (a
+        // whole round ahead, three blocks, cost the tile loop its registers).  A lane's 16 + 16 products
+        // u H of one 32-row block belong to one row (q).
+        typedef RowStage<128> Patch;
+        const Patch sa{st.base, tid}, sb{st.base + Patch::BYTES, tid}, sh{st.base + 2 * Patch::BYTES, tid};
+        constexpr int NPH = 3 * 2 * kTQ2;
+        auto where = [&](int ph, int &valid) -> int64_t {
+            const int r = ph / 3;
             const int brow = row0 + wq * kWaveRowsQ + (r >> 1) * 32;
             valid = min(32, row_end - brow);
             return ((int64_t)brow * NOUT + p0 + wp * 128) * 2 + (r & 1) * 128;
         };
-        int valid;
-        int64_t oh = where(0, valid);
-        RowStage<128>::Rows ra = sa.fetch((const char *)A + oh, (int64_t)NOUT * 2, valid);
-        RowStage<128>::Rows rb = sb.fetch((const char *)B + oh, (int64_t)NOUT * 2, valid);
+        auto ask = [&](int ph) -> Patch::Rows {
+            int valid;
+            const int64_t o = where(ph, valid);
+            const char *src = ph % 3 == 0 ? (const char *)FA : ph % 3 == 1 ? (const char *)FB : (const char *)Hs;
+            return sa.fetch(src + o, (int64_t)NOUT * 2, valid);
+        };
+#ifndef R3_DH_AHEAD
+#define R3_DH_AHEAD 1
+#endif
+        constexpr int AH = R3_DH_AHEAD;   // phases the row fetches run ahead (1 or 2)
+        Patch::Rows rr[2] = {ask(0), ask(AH == 2 ? 1 : 0)};
+        float gq = 0.0f, wsum = 0.0f;
 #pragma unroll
-        for (int r = 0; r < 2 * kTQ2; ++r) {
-            const int tq = r >> 1, half = r & 1;
-            sa.deposit(ra);
-            sb.deposit(rb);
-
-            if (r + 1 < 2 * kTQ2) {
-                int nvalid;
-                const int64_t noh = where(r + 1, nvalid);
-                ra = sa.fetch((const char *)A + noh, (int64_t)NOUT * 2, nvalid);
-                rb = sb.fetch((const char *)B + noh, (int64_t)NOUT * 2, nvalid);
+        for (int ph = 0; ph < NPH; ++ph) {
+            const int r = ph / 3, which = ph % 3, tq = r >> 1, half = r & 1;
+            const int brow = row0 + wq * kWaveRowsQ + tq * 32;
+            const Patch &sp = which == 0 ? sa : which == 1 ? sb : sh;
+            int valid;
+            const int64_t oh = where(ph, valid);
+            sp.deposit(rr[AH == 2 ? (ph & 1) : 0]);
+            if (ph + AH < NPH) rr[AH == 2 ? (ph & 1) : 0] = ask(ph + AH);
+            if (which == 0 && half == 0) {
+                gq = brow + q < row_end ? grow[brow + q] : 0.0f;
+                wsum = 0.0f;
             }
 #pragma unroll
             for (int t = 0; t < 2; ++t)
@@ -338,22 +393,28 @@ rowgemm_kernel(int S, int d, int F, const bf16_t *__restrict__ Q0, const bf16_t 
                 for (int g = 0; g < 4; ++g) {
                     const int tp = half * 2 + t;
                     const int bo = (t * 32 + g * 8 + (lane >> 5) * 4) * 2;
-                    float a[4], b[4], da[4], db[4];
-                    unpack4(sa.get8(q, bo), a);
-                    unpack4(sb.get8(q, bo), b);
+                    float v[4], o[4];
+                    unpack4(sp.get8(q, bo), v);
 #pragma unroll
                     for (int i = 0; i < 4; ++i) {
-                        const float dh = acc[tp][tq][4 * g + i];
-                        const float sg = sigmoid_fast(a[i]);
-                        da[i] = dh * b[i] * sg * (1.0f + a[i] * (1.0f - sg));
-                        db[i] = dh * a[i] * sg;
+                        const float u = acc[tp][tq][4 * g + i];
+                        if (which == 2) {
+                            wsum = fmaf(u, v[i], wsum);
+                            o[i] = gq * v[i];
+                        } else {
+                            o[i] = gq * u * v[i];
+                        }
                     }
-                    sa.put8(q, bo, pack4(da[0], da[1], da[2], da[3]));
-                    sb.put8(q, bo, pack4(db[0], db[1], db[2], db[3]));
+                    sp.put8(q, bo, pack4(o[0], o[1], o[2], o[3]));
                 }
-            oh = where(r, valid);
-            sa.flush((char *)out0 + oh, (int64_t)NOUT * 2, valid);
-            sb.flush((char *)out1 + oh, (int64_t)NOUT * 2, valid);
+            bf16_t *dst = which == 0 ? out0 : which == 1 ? out1 : out2;
+            sp.flush((char *)dst + oh, (int64_t)NOUT * 2, valid);
+            if (which == 2 && half == 1) {
+                // the two lanes that hold row q (k-groups 0 and 1 of the MFMA layout) add up
+                const float w = gq * (wsum + __shfl_xor(wsum, 32, 64));
+                if (lane < 32 && brow + q < row_end)
+                    wpart[(int64_t)(brow + q) * (2 * npt) + 2 * (p0 / kTile) + wp] = w;
+            }
         }
     } else {
 #pragma unroll
@@ -371,7 +432,7 @@ rowgemm_kernel(int S, int d, int F, const bf16_t *__restrict__ Q0, const bf16_t 
             st.flush((char *)out0 + o, (int64_t)NOUT * 2, valid);
         }
     }
-    const int after = tl.finish(mailbox);
+    const int after = tl.finish();
     slot = next;
     next = after;
     cur = nxt;
@@ -383,23 +444,31 @@ rowgemm_kernel(int S, int d, int F, const bf16_t *__restrict__ Q0, const bf16_t 
 // Both operands are [row][feature] matrices, so both tiles are TR; the k loop
 // runs over the expert's rows and the buffer bound zero-fills the tail.
 // ---------------------------------------------------------------------------
+// GATHER: Ps is the un-permuted matrix [nrows, NPd] and row r of the reduction is its row tok[r]
+// (dW_down = Hg^T dy straight from the upstream gradient: no per-slot copy of dy is read).
+template <bool GATHER>
 __global__ void __launch_bounds__(kThreads2, kMinWavesPerSimd)
 wgrad_kernel(int E, int NQd, int NPd, const bf16_t *__restrict__ Qs, const bf16_t *__restrict__ Ps,
-             const int32_t *__restrict__ offsets, float *__restrict__ out, int accumulate, int *ctr,
-             const int32_t *__restrict__ order) {
+             const int32_t *__restrict__ tok, int nrows, const int32_t *__restrict__ offsets,
+             float *__restrict__ out, int accumulate, int *ctr, const int32_t *__restrict__ order) {
     __shared__ __attribute__((aligned(1024))) char s0[kStageBytes];
     __shared__ __attribute__((aligned(1024))) char s1[kStageBytes];
     __shared__ __attribute__((aligned(1024))) char s2[kStageBytes];
     __shared__ __attribute__((aligned(1024))) char s3[kStageBytes];
     __shared__ int mailbox[2];
     const int nqt = NQd / kTile, npt = NPd / kTile;
-    const int wave = threadIdx.x >> 6;
-    const int wp = wave % kWP2, wq = wave / kWP2;
+    const int wp0 = (threadIdx.x >> 6) % kWP2, wq0 = (threadIdx.x >> 6) / kWP2;
     // operands are set up once; a tile only moves their source windows (column offset included)
-    OpTR256 P, Q;
-    P.kswitch = Q.kswitch = 0x7fffffff;
-    P.init(NPd * 2, 0, 128 * wp);
-    Q.init(NQd * 2, 0, kWaveRowsQ * wq);
+    typename std::conditional<GATHER, OpTR256G, OpTR256>::type P;
+    OpTR256 Q;
+    Q.kswitch = 0x7fffffff;
+    if constexpr (GATHER) {
+        P.init(NPd * 2, 128 * wp0);
+    } else {
+        P.kswitch = 0x7fffffff;
+        P.init(NPd * 2, 0, 128 * wp0);
+    }
+    Q.init(NQd * 2, 0, kWaveRowsQ * wq0);
     TileLoop tl(E * nqt * npt, ctr);
     for (int slot = tl.first(), next = tl.second(); tl.valid(slot);) {
     const int id = tl.id(slot);
@@ -409,9 +478,13 @@ wgrad_kernel(int E, int NQd, int NPd, const bf16_t *__restrict__ Qs, const bf16_
     const int qt = rem / npt, pt = rem - qt * npt;
     const int r0 = offsets[e], r1 = offsets[e + 1];
     const int q0 = qt * kTile, p0 = pt * kTile;
-    P.src[0] = Src{(const char *)(Ps + (int64_t)r0 * NPd + p0), clamp_bytes(((int64_t)(r1 - r0) * NPd - p0) * 2),
-                   (uint32_t)(kBK2 * NPd * 2)};
-    P.src[1] = P.src[0];
+    if constexpr (GATHER) {
+        P.aim(Ps, (uint64_t)nrows * NPd * 2, p0 * 2, tok + r0, r1 - r0);
+    } else {
+        P.src[0] = Src{(const char *)(Ps + (int64_t)r0 * NPd + p0), clamp_bytes(((int64_t)(r1 - r0) * NPd - p0) * 2),
+                       (uint32_t)(kBK2 * NPd * 2)};
+        P.src[1] = P.src[0];
+    }
     Q.src[0] = Src{(const char *)(Qs + (int64_t)r0 * NQd + q0), clamp_bytes(((int64_t)(r1 - r0) * NQd - q0) * 2),
                    (uint32_t)(kBK2 * NQd * 2)};
     Q.src[1] = Q.src[0];
@@ -422,8 +495,9 @@ wgrad_kernel(int E, int NQd, int NPd, const bf16_t *__restrict__ Qs, const bf16_
     tl.prefetch();
 
     // per wave: 64 rows (q) x 128 features (p) of f32, as 32-row x 64-feature blocks through LDS
-    const int lane = threadIdx.x & 63;
-    RowStage<256> st{wave_patch(s0, s1, s2, s3)};
+    const int tid = opaque_tid();
+    const int lane = tid & 63, wq = (tid >> 6) / kWP2, wp = (tid >> 6) % kWP2;
+    RowStage<256> st{wave_patch(s0, s1, s2, s3, tid), tid};
     const int q = lane & 31;
     char *o = (char *)(out + (int64_t)e * NQd * NPd);
 #pragma unroll
@@ -470,16 +544,15 @@ wgrad_pair_kernel(int E, int NQd, int NPd, const bf16_t *__restrict__ Qs, const 
     __shared__ int mailbox[2];
     constexpr int BF = 128;  // features of P0 (and of P1) per tile
     const int nqt = NQd / kTile, npt = NPd / BF;
-    const int wave = threadIdx.x >> 6;
-    const int wp = wave % kWP2, wq = wave / kWP2;
+    const int wp0 = (threadIdx.x >> 6) % kWP2, wq0 = (threadIdx.x >> 6) / kWP2;
     OpTR128x2 P;
-    P.init(NPd * 2, 0, 64 * wp);
+    P.init(NPd * 2, 0, 64 * wp0);
     typename std::conditional<GATHER, OpTR256G, OpTR256>::type Q;
     if constexpr (GATHER) {
-        Q.init(NQd * 2, kWaveRowsQ * wq);
+        Q.init(NQd * 2, kWaveRowsQ * wq0);
     } else {
         Q.kswitch = 0x7fffffff;
-        Q.init(NQd * 2, 0, kWaveRowsQ * wq);
+        Q.init(NQd * 2, 0, kWaveRowsQ * wq0);
     }
     TileLoop tl(E * nqt * npt, ctr);
     for (int slot = tl.first(), next = tl.second(); tl.valid(slot);) {
@@ -507,8 +580,9 @@ wgrad_pair_kernel(int E, int NQd, int NPd, const bf16_t *__restrict__ Qs, const 
     tl.prefetch();
 
     // per wave: 64 rows (q) x 64 features (p) of each product, 32-row blocks through LDS
-    const int lane = threadIdx.x & 63;
-    RowStage<256> st{wave_patch(s0, s1, s2, s3)};
+    const int tid = opaque_tid();
+    const int lane = tid & 63, wq = (tid >> 6) / kWP2, wp = (tid >> 6) % kWP2;
+    RowStage<256> st{wave_patch(s0, s1, s2, s3, tid), tid};
     const int q = lane & 31;
 #pragma unroll
     for (int tq = 0; tq < kTQ2; ++tq)
@@ -647,34 +721,35 @@ hipError_t mfma_build_tiles(int E, const int32_t *offsets, int32_t *tiles, hipSt
 
 hipError_t mfma_ffn_forward(int64_t S, int d, int E, int F, const void *Xp, const int32_t *perm, int K, int T,
                             const int32_t *offsets, const int32_t *tiles, const void *Wg, const void *Wu,
-                            const void *Wd, void *Yp, void *H, void *A, void *B, hipStream_t s) {
+                            const void *Wd, void *Yp, void *H, void *FA, void *FB, hipStream_t s) {
     const int mt = max_row_tiles(S, E, kTile);
     {
         ProfScope ps(PROF_FFN1, s);
         if (perm)
             ffn1_kernel<true><<<persistent_grid((int64_t)mt * (F / 128)), kThreads2, 0, s>>>(
                 (int)S, d, F, (const bf16_t *)Xp, perm, K, T, offsets, tiles, (const bf16_t *)Wg, (const bf16_t *)Wu,
-                (bf16_t *)H, (bf16_t *)A, (bf16_t *)B, 0);
+                (bf16_t *)H, (bf16_t *)FA, (bf16_t *)FB);
         else
             ffn1_kernel<false><<<persistent_grid((int64_t)mt * (F / 128)), kThreads2, 0, s>>>(
                 (int)S, d, F, (const bf16_t *)Xp, perm, K, T, offsets, tiles, (const bf16_t *)Wg, (const bf16_t *)Wu,
-                (bf16_t *)H, (bf16_t *)A, (bf16_t *)B, 0);
+                (bf16_t *)H, (bf16_t *)FA, (bf16_t *)FB);
     }
     ProfScope ps(PROF_FFN2, s);
     rowgemm_kernel<0><<<persistent_grid((int64_t)mt * (d / kTile)), kThreads2, 0, s>>>(
         (int)S, d, F, (const bf16_t *)H, nullptr, offsets, tiles, (const bf16_t *)Wd, nullptr, nullptr, nullptr,
-        (bf16_t *)Yp, nullptr, 1);
+        (bf16_t *)Yp, nullptr, nullptr, 0, nullptr, nullptr, nullptr, nullptr);
     return hipGetLastError();
 }
 
-hipError_t mfma_ffn_dh(int64_t S, int d, int E, int F, const void *dYp, const int32_t *offsets,
-                       const int32_t *tiles, const void *Wd, const void *A, const void *B, void *dA, void *dB,
-                       hipStream_t s) {
+hipError_t mfma_ffn_dh(int64_t S, int d, int E, int F, const void *dy, const int32_t *tok, int T, const float *grow,
+                       const int32_t *offsets, const int32_t *tiles, const void *Wd, const void *FA, const void *FB,
+                       const void *H, void *dA, void *dB, void *Hg, float *wpart, hipStream_t s) {
     const int mt = max_row_tiles(S, E, kTile);
     ProfScope ps(PROF_DH, s);
     rowgemm_kernel<1><<<persistent_grid((int64_t)mt * (F / kTile)), kThreads2, 0, s>>>(
-        (int)S, d, F, (const bf16_t *)dYp, nullptr, offsets, tiles, (const bf16_t *)Wd, nullptr,
-        (const bf16_t *)A, (const bf16_t *)B, (bf16_t *)dA, (bf16_t *)dB, 0);
+        (int)S, d, F, (const bf16_t *)dy, nullptr, offsets, tiles, (const bf16_t *)Wd, nullptr,
+        (const bf16_t *)FA, (const bf16_t *)FB, (bf16_t *)dA, (bf16_t *)dB, tok, T, grow, (const bf16_t *)H,
+        (bf16_t *)Hg, wpart);
     return hipGetLastError();
 }
 
@@ -684,18 +759,23 @@ hipError_t mfma_ffn_dxp(int64_t S, int d, int E, int F, const void *dA, const vo
     ProfScope ps(PROF_DXP, s);
     rowgemm_kernel<2><<<persistent_grid((int64_t)mt * (d / kTile)), kThreads2, 0, s>>>(
         (int)S, d, F, (const bf16_t *)dA, (const bf16_t *)dB, offsets, tiles, (const bf16_t *)Wg,
-        (const bf16_t *)Wu, nullptr, nullptr, (bf16_t *)dXp, nullptr, 1);
+        (const bf16_t *)Wu, nullptr, nullptr, (bf16_t *)dXp, nullptr, nullptr, 0, nullptr, nullptr, nullptr, nullptr);
     return hipGetLastError();
 }
 
-hipError_t mfma_wgrad(int E, int NQd, int NPd, const void *Qs, const void *Ps, const int32_t *offsets,
-                      const int32_t *tiles, int launch, float *out, int accumulate, hipStream_t s) {
+hipError_t mfma_wgrad(int E, int NQd, int NPd, const void *Qs, const void *Ps, const int32_t *tok, int nrows,
+                      const int32_t *offsets, const int32_t *tiles, int launch, float *out, int accumulate,
+                      hipStream_t s) {
     const int64_t ntiles = (int64_t)E * (NQd / kTile) * (NPd / kTile);
     ProfScope ps(PROF_WGRAD, s);
-    wgrad_kernel<<<persistent_grid(ntiles), kThreads2, 0, s>>>(E, NQd, NPd, (const bf16_t *)Qs, (const bf16_t *)Ps,
-                                                              offsets, out, accumulate,
-                                                              const_cast<int *>(tiles) + 2 + 8 * launch,
-                                                              tiles + kTileOrder);
+    if (tok)
+        wgrad_kernel<true><<<persistent_grid(ntiles), kThreads2, 0, s>>>(
+            E, NQd, NPd, (const bf16_t *)Qs, (const bf16_t *)Ps, tok, nrows, offsets, out, accumulate,
+            const_cast<int *>(tiles) + 2 + 8 * launch, tiles + kTileOrder);
+    else
+        wgrad_kernel<false><<<persistent_grid(ntiles), kThreads2, 0, s>>>(
+            E, NQd, NPd, (const bf16_t *)Qs, (const bf16_t *)Ps, nullptr, 0, offsets, out, accumulate,
+            const_cast<int *>(tiles) + 2 + 8 * launch, tiles + kTileOrder);
     return hipGetLastError();
 }
 
@@ -716,18 +796,26 @@ hipError_t mfma_wgrad_pair(int E, int NQd, int NPd, const void *Qs, const int32_
 }
 
 // tok[r] = perm[r] / K for r < S (the token whose row sits at position r of the expert-sorted order),
-// followed by `pad` zeros, so that index fetches one past a segment's end stay inside the array
+// followed by `pad` zeros, so that index fetches one past a segment's end stay inside the array;
+// grow[r] = gates[perm[r]], the gate of that row's slot (gates may be NULL: grow is then not written)
 __global__ void __launch_bounds__(256) row_tokens_kernel(int S, int K, int pad, const int32_t *__restrict__ perm,
-                                                         int32_t *__restrict__ tok) {
+                                                         const float *__restrict__ gates, int32_t *__restrict__ tok,
+                                                         float *__restrict__ grow) {
     const int r = blockIdx.x * 256 + threadIdx.x;
-    if (r < S) tok[r] = perm[r] / K;
-    else if (r < S + pad) tok[r] = 0;
+    if (r < S) {
+        const int slot = perm[r];
+        tok[r] = slot / K;
+        if (gates) grow[r] = gates[slot];
+    } else if (r < S + pad) {
+        tok[r] = 0;
+    }
 }
 
 size_t mfma_row_tokens_bytes(int64_t S) { return (size_t)(S + kRowTokensPad) * sizeof(int32_t); }
 
-hipError_t mfma_row_tokens(int S, int K, const int32_t *perm, int32_t *tok, hipStream_t s) {
-    row_tokens_kernel<<<(S + kRowTokensPad + 255) / 256, 256, 0, s>>>(S, K, kRowTokensPad, perm, tok);
+hipError_t mfma_row_tokens(int S, int K, const int32_t *perm, const float *gates, int32_t *tok, float *grow,
+                           hipStream_t s) {
+    row_tokens_kernel<<<(S + kRowTokensPad + 255) / 256, 256, 0, s>>>(S, K, kRowTokensPad, perm, gates, tok, grow);
     return hipGetLastError();
 }
 

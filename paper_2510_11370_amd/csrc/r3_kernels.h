@@ -36,6 +36,12 @@ hipError_t launch_gate_backward(int T, int d, int E, int K, int act, const void 
                                 const float *gates, const int32_t *inv_perm, const void *idx,
                                 int idx_dtype, int64_t stride, void *dYp, float *dz, void *ds_dense,
                                 hipStream_t s);
+// masked-softmax backward from the row parts written by the expert-gradient GEMM:
+// w_j = sum_p wpart[row_j][p] (= g_j dg_j), dz_j = w_j - g_j sum_i w_i; writes dz [T,K] and the dense
+// bf16 ds [T,2E] (hi | lo halves)
+hipError_t launch_gate_backward_parts(int T, int E, int K, int nparts, const float *wpart, const float *gates,
+                                      const int32_t *inv_perm, const void *idx, int idx_dtype, int64_t stride,
+                                      float *dz, void *ds_dense, hipStream_t s);
 hipError_t launch_dx_finish(int T, int d, int E, int K, int act, const void *dXp, const void *WrT,
                             const float *dz, const int32_t *inv_perm, const void *idx, int idx_dtype,
                             int64_t stride, void *dx, hipStream_t s);
@@ -88,25 +94,32 @@ hipError_t mfma_build_tiles(int E, const int32_t *offsets, int32_t *tiles, hipSt
 // through perm in the tile loads
 hipError_t mfma_ffn_forward(int64_t S, int d, int E, int F, const void *Xp, const int32_t *perm, int K, int T,
                             const int32_t *offsets, const int32_t *tiles, const void *Wg, const void *Wu,
-                            const void *Wd, void *Yp, void *H, void *A, void *B, hipStream_t s);
-hipError_t mfma_ffn_dh(int64_t S, int d, int E, int F, const void *dYp, const int32_t *offsets,
-                       const int32_t *tiles, const void *Wd, const void *A, const void *B, void *dA, void *dB,
-                       hipStream_t s);
+                            const void *Wd, void *Yp, void *H, void *FA, void *FB, hipStream_t s);
+// u = dy Wd^T with the rows of dy read through tok (row r is dy[tok[r]], dy is [T,d]); writes dA = g u FA,
+// dB = g u FB, Hg = g H and wpart [S, 2 F/256] f32, whose row sums are g <dy, o> (see rowgemm_kernel<1>)
+hipError_t mfma_ffn_dh(int64_t S, int d, int E, int F, const void *dy, const int32_t *tok, int T, const float *grow,
+                       const int32_t *offsets, const int32_t *tiles, const void *Wd, const void *FA, const void *FB,
+                       const void *H, void *dA, void *dB, void *Hg, float *wpart, hipStream_t s);
 hipError_t mfma_ffn_dxp(int64_t S, int d, int E, int F, const void *dA, const void *dB, const int32_t *offsets,
                         const int32_t *tiles, const void *Wg, const void *Wu, void *dXp, hipStream_t s);
 // `tiles` is the table mfma_build_tiles() filled in this call sequence; `launch` (2..7) picks the
-// tile counters of this launch: 0 and 1 belong to the forward pair and to dh / dxp
-hipError_t mfma_wgrad(int E, int NQd, int NPd, const void *Qs, const void *Ps, const int32_t *offsets,
-                      const int32_t *tiles, int launch, float *out, int accumulate, hipStream_t s);
+// tile counters of this launch: 0 and 1 belong to the forward pair and to dh / dxp.
+// out (+)= Qs^T Ps per expert.  tok != NULL: Ps is the un-permuted [nrows, NPd] matrix and row r of the
+// reduction is its row tok[r] (nrows * NPd * 2 < 2^31)
+hipError_t mfma_wgrad(int E, int NQd, int NPd, const void *Qs, const void *Ps, const int32_t *tok, int nrows,
+                      const int32_t *offsets, const int32_t *tiles, int launch, float *out, int accumulate,
+                      hipStream_t s);
 // out0 (+)= Qs^T P0 and out1 (+)= Qs^T P1 per expert in one pass over Qs.  tok != NULL: Qs is the
 // un-permuted [nrows, NQd] matrix and row r of the reduction is its row tok[r] (a list made by
 // mfma_row_tokens; nrows * NQd * 2 < 2^31)
 hipError_t mfma_wgrad_pair(int E, int NQd, int NPd, const void *Qs, const int32_t *tok, int nrows, const void *P0,
                            const void *P1, const int32_t *offsets, const int32_t *tiles, int launch, float *out0,
                            float *out1, int accumulate, hipStream_t s);
-// tok[r] = perm[r] / K (r < S), padded; mfma_row_tokens_bytes(S) bytes
+// tok[r] = perm[r] / K (r < S), padded; mfma_row_tokens_bytes(S) bytes.  gates != NULL: also
+// grow[r] = gates[perm[r]] (f32 [S])
 size_t mfma_row_tokens_bytes(int64_t S);
-hipError_t mfma_row_tokens(int S, int K, const int32_t *perm, int32_t *tok, hipStream_t s);
+hipError_t mfma_row_tokens(int S, int K, const int32_t *perm, const float *gates, int32_t *tok, float *grow,
+                           hipStream_t s);
 hipError_t mfma_router_logits(int T, int d, int E, const void *x, const void *Wr, const float *bias,
                               float *logits, hipStream_t s);
 hipError_t mfma_dwr(int T, int d, int E, const void *x, const void *ds, float *part, float *dWr, int accumulate,

@@ -65,8 +65,7 @@ struct KcFrag {
     int base;  // per-lane byte offset without the chunk term
     int swz;
     int hi;
-    __device__ __forceinline__ void init(int wave_base) {
-        const int lane = lane_id();
+    __device__ __forceinline__ void init(int wave_base, int lane = lane_id()) {
         const int row = wave_base + (lane & 31);
         constexpr int CH = BK / 8, RPL = 16 / CH;
         base = row * (BK * 2);

@@ -71,8 +71,10 @@ struct Src {
 
 typedef int rsrc_t __attribute__((ext_vector_type(4)));  // buffer descriptor words (wave-uniform)
 
-__device__ __forceinline__ rsrc_t src_rsrc(const Src &s, int kt) {
-    const uint64_t adv = (uint64_t)kt * s.step;
+// `extra`: a further wave-uniform byte advance (the window then starts that much later and is that
+// much shorter, so the bounds check stays exact)
+__device__ __forceinline__ rsrc_t src_rsrc(const Src &s, int kt, uint32_t extra = 0u) {
+    const uint64_t adv = (uint64_t)kt * s.step + extra;
     const uint64_t rest = adv < s.nbytes ? s.nbytes - adv : 0u;
     const uint32_t left = rest > 0x7fffffffu ? 0x7fffffffu : (uint32_t)rest;
     const uint64_t b = (uint64_t)(s.base + adv);
@@ -97,6 +99,16 @@ __device__ __forceinline__ void lds_load16(rsrc_t r, uint32_t dst_wave, int voff
     // (no cache hint: marked non-temporal these loads ran the row-tiled kernels at half speed --
     // the operand tiles live on being shared through L2 by the compute units of an XCD)
     asm volatile("s_mov_b32 m0, %0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds" ::"s"(m0v), "v"(voff), "s"(r)
+                 : "memory");
+}
+
+// The same with a wave-uniform byte offset in an SGPR added to the address.  The hardware's bounds
+// check does not see that offset: only for windows that lie inside their buffer whatever the lane
+// offsets are (weight panels: a tile's 256 rows always exist).
+__device__ __forceinline__ void lds_load16_soff(rsrc_t r, uint32_t dst_wave, int voff, int soff) {
+    const uint32_t m0v = __builtin_amdgcn_readfirstlane(dst_wave);
+    asm volatile("s_mov_b32 m0, %0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds" ::"s"(m0v), "v"(voff), "s"(r),
+                 "s"(__builtin_amdgcn_readfirstlane(soff))
                  : "memory");
 }
 
@@ -457,44 +469,94 @@ constexpr int kLoadsPerWindow = 16;           // tile loads per loader wave per 
 // conflict-free order), applied on the global side.  Chunk i of a wave is 32 rows below chunk
 // i - 1 and has the same swizzle, so one per-lane offset and a stride describe all eight --
 // unless the rows are gathered (ROWS = true): then each lane keeps the offsets of its eight rows.
-template <bool ROWS>
+// STASH (with ROWS): the eight row offsets live in LDS instead of registers (`stash`: 2 x 256 int4
+// outside the tile buffers, one slot pair per loader thread) and are read back at every window issue;
+// for kernels whose tile loop has no eight registers to spare.
+// INSIDE (without ROWS): every row of the window exists (a weight panel), so the 32-row advance from
+// chunk to chunk rides in the load's scalar offset and the lane keeps one offset register; otherwise
+// (rows of an expert's segment, whose tail relies on the bounds check) each chunk has its own.
+template <bool ROWS, bool STASH = false, bool INSIDE = false>
 struct OpKC64 {
     static constexpr bool kIndexed = false, kWindowed = true;
     Src src[2];
     int wswitch;           // window from which src[1] takes over (two-phase reductions)
-    int voff[ROWS ? 8 : 1];
+    int voff[(ROWS && !STASH) ? 8 : 1];
     int step;              // bytes between a lane's consecutive chunks (32 rows)
+    int4 *stash;           // STASH: this thread's first slot; the second is 256 slots on
     KcFrag<kBK3> fr;
+    int tid_;              // the thread index the lane constants were made from (see set_lane)
     __device__ __forceinline__ int lane_chunk() const {
-        const int w = threadIdx.x >> 6, lane = threadIdx.x & 63;
+        const int w = tid_ >> 6, lane = tid_ & 63;
         const int row0 = 8 * (w & 3) + (lane >> 3);
         return ((lane & 7) ^ ((row0 >> 1) & 7)) * 16;
     }
     __device__ __forceinline__ int lane_row(int i) const {   // row of this lane in its chunk i
-        const int w = threadIdx.x >> 6, lane = threadIdx.x & 63;
+        const int w = tid_ >> 6, lane = tid_ & 63;
         return 8 * (w & 3) + (lane >> 3) + 32 * i;
     }
-    __device__ __forceinline__ void init(int ld_bytes, int wave_base) {
-        wswitch = 0x7fffffff;
+    // The per-lane constants (load offset, fragment address parts, stash slot).  A kernel may call this
+    // again for every tile with an opaque copy of threadIdx.x (opaque_tid()): the constants are then
+    // made anew per tile and are not carried through the epilogue in registers.
+    __device__ __forceinline__ void set_lane(int ld_bytes, int wave_base, int tid, int4 *stash_base = nullptr) {
+        tid_ = tid;
         step = 32 * ld_bytes;
-        voff[0] = lane_row(0) * ld_bytes + lane_chunk();
-        fr.init(wave_base);
+        if constexpr (!ROWS) voff[0] = lane_row(0) * ld_bytes + lane_chunk();   // (gathered rows: set_rows())
+        stash = stash_base + (tid & 255);
+        fr.init(wave_base, tid & 63);
+    }
+    __device__ __forceinline__ void init(int ld_bytes, int wave_base, int4 *stash_base = nullptr) {
+        wswitch = 0x7fffffff;
+        set_lane(ld_bytes, wave_base, threadIdx.x, stash_base);
+    }
+    // the byte offsets of this lane's eight gathered rows (ROWS)
+    __device__ __forceinline__ void set_rows(const int (&v)[8]) {
+        if constexpr (STASH) {
+            if ((threadIdx.x >> 6) < kLoaderWaves) {
+                stash[0] = make_int4(v[0], v[1], v[2], v[3]);
+                stash[256] = make_int4(v[4], v[5], v[6], v[7]);
+            }
+        } else if constexpr (ROWS) {
+#pragma unroll
+            for (int i = 0; i < 8; ++i) voff[i] = v[i];
+        }
     }
     // rows: only rows [0, rows) of the window are wanted (a multiple of 64; the rest is left as it is)
     __device__ __forceinline__ void issue_window(int J, uint32_t win, int rows = kTile) const {
         const bool second = J >= wswitch;
         const Src &s = second ? src[1] : src[0];
-        const rsrc_t r = src_rsrc(s, second ? J - wswitch : J);
+        const int Js = second ? J - wswitch : J;
         const int w = threadIdx.x >> 6;
-        if (rows == kTile) {   // the common case as straight-line code
+        const rsrc_t r = src_rsrc(s, Js);
+        if constexpr (!ROWS && INSIDE) {
 #pragma unroll
             for (int i = 0; i < 8; ++i)
-                lds_load16(r, win + 1024 * ((w & 3) + kLoaderWaves * i), ROWS ? voff[ROWS ? i : 0] : voff[0] + i * step);
+                if (rows == kTile || (i < 6 && 32 * i < rows))
+                    lds_load16_soff(r, win + 1024 * ((w & 3) + kLoaderWaves * i), voff[0], i * step);
+            return;
+        }
+        int vo[8];
+        if constexpr (STASH) {
+            // read as inline asm: left to the compiler, the two reads are hoisted out of the window loop
+            // (nothing in it writes the stash) and the eight values are back in registers, or in scratch
+            int4 a, b;
+            asm volatile("ds_read_b128 %0, %2\n\tds_read_b128 %1, %2 offset:4096\n\ts_waitcnt lgkmcnt(0)"
+                         : "=&v"(a), "=&v"(b)
+                         : "v"(lds_addr(stash))
+                         : "memory");
+            vo[0] = a.x; vo[1] = a.y; vo[2] = a.z; vo[3] = a.w;
+            vo[4] = b.x; vo[5] = b.y; vo[6] = b.z; vo[7] = b.w;
+        } else {
+#pragma unroll
+            for (int i = 0; i < 8; ++i) vo[i] = ROWS ? voff[(ROWS && !STASH) ? i : 0] : voff[0] + i * step;
+        }
+        if (rows == kTile) {   // the common case as straight-line code
+#pragma unroll
+            for (int i = 0; i < 8; ++i) lds_load16(r, win + 1024 * ((w & 3) + kLoaderWaves * i), vo[i]);
         } else {
 #pragma unroll
             for (int i = 0; i < 6; ++i)
                 if (32 * i < rows)   // chunk i of a wave holds rows 32 i + 8 (w & 3) ..+7
-                    lds_load16(r, win + 1024 * ((w & 3) + kLoaderWaves * i), ROWS ? voff[ROWS ? i : 0] : voff[0] + i * step);
+                    lds_load16(r, win + 1024 * ((w & 3) + kLoaderWaves * i), vo[i]);
         }
     }
     __device__ __forceinline__ bf16x8_t frag_window(const char *win, int t, int u) const { return fr.read(win, t, u); }
@@ -547,25 +609,30 @@ __device__ __forceinline__ void window_barrier(bool loader) {
 // barrier; later than this shortens the time the loads have).
 template <class POp, class QOp>
 __device__ __forceinline__ void window_compute(Acc2 &acc, Frags &x, Frags &y, const POp &P, const QOp &Q,
-                                               const char *buf, int Jnext, uint32_t bnext, bool load_next, int qrows) {
-    if (load_next) win_issue(P, Jnext, bnext);
+                                               const char *pwin, const char *qwin, int Jnext, uint32_t pnext,
+                                               uint32_t qnext, bool load_next, int qrows) {
+    if (load_next) win_issue(P, Jnext, pnext);
     __builtin_amdgcn_sched_barrier(0);
-    sub_step3(acc, y, x, P, Q, buf, buf + kWinBytes, 0);
-    if (load_next) win_issue(Q, Jnext, bnext + kWinBytes, qrows);
+    sub_step3(acc, y, x, P, Q, pwin, qwin, 0);
+    if (load_next) win_issue(Q, Jnext, qnext, qrows);
     __builtin_amdgcn_sched_barrier(0);
-    sub_step3(acc, x, y, P, Q, buf, buf + kWinBytes, 1);
-    sub_step3(acc, y, x, P, Q, buf, buf + kWinBytes, 2);
-    sub_step3(acc, x, y, P, Q, buf, buf + kWinBytes, 3);
+    sub_step3(acc, x, y, P, Q, pwin, qwin, 1);
+    sub_step3(acc, y, x, P, Q, pwin, qwin, 2);
+    sub_step3(acc, x, y, P, Q, pwin, qwin, 3);
 }
 
-// nw windows of 64 k.  bufA, bufB: the two 64 KB LDS buffers (distinct arrays).  live_rows as in
-// mfma_mainloop2().  Every wave passes the same barriers whatever its role: one after the first
-// window's loads and one per window.
+// nw windows of 64 k.  `lds`: the work-group's 128 KB.  The two P windows sit at 0 and 32 KB, the two
+// Q windows at 64 and 96 KB: a window and its twin are 32 KB apart, which fits the 16-bit offset
+// field of an LDS read, so one address register per operand and sub-step serves both buffers (with
+// P and Q of a buffer side by side the twin was 64 KB away and had registers of its own: eight
+// more, in kernels that have none to spare).  live_rows as in mfma_mainloop2().  Every wave passes
+// the same barriers whatever its role: one after the first window's loads and one per window.
 template <class POp, class QOp>
-__device__ __forceinline__ void mfma_mainloop3(Acc2 &acc, int nw, const POp &P, const QOp &Q, char *bufA, char *bufB,
+__device__ __forceinline__ void mfma_mainloop3(Acc2 &acc, int nw, const POp &P, const QOp &Q, char *lds,
                                                int live_rows = kTile) {
     if (nw <= 0) return;
-    const uint32_t aA = lds_addr(bufA), aB = lds_addr(bufB);
+    char *const pA = lds, *const pB = lds + kWinBytes, *const qA = lds + 2 * kWinBytes, *const qB = lds + 3 * kWinBytes;
+    const uint32_t apA = lds_addr(pA), apB = lds_addr(pB), aqA = lds_addr(qA), aqB = lds_addr(qB);
     const int wave_ = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
     const bool loader = wave_ < kLoaderWaves;
     // rows of the Q window that some wave reads: whole 64-row blocks (a tail tile's dead rows are
@@ -582,16 +649,15 @@ __device__ __forceinline__ void mfma_mainloop3(Acc2 &acc, int nw, const POp &P, 
 #pragma nounroll
             for (int w = 0; w < 2; ++w)
                 if (w < nw) {
-                    const uint32_t a = w ? aB : aA;
-                    win_issue(P, w, a);
-                    win_issue(Q, w, a + kWinBytes, qrows);
+                    win_issue(P, w, w ? apB : apA);
+                    win_issue(Q, w, w ? aqB : aqA, qrows);
                 }
         } else {
-            win_issue(P, 0, aA);
-            win_issue(Q, 0, aA + kWinBytes, qrows);
+            win_issue(P, 0, apA);
+            win_issue(Q, 0, aqA, qrows);
             if (nw > 1) {
-                win_issue(P, 1, aB);
-                win_issue(Q, 1, aB + kWinBytes, qrows);
+                win_issue(P, 1, apB);
+                win_issue(Q, 1, aqB, qrows);
             }
         }
         if (nw > 1 && qrows == kTile)
@@ -603,10 +669,10 @@ __device__ __forceinline__ void mfma_mainloop3(Acc2 &acc, int nw, const POp &P, 
     if ((wave_ / kWP2) * kWaveRowsQ >= live_rows) {
         // this wave's rows are not needed: keep the loads (if it is a loader) and the barriers going
         for (int J = 0; J < nw; J += 2) {
-            if (loader && J > 0 && J + 1 < nw) { win_issue(P, J + 1, aB); win_issue(Q, J + 1, aB + kWinBytes, qrows); }
+            if (loader && J > 0 && J + 1 < nw) { win_issue(P, J + 1, apB); win_issue(Q, J + 1, aqB, qrows); }
             window_barrier(loader);
             if (J + 1 < nw) {
-                if (loader && J + 2 < nw) { win_issue(P, J + 2, aA); win_issue(Q, J + 2, aA + kWinBytes, qrows); }
+                if (loader && J + 2 < nw) { win_issue(P, J + 2, apA); win_issue(Q, J + 2, aqA, qrows); }
                 window_barrier(loader);
             }
         }
@@ -618,10 +684,10 @@ __device__ __forceinline__ void mfma_mainloop3(Acc2 &acc, int nw, const POp &P, 
 #pragma unroll
     for (int j = 0; j < kTQ2; ++j) x.b[j] = bf16x8_t{};
     for (int J = 0; J < nw; J += 2) {
-        window_compute(acc, x, y, P, Q, bufA, J + 1, aB, loader && J > 0 && J + 1 < nw, qrows);
+        window_compute(acc, x, y, P, Q, pA, qA, J + 1, apB, aqB, loader && J > 0 && J + 1 < nw, qrows);
         window_barrier(loader);
         if (J + 1 < nw) {
-            window_compute(acc, x, y, P, Q, bufB, J + 2, aA, loader && J + 2 < nw, qrows);
+            window_compute(acc, x, y, P, Q, pB, qB, J + 2, apA, aqA, loader && J + 2 < nw, qrows);
             window_barrier(loader);
         }
     }
@@ -750,7 +816,37 @@ struct TileLoopT {
     }
 };
 typedef TileLoopT<true> TileLoop;          // tiles of uneven length (weight gradients)
-typedef TileLoopT<false> TileLoopStatic;   // tiles of even length (row tiles)
+
+// The row-tiled kernels' loop: XCD x owns the contiguous range [total x / 8, total (x + 1) / 8) of the
+// tile list (tiles that share an operand panel sit next to each other and so meet in one L2) and its
+// work-groups walk it round-robin.  Two orderings meant to cut the L2's re-fetches of operand panels
+// were measured on the 16384-token layer and dropped: listing the short tail tiles after all full
+// tiles (so that a tail does not knock its work-group half a tile out of step with the others that
+// share its panels) cut the fetched bytes by 7 % (SwiGLU) to 15 % (dXp) and ran 1-3 % slower; making
+// the work-groups of an XCD start each round of tiles together (a bounded wait on a per-XCD counter)
+// cut them by 20 % and ran 12-23 % slower.  An XCD's round of 32 tiles does not line up with an
+// expert's 24-30 tiles, so even in lockstep most weight panels are fetched in two rounds, and the
+// fabric was not what the kernels were waiting for.
+struct RowTileLoop {
+    int start, cnt, stride, iter;
+    __device__ __forceinline__ RowTileLoop(int total) : stride(gridDim.x >> 3), iter(0) {
+        const int xcd = blockIdx.x & 7;
+        start = (int)(((int64_t)total * xcd) >> 3);
+        cnt = (int)(((int64_t)total * (xcd + 1)) >> 3) - start;
+    }
+    __device__ __forceinline__ int first() const { return blockIdx.x >> 3; }
+    __device__ __forceinline__ int second() const { return (blockIdx.x >> 3) + stride; }
+    __device__ __forceinline__ bool valid(int slot) const { return slot < cnt; }
+    __device__ __forceinline__ int id(int slot) const { return start + slot; }
+    // end of a tile: every wave's LDS traffic of the epilogue is complete and the waves have met
+    // before anyone loads the next tile into the stage buffers; returns the slot two after the
+    // current one.  (Not __syncthreads(): its fence would also wait for this tile's global stores.)
+    __device__ __forceinline__ int finish() {
+        asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+        ++iter;
+        return first() + (iter + 1) * stride;
+    }
+};
 
 // Epilogue staging.  The MFMA result layout gives a lane 4 consecutive features of ONE row
 // per register quad, so direct stores are 16-byte pieces scattered over 32 rows per
@@ -760,6 +856,15 @@ typedef TileLoopT<false> TileLoopStatic;   // tiles of even length (row tiles)
 // full 128/256-byte row segments per instruction.  The same patch serves to bring in
 // row-contiguous loads (saved activations, old gradients) for per-quad use.
 // ROWB = payload bytes per row (128 or 256); rows are padded by 16 B against bank conflicts.
+// `tid` is the thread's index as the epilogue sees it: the kernels pass a copy of threadIdx.x that the
+// compiler cannot trace back (opaque_tid()), so that the lane and row constants of the epilogue are
+// worked out after the tile loop instead of being carried through it in registers the loop needs.
+__device__ __forceinline__ int opaque_tid() {
+    int t = threadIdx.x;
+    asm volatile("" : "+v"(t));
+    return t;
+}
+
 template <int ROWB>
 struct RowStage {
     static constexpr int PITCH = ROWB + 16;
@@ -767,12 +872,13 @@ struct RowStage {
     static constexpr int RPI = 64 / LPR;    // rows per instruction
     static constexpr int BYTES = 32 * PITCH;
     char *base;
+    int tid;
     __device__ __forceinline__ void put8(int q, int byte_off, uint2 v) const { *(uint2 *)(base + q * PITCH + byte_off) = v; }
     __device__ __forceinline__ void put16(int q, int byte_off, float4 v) const { *(float4 *)(base + q * PITCH + byte_off) = v; }
     __device__ __forceinline__ uint2 get8(int q, int byte_off) const { return *(const uint2 *)(base + q * PITCH + byte_off); }
     // rows [0, valid) of the patch -> out (byte pointer at row 0), row pitch ld_bytes
     __device__ __forceinline__ void flush(char *out, int64_t ld_bytes, int valid) const {
-        const int lane = threadIdx.x & 63, r = lane / LPR, c = lane % LPR;
+        const int lane = tid & 63, r = lane / LPR, c = lane % LPR;
 #pragma unroll
         for (int i = 0; i < 32 / RPI; ++i) {
             const int row = i * RPI + r;
@@ -788,7 +894,7 @@ struct RowStage {
     }
     // same for f32 rows, adding what is already in memory (accumulate != 0)
     __device__ __forceinline__ void flush_f32(char *out, int64_t ld_bytes, int valid, int accumulate) const {
-        const int lane = threadIdx.x & 63, r = lane / LPR, c = lane % LPR;
+        const int lane = tid & 63, r = lane / LPR, c = lane % LPR;
 #pragma unroll 2
         for (int i = 0; i < 32 / RPI; ++i) {
             const int row = i * RPI + r;
@@ -809,7 +915,7 @@ struct RowStage {
         uint4 v[32 / RPI];
     };
     __device__ __forceinline__ Rows fetch(const char *in, int64_t ld_bytes, int valid) const {
-        const int lane = threadIdx.x & 63, r = lane / LPR, c = lane % LPR;
+        const int lane = tid & 63, r = lane / LPR, c = lane % LPR;
         Rows x;
 #pragma unroll
         for (int i = 0; i < 32 / RPI; ++i) {
@@ -824,7 +930,7 @@ struct RowStage {
         return x;
     }
     __device__ __forceinline__ void deposit(const Rows &x) const {
-        const int lane = threadIdx.x & 63, r = lane / LPR, c = lane % LPR;
+        const int lane = tid & 63, r = lane / LPR, c = lane % LPR;
 #pragma unroll
         for (int i = 0; i < 32 / RPI; ++i) *(uint4 *)(base + (i * RPI + r) * PITCH + c * 16) = x.v[i];
     }
@@ -834,8 +940,8 @@ struct RowStage {
 };
 
 // the wave's private share (128 KB / waves) of the (now idle) stage buffers
-__device__ __forceinline__ char *wave_patch(char *s0, char *s1, char *s2, char *s3) {
-    const int w = threadIdx.x >> 6;
+__device__ __forceinline__ char *wave_patch(char *s0, char *s1, char *s2, char *s3, int tid) {
+    const int w = tid >> 6;
     if constexpr (kWaves2 == 8) {
         char *b = (w >> 1) == 0 ? s0 : (w >> 1) == 1 ? s1 : (w >> 1) == 2 ? s2 : s3;
         return b + (w & 1) * 16384;

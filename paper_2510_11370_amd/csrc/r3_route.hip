@@ -941,6 +941,70 @@ hipError_t launch_gate_backward(int T, int d, int E, int K, int act, const void 
 }
 
 // ---------------------------------------------------------------------------
+// Masked-softmax backward when the expert-gradient GEMM has already formed the dot products: its
+// epilogue leaves, for every row r, `nparts` partial sums whose total is w = g <dy_t, o_r> = g dg.
+//   w_j = sum_p wpart[row_j][p] (p ascending),   dz_j = g_j (dg_j - sum_i g_i dg_i) = w_j - g_j sum_i w_i
+// One thread per slot, a token's K slots in neighbouring lanes; a block owns 256 / KP tokens (KP = K
+// rounded up to a power of two) and writes their dense ds rows [hi(E) | lo(E)] (bf16): zeros first,
+// then the K entries of each token.
+// ---------------------------------------------------------------------------
+template <typename IdxT>
+__global__ void __launch_bounds__(256)
+gate_backward_parts_kernel(int T, int E, int K, int KP, int nparts, const float *__restrict__ wpart,
+                           const float *__restrict__ gates, const int32_t *__restrict__ inv_perm,
+                           const IdxT *__restrict__ idx, int64_t stride, float *__restrict__ dz,
+                           bf16_t *__restrict__ ds) {
+    const int tpb = 256 / KP;                       // tokens per block
+    const int t0 = blockIdx.x * tpb;
+    const int nt = min(tpb, T - t0);
+    // zero this block's ds rows: nt * 2E bf16, contiguous, a multiple of 4 bytes
+    uint32_t *z = (uint32_t *)(ds + (int64_t)t0 * 2 * E);
+    for (int i = threadIdx.x; i < nt * E; i += 256) z[i] = 0u;
+    const int tl = threadIdx.x / KP, j = threadIdx.x % KP;
+    const int t = t0 + tl;
+    const bool live = tl < nt && j < K;
+    float w = 0.0f, g = 0.0f;
+    int e = 0;
+    if (live) {
+        const int row = inv_perm[(int64_t)t * K + j];
+        const float *p = wpart + (int64_t)row * nparts;
+        for (int i = 0; i < nparts; ++i) w += p[i];
+        g = gates[(int64_t)t * K + j];
+        e = min((int)idx[(int64_t)t * stride + j], E - 1);
+    }
+    // sum of w over the token's slots, in a fixed order: KP neighbouring lanes (KP <= 64 divides 64)
+    float mix = w;
+    for (int o = 1; o < KP; o <<= 1) mix += __shfl_xor(mix, o, 64);
+    __syncthreads();                                // the zeros are in before the entries go on top
+    if (live) {
+        const float v = w - g * mix;
+        dz[(int64_t)t * K + j] = v;
+        bf16_t *row = ds + (int64_t)t * 2 * E;
+        const bf16_t hi = f32_to_bf16(v);
+        row[e] = hi;
+        row[E + e] = f32_to_bf16(v - bf16_to_f32(hi));
+    }
+}
+
+hipError_t launch_gate_backward_parts(int T, int E, int K, int nparts, const float *wpart, const float *gates,
+                                      const int32_t *inv_perm, const void *idx, int idx_dtype, int64_t stride,
+                                      float *dz, void *ds_dense, hipStream_t s) {
+    ProfScope ps(PROF_GATE_BWD, s);
+    int KP = 1;
+    while (KP < K) KP <<= 1;                        // K <= kMaxK = 64
+    const int tpb = 256 / KP;
+    const int grid = (T + tpb - 1) / tpb;
+    if (idx_dtype == R3_IDX_U8)
+        gate_backward_parts_kernel<uint8_t><<<grid, 256, 0, s>>>(T, E, K, KP, nparts, wpart, gates, inv_perm,
+                                                                (const uint8_t *)idx, stride, dz, (bf16_t *)ds_dense);
+    else
+        gate_backward_parts_kernel<uint16_t><<<grid, 256, 0, s>>>(T, E, K, KP, nparts, wpart, gates, inv_perm,
+                                                                 (const uint16_t *)idx, stride, dz,
+                                                                 (bf16_t *)ds_dense);
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------
 // Final input gradient, one block per token:
 //   dx[t] = sum_j dXp[row_j]  +  sum_j dz[t,j] * W_r[:, idx_j]
 // WrT is W_r transposed ([E,d], act dtype) so that the router term reads rows.

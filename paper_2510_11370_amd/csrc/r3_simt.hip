@@ -30,12 +30,12 @@ simt_logits_kernel(int Tn, int d, int E, const T *__restrict__ x, const T *__res
     s[i] = acc;
 }
 
-// A = Xp Wg[e], B = Xp Wu[e], H = silu(A) * B
+// A = Xp Wg[e], B = Xp Wu[e], H = silu(A) * B; saved for the backward: FA = B silu'(A), FB = silu(A)
 template <typename T>
 __global__ void __launch_bounds__(256)
 simt_ffn1_kernel(int S, int d, int E, int F, const T *__restrict__ Xp, const int32_t *__restrict__ perm, int K,
                  const int32_t *__restrict__ offsets, const T *__restrict__ Wg, const T *__restrict__ Wu,
-                 T *__restrict__ H, T *__restrict__ A, T *__restrict__ B) {
+                 T *__restrict__ H, T *__restrict__ FA, T *__restrict__ FB) {
     int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (i >= (int64_t)S * F) return;
     int r = (int)(i / F), f = (int)(i - (int64_t)r * F);
@@ -48,9 +48,10 @@ simt_ffn1_kernel(int S, int d, int E, int F, const T *__restrict__ Xp, const int
         a = fmaf(xv, Elem<T>::ld(wg + (int64_t)c * F), a);
         b = fmaf(xv, Elem<T>::ld(wu + (int64_t)c * F), b);
     }
-    Elem<T>::st(H + i, a * sigmoidf_(a) * b);
-    if (A) Elem<T>::st(A + i, a);
-    if (B) Elem<T>::st(B + i, b);
+    const float sg = sigmoidf_(a);
+    Elem<T>::st(H + i, a * sg * b);
+    if (FA) Elem<T>::st(FA + i, b * sg * (1.0f + a * (1.0f - sg)));
+    if (FB) Elem<T>::st(FB + i, a * sg);
 }
 
 // Yp = H Wd[e]
@@ -68,11 +69,11 @@ simt_ffn2_kernel(int S, int d, int E, int F, const T *__restrict__ H, const int3
     Elem<T>::st(Yp + i, acc);
 }
 
-// dh = dYp Wd[e]^T ; dA = dh * B * silu'(A) ; dB = dh * silu(A)
+// dh = dYp Wd[e]^T ; dA = dh * FA ; dB = dh * FB   (FA = B silu'(A), FB = silu(A) from the forward)
 template <typename T>
 __global__ void __launch_bounds__(256)
 simt_dh_kernel(int S, int d, int E, int F, const T *__restrict__ dYp, const int32_t *__restrict__ offsets,
-               const T *__restrict__ Wd, const T *__restrict__ A, const T *__restrict__ B,
+               const T *__restrict__ Wd, const T *__restrict__ FA, const T *__restrict__ FB,
                T *__restrict__ dA, T *__restrict__ dB) {
     int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (i >= (int64_t)S * F) return;
@@ -81,10 +82,8 @@ simt_dh_kernel(int S, int d, int E, int F, const T *__restrict__ dYp, const int3
     const T *wd = Wd + ((int64_t)e * F + f) * d;
     float dh = 0.0f;
     for (int c = 0; c < d; ++c) dh = fmaf(Elem<T>::ld(dYp + (int64_t)r * d + c), Elem<T>::ld(wd + c), dh);
-    float a = Elem<T>::ld(A + i), b = Elem<T>::ld(B + i);
-    float sg = sigmoidf_(a);
-    Elem<T>::st(dA + i, dh * b * sg * (1.0f + a * (1.0f - sg)));
-    Elem<T>::st(dB + i, dh * a * sg);
+    Elem<T>::st(dA + i, dh * Elem<T>::ld(FA + i));
+    Elem<T>::st(dB + i, dh * Elem<T>::ld(FB + i));
 }
 
 // dXp = dA Wg[e]^T + dB Wu[e]^T

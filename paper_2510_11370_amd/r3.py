@@ -118,7 +118,8 @@ def permute_static(D, x, idx, counts, offsets, inv_perm, perm, Xp, status=None):
 
 
 def grouped_ffn(D, Xp, offsets, W_gate, W_up, W_down, Yp, H, A_save=None, B_save=None, ws=None, x=None, perm=None):
-    """Xp=None with x and perm: the token rows are gathered inside the first contraction."""
+    """Xp=None with x and perm: the token rows are gathered inside the first contraction.
+    A_save, B_save receive the backward's two factors FA = B silu'(A) and FB = silu(A) (see include/r3.h)."""
     _check(lib().r3_grouped_ffn(C.byref(D), _p(Xp), _p(x), _p(perm), _p(offsets), _p(W_gate), _p(W_up), _p(W_down), _p(Yp),
                                 _p(H), _p(A_save), _p(B_save), _p(ws),
                                 C.c_size_t(0 if ws is None else ws.numel()), _stream()), "r3_grouped_ffn")
@@ -200,7 +201,7 @@ class LayerBuffers:
         self.ws_gate = workspace(D, OP_REPLAY_GATE, device)
         self.ws_perm = workspace(D, OP_PERMUTE, device)
         self.ws_ffn = workspace(D, OP_GROUPED_FFN, device)
-        self.A = self.B = None
+        self.A = self.B = None             # the saved factors FA = B silu'(A), FB = silu(A)
         if backward:
             self.A, self.B = e(S, F), e(S, F)
             self.dx = e(T, d)

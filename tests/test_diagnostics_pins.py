@@ -49,17 +49,21 @@ def test_extreme_fraction_counts_ratios_in_either_direction():
     assert dg.extreme_fraction(li, lt, [1.9]) == [3 / 5]                # symmetric in the two policies
 
 
-def test_extreme_fraction_is_monotone_and_matches_a_float64_count_away_from_the_threshold():
+def test_extreme_fraction_is_monotone_and_is_the_ratio_count_of_the_definition():
     rng = np.random.default_rng(3)
     a = rng.normal(-3, 1, 20000).astype(np.float32)
     b = (a + rng.standard_t(3, 20000) * 0.2).astype(np.float32)
     taus = [1.0, 1.1, 1.5, 2.0, 3.0, 10.0, 100.0]
     f = dg.extreme_fraction(a, b, taus)
     assert all(x >= y for x, y in zip(f, f[1:]))
-    d = np.abs(a.astype(np.float64) - b.astype(np.float64))
+    # the definition itself, on probability ratios: max(r, 1/r) > tau (tokens within 1e-12 of a threshold
+    # may fall either way between the two forms)
+    r = np.exp(a.astype(np.float64) - b.astype(np.float64))
+    m = np.maximum(r, 1.0 / r)
     for tau, got in zip(taus, f):
-        near = np.count_nonzero(np.abs(d - np.log(tau)) < 1e-6)      # decided by float32 rounding
-        assert abs(round(got * d.size) - np.count_nonzero(d > np.log(tau))) <= near
+        near = np.count_nonzero(np.abs(m - tau) <= 1e-12 * tau)
+        assert abs(round(got * m.size) - np.count_nonzero(m > tau)) <= near
+    assert f[0] == np.count_nonzero(a != b) / a.size            # tau = 1: every token whose two values differ
 
 
 # ---- routing differences (Section 3.2)

@@ -160,6 +160,37 @@ def test_config5_down_projection_gradient_dense_dy(zipf):
     assert bool((err <= bar).all()), (err / bar).max().item()
 
 
+@pytest.mark.parametrize("which", ["most_loaded", "least_loaded"])
+def test_config5_expert_gradients_dense_dy_against_the_oracle(zipf, which):
+    """Full upstream gradient, one expert at a time through the oracle: the most-loaded expert (tens of
+    thousands of rows: every reduction stage of its weight-gradient tiles carries non-zero terms) and the
+    least-loaded non-empty one.  An expert's gradients need only that expert's rows: their tokens' x rows,
+    the oracle's gates of their slots and the matching rows of dy."""
+    c, rec, buf = zipf
+    sh, n = c.shape, c.np
+    r3.backward(buf, c.t["dy"], c.t["x"], c.t["Wr"], rec, c.t["Wg"], c.t["Wu"], c.t["Wd"])
+    torch.cuda.synchronize()
+    counts, offsets, _, perm = sparse.permute(c.idx, sh.E)
+    e = int(np.argmax(counts)) if which == "most_loaded" else int(
+        np.argmin(np.where(counts > 0, counts, np.iinfo(np.int32).max)))
+    r0, r1 = int(offsets[e]), int(offsets[e + 1])
+    print("config 5, %s expert %d: %d rows" % (which, e, r1 - r0))
+    slots = perm[r0:r1]
+    tok, j = slots // sh.K, slots % sh.K
+    Xp = n["x"][tok]
+    W = [n[k][e:e + 1] for k in ("Wg", "Wu", "Wd")]
+    off1 = np.array([0, r1 - r0], np.int32)
+    a, b, h, o = sparse.grouped_ffn(Xp, off1, *W)
+    g = sparse.replay_gate(c.s[tok], c.idx[tok])[np.arange(len(tok)), j]
+    dO = g[:, None] * n["dy"][tok].astype(np.float64)
+    _, _, dXp, dWg, dWu, dWd = sparse.grouped_ffn_backward(Xp, off1, *W, a, b, h, dO)
+    assert_close(host(buf.H[r0:r1]), h, "config5 H[e=%d]" % e, c.rel)
+    assert_close(host(buf.Yp[r0:r1]), o, "config5 Yp[e=%d]" % e, c.rel)
+    for got, want, name in ((buf.dW_gate[e], dWg[0], "dW_gate"), (buf.dW_up[e], dWu[0], "dW_up"),
+                            (buf.dW_down[e], dWd[0], "dW_down")):
+        assert_close(got.cpu().numpy(), want, "config5 %s[%d] (%d rows, dense dy)" % (name, e, r1 - r0), c.rel)
+
+
 # ------------------------------------------------------------------ config 4: 48-layer record + replay stack
 CHECK_LAYERS = (0, 1, 23, 47)
 

@@ -1,4 +1,6 @@
 """Shared helpers of the parity tests: build a seeded case on both sides, compare."""
+import os
+
 import numpy as np
 import torch
 
@@ -10,39 +12,78 @@ from paper_2510_11370_amd import r3, synth
 REL = {"bf16": 1e-2, "f32": 2e-4}
 
 
-def assert_close(gpu, ref, name, rel, sigma=None):
+# Element bar: |gpu-ref| <= rel |ref| + ELEM_C rel s_ij, where s_ij = rms(row i) rms(column j) / rms(ref) is
+# the magnitude an element at (i, j) has when rows and columns each carry their own scale.  The second
+# term is the room for the rounding noise of the bf16 tensors a result passes through (H, Yp, dA/dB, ...
+# each carry up to 2^-9 of their value; summed over a contraction that is a few 1e-3 of the output's local
+# magnitude, normally distributed).  A tensor-wide rms is the wrong yardstick: SwiGLU rows (tokens) are
+# heavy-tailed, the columns of dW_r (experts) differ by their load, and the weight gradient of an expert
+# with a handful of rows is a sum of as few outer products, large where both factors are.  ELEM_C = 1 is
+# about 3.5 sigma of the measured noise (normwise error 2.9e-3 for the weight gradients): tensors of
+# 1e6..1e8 elements then fail on a few hundred elements by chance.  Measured over the full-size cases
+# (about 1e9 compared elements; R3_TOL_LOG records what each call needs): the weight gradients need up to
+# 2.0 on a single element in 6e8, every other tensor less.
+ELEM_C = 2.5
+
+
+def _log(line):
+    path = os.environ.get("R3_TOL_LOG")
+    if path:
+        with open(path, "a") as f:
+            f.write(line + "\n")
+
+
+def assert_close(gpu, ref, name, rel, sigma=None, elem_c=None):
     """The floating-point bar for tensors in the activation dtype and for weight gradients.
 
     1. whole tensor, norm-wise:  |gpu-ref|_2 <= rel |ref|_2                (the stated bar)
     2. every row (last dim), norm-wise: <= 2 rel |row|_2 + rel rms(ref) sqrt(n)
        (a single wrong token or feature row cannot hide in the tensor norm)
-    3. every element: |gpu-ref| <= rel |ref| + 5 rel rms(ref)
-       (outlier guard; bf16 rounding noise of a multi-stage chain has several-sigma tails
-       of a few percent of the rms, a misplaced element is off by about one rms)
+    3. every element: |gpu-ref| <= rel |ref| + ELEM_C rel rms(row) rms(column) / rms(ref)
+       (a misplaced element is off by about the magnitude its row and column have)
     `sigma` (same shape as ref, optional): modelled standard deviation of the error that the bf16
     storage of an upstream tensor induces in this one; 8 sigma is added to bars 2 and 3.  Used for the
     router gradients, where a token's dz = g (dg - sum g dg) is a difference of nearly equal numbers
     and an expert chosen by one or two tokens has no other terms to average that error away.
+    With R3_TOL_LOG=<file> every call appends how much of each bar it used.
     """
+    c = ELEM_C if elem_c is None else elem_c
     gpu = np.asarray(gpu, np.float64)
     ref = np.asarray(ref, np.float64)
     assert gpu.shape == ref.shape, (name, gpu.shape, ref.shape)
     assert np.isfinite(gpu).all(), name
-    nref = np.linalg.norm(ref)
-    err = np.linalg.norm(gpu - ref)
+    n = ref.shape[-1] if ref.ndim >= 1 else 1
+    diff = np.abs(gpu - ref).reshape(-1, n)
+    ref2 = ref.reshape(-1, n)
+    nref = np.linalg.norm(ref2)
+    err = np.linalg.norm(diff)
+    rms = max(nref / np.sqrt(max(ref.size, 1)), 1e-300)
+    rerr = np.linalg.norm(diff, axis=1)
+    rref = np.linalg.norm(ref2, axis=1)
+    sig = None if sigma is None else np.asarray(sigma, np.float64).reshape(-1, n)
+    rslack = 0.0 if sig is None else 8 * np.linalg.norm(sig, axis=1)
+    row_use = rerr / np.maximum(2 * rel * rref + rel * rms * np.sqrt(n) + rslack, 1e-300)
+    # element bar: what multiple of rel * s_ij each element needs beyond rel*|ref| (and the sigma term)
+    rrms = rref / np.sqrt(n)
+    crms = np.linalg.norm(ref2, axis=0) / np.sqrt(ref2.shape[0]) if ref2.shape[0] > 1 else np.full(n, rms)
+    scale = np.maximum(rrms[:, None] * crms[None, :] / rms, 1e-300)
+    over = diff - rel * np.abs(ref2)
+    need_plain = (over / (rel * scale)).max() if over.size else 0.0
+    n_sigma = 0
+    if sig is not None:
+        n_sigma = int((over > c * rel * scale).sum())          # elements that lean on the sigma term
+        over = over - 8 * sig
+    need = (over / (rel * scale)).max() if over.size else 0.0
+    _log("%-34s n=%-10d normwise %.2e (bar %.0e)  worst row %.2f of bar 2  element bar needs c=%.2f%s" % (
+        name, ref.size, err / max(nref, 1e-300), rel, row_use.max() if row_use.size else 0.0, need,
+        "" if sig is None else " (c=%.2f without the 8-sigma term; %d elements lean on it)" % (need_plain, n_sigma)))
     assert err <= rel * nref + 1e-30, "%s: normwise rel err %.3e > %.1e" % (name, err / max(nref, 1e-300), rel)
-    rms = nref / np.sqrt(max(ref.size, 1))
     if ref.ndim >= 2:
-        n = ref.shape[-1]
-        rerr = np.linalg.norm((gpu - ref).reshape(-1, n), axis=1)
-        rref = np.linalg.norm(ref.reshape(-1, n), axis=1)
-        slack = 0.0 if sigma is None else 8 * np.linalg.norm(np.asarray(sigma, np.float64).reshape(-1, n), axis=1)
-        badrow = rerr > 2 * rel * rref + rel * rms * np.sqrt(n) + slack
-        assert not badrow.any(), "%s: %d rows outside tolerance (worst row rel err %.3e)" % (
-            name, badrow.sum(), (rerr / np.maximum(rref, 1e-300)).max())
-    bad = np.abs(gpu - ref) > rel * np.abs(ref) + 5 * rel * rms + (0.0 if sigma is None else 8 * np.asarray(sigma))
-    assert not bad.any(), "%s: %d of %d elements outside tolerance (max abs err %.3e, rms %.3e)" % (
-        name, bad.sum(), bad.size, np.abs(gpu - ref).max(), rms)
+        assert not (row_use > 1).any(), "%s: %d rows outside tolerance (worst row rel err %.3e)" % (
+            name, (row_use > 1).sum(), (rerr / np.maximum(rref, 1e-300)).max())
+    bad = over > c * rel * scale
+    assert not bad.any(), "%s: %d of %d elements outside tolerance (max abs err %.3e, rms %.3e, needs c=%.2f)" % (
+        name, bad.sum(), bad.size, diff.max(), rms, need)
     return err / max(nref, 1e-300)
 
 
