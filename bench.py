@@ -2,11 +2,16 @@
 """Throughput of the replayed MoE layer (record + replay gate + permute + grouped SwiGLU FFN +
 combine + backward) on one MI355X, with the dominant kernel's roofline and the CPU oracle beside it.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload fwdbwd_16k]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload zipf_64k]
 
 One step = one pass of the whole hot path over one batch of seeded synthetic input that is
 already resident in HBM:  r3_record_topk (inference logits -> record), r3_replay_gate,
 r3_permute, r3_grouped_ffn, r3_combine, r3_moe_backward.  Prints ONE JSON line.
+
+The default line is the largest forward+backward configuration (zipf_64k: T=65536, load skewed by a
+Zipf router bias); the 16384-token forward+backward configuration is timed in the same run, K steps
+after W warm-up steps of its own, and reported under "also": {"fwdbwd_16k": ...} with its own kernel
+table and roofline.  --workload NAME times that configuration alone.
 """
 import argparse
 import json
@@ -26,15 +31,17 @@ def kernel_work(sh, idx_bytes=1):
     T, d, E, K, F = sh.T, sh.d, sh.E, sh.K, sh.F
     S = T * K
     eb = 2  # bf16
+    nparts = 2 * (F // 256)   # partial dot products per row left by the down projection's gradient GEMM
     return {
         "record_topk": ("hbm", T * (E * 4 + K * idx_bytes)),
         "agreement": ("hbm", T * (E * 4 + K * idx_bytes)),
         "router_logits": ("hbm", T * (d * eb + E * 4) + d * E * eb),
-        "replay_gate": ("hbm", T * (K * idx_bytes + K * 4 + K * 4)),
+        # logits + gate in one launch (E = 128): x in, gates out, the logits stay on chip
+        "replay_gate": ("hbm", T * (d * eb + K * idx_bytes + K * 4) + d * E * eb),
         "permute_index": ("hbm", T * K * (2 * idx_bytes + 8)),
         "gather_rows": ("hbm", T * (d * eb + K * d * eb + K * 4)),
         "combine": ("hbm", T * (K * d * eb + d * eb + K * 8)),
-        "gate_backward": ("hbm", T * (d * eb + 2 * K * d * eb + K * 12 + E * eb)),
+        "gate_backward": ("hbm", T * (K * (nparts * 4 + 4 + 4 + idx_bytes) + K * 4 + 2 * E * eb)),
         "dx_finish": ("hbm", T * (K * d * eb + d * eb + K * 12) + E * d * eb),
         "router_wgrad": ("mfma", 2.0 * T * d * E),
         "ffn1_swiglu": ("mfma", 4.0 * S * d * F),
@@ -54,15 +61,26 @@ def gemm_bytes(sh, backward):
     return {
         "ffn1_swiglu": S * d * 2 + 2 * W + (3 if backward else 1) * S * F * 2,
         "ffn2_down": S * F * 2 + W + S * d * 2,
-        "ffn_dh": S * d * 2 + W + 4 * S * F * 2,
+        "ffn_dh": S * d * 2 + W + 6 * S * F * 2,               # FA, FB, H in; dA, dB, g*H out
         "ffn_wgrad_down": (S * d + S * F) * 2 + 2 * W,          # f32 gradient out
         "ffn_wgrad_gate_up": (S * d + 2 * S * F) * 2 + 4 * W,
         "ffn_dxp": 2 * S * F * 2 + 2 * W + S * d * 2,
     }
 
 
-def cpu_baseline(sh, tokens):
-    """The oracle, as it stands, on a bounded sample of the same workload (forward + backward)."""
+def cpu_model():
+    try:
+        for line in open("/proc/cpuinfo"):
+            if line.startswith("model name"):
+                return line.split(":", 1)[1].strip()
+    except OSError:
+        pass
+    return "unknown"
+
+
+def cpu_baseline(sh, tokens, tokens_1thread):
+    """The oracle, as it stands, on bounded samples of the same workload (forward + backward): `tokens`
+    tokens on all host cores, then `tokens_1thread` of them on one thread."""
     import numpy as np
     from oracle import sparse
     from paper_2510_11370_amd import synth
@@ -70,13 +88,26 @@ def cpu_baseline(sh, tokens):
     L = {k: (None if v is None else v.numpy()) for k, v in synth.make_layer(sub).items()}
     s = sparse.router_logits(L["x"], L["Wr"], L["bias"])
     idx = sparse.topk_mask((s + L["noise"]).astype(np.float32), sh.K)
-    t0 = time.perf_counter()
-    fwd = sparse.forward(L["x"], L["Wr"], idx, L["Wg"], L["Wu"], L["Wd"], L["bias"])
-    sparse.backward(L["dy"], L["x"], L["Wr"], idx, L["Wg"], L["Wu"], L["Wd"], fwd)
-    dt = time.perf_counter() - t0
-    return {"value": tokens / dt, "unit": "tokens/s", "cores": sparse.num_threads(), "kind": "oracle",
-            "sample": "%d tokens of the same layer (all %d experts' weights), forward+backward, f64, %.1f s"
-                      % (tokens, sh.E, dt)}
+
+    def timed(n):
+        t0 = time.perf_counter()
+        fwd = sparse.forward(L["x"][:n], L["Wr"], idx[:n], L["Wg"], L["Wu"], L["Wd"], L["bias"])
+        sparse.backward(L["dy"][:n], L["x"][:n], L["Wr"], idx[:n], L["Wg"], L["Wu"], L["Wd"], fwd)
+        return time.perf_counter() - t0
+    cores = sparse.num_threads()
+    dt = timed(tokens)
+    out = {"value": tokens / dt, "unit": "tokens/s", "cores": cores, "kind": "oracle",
+           "sample": "%d tokens of the same layer (all %d experts' weights), forward+backward, f64, %.1f s"
+                     % (tokens, sh.E, dt),
+           "cpu_model": cpu_model()}
+    if tokens_1thread > 0:
+        sparse.set_num_threads(1)
+        n1 = min(tokens_1thread, tokens)
+        dt1 = timed(n1)
+        sparse.set_num_threads(cores)
+        out["value_1thread"] = n1 / dt1
+        out["sample_1thread"] = "%d of those tokens on one thread, %.1f s" % (n1, dt1)
+    return out
 
 
 def measured_ceilings(torch, r3, dev):
@@ -241,42 +272,12 @@ def stored_traffic(workload, kernel):
     return None
 
 
-def main():
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", default="fwdbwd_16k")
-    ap.add_argument("--cpu-tokens", type=int, default=4096, help="tokens of the oracle's timed sample (0 = skip)")
-    ap.add_argument("--forward-only", action="store_true")
-    ap.add_argument("--gathered-copy", action="store_true",
-                    help="materialise the expert-sorted copy of the tokens (Xp) instead of reading x through the "
-                         "permutation inside the expert GEMMs")
-    ap.add_argument("--graph", action="store_true",
-                    help="time replays of the step captured in a HIP graph (single-layer workloads) instead of "
-                         "eager launches")
-    ap.add_argument("--no-ceilings", action="store_true", help="skip the calibration kernels after the timed region")
-    ap.add_argument("--calib-copy", action="store_true",
-                    help="after the timed region, run one plain 256 MiB copy kernel (reference point for "
-                         "hardware traffic counters collected around this command)")
-    args = ap.parse_args()
-    if args.gpus != 1:
-        sys.exit("bench.py: this build runs on one GPU only (no sharding, no collectives); use --gpus 1")
-
-    import torch
-    from paper_2510_11370_amd import r3, synth
-    if not torch.cuda.is_available():
-        sys.exit("bench.py: no GPU visible")
-    if args.workload == "diagnostics":
-        torch.cuda.set_device(0)
-        return bench_diagnostics(args, torch, r3, "cuda")
-    if args.workload == "mask_cache":
-        torch.cuda.set_device(0)
-        return bench_mask_cache(args, torch, r3, synth, "cuda")
-    sh = synth.CONFIGS[args.workload]
+def run_layer(args, workload, torch, r3, synth, calib_copy=False):
+    """Time `workload` (a key of synth.CONFIGS): W warm-up steps, then exactly K timed steps; returns the
+    result block (metric line fields, per-kernel table, roofline of the dominant expert GEMM)."""
+    sh = synth.CONFIGS[workload]
     dev = "cuda"
-    torch.cuda.set_device(0)
-    bwd = not args.forward_only and args.workload in ("fwdbwd_16k", "zipf_64k")
+    bwd = not args.forward_only and workload in ("fwdbwd_16k", "zipf_64k")
     L = sh.layers
     D = r3.desc(sh.T, sh.d, sh.E, sh.K, sh.F, sh.act)
     adt = r3.act_dtype(D)
@@ -307,6 +308,7 @@ def main():
             r3.record_topk(D, s_infer[l], record[l], buf.status)
             x = next_x(x, r3.forward(buf, x, Wr[l], record[l], t["Wg"], t["Wu"], t["Wd"], bias=bias))
     del logits
+    buf.status.zero_()      # (the first gate calls above ran on a record that was not made yet)
 
     def step():
         x = t["x"]
@@ -356,7 +358,7 @@ def main():
     prof = r3.profile_read()
     r3.profile_enable(False)
     assert int(buf.status.item()) == 0, "device status word set"
-    if args.calib_copy:
+    if calib_copy:
         src = torch.zeros(256 << 20, dtype=torch.uint8, device=dev)
         dst = torch.empty_like(src)
         r3.profile_copy(dst, src)
@@ -387,11 +389,16 @@ def main():
         kd = kernels[dom]
         roofline = {"kernel": dom, "bound": "mfma", "achieved": kd["achieved"], "peak": PEAK_BF16_TFLOPS,
                     "unit": "TFLOP/s", "frac": kd["frac"], "traffic": None}
-        tr = stored_traffic(args.workload, dom)
+        tr = stored_traffic(workload, dom)
         if tr:   # HBM bytes per launch (fetch + write) from the committed counter summary
             roofline.update(traffic=tr["bytes"], traffic_fetch_bytes=tr["fetch_bytes"],
                             traffic_write_bytes=tr["write_bytes"], traffic_source=tr["source"],
                             algorithmic_hbm_bytes=gbytes.get(dom))
+        # every expert GEMM of the step together: algorithmic FLOP over the sum of their times
+        tot_ms = sum(v["avg_ms"] * v["launches_per_step"] for v in mfma.values())
+        tot_fl = sum(work[k][1] * v["launches_per_step"] for k, v in mfma.items())
+        roofline["all_expert_gemms_TFLOPs"] = round(tot_fl / tot_ms * 1e-9, 1)
+        roofline["all_expert_gemms_frac"] = round(tot_fl / tot_ms * 1e-9 / PEAK_BF16_TFLOPS, 4)
     out = {
         "metric": "tokens/sec for R3 replayed MoE layer fwd+bwd at 1 GPU",
         "value": round(sh.T * L / (ms_per_step * 1e-3), 1), "unit": "tokens/s", "n_gpus": 1,
@@ -399,8 +406,9 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": sh.act,
         "data": "synthetic (seeded; shape of a 128-expert top-8 MoE layer)",
         "config": {"workload": "%s: T=%d d=%d E=%d K=%d F=%d %s%s, record+forward%s" % (
-            args.workload, sh.T, sh.d, sh.E, sh.K, sh.F, sh.act, " x %d layers" % L if L > 1 else "",
-            "+backward" if bwd else "") + (", launched as a HIP graph" if args.graph else ""),
+            workload, sh.T, sh.d, sh.E, sh.K, sh.F, sh.act, " x %d layers" % L if L > 1 else "",
+            "+backward" if bwd else "") + (", Zipf(%.1f) router bias" % sh.zipf_s if sh.zipf_s else "")
+            + (", launched as a HIP graph" if args.graph else ""),
             "rows_per_expert_min_mean_max": [int(counts.min()), float(counts.float().mean()), int(counts.max())]},
         "roofline": roofline, "kernels": kernels,
     }
@@ -412,17 +420,70 @@ def main():
                                                                   round(float(rate.mean()), 4),
                                                                   round(float(rate.max()), 4)]
         out["metric"] = "token-layers/sec for R3 record+replay forward over a %d-layer stack at 1 GPU" % L
+    del buf, t, Wr, dy, record, s_infer
+    torch.cuda.empty_cache()
+    return out
+
+
+DEFAULT_WORKLOAD = "zipf_64k"      # the largest forward+backward configuration
+ALSO_WORKLOAD = "fwdbwd_16k"       # timed in the same run when no --workload is given
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default=None,
+                    help="one of the configurations (fwd_4k, fwdbwd_16k, stack48_128k, zipf_64k), diagnostics or "
+                         "mask_cache; default: zipf_64k, with fwdbwd_16k timed alongside")
+    ap.add_argument("--cpu-tokens", type=int, default=4096, help="tokens of the oracle's timed sample (0 = skip)")
+    ap.add_argument("--cpu-tokens-1thread", type=int, default=256,
+                    help="tokens of that sample timed again on one thread (0 = skip)")
+    ap.add_argument("--forward-only", action="store_true")
+    ap.add_argument("--gathered-copy", action="store_true",
+                    help="materialise the expert-sorted copy of the tokens (Xp) instead of reading x through the "
+                         "permutation inside the expert GEMMs")
+    ap.add_argument("--graph", action="store_true",
+                    help="time replays of the step captured in a HIP graph (single-layer workloads) instead of "
+                         "eager launches")
+    ap.add_argument("--no-ceilings", action="store_true", help="skip the calibration kernels after the timed region")
+    ap.add_argument("--calib-copy", action="store_true",
+                    help="after the timed region, run one plain 256 MiB copy kernel (reference point for "
+                         "hardware traffic counters collected around this command)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on one GPU only (no sharding, no collectives); use --gpus 1")
+
+    import torch
+    from paper_2510_11370_amd import r3, synth
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: no GPU visible")
+    torch.cuda.set_device(0)
+    if args.workload == "diagnostics":
+        return bench_diagnostics(args, torch, r3, "cuda")
+    if args.workload == "mask_cache":
+        return bench_mask_cache(args, torch, r3, synth, "cuda")
+    workload = args.workload or DEFAULT_WORKLOAD
+    out = run_layer(args, workload, torch, r3, synth, calib_copy=args.calib_copy)
+    if args.workload is None:
+        also = run_layer(args, ALSO_WORKLOAD, torch, r3, synth)
+        out["config"]["workload"] += ("  [the line's value; the block under also.%s is the 16384-token "
+                                      "forward+backward configuration, same run, same steps and warm-up]" % ALSO_WORKLOAD)
+        out["also"] = {ALSO_WORKLOAD: {k: also[k] for k in ("value", "unit", "ms_per_step", "config", "roofline",
+                                                             "kernels")}}
+    roofline = out["roofline"]
     if not args.no_ceilings:
-        out["ceilings"] = measured_ceilings(torch, r3, dev)
-        if roofline:   # context only: the same achieved rate against what this machine sustains on such data
-            roofline["frac_of_measured_ceiling"] = round(
-                roofline["achieved"] / out["ceilings"]["mfma_bf16_varied_operands_TFLOPs"], 4)
-            roofline["frac_of_instruction_mix_ceiling"] = round(
-                roofline["achieved"] / out["ceilings"]["gemm_instruction_mix_TFLOPs"], 4)
+        out["ceilings"] = measured_ceilings(torch, r3, "cuda")
+        for rf in [roofline] + [b["roofline"] for b in out.get("also", {}).values()]:
+            if rf:   # context only: the same achieved rate against what this machine sustains on such data
+                rf["frac_of_measured_ceiling"] = round(
+                    rf["achieved"] / out["ceilings"]["mfma_bf16_varied_operands_TFLOPs"], 4)
+                rf["frac_of_instruction_mix_ceiling"] = round(
+                    rf["achieved"] / out["ceilings"]["gemm_instruction_mix_TFLOPs"], 4)
     if args.cpu_tokens > 0:
-        del buf
         torch.cuda.empty_cache()
-        out["cpu_baseline"] = cpu_baseline(sh, args.cpu_tokens)
+        out["cpu_baseline"] = cpu_baseline(synth.CONFIGS[workload], args.cpu_tokens, args.cpu_tokens_1thread)
     print(json.dumps(out))
 
 

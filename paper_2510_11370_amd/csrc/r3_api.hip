@@ -125,15 +125,19 @@ int r3_record_topk(const r3_layer_desc *desc, const float *logits, int64_t ld, v
 int r3_replay_gate(const r3_layer_desc *desc, const void *x, const void *W_r, const float *bias,
                    const void *idx, float *gates, float *logits_out, int64_t *agree_out,
                    int32_t *status_word, void *ws, size_t ws_bytes, void *stream) {
-    (void)status_word;
     Dims m;
     int rc = check_desc(desc, m);
     if (rc) return rc;
     if (!x || !W_r || !idx || !gates) return R3_ERR_INVALID_ARG;
     if (!aligned(x, 16) || !aligned(W_r, 16) || !aligned(gates, 4) || (logits_out && !aligned(logits_out, 16)) ||
-        (bias && !aligned(bias, 16)) || (agree_out && !aligned(agree_out, 8)))
+        (bias && !aligned(bias, 16)) || (agree_out && !aligned(agree_out, 8)) ||
+        (status_word && !aligned(status_word, 4)) || (m.idx == R3_IDX_U16 && !aligned(idx, 2)))
         return R3_ERR_INVALID_ARG;
     hipStream_t s = (hipStream_t)stream;
+    // one launch: the logits stay in the work-group that made them (no workspace needed)
+    if (use_mfma_router(m) && mfma_gate_fused_supported(m.d, m.E, m.K, agree_out != nullptr))
+        return hip_rc(mfma_gate_fused(m.T, m.d, m.E, m.K, x, W_r, bias, idx, m.idx, m.stride, gates, logits_out,
+                                      agree_out, status_word, s));
     float *logits = logits_out;
     if (!logits) {
         if (!ws || ws_bytes < r3_workspace_bytes(desc, R3_OP_REPLAY_GATE) || !aligned(ws, 256))
@@ -144,7 +148,7 @@ int r3_replay_gate(const r3_layer_desc *desc, const void *x, const void *W_r, co
     if (use_mfma_router(m)) e = mfma_router_logits(m.T, m.d, m.E, x, W_r, bias, logits, s);
     else e = simt_router_logits(m.T, m.d, m.E, m.act, x, W_r, bias, logits, s);
     if (e != hipSuccess) return R3_ERR_HIP;
-    e = launch_gate(m.T, m.E, m.K, logits, idx, m.idx, m.stride, gates, s);
+    e = launch_gate(m.T, m.E, m.K, logits, idx, m.idx, m.stride, gates, status_word, s);
     if (e != hipSuccess) return R3_ERR_HIP;
     if (agree_out) e = launch_agreement(m.T, m.E, m.K, logits, idx, m.idx, m.stride, agree_out, s);
     return hip_rc(e);

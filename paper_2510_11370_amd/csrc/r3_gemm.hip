@@ -11,6 +11,7 @@
 #include "r3_kernels.h"
 #include "r3_mfma.h"
 #include "r3_mfma2.h"
+#include "r3_topk.h"
 
 namespace r3 {
 
@@ -644,6 +645,133 @@ logits_kernel(int T, int d, int E, const bf16_t *__restrict__ x, const bf16_t *_
 }
 
 // ---------------------------------------------------------------------------
+// Router logits and replay gate in one kernel (Section 4.1: first equation and the replay-gate
+// equation), for E = 128 experts: a work-group owns BQ tokens and all experts, so a token's whole
+// logits row is in the work-group's accumulators.  The tile (plus bias) goes to LDS as [BQ][E] f32
+// and never to memory unless the caller asks for it (logits_out).  Then 8 lanes take a token:
+//   gates: g_j = exp(s[id_j] - m) / sum_i exp(s[id_i] - m) over the recorded ids (m their maximum);
+//   agreement (optional, K <= 8): the token's own top-K mask from the row (the record kernel's
+//   selection) against the mask of the recorded ids: shared experts and "same set".
+// A recorded id >= E is clamped and raises R3_DATA_IDX_RANGE; a non-finite logit among the recorded
+// ones raises R3_DATA_NONFINITE.  The block adds its agreement counts once (integer atomics).
+// ---------------------------------------------------------------------------
+template <class TL, typename IdxT>
+__global__ void __launch_bounds__(TL::NT, 2)   // two work-groups per compute unit: twice the bytes in flight
+gate_fused_kernel(int T, int d, int K, const bf16_t *__restrict__ x, const bf16_t *__restrict__ Wr,
+                  const float *__restrict__ bias, const IdxT *__restrict__ idx, int64_t stride,
+                  float *__restrict__ gates, float *__restrict__ logits_out, unsigned long long *agree,
+                  int32_t *status) {
+    constexpr int E = TL::BP, PITCH = E + 4;   // floats per LDS row (the pad spreads rows over the banks)
+    static_assert(E == 128, "one work-group holds all experts");
+    extern __shared__ __attribute__((aligned(16))) char lds[];
+    __shared__ unsigned long long part[TL::NWAVES][2];
+    const int t0 = blockIdx.x * TL::BQ;
+    auto fp = [&](int kt, int k, int c) -> uint4 { return ld16(Wr + (int64_t)(kt * TL::BK + k) * E + c * 8); };
+    auto fq = [&](int kt, int r, int c) -> uint4 {
+        return ld16(x + (int64_t)min(t0 + r, T - 1) * d + kt * TL::BK + c * 8);
+    };
+    f32x16_t acc[TL::TP][TL::TQ];
+    zero_acc<TL>(acc);
+    mfma_mainloop_ahead2<TL, true, false>(acc, d / TL::BK, fp, fq, lds);   // ends with a barrier: the stages are free
+    float *sl = (float *)lds;
+    for_each_quad<TL>([&](int tp, int tq, int g, int p, int q) {
+        float4 v = make_float4(acc[tp][tq][4 * g], acc[tp][tq][4 * g + 1], acc[tp][tq][4 * g + 2],
+                               acc[tp][tq][4 * g + 3]);
+        if (bias) {
+            const float4 b = *(const float4 *)(bias + p);
+            v.x += b.x; v.y += b.y; v.z += b.z; v.w += b.w;
+        }
+        *(float4 *)(sl + q * PITCH + p) = v;
+    });
+    __syncthreads();
+    if (logits_out)   // whole rows, 16 bytes per lane
+        for (int i = threadIdx.x; i < TL::BQ * (E / 4); i += TL::NT) {
+            const int q = i / (E / 4), c = i % (E / 4);
+            if (t0 + q < T) *(float4 *)(logits_out + (int64_t)(t0 + q) * E + 4 * c) = *(const float4 *)(sl + q * PITCH + 4 * c);
+        }
+    const int sub = threadIdx.x & 7;
+    int bad = 0;
+    unsigned long long equal = 0, common = 0;
+    for (int q = threadIdx.x >> 3; q < TL::BQ; q += TL::NT / 8) {
+        const int t = t0 + q;
+        const bool live = t < T;
+        const float *row = sl + q * PITCH;
+        const IdxT *id = idx + (int64_t)(live ? t : 0) * stride;
+        // gate: slots sub, sub + 8, ... of the token
+        float m = -INFINITY;
+        for (int j = sub; j < K; j += 8) {
+            int e = (int)id[j];
+            if (e >= E) { bad |= R3_DATA_IDX_RANGE; e = E - 1; }
+            const float z = row[e];
+            if (!(fabsf(z) <= 3.4028235e38f)) bad |= R3_DATA_NONFINITE;
+            m = fmaxf(m, z);
+        }
+        m = fmaxf(m, __shfl_xor(m, 1, 8));
+        m = fmaxf(m, __shfl_xor(m, 2, 8));
+        m = fmaxf(m, __shfl_xor(m, 4, 8));
+        float den = 0.0f;
+        for (int j = sub; j < K; j += 8) den += expf(row[min((int)id[j], E - 1)] - m);
+        den += __shfl_xor(den, 1, 8);
+        den += __shfl_xor(den, 2, 8);
+        den += __shfl_xor(den, 4, 8);
+        const float inv = 1.0f / den;
+        if (live)
+            for (int j = sub; j < K; j += 8) gates[(int64_t)t * K + j] = expf(row[min((int)id[j], E - 1)] - m) * inv;
+        if (agree) {   // K <= 8 (checked by the host)
+            constexpr int NV = E / 32;
+            uint32_t key[NV][4];
+#pragma unroll
+            for (int i = 0; i < NV; ++i) {
+                const float4 v = *(const float4 *)(row + 32 * i + 4 * sub);
+                bool nf;
+                key[i][0] = order_key(v.x, nf);
+                key[i][1] = order_key(v.y, nf);
+                key[i][2] = order_key(v.z, nf);
+                key[i][3] = order_key(v.w, nf);
+            }
+            uint32_t own[NV], rec[NV];
+            topk_mask8<NV>(key, K, sub, own);
+            const int e = sub < K ? min((int)id[sub], E - 1) : -1;
+#pragma unroll
+            for (int i = 0; i < NV; ++i) {
+                uint32_t w = (e >> 5) == i ? 1u << (e & 31) : 0u;   // e = -1 matches no word
+                w |= group8_exchange<0>(w);
+                w |= group8_exchange<1>(w);
+                w |= group8_exchange<2>(w);
+                rec[i] = w;
+            }
+            int shared = 0;
+#pragma unroll
+            for (int i = 0; i < NV; ++i) shared += __popc(own[i] & rec[i]);
+            if (live && sub == 0) {
+                common += (unsigned long long)shared;
+                equal += shared == K;
+            }
+        }
+    }
+    if (bad && status) atomicOr(status, bad);
+    if (agree) {
+        equal = wave_sum(equal);
+        common = wave_sum(common);
+        const int w = threadIdx.x / kWave;
+        if (lane_id() == 0) {
+            part[w][0] = equal;
+            part[w][1] = common;
+        }
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            unsigned long long a0 = 0, a1 = 0;
+            for (int i = 0; i < TL::NWAVES; ++i) {
+                a0 += part[i][0];
+                a1 += part[i][1];
+            }
+            if (a1) atomicAdd(agree + 1, a1);
+            if (a0) atomicAdd(agree, a0);
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------
 // Router weight gradient, split over tokens.  ds arrives as [T, 2E] bf16 with
 // dz split into hi (columns 0..E) and lo (columns E..2E) halves:
 //   part[s][c][e'] = sum_{t in split s} x[t][c] * ds[t][e'],   e' in [0, 2E)
@@ -827,6 +955,39 @@ hipError_t mfma_router_logits(int T, int d, int E, const void *x, const void *Wr
     ProfScope ps(PROF_LOGITS, s);
     logits_kernel<TL><<<tiles, TL::NT, TL::LDS_BYTES, s>>>(T, d, E, (const bf16_t *)x, (const bf16_t *)Wr, bias,
                                                          logits);
+    return hipGetLastError();
+}
+
+bool mfma_gate_fused_supported(int d, int E, int K, bool want_agreement) {
+    return E == 128 && d % 64 == 0 && (!want_agreement || K <= 8);
+}
+
+template <class TL, typename IdxT>
+static void launch_gate_fused(int T, int d, int K, const void *x, const void *Wr, const float *bias, const void *idx,
+                              int64_t stride, float *gates, float *logits_out, int64_t *agree, int32_t *status,
+                              hipStream_t s) {
+    constexpr int LDS = TL::LDS_BYTES > TL::BQ * (TL::BP + 4) * 4 ? TL::LDS_BYTES : TL::BQ * (TL::BP + 4) * 4;
+    allow_lds(gate_fused_kernel<TL, IdxT>, LDS);
+    gate_fused_kernel<TL, IdxT><<<(T + TL::BQ - 1) / TL::BQ, TL::NT, LDS, s>>>(
+        T, d, K, (const bf16_t *)x, (const bf16_t *)Wr, bias, (const IdxT *)idx, stride, gates, logits_out,
+        (unsigned long long *)agree, status);
+}
+
+hipError_t mfma_gate_fused(int T, int d, int E, int K, const void *x, const void *Wr, const float *bias,
+                           const void *idx, int idx_dtype, int64_t stride, float *gates, float *logits_out,
+                           int64_t *agree, int32_t *status, hipStream_t s) {
+    ProfScope ps(PROF_GATE, s);
+    // The kernel lives on bytes in flight (one token tile per work-group, k-tiles in sequence): 128-token
+    // tiles keep 64 KB of x on its way per compute unit; below 32768 tokens they would leave compute
+    // units without a tile, so there 64-token tiles
+    const bool big = T >= 32768;
+    if (idx_dtype == R3_IDX_U8) {
+        if (big) launch_gate_fused<TLDwr, uint8_t>(T, d, K, x, Wr, bias, idx, stride, gates, logits_out, agree, status, s);
+        else launch_gate_fused<TLLogits, uint8_t>(T, d, K, x, Wr, bias, idx, stride, gates, logits_out, agree, status, s);
+    } else {
+        if (big) launch_gate_fused<TLDwr, uint16_t>(T, d, K, x, Wr, bias, idx, stride, gates, logits_out, agree, status, s);
+        else launch_gate_fused<TLLogits, uint16_t>(T, d, K, x, Wr, bias, idx, stride, gates, logits_out, agree, status, s);
+    }
     return hipGetLastError();
 }
 

@@ -22,7 +22,7 @@ struct ProfScope {
 hipError_t launch_record_topk(int T, int E, int K, const float *logits, int64_t ld, void *idx,
                               int idx_dtype, int64_t stride, int32_t *status, hipStream_t s);
 hipError_t launch_gate(int T, int E, int K, const float *logits, const void *idx, int idx_dtype,
-                       int64_t stride, float *gates, hipStream_t s);
+                       int64_t stride, float *gates, int32_t *status, hipStream_t s);
 hipError_t launch_agreement(int T, int E, int K, const float *logits, const void *idx, int idx_dtype,
                             int64_t stride, int64_t *agree, hipStream_t s);
 size_t permute_ws_bytes(int T, int E, int K);
@@ -122,6 +122,11 @@ hipError_t mfma_row_tokens(int S, int K, const int32_t *perm, const float *gates
                            hipStream_t s);
 hipError_t mfma_router_logits(int T, int d, int E, const void *x, const void *Wr, const float *bias,
                               float *logits, hipStream_t s);
+// logits + replay gate (+ agreement counts) in one launch; E = 128 (see gate_fused_kernel)
+bool mfma_gate_fused_supported(int d, int E, int K, bool want_agreement);
+hipError_t mfma_gate_fused(int T, int d, int E, int K, const void *x, const void *Wr, const float *bias,
+                           const void *idx, int idx_dtype, int64_t stride, float *gates, float *logits_out,
+                           int64_t *agree, int32_t *status, hipStream_t s);
 hipError_t mfma_dwr(int T, int d, int E, const void *x, const void *ds, float *part, float *dWr, int accumulate,
                     hipStream_t s);
 

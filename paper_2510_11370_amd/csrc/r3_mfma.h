@@ -187,6 +187,95 @@ __device__ __forceinline__ void mfma_mainloop(f32x16_t (&acc)[TL::TP][TL::TQ], i
     }
 }
 
+// The same loop with the global loads running two k-tiles ahead (two register sets): for skinny
+// contractions that are bound by memory latency, not arithmetic (the router: one token tile per
+// work-group, 32 k-tiles in a row, each otherwise waiting a full round trip for its loads).
+// While tile kt is multiplied, tile kt+1 is on its way into registers (asked for an iteration ago)
+// and tile kt+2 is asked for; tile kt+1 goes to the other LDS stage after the multiplication.
+template <class TL, bool PTR, bool QTR, class FP, class FQ>
+__device__ __forceinline__ void mfma_mainloop_ahead2(f32x16_t (&acc)[TL::TP][TL::TQ], int nk, FP fp, FQ fq,
+                                                     char *lds) {
+    constexpr int BK = TL::BK, NT = TL::NT;
+    const int tid = threadIdx.x;
+    const int wave = tid >> 6;
+    const int wp = wave % TL::WP, wq = wave / TL::WP;
+    uint4 rp[2][TL::NP], rq[2][TL::NQ];
+    auto gload = [&](int kt, uint4 (&p)[TL::NP], uint4 (&q)[TL::NQ]) {
+#pragma unroll
+        for (int i = 0; i < TL::NP; ++i) {
+            const int id = tid + i * NT;
+            if constexpr (PTR) p[i] = fp(kt, id / (TL::BP / 8), id % (TL::BP / 8));
+            else p[i] = fp(kt, id / TL::CH, id % TL::CH);
+        }
+#pragma unroll
+        for (int i = 0; i < TL::NQ; ++i) {
+            const int id = tid + i * NT;
+            if constexpr (QTR) q[i] = fq(kt, id / (TL::BQ / 8), id % (TL::BQ / 8));
+            else q[i] = fq(kt, id / TL::CH, id % TL::CH);
+        }
+    };
+    auto lstore = [&](int stage, const uint4 (&p)[TL::NP], const uint4 (&q)[TL::NQ]) {
+        char *pb = lds + stage * TL::STAGE;
+        char *qb = pb + TL::P_BYTES;
+#pragma unroll
+        for (int i = 0; i < TL::NP; ++i) {
+            const int id = tid + i * NT;
+            int off;
+            if constexpr (PTR) off = tr_off<TL::BP>(id / (TL::BP / 8), id % (TL::BP / 8));
+            else off = kc_off<BK>(id / TL::CH, id % TL::CH);
+            *(uint4 *)(pb + off) = p[i];
+        }
+#pragma unroll
+        for (int i = 0; i < TL::NQ; ++i) {
+            const int id = tid + i * NT;
+            int off;
+            if constexpr (QTR) off = tr_off<TL::BQ>(id / (TL::BQ / 8), id % (TL::BQ / 8));
+            else off = kc_off<BK>(id / TL::CH, id % TL::CH);
+            *(uint4 *)(qb + off) = q[i];
+        }
+    };
+    typename FragSel<PTR, TL::BP, BK>::type pf;
+    typename FragSel<QTR, TL::BQ, BK>::type qf;
+    pf.init(wp * TL::WTP);
+    qf.init(wq * TL::WTQ);
+    auto multiply = [&](int stage) {
+        const char *pb = lds + stage * TL::STAGE;
+        const char *qb = pb + TL::P_BYTES;
+#pragma unroll
+        for (int s = 0; s < BK / 16; ++s) {
+            bf16x8_t a[TL::TP], b[TL::TQ];
+#pragma unroll
+            for (int i = 0; i < TL::TP; ++i) a[i] = pf.read(pb, i, s);
+#pragma unroll
+            for (int j = 0; j < TL::TQ; ++j) b[j] = qf.read(qb, j, s);
+#pragma unroll
+            for (int i = 0; i < TL::TP; ++i)
+#pragma unroll
+                for (int j = 0; j < TL::TQ; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
+        }
+    };
+    if (nk <= 0) return;
+    gload(0, rp[0], rq[0]);
+    if (nk > 1) gload(1, rp[1], rq[1]);
+    lstore(0, rp[0], rq[0]);
+    __syncthreads();
+    // tile kt sits in stage kt & 1 and came through register set kt & 1; unrolled by two so that both
+    // are compile-time constants
+    for (int kt = 0; kt < nk; kt += 2) {
+        if (kt + 2 < nk) gload(kt + 2, rp[0], rq[0]);
+        multiply(0);
+        if (kt + 1 < nk) lstore(1, rp[1], rq[1]);
+        __syncthreads();
+        if (kt + 1 < nk) {
+            if (kt + 3 < nk) gload(kt + 3, rp[1], rq[1]);
+            multiply(1);
+            if (kt + 2 < nk) lstore(0, rp[0], rq[0]);
+            __syncthreads();
+        }
+    }
+}
+
 template <class TL>
 __device__ __forceinline__ void zero_acc(f32x16_t (&acc)[TL::TP][TL::TQ]) {
 #pragma unroll

@@ -4,35 +4,19 @@
 // they move 16-byte vectors per lane, read every input once and use wave-level
 // reductions; none uses floating-point atomics (results are bit-reproducible).
 #include "r3_kernels.h"
+#include "r3_topk.h"
 
 namespace r3 {
 
 // ---------------------------------------------------------------------------
 // TopKMask
 // ---------------------------------------------------------------------------
-// Order-preserving map float -> uint32 (larger float = larger key), with
-// -0 == +0 and every NaN mapped to 0, below -inf.
-__device__ __forceinline__ uint32_t order_key(float v, bool &nonfinite) {
-    uint32_t u = __float_as_uint(v);
-    uint32_t mag = u & 0x7fffffffu;
-    nonfinite = mag >= 0x7f800000u;
-    if (mag > 0x7f800000u) return 0u;      // NaN
-    if (mag == 0u) u = 0u;                 // -0 -> +0
-    return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
-}
-
 // Fast record: 8 lanes per token (8 tokens per wave), K <= 8, E <= 512.
 // Lane `sub` of a token owns the contiguous id range [sub*EPL, (sub+1)*EPL) and keeps its 8
 // largest keys in a sorted register list; three butterfly rounds of bitonic merges leave every
 // lane with the token's 8 largest keys.  The K-th of them is the threshold: keys above it are
 // taken, keys equal to it are taken lowest id first until K are out (prefix counts over the
 // 8 lanes give each lane its quota and its output position, so ids come out ascending).
-__device__ __forceinline__ void cmpx_desc(uint32_t &a, uint32_t &b) {
-    const uint32_t hi = max(a, b), lo = min(a, b);
-    a = hi;
-    b = lo;
-}
-
 template <typename IdxT>
 __global__ void __launch_bounds__(256)
 record_topk_sub8_kernel(int T, int E, int K, int EPL, const float *__restrict__ logits, int64_t ld,
@@ -176,31 +160,6 @@ record_topk_wave_kernel(int T, int E, int K, const float *__restrict__ logits, i
 // merges express "above the threshold" and "equal to it" as E-bit masks, OR-ed over the 8 lanes.
 // The recorded set is the first mask plus the lowest-id bits of the second up to K; lane `sub`
 // writes its sub-th set bit, so the K ids land ascending in one 8-byte segment.
-// Value of lane `partner(lane)` inside each group of 8 lanes, through DPP (a VALU move, no LDS
-// round trip): STEP 0: lane^1, STEP 1: lane^2 (quad permutes), STEP 2: 7 - lane%8 (half-row
-// mirror).  After the three steps every lane of a group has met every other one.
-template <int STEP>
-__device__ __forceinline__ uint32_t group8_exchange(uint32_t v) {
-    constexpr int ctrl = STEP == 0 ? 0xB1 : STEP == 1 ? 0x4E : 0x141;
-    return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, ctrl, 0xf, 0xf, false);
-}
-
-__device__ __forceinline__ uint32_t umed3(uint32_t a, uint32_t b, uint32_t c) {
-    return max(min(a, b), min(max(a, b), c));
-}
-
-template <int STEP>
-__device__ __forceinline__ void merge_top8(uint32_t (&top)[8]) {
-    uint32_t other[8];
-#pragma unroll
-    for (int j = 0; j < 8; ++j) other[j] = group8_exchange<STEP>(top[j]);
-#pragma unroll
-    for (int j = 0; j < 8; ++j) top[j] = max(top[j], other[7 - j]);
-    cmpx_desc(top[0], top[4]); cmpx_desc(top[1], top[5]); cmpx_desc(top[2], top[6]); cmpx_desc(top[3], top[7]);
-    cmpx_desc(top[0], top[2]); cmpx_desc(top[1], top[3]); cmpx_desc(top[4], top[6]); cmpx_desc(top[5], top[7]);
-    cmpx_desc(top[0], top[1]); cmpx_desc(top[2], top[3]); cmpx_desc(top[4], top[5]); cmpx_desc(top[6], top[7]);
-}
-
 template <typename IdxT, int NV>
 __global__ void __launch_bounds__(256)
 record_topk_vec_kernel(int T, int K, const float *__restrict__ logits, int64_t ld, IdxT *__restrict__ idx,
@@ -220,70 +179,8 @@ record_topk_vec_kernel(int T, int K, const float *__restrict__ logits, int64_t l
         key[i][2] = order_key(v.z, nf); bad |= nf;
         key[i][3] = order_key(v.w, nf); bad |= nf;
     }
-    uint32_t top[8];
-#pragma unroll
-    for (int j = 0; j < 8; ++j) top[j] = 0u;
-    // insertion into the descending list: new top[j] = median(top[j-1], top[j], v), one v_med3_u32
-#pragma unroll
-    for (int i = 0; i < NV; ++i)
-#pragma unroll
-        for (int c = 0; c < 4; ++c) {
-            const uint32_t v = key[i][c];
-            uint32_t nt[8];
-            nt[0] = max(top[0], v);
-#pragma unroll
-            for (int j = 1; j < 8; ++j) nt[j] = umed3(top[j - 1], top[j], v);
-#pragma unroll
-            for (int j = 0; j < 8; ++j) top[j] = nt[j];
-        }
-    merge_top8<0>(top);
-    merge_top8<1>(top);
-    merge_top8<2>(top);
-    uint32_t thr = 0u;
-#pragma unroll
-    for (int j = 0; j < 8; ++j)
-        if (j == K - 1) thr = top[j];
-    uint32_t gt[NV], eq[NV];
-#pragma unroll
-    for (int i = 0; i < NV; ++i) {
-        uint32_t g = 0u, q = 0u;
-#pragma unroll
-        for (int c = 0; c < 4; ++c) {
-            g |= (uint32_t)(key[i][c] > thr) << c;
-            q |= (uint32_t)(key[i][c] == thr) << c;
-        }
-        gt[i] = g << (4 * sub);
-        eq[i] = q << (4 * sub);
-    }
-#pragma unroll
-    for (int i = 0; i < NV; ++i) {
-        gt[i] |= group8_exchange<0>(gt[i]);
-        eq[i] |= group8_exchange<0>(eq[i]);
-        gt[i] |= group8_exchange<1>(gt[i]);
-        eq[i] |= group8_exchange<1>(eq[i]);
-        gt[i] |= group8_exchange<2>(gt[i]);
-        eq[i] |= group8_exchange<2>(eq[i]);
-    }
-    int quota = K;
-#pragma unroll
-    for (int i = 0; i < NV; ++i) quota -= __popc(gt[i]);
-    // equal keys: lowest ids first, `quota` of them
-#pragma unroll
-    for (int i = 0; i < NV; ++i) {
-        uint32_t w = eq[i];
-        const int c = __popc(w);
-        if (c <= quota) {
-            gt[i] |= w;
-            quota -= c;
-        } else {
-            while (quota > 0) {
-                const uint32_t b = w & (0u - w);
-                gt[i] |= b;
-                w ^= b;
-                --quota;
-            }
-        }
-    }
+    uint32_t gt[NV];
+    topk_mask8<NV>(key, K, sub, gt);
     // lane `sub` emits the sub-th selected id
     int want = sub, id = -1;
 #pragma unroll
@@ -353,15 +250,22 @@ hipError_t launch_record_topk(int T, int E, int K, const float *logits, int64_t 
 template <typename IdxT>
 __global__ void __launch_bounds__(256)
 gate_kernel(int T, int E, int K, const float *__restrict__ logits, const IdxT *__restrict__ idx,
-            int64_t stride, float *__restrict__ gates) {
+            int64_t stride, float *__restrict__ gates, int32_t *status) {
     const int t = blockIdx.x * blockDim.x + threadIdx.x;
     if (t >= T) return;
     const IdxT *id = idx + (int64_t)t * stride;
     const float *row = logits + (int64_t)t * E;
     float m = -INFINITY;
+    int bad = 0;
     for (int j = 0; j < K; ++j) {
-        int e = min((int)id[j], E - 1);
-        m = fmaxf(m, row[e]);
+        int e = (int)id[j];
+        if (e >= E) {
+            bad |= R3_DATA_IDX_RANGE;
+            e = E - 1;
+        }
+        const float z = row[e];
+        if (!(fabsf(z) <= 3.4028235e38f)) bad |= R3_DATA_NONFINITE;
+        m = fmaxf(m, z);
     }
     float den = 0.0f;
     for (int j = 0; j < K; ++j) {
@@ -372,16 +276,17 @@ gate_kernel(int T, int E, int K, const float *__restrict__ logits, const IdxT *_
     }
     float inv = 1.0f / den;
     for (int j = 0; j < K; ++j) gates[(int64_t)t * K + j] *= inv;
+    if (bad && status) atomicOr(status, bad);
 }
 
 hipError_t launch_gate(int T, int E, int K, const float *logits, const void *idx, int idx_dtype,
-                       int64_t stride, float *gates, hipStream_t s) {
+                       int64_t stride, float *gates, int32_t *status, hipStream_t s) {
     ProfScope ps(PROF_GATE, s);
     int grid = (T + 255) / 256;
     if (idx_dtype == R3_IDX_U8)
-        gate_kernel<uint8_t><<<grid, 256, 0, s>>>(T, E, K, logits, (const uint8_t *)idx, stride, gates);
+        gate_kernel<uint8_t><<<grid, 256, 0, s>>>(T, E, K, logits, (const uint8_t *)idx, stride, gates, status);
     else
-        gate_kernel<uint16_t><<<grid, 256, 0, s>>>(T, E, K, logits, (const uint16_t *)idx, stride, gates);
+        gate_kernel<uint16_t><<<grid, 256, 0, s>>>(T, E, K, logits, (const uint16_t *)idx, stride, gates, status);
     return hipGetLastError();
 }
 

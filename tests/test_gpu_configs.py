@@ -9,7 +9,7 @@ import torch
 
 from oracle import sparse
 from paper_2510_11370_amd import r3, synth
-from util import Case, assert_close, assert_gates_close, host
+from util import Case, assert_close, assert_gates_close, host, router_gradient_sigma
 
 pytestmark = pytest.mark.gpu
 
@@ -113,8 +113,11 @@ def test_config5_forward_and_backward_on_samples(zipf):
     assert_close(host(buf.dx[sel]), bwd["dx"], "dx[sample]", c.rel)
     rest = np.setdiff1d(np.arange(sh.T), tok)[:: max(1, sh.T // 4096)]
     assert not buf.dx[torch.from_numpy(rest).cuda()].any()
-    assert_close(buf.dW_r.cpu().numpy(), bwd["dWr"], "dW_r", c.rel)
-    assert_close(dbias.cpu().numpy(), bwd["dbias"], "dbias", c.rel)
+    # (a rare expert's column of dW_r comes from one or two sampled tokens: the modelled rounding error of
+    # their dz, from oracle quantities, is part of the bar as in the small-shape chain tests)
+    sig_w, sig_b = router_gradient_sigma(n["x"][tok], n["dy"][tok], c.idx[tok], ref, sh.E)
+    assert_close(buf.dW_r.cpu().numpy(), bwd["dWr"], "dW_r", c.rel, sigma=sig_w)
+    assert_close(dbias.cpu().numpy(), bwd["dbias"], "dbias", c.rel, sigma=sig_b)
     touched = np.unique(c.idx[tok])
     rng = np.random.default_rng(6)
     check = {int(np.argmax(counts)), rare, *rng.choice(touched, 2, replace=False).tolist()}

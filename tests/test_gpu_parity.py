@@ -176,6 +176,33 @@ def test_replay_gate_and_logits(name):
     assert torch.equal(gates, gates2)
 
 
+@pytest.mark.parametrize("E,d", [(128, 256), (16, 48)])       # the one-launch kernel; the plain kernels
+def test_replay_gate_flags_bad_record_and_nonfinite_logits(E, d):
+    T, K = 200, 4
+    D = r3.desc(T, d, E, K, 256)
+    g = torch.Generator(device="cuda").manual_seed(5)
+    x = torch.randn(T, d, generator=g, device="cuda").to(torch.bfloat16)
+    Wr = (torch.randn(d, E, generator=g, device="cuda") * d ** -0.5).to(torch.bfloat16)
+    idx = _random_record(T, E, K, 9)
+    gates = torch.empty(T, K, dtype=torch.float32, device="cuda")
+    ws = r3.workspace(D, r3.OP_REPLAY_GATE)
+
+    def status_after(xx, rec):
+        status = torch.zeros(1, dtype=torch.int32, device="cuda")
+        r3.replay_gate(D, xx, Wr, idx_dev(rec, D), gates, status=status, ws=ws)
+        sync()
+        return int(status.item())
+
+    assert status_after(x, idx) == 0
+    assert torch.isfinite(gates).all() and torch.allclose(gates.sum(dim=1), torch.ones(T, device="cuda"), atol=1e-5)
+    bad = idx.copy()
+    bad[17, 1] = 250                                   # an expert id >= E
+    assert status_after(x, bad) == r3.DATA_IDX_RANGE
+    xn = x.clone()
+    xn[33, 7] = float("inf")                           # every logit of token 33 is inf or NaN
+    assert status_after(xn, idx) == r3.DATA_NONFINITE
+
+
 def test_recompute_routing_replay_is_plain_topk_gating():
     """The variant that records from the training engine's own logits (Related Works, "Routing Replay"):
     r3_record_topk on the layer's training logits, replayed into the same layer.  With an unchanged model
