@@ -467,6 +467,7 @@ def main():
     workload = args.workload or DEFAULT_WORKLOAD
     out = run_layer(args, workload, torch, r3, synth, calib_copy=args.calib_copy)
     if args.workload is None:
+        time.sleep(3.0)   # let the card's power and clock state settle after the first workload
         also = run_layer(args, ALSO_WORKLOAD, torch, r3, synth)
         out["config"]["workload"] += ("  [the line's value; the block under also.%s is the 16384-token "
                                       "forward+backward configuration, same run, same steps and warm-up]" % ALSO_WORKLOAD)

@@ -13,10 +13,13 @@
  * the slots are sorted by expert.
  *
  * Conventions for every call
- *  - All data pointers are DEVICE pointers owned by the caller.  The library
- *    allocates nothing, frees nothing and keeps no state between calls.
- *    Scratch comes from a caller workspace of at least
- *    r3_workspace_bytes(desc, op) bytes, 256-byte aligned.
+ *  - All data pointers are DEVICE pointers owned by the caller.  The calls
+ *    declared in this header allocate nothing, free nothing and keep no state
+ *    between calls (the one exception is spelled out at r3_permute_static: a
+ *    fixed scratch array and its cached address).  Scratch comes from a caller
+ *    workspace of at least r3_workspace_bytes(desc, op) bytes, 256-byte
+ *    aligned.  (The measurement aids of r3_profile.h are not part of the
+ *    method and do keep state: event pools and an on/off flag.)
  *  - `stream` is a hipStream_t (NULL = the default stream).  Calls enqueue work
  *    and return; there is no hidden synchronisation.
  *  - Matrices are row-major and dense.  Activations and weights have the dtype
@@ -272,52 +275,6 @@ int r3_mask_cache_gather(int idx_dtype, int L, int K, int P, const void *pages, 
                          const int32_t *block_table, int nseq, int max_blocks,
                          const int32_t *seq_start, int64_t T, void *out, int32_t *status_word,
                          void *stream);
-
-/*
- * Measurement aid (not part of the method): per-kernel timing with HIP events
- * recorded on the launch stream.  r3_profile_enable(1) clears the counters and
- * starts recording (at most 512 launches per kernel are kept), (0) stops.
- * r3_profile_read waits for the recorded events and returns the summed
- * duration in milliseconds and the number of launches of kernel `tag`
- * (0 <= tag < r3_profile_tags()); r3_profile_name names it.
- */
-int r3_profile_enable(int on);
-int r3_profile_tags(void);
-const char *r3_profile_name(int tag);
-int r3_profile_read(int tag, double *total_ms, int *launches);
-
-/*
- * Measurement aid: a plain device-to-device copy kernel (`calib_copy_kernel`)
- * of `bytes` bytes (a multiple of 16; dst and src 16-byte aligned device
- * pointers, not overlapping).  It reads `bytes` and writes `bytes` of HBM and
- * nothing else, so hardware traffic counters read for it give the factor that
- * converts those counters to bytes for the other kernels of the same run.
- */
-int r3_profile_copy(void *dst, const void *src, size_t bytes, void *stream);
-
-/*
- * Measurement aid: a pure bf16 MFMA issue loop (`calib_mfma_kernel`, one
- * work-group of 8 waves per compute unit, 8 independent 32x32x16 accumulator
- * tiles per wave, operands in registers, no memory traffic) of `iters`
- * iterations; random_operands != 0 fills the operand registers with varied bit
- * patterns, 0 with one constant.  It does 2*32*32*16 * 8 * iters * 8 * grid
- * FLOP (r3_profile_mfma_flops); timed by the caller it gives the matrix rate
- * this machine sustains under its power limit, which depends on the operand
- * data.  `sink` is a device float the kernel may write (never in practice).
- */
-int r3_profile_mfma(int iters, int random_operands, float *sink, void *stream);
-double r3_profile_mfma_flops(int iters);
-
-/*
- * Measurement aid: the same MFMA loop fed the way the expert GEMMs feed theirs
- * (`calib_mix_kernel`): per 8 MFMAs a wave reads 6 fragments from LDS, and per
- * 16 MFMAs of each wave the work-group brings 32 KB into LDS with direct
- * global->LDS loads from `src_1mib` (device, 1 MiB, 16-byte aligned, finite
- * bf16 values; stays cache-resident).  No barriers, epilogues or HBM misses:
- * the rate a perfect schedule of that instruction mix reaches under the power
- * limit.  Same FLOP count as r3_profile_mfma (r3_profile_mfma_flops).
- */
-int r3_profile_gemm_mix(int iters, const void *src_1mib, float *sink, void *stream);
 
 #ifdef __cplusplus
 }

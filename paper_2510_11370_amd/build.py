@@ -9,7 +9,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libr3.so")
 SOURCES = ["r3_api.hip", "r3_route.hip", "r3_simt.hip", "r3_gemm.hip", "r3_diag.hip", "r3_cache.hip", "r3_prof.hip"]
-HEADERS = ["r3_common.h", "r3_kernels.h", "r3_mfma.h", "r3_mfma2.h"]
+HEADERS = ["r3_common.h", "r3_kernels.h", "r3_mfma.h", "r3_mfma2.h", "r3_topk.h"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
@@ -28,7 +28,7 @@ def build(force: bool = False, verbose: bool = False) -> str:
     """Compile every kernel file and link the shared library."""
     objdir = os.path.join(HERE, "_build")
     os.makedirs(objdir, exist_ok=True)
-    hdrs = [os.path.join(CSRC, h) for h in HEADERS] + [os.path.join(ROOT, "include", "r3.h")]
+    hdrs = [os.path.join(CSRC, h) for h in HEADERS] + [os.path.join(ROOT, "include", h) for h in ("r3.h", "r3_profile.h")]
 
     def compile_one(src):
         obj = os.path.join(objdir, src.replace(".hip", ".o"))

@@ -1,8 +1,11 @@
-// Per-kernel timing with HIP events (measurement aid, see include/r3.h).
+// Per-kernel timing with HIP events and the calibration kernels (measurement aids, see
+// include/r3_profile.h).
+#include <atomic>
 #include <mutex>
 #include <vector>
 
 #include "r3_kernels.h"
+#include "r3_profile.h"
 
 namespace r3 {
 namespace {
@@ -12,7 +15,7 @@ struct TagState {
     int used = 0;
 };
 std::mutex g_mu;
-bool g_on = false;
+std::atomic<bool> g_on{false};   // read without the lock by every launch: off means "touch nothing"
 TagState g_tags[PROF_NTAGS];
 const char *kNames[PROF_NTAGS] = {"record_topk", "router_logits", "replay_gate", "permute_index",
                                   "gather_rows", "ffn1_swiglu", "ffn2_down", "combine", "gate_backward",
@@ -22,8 +25,9 @@ const char *kNames[PROF_NTAGS] = {"record_topk", "router_logits", "replay_gate",
 }  // namespace
 
 ProfScope::ProfScope(int tag_, hipStream_t s_) : tag(tag_), slot(-1), s(s_) {
+    if (!g_on.load(std::memory_order_relaxed)) return;
     std::lock_guard<std::mutex> lk(g_mu);
-    if (!g_on) return;
+    if (!g_on.load(std::memory_order_relaxed)) return;
     TagState &t = g_tags[tag];
     if (t.used >= kPool) return;
     if ((int)t.start.size() <= t.used) {
@@ -145,9 +149,9 @@ extern "C" {
 
 int r3_profile_enable(int on) {
     std::lock_guard<std::mutex> lk(g_mu);
-    g_on = on != 0;
-    if (g_on)
+    if (on)
         for (auto &t : g_tags) t.used = 0;
+    g_on.store(on != 0, std::memory_order_relaxed);
     return R3_OK;
 }
 
