@@ -5,8 +5,9 @@ combine + backward) on one MI355X, with the dominant kernel's roofline and the C
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload zipf_64k]
 
 One step = one pass of the whole hot path over one batch of seeded synthetic input that is
-already resident in HBM:  r3_record_topk (inference logits -> record), r3_replay_gate,
-r3_permute, r3_grouped_ffn, r3_combine, r3_moe_backward.  Prints ONE JSON line.
+already resident in HBM:  r3_record_topk (inference logits -> record), the replayed forward
+(r3_moe_forward: gate, dispatch, grouped SwiGLU FFN, combination; --six-calls runs the same steps as
+r3_replay_gate, r3_permute, r3_grouped_ffn, r3_combine), r3_moe_backward.  Prints ONE JSON line.
 
 The default line is the largest forward+backward configuration (zipf_64k: T=65536, load skewed by a
 Zipf router bias); the 16384-token forward+backward configuration is timed in the same run, K steps
@@ -310,12 +311,15 @@ def run_layer(args, workload, torch, r3, synth, calib_copy=False):
     del logits
     buf.status.zero_()      # (the first gate calls above ran on a record that was not made yet)
 
+    # the forward: one C call (r3_moe_forward, gate folded into the expert network) unless --six-calls
+    fwd_call = r3.forward if (args.six_calls or args.gathered_copy) else r3.forward_one_call
+
     def step():
         x = t["x"]
         for l in range(L):
             r3.record_topk(D, s_infer[l], record[l], buf.status)
-            y = r3.forward(buf, x, Wr[l], record[l], t["Wg"], t["Wu"], t["Wd"], bias=bias,
-                           agree_out=agree[l] if L > 1 else None)
+            y = fwd_call(buf, x, Wr[l], record[l], t["Wg"], t["Wu"], t["Wd"], bias=bias,
+                         agree_out=agree[l] if L > 1 else None)
             if bwd:
                 r3.backward(buf, dy, x, Wr[l], record[l], t["Wg"], t["Wu"], t["Wd"])
             if L > 1:
@@ -444,6 +448,9 @@ def main():
     ap.add_argument("--gathered-copy", action="store_true",
                     help="materialise the expert-sorted copy of the tokens (Xp) instead of reading x through the "
                          "permutation inside the expert GEMMs")
+    ap.add_argument("--six-calls", action="store_true",
+                    help="run the forward as r3_replay_gate, r3_permute, r3_grouped_ffn, r3_combine instead of the "
+                         "one-call r3_moe_forward (the backward then also scales H by the gates itself)")
     ap.add_argument("--graph", action="store_true",
                     help="time replays of the step captured in a HIP graph (single-layer workloads) instead of "
                          "eager launches")

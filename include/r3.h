@@ -61,14 +61,18 @@ typedef enum r3_op {
     R3_OP_REPLAY_GATE = 0,
     R3_OP_PERMUTE = 1,
     R3_OP_GROUPED_FFN = 2,
-    R3_OP_BACKWARD = 3
+    R3_OP_BACKWARD = 3,
+    R3_OP_FORWARD = 4       /* r3_moe_forward */
 } r3_op;
+
+enum { R3_FLAG_GATED_H = 1 };         /* desc->flags */
 
 typedef struct r3_layer_desc {
     int32_t T, d, E, K, F;
     int32_t act;              /* R3_BF16 or R3_F32                                  */
     int32_t idx;              /* R3_IDX_U8 (E <= 256) or R3_IDX_U16 (E <= 65536)     */
-    int32_t reserved;         /* must be 0                                          */
+    int32_t flags;            /* 0, or R3_FLAG_GATED_H for r3_moe_backward after
+                                 r3_moe_forward (see there)                          */
     int64_t idx_token_stride; /* elements between two tokens' records; 0 means K.
                                  K gives a layer-major record [L][T][K]; L*K a
                                  token-major one [T][L][K] (Section 4.2: the
@@ -173,6 +177,32 @@ int r3_combine(const r3_layer_desc *desc, const void *Yp, const float *gates,
                const int32_t *inv_perm, void *y, void *stream);
 
 /*
+ * The replayed forward in one call (Section 4.1: router logits, replay gate,
+ * and the replay-output equation y = sum_i g_i E_i(x) over the recorded
+ * experts).  Same results as r3_replay_gate, r3_permute (without the gathered
+ * copy), r3_grouped_ffn and r3_combine in a row, to the same tolerance, with
+ * the gate folded into the expert network: the first contraction's epilogue
+ * stores g_r * silu(A) * B for row r (g_r the gate of the row's slot), so the
+ * down projection yields the gated rows g_i E_i(x) and the combination is a
+ * plain sum of each token's K rows (j ascending, f32, one rounding).  The
+ * gradient of W_down then finds its row operand ready, and the backward
+ * neither forms g * dy per slot nor reads the expert outputs.
+ * Outputs: y [T,d]; gates [T,K]; counts, offsets, inv_perm, perm as
+ * r3_permute; H [T*K,F] = g * silu(A) * B (NOT r3_grouped_ffn's H); FA_save,
+ * FB_save [T*K,F] as r3_grouped_ffn (both NULL: forward only); Yp [T*K,d] =
+ * the gated rows.  logits_out, agree_out, status_word: as r3_replay_gate and
+ * r3_permute.  ws: r3_workspace_bytes(desc, R3_OP_FORWARD).  desc->flags is
+ * ignored.  To differentiate, pass these tensors to r3_moe_backward with
+ * desc->flags = R3_FLAG_GATED_H.  Needs T*d*sizeof(act) < 2^31.
+ */
+int r3_moe_forward(const r3_layer_desc *desc, const void *x, const void *W_r, const float *bias,
+                   const void *idx, const void *W_gate, const void *W_up, const void *W_down,
+                   void *y, float *gates, int32_t *counts, int32_t *offsets, int32_t *inv_perm,
+                   int32_t *perm, void *Yp, void *H, void *FA_save, void *FB_save,
+                   float *logits_out, int64_t *agree_out, int32_t *status_word, void *ws,
+                   size_t ws_bytes, void *stream);
+
+/*
  * Backward of the replayed layer (Section 4.1, purpose (b): the gradient still
  * reaches the router logits through the softmax; the recorded mask is a
  * constant).  Given dy [T,d] act and the forward's tensors (FA, FB, H as
@@ -189,6 +219,9 @@ int r3_combine(const r3_layer_desc *desc, const void *Yp, const float *gates,
  * <dy W_down^T, H>), so no per-slot copy of dy is made and Yp is not read: Yp
  * and Xp may be NULL.  Other shapes and f32 run plain kernels, which need Xp
  * and Yp and do not read perm.
+ * desc->flags = R3_FLAG_GATED_H: H and Yp are the gate-scaled tensors that
+ * r3_moe_forward wrote (H = g silu(A) B, Yp = g o); perm is then required on
+ * every path and Xp may be NULL on every path.
  */
 int r3_moe_backward(const r3_layer_desc *desc, const void *dy, const void *x,
                     const void *W_r, const void *idx, const float *gates,

@@ -12,21 +12,21 @@ using namespace r3;
 namespace {
 
 struct Dims {
-    int T, d, E, K, F, act, idx;
+    int T, d, E, K, F, act, idx, flags;
     int64_t stride, S;
     int eb;  // bytes per activation element
 };
 
 int check_desc(const r3_layer_desc *D, Dims &m) {
     if (!D) return R3_ERR_INVALID_ARG;
-    if (D->T <= 0 || D->d <= 0 || D->E <= 0 || D->K <= 0 || D->F <= 0 || D->K > D->E || D->reserved != 0)
+    if (D->T <= 0 || D->d <= 0 || D->E <= 0 || D->K <= 0 || D->F <= 0 || D->K > D->E || (D->flags & ~R3_FLAG_GATED_H) != 0)
         return R3_ERR_INVALID_ARG;
     if (D->act != R3_BF16 && D->act != R3_F32) return R3_ERR_INVALID_ARG;
     if (D->idx != R3_IDX_U8 && D->idx != R3_IDX_U16) return R3_ERR_INVALID_ARG;
     if (D->idx_token_stride != 0 && D->idx_token_stride < D->K) return R3_ERR_INVALID_ARG;
     if ((D->idx == R3_IDX_U8 && D->E > 256) || D->E > kMaxE || D->K > kMaxK) return R3_ERR_UNSUPPORTED;
     if ((int64_t)D->T * D->K > 0x7fffffffLL / 2) return R3_ERR_UNSUPPORTED;
-    m.T = D->T; m.d = D->d; m.E = D->E; m.K = D->K; m.F = D->F; m.act = D->act; m.idx = D->idx;
+    m.T = D->T; m.d = D->d; m.E = D->E; m.K = D->K; m.F = D->F; m.act = D->act; m.idx = D->idx; m.flags = D->flags;
     m.stride = D->idx_token_stride ? D->idx_token_stride : D->K;
     m.S = (int64_t)D->T * D->K;
     m.eb = D->act == R3_BF16 ? 2 : 4;
@@ -58,10 +58,26 @@ BwdWs bwd_layout(const Dims &m) {
     w.dB = take((size_t)m.S * m.F * m.eb);
     w.tiles = take(mf ? mfma_tiles_bytes(m.S, m.E) : 0);
     w.part = take(use_mfma_router(m) ? mfma_dwr_ws_bytes(m.T, m.d, m.E) : 0);
-    w.tok = take(mf ? mfma_row_tokens_bytes(m.S) : 0);           // row -> token list
+    w.tok = take(mfma_row_tokens_bytes(m.S));                    // row -> token list
     w.Hg = take(mf ? (size_t)m.S * m.F * m.eb : 0);              // gate-scaled H rows
     w.grow = take(mf ? (size_t)m.S * sizeof(float) : 0);         // row -> gate list
     w.wpart = take(mf ? (size_t)m.S * row_parts(m) * sizeof(float) : 0);
+    w.total = o;
+    return w;
+}
+
+struct FwdWs {
+    size_t gate, perm, ffn, tok, grow, total;
+};
+FwdWs fwd_layout(const Dims &m) {
+    FwdWs w;
+    size_t o = 0;
+    auto take = [&](size_t bytes) { size_t at = o; o += align_up(bytes, 256); return at; };
+    w.gate = take((size_t)m.T * m.E * sizeof(float));
+    w.perm = take(permute_ws_bytes(m.T, m.E, m.K));
+    w.ffn = take(use_mfma_ffn(m) ? mfma_tiles_bytes(m.S, m.E) : 0);
+    w.tok = take(mfma_row_tokens_bytes(m.S));
+    w.grow = take((size_t)m.S * sizeof(float));
     w.total = o;
     return w;
 }
@@ -107,6 +123,7 @@ size_t r3_workspace_bytes(const r3_layer_desc *desc, r3_op op) {
         case R3_OP_PERMUTE: return permute_ws_bytes(m.T, m.E, m.K);
         case R3_OP_GROUPED_FFN: return use_mfma_ffn(m) ? mfma_tiles_bytes(m.S, m.E) : 0;
         case R3_OP_BACKWARD: return bwd_layout(m).total;
+        case R3_OP_FORWARD: return fwd_layout(m).total;
     }
     return 0;
 }
@@ -204,9 +221,10 @@ int r3_grouped_ffn(const r3_layer_desc *desc, const void *Xp, const void *x, con
         int32_t *tiles = (int32_t *)ws;
         if (mfma_build_tiles(m.E, offsets, tiles, s) != hipSuccess) return R3_ERR_HIP;
         return hip_rc(mfma_ffn_forward(m.S, m.d, m.E, m.F, rows, via, m.K, m.T, offsets, tiles, W_gate, W_up, W_down,
-                                       Yp, H, FA_save, FB_save, s));
+                                       Yp, H, FA_save, FB_save, nullptr, s));
     }
-    if (simt_ffn1((int)m.S, m.d, m.E, m.F, m.act, rows, via, m.K, offsets, W_gate, W_up, H, FA_save, FB_save, s) !=
+    if (simt_ffn1((int)m.S, m.d, m.E, m.F, m.act, rows, via, m.K, offsets, W_gate, W_up, H, FA_save, FB_save, nullptr,
+                  s) !=
         hipSuccess)
         return R3_ERR_HIP;
     return hip_rc(simt_ffn2((int)m.S, m.d, m.E, m.F, m.act, H, offsets, W_down, Yp, s));
@@ -223,6 +241,52 @@ int r3_combine(const r3_layer_desc *desc, const void *Yp, const float *gates, co
     return hip_rc(launch_combine(m.T, m.d, m.K, m.act, Yp, gates, inv_perm, y, (hipStream_t)stream));
 }
 
+int r3_moe_forward(const r3_layer_desc *desc, const void *x, const void *W_r, const float *bias, const void *idx,
+                   const void *W_gate, const void *W_up, const void *W_down, void *y, float *gates, int32_t *counts,
+                   int32_t *offsets, int32_t *inv_perm, int32_t *perm, void *Yp, void *H, void *FA_save,
+                   void *FB_save, float *logits_out, int64_t *agree_out, int32_t *status_word, void *ws,
+                   size_t ws_bytes, void *stream) {
+    Dims m;
+    int rc = check_desc(desc, m);
+    if (rc) return rc;
+    if (!x || !W_gate || !W_up || !W_down || !y || !Yp || !H || ((FA_save == nullptr) != (FB_save == nullptr)))
+        return R3_ERR_INVALID_ARG;   // (the other pointers are checked by the steps)
+    if (!aligned(y, 16) || !aligned(Yp, 16) || !aligned(H, 16) || !aligned(FA_save, 16) || !aligned(FB_save, 16) ||
+        !aligned(W_gate, 16) || !aligned(W_up, 16) || !aligned(W_down, 16))
+        return R3_ERR_INVALID_ARG;
+    if ((int64_t)m.T * m.d * m.eb > 0x7fffffffLL) return R3_ERR_UNSUPPORTED;   // rows are read through perm
+    const FwdWs w = fwd_layout(m);
+    if (!ws || ws_bytes < w.total || !aligned(ws, 256)) return R3_ERR_WORKSPACE;
+    char *base = (char *)ws;
+    hipStream_t s = (hipStream_t)stream;
+    r3_layer_desc plain = *desc;
+    plain.flags = 0;
+    rc = r3_replay_gate(&plain, x, W_r, bias, idx, gates, logits_out, agree_out, status_word, base + w.gate,
+                        w.perm - w.gate, stream);
+    if (rc) return rc;
+    rc = r3_permute(&plain, nullptr, idx, counts, offsets, inv_perm, perm, nullptr, status_word, base + w.perm,
+                    w.ffn - w.perm, stream);
+    if (rc) return rc;
+    // the gate of every expert-sorted row: the first contraction's epilogue scales H with it, so the
+    // down projection yields gated rows and the combination is a plain sum of each token's K rows
+    int32_t *tok = (int32_t *)(base + w.tok);
+    float *grow = (float *)(base + w.grow);
+    if (mfma_row_tokens((int)m.S, m.K, perm, gates, tok, grow, s) != hipSuccess) return R3_ERR_HIP;
+    if (use_mfma_ffn(m)) {
+        int32_t *tiles = (int32_t *)(base + w.ffn);
+        if (mfma_build_tiles(m.E, offsets, tiles, s) != hipSuccess) return R3_ERR_HIP;
+        if (mfma_ffn_forward(m.S, m.d, m.E, m.F, x, perm, m.K, m.T, offsets, tiles, W_gate, W_up, W_down, Yp, H,
+                             FA_save, FB_save, grow, s) != hipSuccess)
+            return R3_ERR_HIP;
+    } else {
+        if (simt_ffn1((int)m.S, m.d, m.E, m.F, m.act, x, perm, m.K, offsets, W_gate, W_up, H, FA_save, FB_save, grow,
+                      s) != hipSuccess)
+            return R3_ERR_HIP;
+        if (simt_ffn2((int)m.S, m.d, m.E, m.F, m.act, H, offsets, W_down, Yp, s) != hipSuccess) return R3_ERR_HIP;
+    }
+    return hip_rc(launch_combine(m.T, m.d, m.K, m.act, Yp, nullptr, inv_perm, y, s));
+}
+
 int r3_moe_backward(const r3_layer_desc *desc, const void *dy, const void *x, const void *W_r,
                     const void *idx, const float *gates, const int32_t *inv_perm, const int32_t *perm,
                     const int32_t *offsets, const void *Xp, const void *FA, const void *FB, const void *H,
@@ -233,6 +297,7 @@ int r3_moe_backward(const r3_layer_desc *desc, const void *dy, const void *x, co
     int rc = check_desc(desc, m);
     if (rc) return rc;
     const bool mf = use_mfma_ffn(m);
+    const bool gated = (m.flags & R3_FLAG_GATED_H) != 0;   // H = g H and Yp = g o, as r3_moe_forward leaves them
     const void *ptrs[] = {dy, x, W_r, idx, gates, inv_perm, offsets, FA, FB, H, W_gate, W_up, W_down,
                           dx, dW_r, dW_gate, dW_up, dW_down};
     for (const void *p : ptrs)
@@ -245,8 +310,8 @@ int r3_moe_backward(const r3_layer_desc *desc, const void *dy, const void *x, co
         // rows of dy (and of x when there is no Xp) are read through perm inside the tile loads
         if (!perm || !aligned(perm, 4)) return R3_ERR_INVALID_ARG;
         if ((int64_t)m.T * m.d * m.eb >= (1ll << 31)) return R3_ERR_UNSUPPORTED;   // 32-bit row offsets
-    } else if (!Yp || !Xp) {
-        return Xp ? R3_ERR_INVALID_ARG : R3_ERR_UNSUPPORTED;   // the plain kernels need both copies
+    } else if (!Yp || ((!Xp || gated) && (!perm || !aligned(perm, 4)))) {
+        return R3_ERR_INVALID_ARG;   // the plain kernels need Yp, and Xp or perm (perm after r3_moe_forward)
     }
     const BwdWs w = bwd_layout(m);
     if (!ws || ws_bytes < w.total || !aligned(ws, 256)) return R3_ERR_WORKSPACE;
@@ -262,7 +327,7 @@ int r3_moe_backward(const r3_layer_desc *desc, const void *dy, const void *x, co
         // list and leaves the dot products the masked softmax needs (no g*dy copy, no read of Yp)
         int32_t *tiles = (int32_t *)(base + w.tiles), *tok = (int32_t *)(base + w.tok);
         float *grow = (float *)(base + w.grow), *wpart = (float *)(base + w.wpart);
-        void *Hg = base + w.Hg;
+        void *Hg = gated ? nullptr : base + w.Hg;
         if (mfma_row_tokens(S, m.K, perm, gates, tok, grow, s) != hipSuccess) return R3_ERR_HIP;
         if (mfma_build_tiles(m.E, offsets, tiles, s) != hipSuccess) return R3_ERR_HIP;
         if (mfma_ffn_dh(m.S, m.d, m.E, m.F, dy, tok, m.T, grow, offsets, tiles, W_down, FA, FB, H, dA, dB, Hg, wpart,
@@ -271,7 +336,8 @@ int r3_moe_backward(const r3_layer_desc *desc, const void *dy, const void *x, co
         if (launch_gate_backward_parts(m.T, m.E, m.K, row_parts(m), wpart, gates, inv_perm, idx, m.idx, m.stride, dz,
                                        ds, s) != hipSuccess)
             return R3_ERR_HIP;
-        if (mfma_wgrad(m.E, m.F, m.d, Hg, dy, tok, m.T, offsets, tiles, 2, dW_down, accumulate, s) != hipSuccess)
+        if (mfma_wgrad(m.E, m.F, m.d, gated ? H : Hg, dy, tok, m.T, offsets, tiles, 2, dW_down, accumulate, s) !=
+            hipSuccess)
             return R3_ERR_HIP;
         if (mfma_wgrad_pair(m.E, m.d, m.F, Xp ? Xp : x, Xp ? nullptr : tok, m.T, dA, dB, offsets, tiles, 3, dW_gate,
                             dW_up, accumulate, s) != hipSuccess)
@@ -282,12 +348,25 @@ int r3_moe_backward(const r3_layer_desc *desc, const void *dy, const void *x, co
         // combine and masked softmax:  dYp = g*dy per slot, dz, dense ds
         void *dYp = dXp;  // dYp is dead once dW_down and dH are done
         if (launch_gate_backward(m.T, m.d, m.E, m.K, m.act, dy, Yp, gates, inv_perm, idx, m.idx, m.stride, dYp, dz,
-                                 ds, s) != hipSuccess)
+                                 ds, gated ? 1 : 0, s) != hipSuccess)
             return R3_ERR_HIP;
         if (simt_dh(S, m.d, m.E, m.F, m.act, dYp, offsets, W_down, FA, FB, dA, dB, s) != hipSuccess) return R3_ERR_HIP;
-        if (simt_wgrad(m.E, m.F, m.d, m.act, H, dYp, offsets, dW_down, accumulate, s) != hipSuccess) return R3_ERR_HIP;
-        if (simt_wgrad(m.E, m.d, m.F, m.act, Xp, dA, offsets, dW_gate, accumulate, s) != hipSuccess) return R3_ERR_HIP;
-        if (simt_wgrad(m.E, m.d, m.F, m.act, Xp, dB, offsets, dW_up, accumulate, s) != hipSuccess) return R3_ERR_HIP;
+        const int32_t *tok = nullptr;
+        if (gated || !Xp) {   // rows of dy / x through the row -> token list
+            int32_t *t = (int32_t *)(base + w.tok);
+            if (mfma_row_tokens(S, m.K, perm, nullptr, t, nullptr, s) != hipSuccess) return R3_ERR_HIP;
+            tok = t;
+        }
+        // gated: H is g H already, so its partner is the plain dy row, not g dy
+        e = gated ? simt_wgrad(m.E, m.F, m.d, m.act, H, nullptr, dy, tok, offsets, dW_down, accumulate, s)
+                  : simt_wgrad(m.E, m.F, m.d, m.act, H, nullptr, dYp, nullptr, offsets, dW_down, accumulate, s);
+        if (e != hipSuccess) return R3_ERR_HIP;
+        const void *rows = Xp ? Xp : x;          // the token rows, gathered or through the list
+        const int32_t *rtok = Xp ? nullptr : tok;
+        if (simt_wgrad(m.E, m.d, m.F, m.act, rows, rtok, dA, nullptr, offsets, dW_gate, accumulate, s) != hipSuccess)
+            return R3_ERR_HIP;
+        if (simt_wgrad(m.E, m.d, m.F, m.act, rows, rtok, dB, nullptr, offsets, dW_up, accumulate, s) != hipSuccess)
+            return R3_ERR_HIP;
         if (simt_dxp(S, m.d, m.E, m.F, m.act, dA, dB, offsets, W_gate, W_up, dXp, s) != hipSuccess) return R3_ERR_HIP;
     }
     // router:  dW_r = x^T ds, dbias = column sums

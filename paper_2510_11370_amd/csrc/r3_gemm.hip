@@ -121,7 +121,8 @@ template <bool GATHER>
 __global__ void __launch_bounds__(kThreads2, kMinWavesPerSimd)
 ffn1_kernel(int S, int d, int F, const bf16_t *__restrict__ Xp, const int32_t *__restrict__ perm, int K, int T,
             const int32_t *__restrict__ offsets, const int32_t *__restrict__ tiles, const bf16_t *__restrict__ Wg,
-            const bf16_t *__restrict__ Wu, bf16_t *__restrict__ H, bf16_t *__restrict__ FA, bf16_t *__restrict__ FB) {
+            const bf16_t *__restrict__ Wu, bf16_t *__restrict__ H, bf16_t *__restrict__ FA, bf16_t *__restrict__ FB,
+            const float *__restrict__ grow) {
     __shared__ __attribute__((aligned(1024))) char lds[2 * kSuperBytes];   // one piece: a tail tile lays it out differently
     char *const bufA = lds, *const bufB = lds + kSuperBytes;
     char *const s0 = bufA, *const s1 = bufA + kStageBytes, *const s2 = bufB, *const s3 = bufB + kStageBytes;
@@ -192,6 +193,9 @@ ffn1_kernel(int S, int d, int F, const bf16_t *__restrict__ Xp, const int32_t *_
         const int valid = min(32, row_end - brow);             // may be <= 0
         const int64_t o = ((int64_t)brow * F + f0 + wp * 64) * 2;  // byte offset of the block
         RowStage<128> sh{patch, tid}, sa{patch + RowStage<128>::BYTES, tid}, sb{patch + 2 * RowStage<128>::BYTES, tid};
+        // grow != NULL: H leaves as g H, g the gate of the row's slot (the down projection then yields
+        // gated rows and the gradient of W_down finds its row operand ready); FA and FB are not scaled
+        const float gq = grow ? (brow + q < row_end ? grow[brow + q] : 0.0f) : 1.0f;
 #pragma unroll
         for (int tp = 0; tp < 2; ++tp)
 #pragma unroll
@@ -202,7 +206,7 @@ ffn1_kernel(int S, int d, int F, const bf16_t *__restrict__ Xp, const int32_t *_
                     const float a = acc[tp][tq][4 * g + i], b = acc[tp + 2][tq][4 * g + i];
                     const float sg = sigmoid_fast(a);
                     fb[i] = a * sg;                                  // silu(a)
-                    h[i] = fb[i] * b;
+                    h[i] = gq * (fb[i] * b);
                     fa[i] = b * fmaf(fb[i], 1.0f - sg, sg);          // b silu'(a), silu'(a) = sg (1 + a (1 - sg))
                 }
                 const int bo = (tp * 32 + g * 8 + (lane >> 5) * 4) * 2;
@@ -237,10 +241,12 @@ ffn1_kernel(int S, int d, int F, const bf16_t *__restrict__ Xp, const int32_t *_
 //           wpart[row][2 pt + wp] = g * sum over this wave's 128 features of u H
 //         The parts of a row add up to g <dy, o> = g dg (o = H Wd: <dy, H Wd> = <dy Wd^T, H>), which is
 //         all the masked-softmax backward needs, so the expert outputs are not read again either.
+//         GATED: the forward already stored g H in place of H (one-call forward); the parts are then
+//         sums of u (g H) and nothing is written for H.
 // MODE 2: dXp = dA Wg^T + dB Wu^T   P from Wg[e], Wu[e] [d,F] (KC: rows c), K = 2F
 //         (two-phase reduction: first F over (dA, Wg), then F over (dB, Wu))
 // ---------------------------------------------------------------------------
-template <int MODE>
+template <int MODE, bool GATED = false>
 __global__ void __launch_bounds__(kThreads2, kMinWavesPerSimd)
 rowgemm_kernel(int S, int d, int F, const bf16_t *__restrict__ Q0, const bf16_t *__restrict__ Q1,
                const int32_t *__restrict__ offsets, const int32_t *__restrict__ tiles,
@@ -356,7 +362,7 @@ rowgemm_kernel(int S, int d, int F, const bf16_t *__restrict__ Q0, const bf16_t 
         // u H of one 32-row block belong to one row (q).
         typedef RowStage<128> Patch;
         const Patch sa{st.base, tid}, sb{st.base + Patch::BYTES, tid}, sh{st.base + 2 * Patch::BYTES, tid};
-        constexpr int NPH = 3 * 2 * kTQ2;
+        constexpr int NPH = 3 * 2 * kTQ2;   // (GATED: the H phases only read)
         auto where = [&](int ph, int &valid) -> int64_t {
             const int r = ph / 3;
             const int brow = row0 + wq * kWaveRowsQ + (r >> 1) * 32;
@@ -406,13 +412,13 @@ rowgemm_kernel(int S, int d, int F, const bf16_t *__restrict__ Q0, const bf16_t 
                             o[i] = gq * u * v[i];
                         }
                     }
-                    sp.put8(q, bo, pack4(o[0], o[1], o[2], o[3]));
+                    if (!(GATED && which == 2)) sp.put8(q, bo, pack4(o[0], o[1], o[2], o[3]));
                 }
             bf16_t *dst = which == 0 ? out0 : which == 1 ? out1 : out2;
-            sp.flush((char *)dst + oh, (int64_t)NOUT * 2, valid);
+            if (!(GATED && which == 2)) sp.flush((char *)dst + oh, (int64_t)NOUT * 2, valid);
             if (which == 2 && half == 1) {
                 // the two lanes that hold row q (k-groups 0 and 1 of the MFMA layout) add up
-                const float w = gq * (wsum + __shfl_xor(wsum, 32, 64));
+                const float w = (GATED ? 1.0f : gq) * (wsum + __shfl_xor(wsum, 32, 64));
                 if (lane < 32 && brow + q < row_end)
                     wpart[(int64_t)(brow + q) * (2 * npt) + 2 * (p0 / kTile) + wp] = w;
             }
@@ -849,18 +855,19 @@ hipError_t mfma_build_tiles(int E, const int32_t *offsets, int32_t *tiles, hipSt
 
 hipError_t mfma_ffn_forward(int64_t S, int d, int E, int F, const void *Xp, const int32_t *perm, int K, int T,
                             const int32_t *offsets, const int32_t *tiles, const void *Wg, const void *Wu,
-                            const void *Wd, void *Yp, void *H, void *FA, void *FB, hipStream_t s) {
+                            const void *Wd, void *Yp, void *H, void *FA, void *FB, const float *grow,
+                            hipStream_t s) {
     const int mt = max_row_tiles(S, E, kTile);
     {
         ProfScope ps(PROF_FFN1, s);
         if (perm)
             ffn1_kernel<true><<<persistent_grid((int64_t)mt * (F / 128)), kThreads2, 0, s>>>(
                 (int)S, d, F, (const bf16_t *)Xp, perm, K, T, offsets, tiles, (const bf16_t *)Wg, (const bf16_t *)Wu,
-                (bf16_t *)H, (bf16_t *)FA, (bf16_t *)FB);
+                (bf16_t *)H, (bf16_t *)FA, (bf16_t *)FB, grow);
         else
             ffn1_kernel<false><<<persistent_grid((int64_t)mt * (F / 128)), kThreads2, 0, s>>>(
                 (int)S, d, F, (const bf16_t *)Xp, perm, K, T, offsets, tiles, (const bf16_t *)Wg, (const bf16_t *)Wu,
-                (bf16_t *)H, (bf16_t *)FA, (bf16_t *)FB);
+                (bf16_t *)H, (bf16_t *)FA, (bf16_t *)FB, grow);
     }
     ProfScope ps(PROF_FFN2, s);
     rowgemm_kernel<0><<<persistent_grid((int64_t)mt * (d / kTile)), kThreads2, 0, s>>>(
@@ -874,10 +881,17 @@ hipError_t mfma_ffn_dh(int64_t S, int d, int E, int F, const void *dy, const int
                        const void *H, void *dA, void *dB, void *Hg, float *wpart, hipStream_t s) {
     const int mt = max_row_tiles(S, E, kTile);
     ProfScope ps(PROF_DH, s);
-    rowgemm_kernel<1><<<persistent_grid((int64_t)mt * (F / kTile)), kThreads2, 0, s>>>(
-        (int)S, d, F, (const bf16_t *)dy, nullptr, offsets, tiles, (const bf16_t *)Wd, nullptr,
-        (const bf16_t *)FA, (const bf16_t *)FB, (bf16_t *)dA, (bf16_t *)dB, tok, T, grow, (const bf16_t *)H,
-        (bf16_t *)Hg, wpart);
+    const int grid = persistent_grid((int64_t)mt * (F / kTile));
+    if (Hg)
+        rowgemm_kernel<1, false><<<grid, kThreads2, 0, s>>>(
+            (int)S, d, F, (const bf16_t *)dy, nullptr, offsets, tiles, (const bf16_t *)Wd, nullptr,
+            (const bf16_t *)FA, (const bf16_t *)FB, (bf16_t *)dA, (bf16_t *)dB, tok, T, grow, (const bf16_t *)H,
+            (bf16_t *)Hg, wpart);
+    else   // H already holds the gate-scaled rows
+        rowgemm_kernel<1, true><<<grid, kThreads2, 0, s>>>(
+            (int)S, d, F, (const bf16_t *)dy, nullptr, offsets, tiles, (const bf16_t *)Wd, nullptr,
+            (const bf16_t *)FA, (const bf16_t *)FB, (bf16_t *)dA, (bf16_t *)dB, tok, T, grow, (const bf16_t *)H,
+            nullptr, wpart);
     return hipGetLastError();
 }
 

@@ -32,10 +32,11 @@ hipError_t launch_permute(int T, int d, int E, int K, int elem_bytes, const void
                           hipStream_t s);
 hipError_t launch_combine(int T, int d, int K, int act, const void *Yp, const float *gates,
                           const int32_t *inv_perm, void *y, hipStream_t s);
+// gated != 0: Yp holds gate-scaled rows (g o), so <dy, Yp_j> is already g_j dg_j
 hipError_t launch_gate_backward(int T, int d, int E, int K, int act, const void *dy, const void *Yp,
                                 const float *gates, const int32_t *inv_perm, const void *idx,
                                 int idx_dtype, int64_t stride, void *dYp, float *dz, void *ds_dense,
-                                hipStream_t s);
+                                int gated, hipStream_t s);
 // masked-softmax backward from the row parts written by the expert-gradient GEMM:
 // w_j = sum_p wpart[row_j][p] (= g_j dg_j), dz_j = w_j - g_j sum_i w_i; writes dz [T,K] and the dense
 // bf16 ds [T,2E] (hi | lo halves)
@@ -70,17 +71,19 @@ hipError_t launch_cache_gather(int idx_bytes, int L, int K, int P, const void *p
 hipError_t simt_router_logits(int T, int d, int E, int act, const void *x, const void *Wr, const float *bias,
                               float *logits, hipStream_t s);
 // perm != NULL: `Xp` is x [T,d] and row r of the grouped operand is x[perm[r] / K] (no gathered copy)
+// grow != NULL: H is stored scaled by the row's gate (grow [S] f32)
 hipError_t simt_ffn1(int S, int d, int E, int F, int act, const void *Xp, const int32_t *perm, int K,
                      const int32_t *offsets, const void *Wg, const void *Wu, void *H, void *A, void *B,
-                     hipStream_t s);
+                     const float *grow, hipStream_t s);
 hipError_t simt_ffn2(int S, int d, int E, int F, int act, const void *H, const int32_t *offsets, const void *Wd,
                      void *Yp, hipStream_t s);
 hipError_t simt_dh(int S, int d, int E, int F, int act, const void *dYp, const int32_t *offsets, const void *Wd,
                    const void *A, const void *B, void *dA, void *dB, hipStream_t s);
 hipError_t simt_dxp(int S, int d, int E, int F, int act, const void *dA, const void *dB, const int32_t *offsets,
                     const void *Wg, const void *Wu, void *dXp, hipStream_t s);
-hipError_t simt_wgrad(int E, int NP, int NQ, int act, const void *P, const void *Q, const int32_t *offsets,
-                      float *out, int accumulate, hipStream_t s);
+// ptok / qtok != NULL: that operand is an un-permuted matrix and row r of the reduction is its row tok[r]
+hipError_t simt_wgrad(int E, int NP, int NQ, int act, const void *P, const int32_t *ptok, const void *Q,
+                      const int32_t *qtok, const int32_t *offsets, float *out, int accumulate, hipStream_t s);
 hipError_t simt_dwr(int T, int d, int E, int act, const void *x, const void *ds, float *dWr, int accumulate,
                     hipStream_t s);
 
@@ -94,9 +97,11 @@ hipError_t mfma_build_tiles(int E, const int32_t *offsets, int32_t *tiles, hipSt
 // through perm in the tile loads
 hipError_t mfma_ffn_forward(int64_t S, int d, int E, int F, const void *Xp, const int32_t *perm, int K, int T,
                             const int32_t *offsets, const int32_t *tiles, const void *Wg, const void *Wu,
-                            const void *Wd, void *Yp, void *H, void *FA, void *FB, hipStream_t s);
+                            const void *Wd, void *Yp, void *H, void *FA, void *FB, const float *grow,
+                            hipStream_t s);
 // u = dy Wd^T with the rows of dy read through tok (row r is dy[tok[r]], dy is [T,d]); writes dA = g u FA,
-// dB = g u FB, Hg = g H and wpart [S, 2 F/256] f32, whose row sums are g <dy, o> (see rowgemm_kernel<1>)
+// dB = g u FB, Hg = g H and wpart [S, 2 F/256] f32, whose row sums are g <dy, o> (see rowgemm_kernel<1>).
+// Hg == NULL: H already holds g H (the one-call forward wrote it so) and nothing is written for it
 hipError_t mfma_ffn_dh(int64_t S, int d, int E, int F, const void *dy, const int32_t *tok, int T, const float *grow,
                        const int32_t *offsets, const int32_t *tiles, const void *Wd, const void *FA, const void *FB,
                        const void *H, void *dA, void *dB, void *Hg, float *wpart, hipStream_t s);
@@ -117,7 +122,7 @@ hipError_t mfma_wgrad_pair(int E, int NQd, int NPd, const void *Qs, const int32_
                            float *out1, int accumulate, hipStream_t s);
 // tok[r] = perm[r] / K (r < S), padded; mfma_row_tokens_bytes(S) bytes.  gates != NULL: also
 // grow[r] = gates[perm[r]] (f32 [S])
-size_t mfma_row_tokens_bytes(int64_t S);
+size_t mfma_row_tokens_bytes(int64_t S);   // (the kernel is plain: every path may use it)
 hipError_t mfma_row_tokens(int S, int K, const int32_t *perm, const float *gates, int32_t *tok, float *grow,
                            hipStream_t s);
 hipError_t mfma_router_logits(int T, int d, int E, const void *x, const void *Wr, const float *bias,

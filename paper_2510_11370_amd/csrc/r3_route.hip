@@ -645,7 +645,7 @@ combine_kernel(int Krt, int row_vecs, const typename VecIO<T, VEC>::V *__restric
     __shared__ float g[kMaxK];
     if (threadIdx.x < (unsigned)K) {
         rows[threadIdx.x] = inv_perm[(int64_t)t * K + threadIdx.x];
-        g[threadIdx.x] = gates[(int64_t)t * K + threadIdx.x];
+        g[threadIdx.x] = gates ? gates[(int64_t)t * K + threadIdx.x] : 1.0f;   // no gates: rows arrive gated
     }
     __syncthreads();
     for (int c = threadIdx.x; c < row_vecs; c += blockDim.x) {
@@ -715,7 +715,7 @@ gate_backward_kernel(int E, int Krt, int row_vecs, const typename VecIO<T, VEC>:
                      const typename VecIO<T, VEC>::V *__restrict__ Yp, const float *__restrict__ gates,
                      const int32_t *__restrict__ inv_perm, const IdxT *__restrict__ idx, int64_t stride,
                      typename VecIO<T, VEC>::V *__restrict__ dYp, float *__restrict__ dz,
-                     T *__restrict__ ds_dense) {
+                     T *__restrict__ ds_dense, int gated) {
     typedef VecIO<T, VEC> IO;
     const int K = KT > 0 ? KT : Krt;
     const int t = blockIdx.x;
@@ -791,9 +791,10 @@ gate_backward_kernel(int E, int Krt, int row_vecs, const typename VecIO<T, VEC>:
     }
     __syncthreads();
     if (threadIdx.x < (unsigned)K) {
+        // gated: the rows of Yp are g o, so the dot products are already g_j dg_j
         float mix = 0.0f;
-        for (int j = 0; j < K; ++j) mix = fmaf(g[j], dgs[j], mix);
-        float v = g[threadIdx.x] * (dgs[threadIdx.x] - mix);
+        for (int j = 0; j < K; ++j) mix = gated ? mix + dgs[j] : fmaf(g[j], dgs[j], mix);
+        float v = gated ? dgs[threadIdx.x] - g[threadIdx.x] * mix : g[threadIdx.x] * (dgs[threadIdx.x] - mix);
         dz[(int64_t)t * K + threadIdx.x] = v;
         if (ds_dense) {
             int e = min((int)idx[(int64_t)t * stride + threadIdx.x], E - 1);
@@ -808,41 +809,41 @@ template <typename T, int VEC>
 static hipError_t gate_backward_dispatch(int Tn, int E, int K, int row_vecs, const void *dy, const void *Yp,
                                          const float *gates, const int32_t *inv_perm, const void *idx,
                                          int idx_dtype, int64_t stride, void *dYp, float *dz,
-                                         void *ds_dense, hipStream_t s) {
+                                         void *ds_dense, int gated, hipStream_t s) {
     typedef typename VecIO<T, VEC>::V V;
     if (idx_dtype == R3_IDX_U8 && K == 8 && VEC > 1)
         gate_backward_kernel<T, VEC, uint8_t, 8><<<Tn, 256, 0, s>>>(E, K, row_vecs, (const V *)dy, (const V *)Yp,
                                                                   gates, inv_perm, (const uint8_t *)idx,
-                                                                  stride, (V *)dYp, dz, (T *)ds_dense);
+                                                                  stride, (V *)dYp, dz, (T *)ds_dense, gated);
     else if (idx_dtype == R3_IDX_U8)
         gate_backward_kernel<T, VEC, uint8_t, 0><<<Tn, 256, 0, s>>>(E, K, row_vecs, (const V *)dy, (const V *)Yp,
                                                                   gates, inv_perm, (const uint8_t *)idx,
-                                                                  stride, (V *)dYp, dz, (T *)ds_dense);
+                                                                  stride, (V *)dYp, dz, (T *)ds_dense, gated);
     else
         gate_backward_kernel<T, VEC, uint16_t, 0><<<Tn, 256, 0, s>>>(E, K, row_vecs, (const V *)dy,
                                                                    (const V *)Yp, gates, inv_perm,
                                                                    (const uint16_t *)idx, stride, (V *)dYp,
-                                                                   dz, (T *)ds_dense);
+                                                                   dz, (T *)ds_dense, gated);
     return hipGetLastError();
 }
 
 hipError_t launch_gate_backward(int T, int d, int E, int K, int act, const void *dy, const void *Yp,
                                 const float *gates, const int32_t *inv_perm, const void *idx,
                                 int idx_dtype, int64_t stride, void *dYp, float *dz, void *ds_dense,
-                                hipStream_t s) {
+                                int gated, hipStream_t s) {
     ProfScope ps(PROF_GATE_BWD, s);
     if (act == R3_BF16) {
         if (d % 8 == 0)
             return gate_backward_dispatch<bf16_t, 8>(T, E, K, d / 8, dy, Yp, gates, inv_perm, idx, idx_dtype,
-                                                     stride, dYp, dz, ds_dense, s);
+                                                     stride, dYp, dz, ds_dense, gated, s);
         return gate_backward_dispatch<bf16_t, 1>(T, E, K, d, dy, Yp, gates, inv_perm, idx, idx_dtype, stride,
-                                                 dYp, dz, ds_dense, s);
+                                                 dYp, dz, ds_dense, gated, s);
     }
     if (d % 4 == 0)
         return gate_backward_dispatch<float, 4>(T, E, K, d / 4, dy, Yp, gates, inv_perm, idx, idx_dtype,
-                                                stride, dYp, dz, ds_dense, s);
+                                                stride, dYp, dz, ds_dense, gated, s);
     return gate_backward_dispatch<float, 1>(T, E, K, d, dy, Yp, gates, inv_perm, idx, idx_dtype, stride, dYp,
-                                            dz, ds_dense, s);
+                                            dz, ds_dense, gated, s);
 }
 
 // ---------------------------------------------------------------------------

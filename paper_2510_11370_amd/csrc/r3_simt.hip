@@ -35,7 +35,7 @@ template <typename T>
 __global__ void __launch_bounds__(256)
 simt_ffn1_kernel(int S, int d, int E, int F, const T *__restrict__ Xp, const int32_t *__restrict__ perm, int K,
                  const int32_t *__restrict__ offsets, const T *__restrict__ Wg, const T *__restrict__ Wu,
-                 T *__restrict__ H, T *__restrict__ FA, T *__restrict__ FB) {
+                 T *__restrict__ H, T *__restrict__ FA, T *__restrict__ FB, const float *__restrict__ grow) {
     int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (i >= (int64_t)S * F) return;
     int r = (int)(i / F), f = (int)(i - (int64_t)r * F);
@@ -49,7 +49,7 @@ simt_ffn1_kernel(int S, int d, int E, int F, const T *__restrict__ Xp, const int
         b = fmaf(xv, Elem<T>::ld(wu + (int64_t)c * F), b);
     }
     const float sg = sigmoidf_(a);
-    Elem<T>::st(H + i, a * sg * b);
+    Elem<T>::st(H + i, (grow ? grow[r] : 1.0f) * (a * sg * b));
     if (FA) Elem<T>::st(FA + i, b * sg * (1.0f + a * (1.0f - sg)));
     if (FB) Elem<T>::st(FB + i, a * sg);
 }
@@ -104,10 +104,12 @@ simt_dxp_kernel(int S, int d, int E, int F, const T *__restrict__ dA, const T *_
 }
 
 // out[e][p][q] (+)= sum_{r in expert e} P[r][p] * Q[r][q]   (weight gradients)
+// ptok / qtok != NULL: that operand is an un-permuted matrix and row r of the reduction is its row tok[r]
 template <typename T>
 __global__ void __launch_bounds__(256)
-simt_wgrad_kernel(int E, int NP, int NQ, const T *__restrict__ P, const T *__restrict__ Q,
-                  const int32_t *__restrict__ offsets, float *__restrict__ out, int accumulate) {
+simt_wgrad_kernel(int E, int NP, int NQ, const T *__restrict__ P, const int32_t *__restrict__ ptok,
+                  const T *__restrict__ Q, const int32_t *__restrict__ qtok, const int32_t *__restrict__ offsets,
+                  float *__restrict__ out, int accumulate) {
     int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (i >= (int64_t)E * NP * NQ) return;
     int e = (int)(i / ((int64_t)NP * NQ));
@@ -115,7 +117,8 @@ simt_wgrad_kernel(int E, int NP, int NQ, const T *__restrict__ P, const T *__res
     int p = (int)(rem / NQ), q = (int)(rem - (int64_t)p * NQ);
     float acc = 0.0f;
     for (int r = offsets[e]; r < offsets[e + 1]; ++r)
-        acc = fmaf(Elem<T>::ld(P + (int64_t)r * NP + p), Elem<T>::ld(Q + (int64_t)r * NQ + q), acc);
+        acc = fmaf(Elem<T>::ld(P + (int64_t)(ptok ? ptok[r] : r) * NP + p),
+                   Elem<T>::ld(Q + (int64_t)(qtok ? qtok[r] : r) * NQ + q), acc);
     out[i] = accumulate ? out[i] + acc : acc;
 }
 
@@ -152,10 +155,10 @@ hipError_t simt_router_logits(int T, int d, int E, int act, const void *x, const
 
 hipError_t simt_ffn1(int S, int d, int E, int F, int act, const void *Xp, const int32_t *perm, int K,
                      const int32_t *offsets, const void *Wg, const void *Wu, void *H, void *A, void *B,
-                     hipStream_t s) {
+                     const float *grow, hipStream_t s) {
     int g = blocks_for((int64_t)S * F);
-    R3_BY_ACT(act, (simt_ffn1_kernel<bf16_t><<<g, 256, 0, s>>>(S, d, E, F, (const bf16_t *)Xp, perm, K, offsets, (const bf16_t *)Wg, (const bf16_t *)Wu, (bf16_t *)H, (bf16_t *)A, (bf16_t *)B)),
-              (simt_ffn1_kernel<float><<<g, 256, 0, s>>>(S, d, E, F, (const float *)Xp, perm, K, offsets, (const float *)Wg, (const float *)Wu, (float *)H, (float *)A, (float *)B)));
+    R3_BY_ACT(act, (simt_ffn1_kernel<bf16_t><<<g, 256, 0, s>>>(S, d, E, F, (const bf16_t *)Xp, perm, K, offsets, (const bf16_t *)Wg, (const bf16_t *)Wu, (bf16_t *)H, (bf16_t *)A, (bf16_t *)B, grow)),
+              (simt_ffn1_kernel<float><<<g, 256, 0, s>>>(S, d, E, F, (const float *)Xp, perm, K, offsets, (const float *)Wg, (const float *)Wu, (float *)H, (float *)A, (float *)B, grow)));
     return hipGetLastError();
 }
 
@@ -183,11 +186,11 @@ hipError_t simt_dxp(int S, int d, int E, int F, int act, const void *dA, const v
     return hipGetLastError();
 }
 
-hipError_t simt_wgrad(int E, int NP, int NQ, int act, const void *P, const void *Q, const int32_t *offsets,
-                      float *out, int accumulate, hipStream_t s) {
+hipError_t simt_wgrad(int E, int NP, int NQ, int act, const void *P, const int32_t *ptok, const void *Q,
+                      const int32_t *qtok, const int32_t *offsets, float *out, int accumulate, hipStream_t s) {
     int g = blocks_for((int64_t)E * NP * NQ);
-    R3_BY_ACT(act, (simt_wgrad_kernel<bf16_t><<<g, 256, 0, s>>>(E, NP, NQ, (const bf16_t *)P, (const bf16_t *)Q, offsets, out, accumulate)),
-              (simt_wgrad_kernel<float><<<g, 256, 0, s>>>(E, NP, NQ, (const float *)P, (const float *)Q, offsets, out, accumulate)));
+    R3_BY_ACT(act, (simt_wgrad_kernel<bf16_t><<<g, 256, 0, s>>>(E, NP, NQ, (const bf16_t *)P, ptok, (const bf16_t *)Q, qtok, offsets, out, accumulate)),
+              (simt_wgrad_kernel<float><<<g, 256, 0, s>>>(E, NP, NQ, (const float *)P, ptok, (const float *)Q, qtok, offsets, out, accumulate)));
     return hipGetLastError();
 }
 

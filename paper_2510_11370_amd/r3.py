@@ -14,12 +14,13 @@ LIB_PATH = os.path.join(_HERE, "libr3.so")
 
 BF16, F32 = 0, 1
 IDX_U8, IDX_U16 = 0, 1
-OP_REPLAY_GATE, OP_PERMUTE, OP_GROUPED_FFN, OP_BACKWARD = 0, 1, 2, 3
+OP_REPLAY_GATE, OP_PERMUTE, OP_GROUPED_FFN, OP_BACKWARD, OP_FORWARD = 0, 1, 2, 3, 4
+FLAG_GATED_H = 1
 DATA_IDX_RANGE, DATA_IDX_DUP, DATA_NONFINITE = 1, 2, 4
 _STATUS = {1: "R3_ERR_INVALID_ARG", 2: "R3_ERR_UNSUPPORTED", 3: "R3_ERR_WORKSPACE", 4: "R3_ERR_HIP"}
 
 EXPORTS = ["r3_version", "r3_workspace_bytes", "r3_record_topk", "r3_replay_gate", "r3_permute",
-           "r3_permute_static", "r3_grouped_ffn", "r3_combine", "r3_moe_backward", "r3_profile_enable", "r3_profile_tags",
+           "r3_permute_static", "r3_grouped_ffn", "r3_combine", "r3_moe_forward", "r3_moe_backward", "r3_profile_enable", "r3_profile_tags",
            "r3_profile_name", "r3_profile_read", "r3_profile_copy",
            "r3_profile_mfma", "r3_profile_mfma_flops", "r3_profile_gemm_mix", "r3_routing_diff", "r3_policy_discrepancy",
            "r3_policy_workspace_bytes", "r3_mask_cache_append", "r3_mask_cache_gather"]
@@ -27,7 +28,7 @@ EXPORTS = ["r3_version", "r3_workspace_bytes", "r3_record_topk", "r3_replay_gate
 
 class LayerDesc(C.Structure):
     _fields_ = [("T", C.c_int32), ("d", C.c_int32), ("E", C.c_int32), ("K", C.c_int32),
-                ("F", C.c_int32), ("act", C.c_int32), ("idx", C.c_int32), ("reserved", C.c_int32),
+                ("F", C.c_int32), ("act", C.c_int32), ("idx", C.c_int32), ("flags", C.c_int32),
                 ("idx_token_stride", C.c_int64)]
 
 
@@ -129,6 +130,20 @@ def combine(D, Yp, gates, inv_perm, y):
     _check(lib().r3_combine(C.byref(D), _p(Yp), _p(gates), _p(inv_perm), _p(y), _stream()), "r3_combine")
 
 
+def moe_forward(D, x, W_r, idx, W_gate, W_up, W_down, y, gates, counts, offsets, inv_perm, perm, Yp, H, ws,
+                FA_save=None, FB_save=None, bias=None, logits_out=None, agree_out=None, status=None):
+    """The replayed forward in one call; H and Yp come out gate-scaled (differentiate with gated_desc(D))."""
+    _check(lib().r3_moe_forward(C.byref(D), _p(x), _p(W_r), _p(bias), _p(idx), _p(W_gate), _p(W_up), _p(W_down),
+                                _p(y), _p(gates), _p(counts), _p(offsets), _p(inv_perm), _p(perm), _p(Yp), _p(H),
+                                _p(FA_save), _p(FB_save), _p(logits_out), _p(agree_out), _p(status), _p(ws),
+                                C.c_size_t(ws.numel()), _stream()), "r3_moe_forward")
+
+
+def gated_desc(D):
+    """A copy of D with R3_FLAG_GATED_H set: what r3_moe_backward takes after r3_moe_forward."""
+    return LayerDesc(D.T, D.d, D.E, D.K, D.F, D.act, D.idx, FLAG_GATED_H, D.idx_token_stride)
+
+
 def moe_backward(D, dy, x, W_r, idx, gates, inv_perm, perm, offsets, Xp, A, B, H, Yp, W_gate, W_up, W_down,
                  dx, dW_r, dW_gate, dW_up, dW_down, ws, dbias=None, accumulate=False):
     _check(lib().r3_moe_backward(C.byref(D), _p(dy), _p(x), _p(W_r), _p(idx), _p(gates), _p(inv_perm),
@@ -201,6 +216,8 @@ class LayerBuffers:
         self.ws_gate = workspace(D, OP_REPLAY_GATE, device)
         self.ws_perm = workspace(D, OP_PERMUTE, device)
         self.ws_ffn = workspace(D, OP_GROUPED_FFN, device)
+        self.ws_fwd = None         # made on first use by forward_one_call()
+        self.gated = False         # whether H / Yp hold gate-scaled rows (set by the forward that filled them)
         self.A = self.B = None             # the saved factors FA = B silu'(A), FB = silu(A)
         if backward:
             self.A, self.B = e(S, F), e(S, F)
@@ -213,7 +230,7 @@ class LayerBuffers:
 
 
 def forward(buf, x, W_r, idx, W_gate, W_up, W_down, bias=None, logits_out=None, agree_out=None):
-    """The replayed forward: gate -> permute -> grouped FFN -> combine (four C calls)."""
+    """The replayed forward as four C calls: gate -> permute -> grouped FFN -> combine."""
     D = buf.D
     replay_gate(D, x, W_r, idx, buf.gates, bias=bias, logits_out=logits_out, agree_out=agree_out,
                 status=buf.status, ws=buf.ws_gate)
@@ -221,12 +238,27 @@ def forward(buf, x, W_r, idx, W_gate, W_up, W_down, bias=None, logits_out=None, 
     grouped_ffn(D, buf.Xp, buf.offsets, W_gate, W_up, W_down, buf.Yp, buf.H, buf.A, buf.B, ws=buf.ws_ffn,
                 x=x, perm=buf.perm)
     combine(D, buf.Yp, buf.gates, buf.inv_perm, buf.y)
+    buf.gated = False
+    return buf.y
+
+
+def forward_one_call(buf, x, W_r, idx, W_gate, W_up, W_down, bias=None, logits_out=None, agree_out=None):
+    """The replayed forward as one C call (r3_moe_forward): buf.H and buf.Yp then hold gate-scaled rows."""
+    D = buf.D
+    if buf.ws_fwd is None:
+        buf.ws_fwd = workspace(D, OP_FORWARD, buf.status.device)
+    moe_forward(D, x, W_r, idx, W_gate, W_up, W_down, buf.y, buf.gates, buf.counts, buf.offsets, buf.inv_perm,
+                buf.perm, buf.Yp, buf.H, buf.ws_fwd, FA_save=buf.A, FB_save=buf.B, bias=bias, logits_out=logits_out,
+                agree_out=agree_out, status=buf.status)
+    buf.gated = True
     return buf.y
 
 
 def backward(buf, dy, x, W_r, idx, W_gate, W_up, W_down, dbias=None, accumulate=False):
-    D = buf.D
-    moe_backward(D, dy, x, W_r, idx, buf.gates, buf.inv_perm, buf.perm, buf.offsets, buf.Xp, buf.A, buf.B,
+    """r3_moe_backward on the buffers' saved tensors (told whether the last forward left them gate-scaled)."""
+    D = gated_desc(buf.D) if buf.gated else buf.D
+    moe_backward(D, dy, x, W_r, idx, buf.gates, buf.inv_perm, buf.perm, buf.offsets,
+                 None if buf.gated else buf.Xp, buf.A, buf.B,
                  buf.H, buf.Yp, W_gate, W_up, W_down, buf.dx, buf.dW_r, buf.dW_gate, buf.dW_up, buf.dW_down,
                  buf.ws_bwd, dbias=dbias, accumulate=accumulate)
 

@@ -344,22 +344,66 @@ def test_backward_chain(name, simt):
     sync()
     for k in ("dW_r", "dW_gate", "dW_up", "dW_down"):
         assert torch.allclose(getattr(buf, k), 2 * keep[k], rtol=1e-5, atol=1e-6 * float(keep[k].abs().max())), k
-    # without the gathered copy of the tokens: forward and backward read x through perm inside the expert
-    # GEMMs' tile loads; every result is the same bit for bit (MFMA shapes; the others say unsupported)
+    # without the gathered copy of the tokens: forward and backward read x through perm (inside the expert
+    # GEMMs' tile loads, or row by row in the plain kernels); every result is the same bit for bit
     buf2 = r3.LayerBuffers(c.D, backward=True, gathered_copy=False)
-    mfma = name.startswith("mfma") and not simt
-    if mfma:
-        r3.forward(buf2, c.t["x"], c.t["Wr"], c.t["idx"], c.t["Wg"], c.t["Wu"], c.t["Wd"], bias=c.t["bias"])
-        r3.backward(buf2, c.t["dy"], c.t["x"], c.t["Wr"], c.t["idx"], c.t["Wg"], c.t["Wu"], c.t["Wd"])
-        sync()
-        assert buf2.Xp is None and int(buf2.status.item()) == 0
-        for k, v in keep.items():
-            assert torch.equal(getattr(buf2, k), v), k
-    else:
-        r3.forward(buf2, c.t["x"], c.t["Wr"], c.t["idx"], c.t["Wg"], c.t["Wu"], c.t["Wd"], bias=c.t["bias"])
-        with pytest.raises(r3.R3Error, match="UNSUPPORTED"):
-            r3.backward(buf2, c.t["dy"], c.t["x"], c.t["Wr"], c.t["idx"], c.t["Wg"], c.t["Wu"], c.t["Wd"])
-        sync()
+    r3.forward(buf2, c.t["x"], c.t["Wr"], c.t["idx"], c.t["Wg"], c.t["Wu"], c.t["Wd"], bias=c.t["bias"])
+    r3.backward(buf2, c.t["dy"], c.t["x"], c.t["Wr"], c.t["idx"], c.t["Wg"], c.t["Wu"], c.t["Wd"])
+    sync()
+    assert buf2.Xp is None and int(buf2.status.item()) == 0
+    for k, v in keep.items():
+        assert torch.equal(getattr(buf2, k), v), k
+
+
+@pytest.mark.parametrize("name,simt", [("config1_f32", False), ("odd_bf16", False), ("mfma_small", False),
+                                       ("mfma_ragged", False), ("mfma_fewexperts", False), ("mfma_small", True),
+                                       ("mfma_u16", False), ("mfma_wide", False), ("mfma_tall", False)])
+def test_one_call_forward_and_its_backward(name, simt):
+    """r3_moe_forward (gate folded into the expert network: H and Yp come out gate-scaled, the combination
+    is a plain sum) and r3_moe_backward told so, against the oracle's forward and backward."""
+    if simt:
+        os.environ["R3_FORCE_SIMT"] = "1"
+    c = Case(SHAPES[name], backward=True, scale_w=5.0)
+    n, sh = c.np, c.shape
+    fwd = sparse.forward(n["x"], n["Wr"], c.idx, n["Wg"], n["Wu"], n["Wd"], n["bias"])
+    ref = sparse.backward(n["dy"], n["x"], n["Wr"], c.idx, n["Wg"], n["Wu"], n["Wd"], fwd, want_dbias=True)
+    buf = r3.LayerBuffers(c.D, backward=True, gathered_copy=False)
+    agree = torch.zeros(2, dtype=torch.int64, device="cuda")
+    r3.forward_one_call(buf, c.t["x"], c.t["Wr"], c.t["idx"], c.t["Wg"], c.t["Wu"], c.t["Wd"], bias=c.t["bias"],
+                        agree_out=agree)
+    sync()
+    assert int(buf.status.item()) == 0
+    for k in ("counts", "offsets", "inv_perm", "perm"):
+        assert np.array_equal(getattr(buf, k).cpu().numpy(), fwd[k]), k
+    assert_gates_close(buf.gates.cpu().numpy(), fwd["g"])
+    grow = fwd["g"].reshape(-1)[fwd["perm"]]                       # the gate of every expert-sorted row
+    assert_close(host(buf.H), grow[:, None] * fwd["h"], "g*H", c.rel)
+    assert_close(host(buf.Yp), grow[:, None] * fwd["o"], "g*o", c.rel)
+    assert_close(host(buf.y), fwd["y"], "y", c.rel)
+    assert 0 < int(agree[0]) <= sh.T and int(agree[1]) <= sh.T * sh.K
+    dbias = torch.zeros(sh.E, dtype=torch.float32, device="cuda")
+    r3.backward(buf, c.t["dy"], c.t["x"], c.t["Wr"], c.t["idx"], c.t["Wg"], c.t["Wu"], c.t["Wd"], dbias=dbias)
+    sync()
+    assert buf.gated
+    assert_close(host(buf.dx), ref["dx"], "dx", c.rel)
+    sig_w, sig_b = (None, None) if sh.act == "f32" else router_gradient_sigma(n["x"], n["dy"], c.idx, fwd, sh.E)
+    assert_close(buf.dW_r.cpu().numpy(), ref["dWr"], "dW_r", c.rel, sig_w)
+    assert_close(dbias.cpu().numpy(), ref["dbias"], "dbias", c.rel, sig_b)
+    for got, key in ((buf.dW_gate, "dWg"), (buf.dW_up, "dWu"), (buf.dW_down, "dWd")):
+        got = got.cpu().numpy()
+        for e in range(sh.E):
+            if fwd["counts"][e] == 0:
+                assert not got[e].any(), (key, e)
+            else:   # per expert tensor, norm-wise (an expert with two or three rows has no element scale)
+                nr = np.linalg.norm(ref[key][e])
+                assert np.linalg.norm(got[e] - ref[key][e]) <= c.rel * nr + 1e-30, (key, e)
+    # a second pass over the same buffers is bit-identical
+    keep = {k: getattr(buf, k).clone() for k in ("y", "dx", "dW_r", "dW_gate", "dW_up", "dW_down")}
+    r3.forward_one_call(buf, c.t["x"], c.t["Wr"], c.t["idx"], c.t["Wg"], c.t["Wu"], c.t["Wd"], bias=c.t["bias"])
+    r3.backward(buf, c.t["dy"], c.t["x"], c.t["Wr"], c.t["idx"], c.t["Wg"], c.t["Wu"], c.t["Wd"])
+    sync()
+    for k, v in keep.items():
+        assert torch.equal(getattr(buf, k), v), k
 
 
 def test_router_gradient_is_zero_off_the_replayed_set():
