@@ -463,6 +463,7 @@ wgrad_kernel(int E, int NQd, int NPd, const bf16_t *__restrict__ Qs, const bf16_
     __shared__ __attribute__((aligned(1024))) char s2[kStageBytes];
     __shared__ __attribute__((aligned(1024))) char s3[kStageBytes];
     __shared__ int mailbox[2];
+    __shared__ __attribute__((aligned(256))) char ring[GATHER ? kIndexRingBytes : 16];
     const int nqt = NQd / kTile, npt = NPd / kTile;
     const int wp0 = (threadIdx.x >> 6) % kWP2, wq0 = (threadIdx.x >> 6) / kWP2;
     // operands are set up once; a tile only moves their source windows (column offset included)
@@ -470,7 +471,7 @@ wgrad_kernel(int E, int NQd, int NPd, const bf16_t *__restrict__ Qs, const bf16_
     OpTR256 Q;
     Q.kswitch = 0x7fffffff;
     if constexpr (GATHER) {
-        P.init(NPd * 2, 128 * wp0);
+        P.init(NPd * 2, 128 * wp0, ring);
     } else {
         P.kswitch = 0x7fffffff;
         P.init(NPd * 2, 0, 128 * wp0);
@@ -549,6 +550,7 @@ wgrad_pair_kernel(int E, int NQd, int NPd, const bf16_t *__restrict__ Qs, const 
     __shared__ __attribute__((aligned(1024))) char s2[kStageBytes];
     __shared__ __attribute__((aligned(1024))) char s3[kStageBytes];
     __shared__ int mailbox[2];
+    __shared__ __attribute__((aligned(256))) char ring[GATHER ? kIndexRingBytes : 16];
     constexpr int BF = 128;  // features of P0 (and of P1) per tile
     const int nqt = NQd / kTile, npt = NPd / BF;
     const int wp0 = (threadIdx.x >> 6) % kWP2, wq0 = (threadIdx.x >> 6) / kWP2;
@@ -556,7 +558,7 @@ wgrad_pair_kernel(int E, int NQd, int NPd, const bf16_t *__restrict__ Qs, const 
     P.init(NPd * 2, 0, 64 * wp0);
     typename std::conditional<GATHER, OpTR256G, OpTR256>::type Q;
     if constexpr (GATHER) {
-        Q.init(NQd * 2, kWaveRowsQ * wq0);
+        Q.init(NQd * 2, kWaveRowsQ * wq0, ring);
     } else {
         Q.kswitch = 0x7fffffff;
         Q.init(NQd * 2, 0, kWaveRowsQ * wq0);

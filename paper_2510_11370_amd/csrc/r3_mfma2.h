@@ -55,7 +55,6 @@ constexpr int kReadsPerMfma = 1;
 #endif
 constexpr int kLoaderWaves = 4;
 constexpr int kWaveRowsQ = 32 * kTQ2;            // output rows (Q) per wave
-constexpr int kLoadsPerStage = 8;                // buffer loads per loader wave per stage (4 per operand)
 constexpr uint32_t kRsrcFlags = 0x00020000u;
 
 typedef __attribute__((address_space(3))) void *lds_void_ptr;
@@ -166,6 +165,7 @@ struct DmaTR {
 // A second Src set takes over from k-tile `kswitch` on (two-phase reductions).
 struct OpKC256 {
     static constexpr bool kIndexed = false, kWindowed = false;
+    static constexpr int kLoads = 4;
     static constexpr int kDsReads = kTP2, kDsReadsQ = kTQ2;  // ds_read_b128 per sub-step as P / as Q
     Src src[2];
     int kswitch;
@@ -185,6 +185,7 @@ struct OpKC256 {
 
 struct OpTR256 {
     static constexpr bool kIndexed = false, kWindowed = false;
+    static constexpr int kLoads = 4;
     static constexpr int kDsReads = 2 * kTP2, kDsReadsQ = 2 * kTQ2;  // two ds_read_b64_tr_b16 per fragment
     Src src[2];
     int kswitch;
@@ -204,6 +205,7 @@ struct OpTR256 {
 
 struct OpTR128x2 {
     static constexpr bool kIndexed = false, kWindowed = false;
+    static constexpr int kLoads = 4;
     static constexpr int kDsReads = 2 * kTP2, kDsReadsQ = 2 * kTQ2;
     Src src[2];  // sub-tile 0, sub-tile 1
     DmaTR<128> dma;
@@ -223,42 +225,45 @@ struct OpTR128x2 {
 
 // Transposed 256-feature tile whose k-rows are gathered through an index: k-row r of the reduction is
 // row rows[r] of a row-major matrix of `ld_bytes` per row, so a permuted copy of that matrix never has
-// to exist.  A chunk of the tile is two k-rows; their two indices are fetched with scalar loads one
-// stage ahead of the tile loads that use them (scalar loads do not touch the vector-memory counter
-// that paces the stages), and each lane builds its own row address.  k-rows >= n read as zero (an
-// offset outside the buffer window).  `rows` must be readable up to index n (one past the live rows).
+// to exist.  A chunk of the tile is two k-rows, and a loader wave owns four chunks of a stage, i.e. eight
+// consecutive entries of the index list.  Those eight entries travel like the tiles do: two stages
+// ahead of the tile loads that use them, one more buffer load per loader wave per stage brings them
+// straight into a small LDS ring of the wave's own (counted by the same vector-memory counter that
+// paces the stages, so they have landed when the stage barrier lets the wave go on); the wave reads
+// its four entries back with one LDS read and each lane builds its own row address.  (With scalar
+// loads instead the compiler waits for them right where they are issued, every stage: measured 19 %
+// on the long reductions of a skewed batch.)  Only the first two stages of a tile, which nothing ran
+// ahead of, take their entries with scalar loads.  k-rows >= n read as zero (an offset outside the
+// buffer window).  `rows` must be readable up to index n + 7.
 typedef const __attribute__((address_space(4))) int32_t *const_i32_ptr;
+constexpr int kIndexRingBytes = kLoaderWaves * 4 * 256;  // per loader wave: four slots of one 64-lane dword load
 struct OpTR256G {
     static constexpr int kDsReads = 2 * kTP2, kDsReadsQ = 2 * kTQ2;
     static constexpr bool kIndexed = true, kWindowed = false;
+    static constexpr int kLoads = 5;             // four tile loads and one index load
     static constexpr int kOutside = 0x7ffffff0;  // beyond any window (windows are < 2^31 bytes)
-    rsrc_t rs;
+    rsrc_t rs, rsi;        // the matrix; the tile's index list
     const_i32_ptr rows;
     int n, ld_bytes, wl;
+    uint32_t ring;         // LDS address of this wave's ring
     int cvoff[4];
-    mutable int pend[8];   // indices of this wave's eight k-rows of the next stage to issue
     TrFrag<256> fr;
-    __device__ __forceinline__ void init(int ld_bytes_, int wave_base) {
+    __device__ __forceinline__ void init(int ld_bytes_, int wave_base, const void *ring_base) {
         wl = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6) & 3);
+        ring = __builtin_amdgcn_readfirstlane((int)(lds_addr(ring_base) + 1024u * wl));
         ld_bytes = ld_bytes_;
         fr.init(wave_base);
-    }
-    // loader wave wl owns chunks 4 wl .. 4 wl + 3 of a stage, i.e. k-rows 8 wl .. 8 wl + 7: eight
-    // consecutive entries of the index list (past the live rows the base is held at n: unused values)
-    __device__ __forceinline__ void fetch(int kt) const {
-        const int base = min(kt * kBK2 + 8 * wl, n);
-#pragma unroll
-        for (int j = 0; j < 8; ++j) pend[j] = rows[base + j];
     }
     // point at a tile: the whole matrix (`bytes` < 2^31), feature offset col_bytes, index list, live k-rows
     __device__ __forceinline__ void aim(const void *matrix, uint64_t bytes, int col_bytes, const int32_t *rows_, int n_) {
         rs = src_rsrc(Src{(const char *)matrix, bytes, 0u}, 0);
-        // wave-uniform by construction (a tile's coordinates); said so, so that the index fetches are
-        // scalar loads -- as vector loads they would count against the stage pacing
+        n = __builtin_amdgcn_readfirstlane(n_);
+        rsi = src_rsrc(Src{(const char *)rows_, (uint64_t)(n + 8) * 4u, 0u}, 0);
+        // wave-uniform by construction (a tile's coordinates); said so, so that the first stages'
+        // index fetches are scalar loads
         const uint64_t ra = (uint64_t)rows_;
         rows = (const_i32_ptr)(((uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(ra >> 32)) << 32) |
                                (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)ra));
-        n = __builtin_amdgcn_readfirstlane(n_);
         col_bytes = __builtin_amdgcn_readfirstlane(col_bytes);
         const int lane = threadIdx.x & 63, pc = lane & 31;
 #pragma unroll
@@ -266,27 +271,52 @@ struct OpTR256G {
             const int k = 2 * i + (lane >> 5);   // k-row within the wave's eight; 8 wl does not change k & 3
             cvoff[i] = col_bytes + ((((pc >> 2) ^ (k & 3)) << 2) | (pc & 3)) * 16;
         }
-        fetch(0);
     }
+    // The wave's eight entries of stage kt into ring slot kt & 3.  Lane p < 8 fetches the entry of
+    // k-row 2 (p & 3) + (p >> 2), so that the four entries a half-wave needs (it loads the even or the
+    // odd k-rows of the wave's chunks) lie side by side; the other lanes point outside the window and
+    // store zeros.  Past the live rows the base is held at n: unused values.
+    __device__ __forceinline__ void issue_index(int kt) const {
+        const int lane = threadIdx.x & 63;
+        const int base = min(kt * kBK2 + 8 * wl, n);
+        const int voff = lane < 8 ? (base + 2 * (lane & 3) + (lane >> 2)) * 4 : kOutside;
+        const uint32_t m0v = __builtin_amdgcn_readfirstlane(ring + 256u * (kt & 3));
+        asm volatile("s_mov_b32 m0, %0\n\tbuffer_load_dword %1, %2, 0 offen lds" ::"s"(m0v), "v"(voff), "s"(rsi)
+                     : "memory");
+    }
+    __device__ __forceinline__ void chunk_load(int kt, uint32_t tile, int i, int row) const {
+        const int lane = threadIdx.x & 63;
+        const int k = kt * kBK2 + 8 * wl + 2 * i + (lane >> 5);
+        const int voff = k < n ? row * ld_bytes + cvoff[i] : kOutside;
+        lds_load16(rs, tile + 1024 * (4 * wl + i), voff);
+    }
+    // stages 0 and 1 of a tile: entries by scalar loads; the ring is started for stages 2 and 3
+    __device__ __forceinline__ void issue_first(int kt, uint32_t tile) const {
+        const int lane = threadIdx.x & 63;
+        const int base = min(kt * kBK2 + 8 * wl, n);
+        const int e0 = rows[base], e1 = rows[base + 1], e2 = rows[base + 2], e3 = rows[base + 3];
+        const int e4 = rows[base + 4], e5 = rows[base + 5], e6 = rows[base + 6], e7 = rows[base + 7];
+        issue_index(kt + 2);
+        const bool odd = lane & 32;
+        chunk_load(kt, tile, 0, odd ? e1 : e0);
+        chunk_load(kt, tile, 1, odd ? e3 : e2);
+        chunk_load(kt, tile, 2, odd ? e5 : e4);
+        chunk_load(kt, tile, 3, odd ? e7 : e6);
+    }
+    // stage kt >= 2: its entries are in the ring (asked for at stage kt - 2, two stage barriers ago)
     __device__ __forceinline__ void issue(int kt, uint32_t tile) const {
         const int lane = threadIdx.x & 63;
-        // the next stage's indices are asked for first, so that the scalar loads' latency runs
-        // under the address arithmetic and the four tile loads of this stage
-        int nxt[8];
-        {
-            const int base = min((kt + 1) * kBK2 + 8 * wl, n);
-#pragma unroll
-            for (int j = 0; j < 8; ++j) nxt[j] = rows[base + j];
-        }
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const int k = kt * kBK2 + 8 * wl + 2 * i + (lane >> 5);
-            const int row = (lane & 32) ? pend[2 * i + 1] : pend[2 * i];
-            const int voff = k < n ? row * ld_bytes + cvoff[i] : kOutside;
-            lds_load16(rs, tile + 1024 * (4 * wl + i), voff);
-        }
-#pragma unroll
-        for (int j = 0; j < 8; ++j) pend[j] = nxt[j];
+        int4 v;
+        // inline asm: the compiler knows of no store to the ring and would read it once, ahead of the loop
+        asm volatile("ds_read_b128 %0, %1\n\ts_waitcnt lgkmcnt(0)"
+                     : "=v"(v)
+                     : "v"(ring + 256u * (kt & 3) + 16u * (lane >> 5))
+                     : "memory");
+        issue_index(kt + 2);
+        chunk_load(kt, tile, 0, v.x);
+        chunk_load(kt, tile, 1, v.y);
+        chunk_load(kt, tile, 2, v.z);
+        chunk_load(kt, tile, 3, v.w);
     }
     __device__ __forceinline__ bf16x8_t frag(const char *tile, int t, int s) const { return fr.read(tile, t, s); }
 };
@@ -362,12 +392,19 @@ __device__ __forceinline__ void stage_compute(Acc2 &acc, Frags &x, Frags &y, con
 // of the next stage has landed); everyone waits for its LDS reads; then the waves meet.  A
 // bare s_barrier is used on purpose: __syncthreads() carries a fence for which the compiler
 // drains every outstanding load, including the ones just issued two stages ahead.
+template <int vm>   // vm: buffer loads per loader wave per stage (both operands)
 __device__ __forceinline__ void stage_barrier(bool loader) {
     // s_waitcnt simm16: vmcnt[3:0] | expcnt[6:4] | lgkmcnt[11:8] | vmcnt_hi[15:14]
-    constexpr int vm = kLoadsPerStage;
     if (loader) __builtin_amdgcn_s_waitcnt((vm & 15) | (7 << 4) | (0 << 8) | ((vm >> 4) << 14));
     else __builtin_amdgcn_s_waitcnt(15 | (7 << 4) | (0 << 8) | (3 << 14));
     __builtin_amdgcn_s_barrier();
+}
+
+// stage 0 or 1 of a tile for either operand kind
+template <class Op>
+__device__ __forceinline__ void issue_first(const Op &op, int kt, uint32_t tile) {
+    if constexpr (Op::kIndexed) op.issue_first(kt, tile);
+    else op.issue(kt, tile);
 }
 
 // nk k-tiles of 32.  st0..st3: the four 32 KB LDS stages (distinct arrays).
@@ -378,6 +415,7 @@ template <class POp, class QOp>
 __device__ __forceinline__ void mfma_mainloop2(Acc2 &acc, int nk, const POp &P, const QOp &Q, char *st0, char *st1,
                                                char *st2, char *st3, int live_rows = kTile) {
     if (nk <= 0) return;
+    constexpr int NL = POp::kLoads + QOp::kLoads;
     const uint32_t a0 = lds_addr(st0), a1 = lds_addr(st1), a2 = lds_addr(st2), a3 = lds_addr(st3);
     const int wave_ = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
     // wave-uniform, and visibly so (scalar branch instead of exec masking)
@@ -385,21 +423,21 @@ __device__ __forceinline__ void mfma_mainloop2(Acc2 &acc, int nk, const POp &P, 
     if ((wave_ / kWP2) * kWaveRowsQ >= live_rows) {
         // this wave's rows are not needed: keep the loads (if it is a loader) and the barriers going
         if (loader) {
-            P.issue(0, a0);
-            Q.issue(0, a0 + kOperandBytes);
-            P.issue(1, a1);
-            Q.issue(1, a1 + kOperandBytes);
+            issue_first(P, 0, a0);
+            issue_first(Q, 0, a0 + kOperandBytes);
+            issue_first(P, 1, a1);
+            issue_first(Q, 1, a1 + kOperandBytes);
         }
-        stage_barrier(loader);
+        stage_barrier<NL>(loader);
         for (int kt = 0; kt < nk; kt += 4) {
             if (loader) { P.issue(kt + 2, a2); Q.issue(kt + 2, a2 + kOperandBytes); }
-            stage_barrier(loader);
+            stage_barrier<NL>(loader);
             if (loader && kt + 1 < nk) { P.issue(kt + 3, a3); Q.issue(kt + 3, a3 + kOperandBytes); }
-            stage_barrier(loader);
+            stage_barrier<NL>(loader);
             if (loader && kt + 2 < nk) { P.issue(kt + 4, a0); Q.issue(kt + 4, a0 + kOperandBytes); }
-            stage_barrier(loader);
+            stage_barrier<NL>(loader);
             if (loader && kt + 3 < nk) { P.issue(kt + 5, a1); Q.issue(kt + 5, a1 + kOperandBytes); }
-            stage_barrier(loader);
+            stage_barrier<NL>(loader);
         }
         __builtin_amdgcn_s_waitcnt(0 | (7 << 4) | (15 << 8));
         __builtin_amdgcn_s_barrier();
@@ -413,17 +451,17 @@ __device__ __forceinline__ void mfma_mainloop2(Acc2 &acc, int nk, const POp &P, 
 #pragma nounroll
             for (int st = 0; st < 2; ++st) {
                 const uint32_t a = st == 0 ? a0 : a1;
-                P.issue(st, a);
-                Q.issue(st, a + kOperandBytes);
+                issue_first(P, st, a);
+                issue_first(Q, st, a + kOperandBytes);
             }
         } else {
-            P.issue(0, a0);
-            Q.issue(0, a0 + kOperandBytes);
-            P.issue(1, a1);
-            Q.issue(1, a1 + kOperandBytes);
+            issue_first(P, 0, a0);
+            issue_first(Q, 0, a0 + kOperandBytes);
+            issue_first(P, 1, a1);
+            issue_first(Q, 1, a1 + kOperandBytes);
         }
     }
-    stage_barrier(loader);
+    stage_barrier<NL>(loader);
     Frags x, y;
 #pragma unroll
     for (int i = 0; i < kTP2; ++i) x.a[i] = bf16x8_t{};
@@ -432,13 +470,13 @@ __device__ __forceinline__ void mfma_mainloop2(Acc2 &acc, int nk, const POp &P, 
     // single loop exit (no break) keeps the accumulators in place
     for (int kt = 0; kt < nk; kt += 4) {
         stage_compute(acc, x, y, P, Q, st0, kt + 2, a2, loader);
-        stage_barrier(loader);
+        stage_barrier<NL>(loader);
         if (kt + 1 < nk) stage_compute(acc, x, y, P, Q, st1, kt + 3, a3, loader);
-        stage_barrier(loader);
+        stage_barrier<NL>(loader);
         if (kt + 2 < nk) stage_compute(acc, x, y, P, Q, st2, kt + 4, a0, loader);
-        stage_barrier(loader);
+        stage_barrier<NL>(loader);
         if (kt + 3 < nk) stage_compute(acc, x, y, P, Q, st3, kt + 5, a1, loader);
-        stage_barrier(loader);
+        stage_barrier<NL>(loader);
     }
     mfma_block(acc, x);
     // loads for stages past the end are still in flight: drain them, and meet, before anyone
