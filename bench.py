@@ -54,15 +54,16 @@ def kernel_work(sh, idx_bytes=1):
     }
 
 
-def gemm_bytes(sh, backward):
-    """Algorithmic HBM bytes of one launch of each expert GEMM (operands once in, results once out)."""
+def gemm_bytes(sh, backward, gated=True):
+    """Algorithmic HBM bytes of one launch of each expert GEMM (operands once in, results once out).
+    gated: H was saved with the gate folded in (one-call forward), so the backward writes no g*H."""
     d, E, F = sh.d, sh.E, sh.F
     S = sh.T * sh.K
     W = E * d * F * 2
     return {
         "ffn1_swiglu": S * d * 2 + 2 * W + (3 if backward else 1) * S * F * 2,
         "ffn2_down": S * F * 2 + W + S * d * 2,
-        "ffn_dh": S * d * 2 + W + 6 * S * F * 2,               # FA, FB, H in; dA, dB, g*H out
+        "ffn_dh": S * d * 2 + W + (5 if gated else 6) * S * F * 2,   # FA, FB, H in; dA, dB (and g*H) out
         "ffn_wgrad_down": (S * d + S * F) * 2 + 2 * W,          # f32 gradient out
         "ffn_wgrad_gate_up": (S * d + 2 * S * F) * 2 + 4 * W,
         "ffn_dxp": 2 * S * F * 2 + 2 * W + S * d * 2,
@@ -372,7 +373,7 @@ def run_layer(args, workload, torch, r3, synth, calib_copy=False):
 
     ms_per_step = wall * 1e3 / args.steps
     work = kernel_work(sh, 1 if D.idx == r3.IDX_U8 else 2)
-    gbytes = gemm_bytes(sh, bwd)
+    gbytes = gemm_bytes(sh, bwd, gated=fwd_call is r3.forward_one_call)
     kernels = {}
     for name, (ms, n) in prof.items():
         kind, amount = work[name]
