@@ -219,7 +219,7 @@ int r3_grouped_ffn(const r3_layer_desc *desc, const void *Xp, const void *x, con
     if (use_mfma_ffn(m)) {
         if (!ws || ws_bytes < mfma_tiles_bytes(m.S, m.E) || !aligned(ws, 256)) return R3_ERR_WORKSPACE;
         int32_t *tiles = (int32_t *)ws;
-        if (mfma_build_tiles(m.E, offsets, tiles, s) != hipSuccess) return R3_ERR_HIP;
+        if (mfma_build_tiles(m.E, offsets, tiles, -1, s) != hipSuccess) return R3_ERR_HIP;
         return hip_rc(mfma_ffn_forward(m.S, m.d, m.E, m.F, rows, via, m.K, m.T, offsets, tiles, W_gate, W_up, W_down,
                                        Yp, H, FA_save, FB_save, nullptr, s));
     }
@@ -274,7 +274,7 @@ int r3_moe_forward(const r3_layer_desc *desc, const void *x, const void *W_r, co
     if (mfma_row_tokens((int)m.S, m.K, perm, gates, tok, grow, s) != hipSuccess) return R3_ERR_HIP;
     if (use_mfma_ffn(m)) {
         int32_t *tiles = (int32_t *)(base + w.ffn);
-        if (mfma_build_tiles(m.E, offsets, tiles, s) != hipSuccess) return R3_ERR_HIP;
+        if (mfma_build_tiles(m.E, offsets, tiles, -1, s) != hipSuccess) return R3_ERR_HIP;
         if (mfma_ffn_forward(m.S, m.d, m.E, m.F, x, perm, m.K, m.T, offsets, tiles, W_gate, W_up, W_down, Yp, H,
                              FA_save, FB_save, grow, s) != hipSuccess)
             return R3_ERR_HIP;
@@ -329,15 +329,19 @@ int r3_moe_backward(const r3_layer_desc *desc, const void *dy, const void *x, co
         float *grow = (float *)(base + w.grow), *wpart = (float *)(base + w.wpart);
         void *Hg = gated ? nullptr : base + w.Hg;
         if (mfma_row_tokens(S, m.K, perm, gates, tok, grow, s) != hipSuccess) return R3_ERR_HIP;
-        if (mfma_build_tiles(m.E, offsets, tiles, s) != hipSuccess) return R3_ERR_HIP;
+        // a heavily loaded expert's dW_down reduction is cut into parts; their partial products sit in
+        // the dXp buffer, which nothing uses before the parts are summed
+        const size_t slot_bytes = (size_t)m.F * m.d * sizeof(float);
+        const int split = mfma_wgrad_split_rows(m.S, (m.F / 256) * (m.d / 256), (size_t)m.S * m.d * m.eb, slot_bytes);
+        if (mfma_build_tiles(m.E, offsets, tiles, split, s) != hipSuccess) return R3_ERR_HIP;
         if (mfma_ffn_dh(m.S, m.d, m.E, m.F, dy, tok, m.T, grow, offsets, tiles, W_down, FA, FB, H, dA, dB, Hg, wpart,
                         s) != hipSuccess)
             return R3_ERR_HIP;
         if (launch_gate_backward_parts(m.T, m.E, m.K, row_parts(m), wpart, gates, inv_perm, idx, m.idx, m.stride, dz,
                                        ds, s) != hipSuccess)
             return R3_ERR_HIP;
-        if (mfma_wgrad(m.E, m.F, m.d, gated ? H : Hg, dy, tok, m.T, offsets, tiles, 2, dW_down, accumulate, s) !=
-            hipSuccess)
+        if (mfma_wgrad(m.E, m.F, m.d, gated ? H : Hg, dy, tok, m.T, tiles, 2, dW_down, split ? (float *)dXp : nullptr,
+                       accumulate, s) != hipSuccess)
             return R3_ERR_HIP;
         if (mfma_wgrad_pair(m.E, m.d, m.F, Xp ? Xp : x, Xp ? nullptr : tok, m.T, dA, dB, offsets, tiles, 3, dW_gate,
                             dW_up, accumulate, s) != hipSuccess)

@@ -16,41 +16,109 @@
 namespace r3 {
 
 // ---------------------------------------------------------------------------
-// Row-tile table: tiles[0] = number of tiles, tiles[2 .. 2+64) = the tile counters of up to
-// eight persistent launches (8 XCDs each, zeroed here), tiles[66 .. 66+kMaxE) = the experts in
-// descending order of row count (ties by id), then (expert, row0) pairs from tiles[kTileHdr].
-// One block; row tiles list experts in ascending order, rows ascending.
-// The weight-gradient kernels, whose tiles last as long as their expert has rows, take experts in
-// that order (dealt out evenly to the 8 XCD shares of the tile list): with the shared tile
-// counter that is longest-first scheduling, and a heavily loaded expert no longer starts late
-// and finishes alone.
+// Tile table, built by one block per pass:
+//   tiles[0] = number of row tiles; tiles[1] = number of reduction segments (a multiple of 8);
+//   tiles[2 .. 2+64) = the tile counters of up to eight persistent launches (8 XCDs each, zeroed here);
+//   tiles[kTileOrder ..) = the experts in descending order of row count (ties by id), dealt out evenly
+//     to the 8 XCD shares of a tile list;
+//   tiles[kTileSeg ..)  = reduction segments (expert, row0, row1, slot), longest first, dealt the same way;
+//   tiles[kTileHot ..)  = number of split experts, then (expert, first slot, slots) for each;
+//   tiles[kTileHdr ..)  = row tiles as (expert, row0) pairs, experts ascending, rows ascending.
+// The weight-gradient kernels' tiles last as long as their expert has rows: taken longest first from a
+// shared counter, a heavily loaded expert no longer starts late and finishes alone.  A segment is an
+// expert's whole row range, or, when `split_rows` > 0, one of ceil(n / split_rows) equal parts of it
+// (a multiple of 32 rows each): under a skewed load one expert's reduction can be longer than a compute
+// unit's fair share of the whole launch, and no order of whole experts balances that.  Part 0 of an
+// expert has slot -1 (its product goes to the gradient itself), part p > 0 has its own slot >= 0 in a
+// scratch array of partial products, which a second launch adds to the gradient in slot order, so the
+// result does not depend on which work-group ran what.  Segments that only pad the list to a multiple of
+// 8 have slot -2 and are skipped.  At most kMaxSplitSlots slots are handed out (the caller's split_rows
+// >= S / kMaxSplitSlots guarantees that this is never the binding limit).
 // ---------------------------------------------------------------------------
 constexpr int kRowTokensPad = 64;   // zeros after the row->token list
+constexpr int kMaxSplitSlots = 32;
+constexpr int kMaxSegs = kMaxE + kMaxSplitSlots + 8;
 constexpr int kTileOrder = 2 + 64;
-constexpr int kTileHdr = kTileOrder + kMaxE;
+constexpr int kTileSeg = kTileOrder + kMaxE;
+constexpr int kTileHot = kTileSeg + 4 * kMaxSegs;
+constexpr int kTileHdr = kTileHot + 1 + 3 * kMaxSplitSlots + 3;
 __device__ __forceinline__ int *tile_counters(const int32_t *tiles, int launch) {
     return const_cast<int *>(tiles) + 2 + 8 * launch;
 }
+// position of the item of rank `rank` among n (a multiple of 8) when the list is cut into 8 contiguous
+// shares: dealt in serpentine order, so that every share holds an equal mix, heaviest first
+__device__ __forceinline__ int dealt_position(int rank, int n) {
+    const int j = rank >> 3, c = rank & 7;
+    return ((j & 1) ? 7 - c : c) * (n >> 3) + j;
+}
 __global__ void __launch_bounds__(1024)
-build_row_tiles_kernel(int E, int BQ, const int32_t *__restrict__ offsets, int32_t *__restrict__ tiles) {
+build_row_tiles_kernel(int E, int BQ, const int32_t *__restrict__ offsets, int32_t *__restrict__ tiles,
+                       int split_rows) {
     __shared__ int32_t start[kMaxE + 1];
     __shared__ int32_t off[kMaxE + 1];
+    __shared__ int32_t seg0[kMaxE + 1];     // first segment of expert e
+    __shared__ int32_t seglen[kMaxSegs];    // rows of every segment (-1: padding)
+    __shared__ int32_t nseg_s;
     // the offsets come in once, in parallel (read one by one by a single thread they cost a memory
     // round trip each, and this kernel sits between two others on every pass)
     for (int e = threadIdx.x; e <= E; e += blockDim.x) off[e] = offsets[e];
     __syncthreads();
-    // row tiles per expert (the division in parallel), then one thread adds them up
-    for (int e = threadIdx.x; e < E; e += blockDim.x) start[e + 1] = (off[e + 1] - off[e] + BQ - 1) / BQ;
+    // Row tiles, parts and split experts per expert, then their running sums over the experts: every
+    // thread takes kMaxE / 1024 neighbouring experts and the block scans the threads' totals.  (One
+    // thread adding them up one after the other pays an LDS round trip per expert: 6 us for 128 experts,
+    // in a kernel that sits between two others on every pass.)
+    constexpr int PER = kMaxE / 1024;
+    __shared__ int32_t scan[3][1024];
+    int nt[PER], np[PER], tot[3] = {0, 0, 0};
+#pragma unroll
+    for (int i = 0; i < PER; ++i) {
+        const int e = PER * threadIdx.x + i;
+        const int n = e < E ? off[e + 1] - off[e] : 0;
+        nt[i] = e < E ? (n + BQ - 1) / BQ : 0;
+        np[i] = e < E ? (split_rows > 0 ? max(1, (n + split_rows - 1) / split_rows) : 1) : 0;
+        tot[0] += nt[i];
+        tot[1] += np[i];
+        tot[2] += np[i] > 1;
+    }
+    for (int k = 0; k < 3; ++k) scan[k][threadIdx.x] = tot[k];
     __syncthreads();
-    if (threadIdx.x == 0) {
-        int run = 0;
-        start[0] = 0;
-        for (int e = 1; e <= E; ++e) {
-            run += start[e];
-            start[e] = run;
+    for (int dlt = 1; dlt < 1024; dlt <<= 1) {
+        int v[3];
+        for (int k = 0; k < 3; ++k) v[k] = (int)threadIdx.x >= dlt ? scan[k][threadIdx.x - dlt] : 0;
+        __syncthreads();
+        for (int k = 0; k < 3; ++k) scan[k][threadIdx.x] += v[k];
+        __syncthreads();
+    }
+    // more parts than there are slots for (the caller's split_rows rules that out): no splitting at all
+    const bool split = scan[1][1023] - E <= kMaxSplitSlots;
+    {
+        int run[3];
+        for (int k = 0; k < 3; ++k) run[k] = scan[k][threadIdx.x] - tot[k];   // exclusive
+#pragma unroll
+        for (int i = 0; i < PER; ++i) {
+            const int e = PER * threadIdx.x + i;
+            if (e < E) {
+                start[e] = run[0];
+                seg0[e] = split ? run[1] : e;
+                if (split && np[i] > 1) {   // slots are handed out in expert order: segments before e minus experts before e
+                    tiles[kTileHot + 1 + 3 * run[2]] = e;
+                    tiles[kTileHot + 2 + 3 * run[2]] = run[1] - e;
+                    tiles[kTileHot + 3 + 3 * run[2]] = np[i] - 1;
+                }
+            }
+            run[0] += nt[i];
+            run[1] += np[i];
+            run[2] += np[i] > 1;
         }
-        tiles[0] = run;
-        tiles[1] = 0;
+    }
+    if (threadIdx.x == 1023) {
+        const int segs = split ? scan[1][1023] : E;
+        start[E] = scan[0][1023];
+        seg0[E] = segs;
+        tiles[0] = scan[0][1023];
+        tiles[kTileHot] = split ? scan[2][1023] : 0;
+        nseg_s = (segs + 7) & ~7;
+        tiles[1] = nseg_s;
     }
     if (threadIdx.x < 64) tiles[2 + threadIdx.x] = 0;
     for (int e = threadIdx.x; e < E; e += blockDim.x) {
@@ -60,14 +128,7 @@ build_row_tiles_kernel(int E, int BQ, const int32_t *__restrict__ offsets, int32
             const int m = off[o + 1] - off[o];
             rank += (m > n) || (m == n && o < e);
         }
-        // the tile list is cut into 8 contiguous XCD shares: deal the ranked experts out to the
-        // shares in serpentine order, so that every share holds an equal mix, heaviest first
-        int pos = rank;
-        if (E % 8 == 0) {
-            const int j = rank >> 3, c = rank & 7;
-            pos = ((j & 1) ? 7 - c : c) * (E >> 3) + j;
-        }
-        tiles[kTileOrder + pos] = e;
+        tiles[kTileOrder + (E % 8 == 0 ? dealt_position(rank, E) : rank)] = e;
     }
     __syncthreads();
     for (int e = threadIdx.x; e < E; e += blockDim.x) {
@@ -77,6 +138,39 @@ build_row_tiles_kernel(int E, int BQ, const int32_t *__restrict__ offsets, int32
             tiles[kTileHdr + 1 + 2 * (start[e] + i)] = off[e] + i * BQ;
         }
     }
+    if (split_rows < 0) return;   // (a pass with no weight gradients needs no segments)
+    const int nseg = nseg_s;
+    // part lengths: equal parts, a multiple of 32 rows, the last one takes what is left
+    for (int e = threadIdx.x; e < E; e += blockDim.x) {
+        const int n = off[e + 1] - off[e], parts = seg0[e + 1] - seg0[e];
+        const int len = parts > 1 ? ((n + parts - 1) / parts + 31) & ~31 : n;
+        for (int p = 0; p < parts; ++p) seglen[seg0[e] + p] = max(0, min(len, n - p * len));
+    }
+    for (int i = seg0[E] + threadIdx.x; i < nseg; i += blockDim.x) seglen[i] = -1;
+    __syncthreads();
+    // rank every segment by length (ties by position) and write it where it is dealt to
+    for (int e = threadIdx.x; e < E; e += blockDim.x) {
+        const int n = off[e + 1] - off[e], parts = seg0[e + 1] - seg0[e];
+        const int len = parts > 1 ? ((n + parts - 1) / parts + 31) & ~31 : n;
+        const int slot = seg0[e] - e;   // slots were handed out in expert order (used if parts > 1)
+        for (int p = 0; p < parts; ++p) {
+            const int i = seg0[e] + p, m = seglen[i];
+            int rank = 0;
+            for (int o = 0; o < nseg; ++o) rank += (seglen[o] > m) || (seglen[o] == m && o < i);
+            int32_t *sg = tiles + kTileSeg + 4 * dealt_position(rank, nseg);
+            const int r0 = off[e] + min(p * len, n);
+            sg[0] = e;
+            sg[1] = r0;
+            sg[2] = r0 + m;
+            sg[3] = p == 0 ? -1 : slot + p - 1;
+        }
+    }
+    for (int i = seg0[E] + threadIdx.x; i < nseg; i += blockDim.x) {
+        int rank = 0;
+        for (int o = 0; o < nseg; ++o) rank += (seglen[o] > -1) || (seglen[o] == -1 && o < i);
+        int32_t *sg = tiles + kTileSeg + 4 * dealt_position(rank, nseg);
+        sg[0] = 0; sg[1] = 0; sg[2] = 0; sg[3] = -2;
+    }
 }
 
 static inline int max_row_tiles(int64_t S, int E, int BQ) { return (int)(S / BQ) + E; }
@@ -84,7 +178,7 @@ static inline int grid_for(int64_t tiles) { return (int)((tiles + 7) / 8 * 8); }
 
 // Grid of a persistent launch: one work-group per compute unit of the current device (a
 // multiple of 8, so that every XCD gets the same number), fewer when there are fewer tiles.
-static int persistent_grid(int64_t max_tiles) {
+static int device_cus() {
     static int cus[64] = {0};
     int dev = 0;
     if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) dev = 0;
@@ -93,8 +187,12 @@ static int persistent_grid(int64_t max_tiles) {
         if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n < 8) n = 256;
         cus[dev] = n / 8 * 8;
     }
-    const int64_t g = grid_for(max_tiles);
-    return (int)(g < cus[dev] ? g : cus[dev]);
+    return cus[dev];
+}
+static int persistent_grid(int64_t max_tiles) {
+    const int cus = device_cus();
+    const int64_t g = (max_tiles + 7) / 8 * 8;
+    return (int)(g < cus ? g : cus);
 }
 
 __device__ __forceinline__ uint2 pack4(float a, float b, float c, float d) {
@@ -455,9 +553,9 @@ rowgemm_kernel(int S, int d, int F, const bf16_t *__restrict__ Q0, const bf16_t 
 // (dW_down = Hg^T dy straight from the upstream gradient: no per-slot copy of dy is read).
 template <bool GATHER>
 __global__ void __launch_bounds__(kThreads2, kMinWavesPerSimd)
-wgrad_kernel(int E, int NQd, int NPd, const bf16_t *__restrict__ Qs, const bf16_t *__restrict__ Ps,
-             const int32_t *__restrict__ tok, int nrows, const int32_t *__restrict__ offsets,
-             float *__restrict__ out, int accumulate, int *ctr, const int32_t *__restrict__ order) {
+wgrad_kernel(int NQd, int NPd, const bf16_t *__restrict__ Qs, const bf16_t *__restrict__ Ps,
+             const int32_t *__restrict__ tok, int nrows, const int32_t *__restrict__ tiles,
+             float *__restrict__ out, float *__restrict__ part, int accumulate, int *ctr) {
     __shared__ __attribute__((aligned(1024))) char s0[kStageBytes];
     __shared__ __attribute__((aligned(1024))) char s1[kStageBytes];
     __shared__ __attribute__((aligned(1024))) char s2[kStageBytes];
@@ -477,15 +575,17 @@ wgrad_kernel(int E, int NQd, int NPd, const bf16_t *__restrict__ Qs, const bf16_
         P.init(NPd * 2, 0, 128 * wp0);
     }
     Q.init(NQd * 2, 0, kWaveRowsQ * wq0);
-    TileLoop tl(E * nqt * npt, ctr);
+    // tiles of one reduction segment (an expert's rows, or one part of them) are neighbours in the list
+    TileLoop tl(tiles[1] * nqt * npt, ctr);
     for (int slot = tl.first(), next = tl.second(); tl.valid(slot);) {
     const int id = tl.id(slot);
     const int eo = id / (nqt * npt);
     const int rem = id - eo * nqt * npt;
-    const int e = order[eo];
+    const int32_t *sg = tiles + kTileSeg + 4 * eo;
+    const int e = sg[0], r0 = sg[1], r1 = sg[2], pslot = sg[3];
     const int qt = rem / npt, pt = rem - qt * npt;
-    const int r0 = offsets[e], r1 = offsets[e + 1];
     const int q0 = qt * kTile, p0 = pt * kTile;
+    if (pslot != -2) {   // (a segment that only pads the list has no tile)
     if constexpr (GATHER) {
         P.aim(Ps, (uint64_t)nrows * NPd * 2, p0 * 2, tok + r0, r1 - r0);
     } else {
@@ -507,7 +607,9 @@ wgrad_kernel(int E, int NQd, int NPd, const bf16_t *__restrict__ Qs, const bf16_
     const int lane = tid & 63, wq = (tid >> 6) / kWP2, wp = (tid >> 6) % kWP2;
     RowStage<256> st{wave_patch(s0, s1, s2, s3, tid), tid};
     const int q = lane & 31;
-    char *o = (char *)(out + (int64_t)e * NQd * NPd);
+    // part 0 of an expert's rows goes to the gradient, a later part to its own slot of partial products
+    char *o = (char *)(pslot < 0 ? out + (int64_t)e * NQd * NPd : part + (int64_t)pslot * NQd * NPd);
+    const int add = pslot < 0 ? accumulate : 0;
 #pragma unroll
     for (int tq = 0; tq < kTQ2; ++tq)
 #pragma unroll
@@ -522,8 +624,11 @@ wgrad_kernel(int E, int NQd, int NPd, const bf16_t *__restrict__ Qs, const bf16_
                                          acc[tp][tq][4 * g + 3]));
                 }
             const int64_t off = ((int64_t)(q0 + wq * kWaveRowsQ + tq * 32) * NPd + p0 + wp * 128 + half * 64) * 4;
-            st.flush_f32(o + off, (int64_t)NPd * 4, 32, accumulate);
+            st.flush_f32(o + off, (int64_t)NPd * 4, 32, add);
         }
+    } else {
+        tl.prefetch();
+    }
     const int after = tl.finish(mailbox);
     slot = next;
     next = after;
@@ -833,6 +938,28 @@ split_reduce_kernel(int d, int E, int nsplit, const float *__restrict__ part, fl
 }
 
 // ---------------------------------------------------------------------------
+// The partial products of split reductions into their gradients: for every split expert, in slot order
+// (a fixed order: the sum does not depend on the launch shape).  n4 = float4s per expert matrix.
+// ---------------------------------------------------------------------------
+__global__ void __launch_bounds__(256)
+wgrad_parts_kernel(int64_t n4, const int32_t *__restrict__ tiles, float *__restrict__ out,
+                   const float *__restrict__ part) {
+    const int hot = tiles[kTileHot];
+    for (int j = 0; j < hot; ++j) {
+        const int e = tiles[kTileHot + 1 + 3 * j], s0 = tiles[kTileHot + 2 + 3 * j], ns = tiles[kTileHot + 3 + 3 * j];
+        float4 *o = (float4 *)out + (int64_t)e * n4;
+        for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n4; i += (int64_t)gridDim.x * blockDim.x) {
+            float4 a = o[i];
+            for (int p = 0; p < ns; ++p) {
+                const float4 b = ((const float4 *)part)[(int64_t)(s0 + p) * n4 + i];
+                a.x += b.x; a.y += b.y; a.z += b.z; a.w += b.w;
+            }
+            o[i] = a;
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------
 // host side
 // ---------------------------------------------------------------------------
 typedef TileCfg<128, 64, 2, 2, 64> TLLogits;   // router: 128 experts x 64 tokens
@@ -850,8 +977,8 @@ static void allow_lds(K kernel, int bytes) {
     (void)hipFuncSetAttribute((const void *)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
 }
 
-hipError_t mfma_build_tiles(int E, const int32_t *offsets, int32_t *tiles, hipStream_t s) {
-    build_row_tiles_kernel<<<1, 1024, 0, s>>>(E, kTile, offsets, tiles);
+hipError_t mfma_build_tiles(int E, const int32_t *offsets, int32_t *tiles, int split_rows, hipStream_t s) {
+    build_row_tiles_kernel<<<1, 1024, 0, s>>>(E, kTile, offsets, tiles, split_rows);
     return hipGetLastError();
 }
 
@@ -907,19 +1034,32 @@ hipError_t mfma_ffn_dxp(int64_t S, int d, int E, int F, const void *dA, const vo
     return hipGetLastError();
 }
 
+// Rows per part of a split reduction for a launch whose segments have `tiles_per_seg` tiles each: a tile
+// should not last longer than a third of a compute unit's fair share of the launch (0: never split).
+// Never below S / kMaxSplitSlots, so that the slots always suffice.
+int mfma_wgrad_split_rows(int64_t S, int tiles_per_seg, size_t part_bytes_available, size_t bytes_per_slot) {
+    if (part_bytes_available < (size_t)kMaxSplitSlots * bytes_per_slot) return 0;
+    const int cus = device_cus();
+    int64_t r = S * tiles_per_seg / (3 * (int64_t)cus);
+    r = std::max<int64_t>(r, (S + kMaxSplitSlots - 1) / kMaxSplitSlots);
+    r = std::max<int64_t>(r, 2048);
+    r = (r + 31) / 32 * 32;
+    return r >= S ? 0 : (int)r;
+}
+
 hipError_t mfma_wgrad(int E, int NQd, int NPd, const void *Qs, const void *Ps, const int32_t *tok, int nrows,
-                      const int32_t *offsets, const int32_t *tiles, int launch, float *out, int accumulate,
-                      hipStream_t s) {
-    const int64_t ntiles = (int64_t)E * (NQd / kTile) * (NPd / kTile);
+                      const int32_t *tiles, int launch, float *out, float *part, int accumulate, hipStream_t s) {
+    const int64_t ntiles = (int64_t)(E + kMaxSplitSlots + 8) * (NQd / kTile) * (NPd / kTile);
     ProfScope ps(PROF_WGRAD, s);
     if (tok)
         wgrad_kernel<true><<<persistent_grid(ntiles), kThreads2, 0, s>>>(
-            E, NQd, NPd, (const bf16_t *)Qs, (const bf16_t *)Ps, tok, nrows, offsets, out, accumulate,
-            const_cast<int *>(tiles) + 2 + 8 * launch, tiles + kTileOrder);
+            NQd, NPd, (const bf16_t *)Qs, (const bf16_t *)Ps, tok, nrows, tiles, out, part, accumulate,
+            const_cast<int *>(tiles) + 2 + 8 * launch);
     else
         wgrad_kernel<false><<<persistent_grid(ntiles), kThreads2, 0, s>>>(
-            E, NQd, NPd, (const bf16_t *)Qs, (const bf16_t *)Ps, nullptr, 0, offsets, out, accumulate,
-            const_cast<int *>(tiles) + 2 + 8 * launch, tiles + kTileOrder);
+            NQd, NPd, (const bf16_t *)Qs, (const bf16_t *)Ps, nullptr, 0, tiles, out, part, accumulate,
+            const_cast<int *>(tiles) + 2 + 8 * launch);
+    if (part) wgrad_parts_kernel<<<512, 256, 0, s>>>((int64_t)NQd * NPd / 4, tiles, out, part);
     return hipGetLastError();
 }
 

@@ -92,7 +92,12 @@ bool mfma_ffn_supported(int d, int F);
 bool mfma_router_supported(int d, int E);
 size_t mfma_tiles_bytes(int64_t S, int E);
 size_t mfma_dwr_ws_bytes(int T, int d, int E);
-hipError_t mfma_build_tiles(int E, const int32_t *offsets, int32_t *tiles, hipStream_t s);
+// split_rows > 0: experts with more rows than that are cut into parts of at most that many rows for the
+// down-projection weight gradient (mfma_wgrad_split_rows picks it); 0: never; < 0: the pass has no
+// weight gradients and the table gets no reduction segments at all
+hipError_t mfma_build_tiles(int E, const int32_t *offsets, int32_t *tiles, int split_rows, hipStream_t s);
+// 0 unless `part_bytes_available` holds the partial products of every slot a split may use
+int mfma_wgrad_split_rows(int64_t S, int tiles_per_seg, size_t part_bytes_available, size_t bytes_per_slot);
 // perm != NULL: `Xp` is x [T,d] (T*d*2 bytes readable) and the first contraction gathers its rows
 // through perm in the tile loads
 hipError_t mfma_ffn_forward(int64_t S, int d, int E, int F, const void *Xp, const int32_t *perm, int K, int T,
@@ -110,10 +115,11 @@ hipError_t mfma_ffn_dxp(int64_t S, int d, int E, int F, const void *dA, const vo
 // `tiles` is the table mfma_build_tiles() filled in this call sequence; `launch` (2..7) picks the
 // tile counters of this launch: 0 and 1 belong to the forward pair and to dh / dxp.
 // out (+)= Qs^T Ps per expert.  tok != NULL: Ps is the un-permuted [nrows, NPd] matrix and row r of the
-// reduction is its row tok[r] (nrows * NPd * 2 < 2^31)
+// reduction is its row tok[r] (nrows * NPd * 2 < 2^31).  The reduction segments come from the table (an
+// expert's rows, or parts of them when the table was built with split_rows > 0: then `part` must hold
+// the partial products, and a second launch adds them to the gradient in a fixed order)
 hipError_t mfma_wgrad(int E, int NQd, int NPd, const void *Qs, const void *Ps, const int32_t *tok, int nrows,
-                      const int32_t *offsets, const int32_t *tiles, int launch, float *out, int accumulate,
-                      hipStream_t s);
+                      const int32_t *tiles, int launch, float *out, float *part, int accumulate, hipStream_t s);
 // out0 (+)= Qs^T P0 and out1 (+)= Qs^T P1 per expert in one pass over Qs.  tok != NULL: Qs is the
 // un-permuted [nrows, NQd] matrix and row r of the reduction is its row tok[r] (a list made by
 // mfma_row_tokens; nrows * NQd * 2 < 2^31)

@@ -32,6 +32,9 @@ SHAPES = {
     # other widths: 12 / 8 and 16 / 20 windows of 64 k in the row-tiled GEMMs, 3 / 4 and 2 / 5 column tiles
     "mfma_wide": SH(T=900, d=768, E=128, K=4, F=512, act="bf16", sigma=0.02, zipf_s=0.8, seed=27),
     "mfma_tall": SH(T=1500, d=1024, E=128, K=2, F=1280, act="bf16", sigma=0.02, seed=28),
+    # a load so skewed that four experts hold nearly every token (about 4600 rows each): their dW_down
+    # reductions are cut into three parts whose partial products are summed by a second launch
+    "mfma_skewed": SH(T=4608, d=256, E=128, K=4, F=256, act="bf16", sigma=0.02, zipf_s=2.5, seed=29),
 }
 
 
@@ -309,7 +312,7 @@ def test_forward_chain(name, simt):
 @pytest.mark.parametrize("name,simt", [("config1_f32", False), ("odd_f32", False), ("odd_bf16", False),
                                        ("mfma_small", False), ("mfma_ragged", False),
                                        ("mfma_fewexperts", False), ("mfma_small", True), ("mfma_u16", False), ("mfma_u16", True),
-                                       ("mfma_wide", False), ("mfma_tall", False)])
+                                       ("mfma_wide", False), ("mfma_tall", False), ("mfma_skewed", False)])
 def test_backward_chain(name, simt):
     if simt:
         os.environ["R3_FORCE_SIMT"] = "1"
@@ -357,7 +360,8 @@ def test_backward_chain(name, simt):
 
 @pytest.mark.parametrize("name,simt", [("config1_f32", False), ("odd_bf16", False), ("mfma_small", False),
                                        ("mfma_ragged", False), ("mfma_fewexperts", False), ("mfma_small", True),
-                                       ("mfma_u16", False), ("mfma_wide", False), ("mfma_tall", False)])
+                                       ("mfma_u16", False), ("mfma_wide", False), ("mfma_tall", False),
+                                       ("mfma_skewed", False)])
 def test_one_call_forward_and_its_backward(name, simt):
     """r3_moe_forward (gate folded into the expert network: H and Yp come out gate-scaled, the combination
     is a plain sum) and r3_moe_backward told so, against the oracle's forward and backward."""
@@ -381,6 +385,8 @@ def test_one_call_forward_and_its_backward(name, simt):
     assert_close(host(buf.Yp), grow[:, None] * fwd["o"], "g*o", c.rel)
     assert_close(host(buf.y), fwd["y"], "y", c.rel)
     assert 0 < int(agree[0]) <= sh.T and int(agree[1]) <= sh.T * sh.K
+    if name == "mfma_skewed":
+        assert fwd["counts"].max() > 4096      # (what makes the backward split a reduction)
     dbias = torch.zeros(sh.E, dtype=torch.float32, device="cuda")
     r3.backward(buf, c.t["dy"], c.t["x"], c.t["Wr"], c.t["idx"], c.t["Wg"], c.t["Wu"], c.t["Wd"], dbias=dbias)
     sync()
