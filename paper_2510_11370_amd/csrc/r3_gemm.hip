@@ -890,6 +890,10 @@ gate_fused_kernel(int T, int d, int K, const bf16_t *__restrict__ x, const bf16_
 //   part[s][c][e'] = sum_{t in split s} x[t][c] * ds[t][e'],   e' in [0, 2E)
 // followed by a fixed-order sum over the splits and over (hi, lo).
 // (E below is the width of ds, i.e. twice the number of experts.)
+// A work-group takes 128 hidden columns and, with E = 128 experts, the whole width of ds, so x is
+// read once; 16 splits of the tokens fill the chip with d / 128 tiles each and leave 16 partial
+// matrices (with 128 x 128 tiles and a split per 512 tokens x was read twice and the partials, 67 MB
+// at 16384 tokens, moved more bytes than x itself).
 // ---------------------------------------------------------------------------
 template <class TL>
 __global__ void __launch_bounds__(TL::NT)
@@ -913,7 +917,8 @@ dwr_partial_kernel(int T, int d, int E, int rows_per_split, const bf16_t *__rest
     };
     f32x16_t acc[TL::TP][TL::TQ];
     zero_acc<TL>(acc);
-    mfma_mainloop<TL, true, true>(acc, (max(r1 - r0, 0) + TL::BK - 1) / TL::BK, fp, fq, lds);
+    // bound by the stream of x: two k-tiles in flight per work-group
+    mfma_mainloop_ahead2<TL, true, true>(acc, (max(r1 - r0, 0) + TL::BK - 1) / TL::BK, fp, fq, lds);
     float *o = part + (int64_t)sp * d * E;
     for_each_quad<TL>([&](int tp, int tq, int g, int p, int q) {
         *(float4 *)(o + (int64_t)(q0 + q) * E + p0 + p) =
@@ -963,7 +968,8 @@ wgrad_parts_kernel(int64_t n4, const int32_t *__restrict__ tiles, float *__restr
 // host side
 // ---------------------------------------------------------------------------
 typedef TileCfg<128, 64, 2, 2, 64> TLLogits;   // router: 128 experts x 64 tokens
-typedef TileCfg<128, 128, 2, 2, 64> TLDwr;     // router wgrad: 128 experts x 128 hidden
+typedef TileCfg<128, 128, 2, 2, 64> TLDwr;     // router (large batches): 128 experts x 128 tokens
+typedef TileCfg<256, 128, 2, 2, 64> TLDwrW;    // router wgrad: 256 columns of ds (hi, lo) x 128 hidden
 
 bool mfma_ffn_supported(int d, int F) { return d % 256 == 0 && F % 256 == 0 && d >= 256 && F >= 256; }
 bool mfma_router_supported(int d, int E) { return E % 128 == 0 && d % 128 == 0; }  // 2E % 128 for ds
@@ -1149,7 +1155,7 @@ hipError_t mfma_gate_fused(int T, int d, int E, int K, const void *x, const void
 
 static int dwr_splits(int T) {
     int s = (T + 511) / 512;
-    return s < 1 ? 1 : (s > 64 ? 64 : s);
+    return s < 1 ? 1 : (s > 16 ? 16 : s);
 }
 size_t mfma_dwr_ws_bytes(int T, int d, int E) {
     return align_up((size_t)dwr_splits(T) * d * 2 * E * sizeof(float), 256);
@@ -1157,8 +1163,8 @@ size_t mfma_dwr_ws_bytes(int T, int d, int E) {
 
 hipError_t mfma_dwr(int T, int d, int E, const void *x, const void *ds, float *part, float *dWr, int accumulate,
                     hipStream_t s) {
-    typedef TLDwr TL;
     const int ns = dwr_splits(T);
+    typedef TLDwrW TL;
     int rows = (T + ns - 1) / ns;
     rows = (rows + TL::BK - 1) / TL::BK * TL::BK;
     allow_lds(dwr_partial_kernel<TL>, TL::LDS_BYTES);
