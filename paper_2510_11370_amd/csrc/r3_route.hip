@@ -369,6 +369,27 @@ hipError_t launch_agreement(int T, int E, int K, const float *logits, const void
 //   pass 4: row gather, one read of x[t] feeding its K destination rows
 // The placement never depends on arrival order, so perm is unique.
 // ---------------------------------------------------------------------------
+// A wave's chunk is walked 64 slots at a time, kPermBatch such steps per batch: the ids of a whole
+// batch are fetched before any of them is used, so the wave pays one memory round trip per batch
+// instead of one per step.
+constexpr int kPermBatch = 16;
+// slot -> (token, position) in 32-bit arithmetic (T*K < 2^31), a shift when K is a power of two:
+// a 64-bit division by a run-time K is some hundred instructions, and these kernels did two per slot
+struct SlotSplit {
+    int K, shift;
+    __device__ __forceinline__ explicit SlotSplit(int K_) : K(K_), shift((K_ & (K_ - 1)) == 0 ? __ffs(K_) - 1 : -1) {}
+    __device__ __forceinline__ void operator()(int sl, int &t, int &j) const {
+        if (shift >= 0) {
+            t = sl >> shift;
+            j = sl & (K - 1);
+        } else {
+            t = (int)((unsigned)sl / (unsigned)K);
+            j = sl - t * K;
+        }
+    }
+};
+constexpr int kWaitLds = 15 | (7 << 4) | (0 << 8) | (3 << 14);   // s_waitcnt lgkmcnt(0): LDS only, not the stores
+
 template <typename IdxT>
 __global__ void __launch_bounds__(256)
 permute_hist_kernel(int T, int E, int K, const IdxT *__restrict__ idx, int64_t stride, int chunk,
@@ -380,21 +401,46 @@ permute_hist_kernel(int T, int E, int K, const IdxT *__restrict__ idx, int64_t s
     for (int e = lane; e < E; e += kWave) hist[e] = 0;
     __syncthreads();
     if (c >= nchunks) return;
-    const int64_t S = (int64_t)T * K;
-    const int64_t s0 = (int64_t)c * chunk;
+    const int S = T * K, s0 = c * chunk;
+    const SlotSplit split(K);
+    // a token's K ids sit in K neighbouring lanes of one step when K divides 64 (chunks start at
+    // multiples of 64): then the duplicate check compares lanes instead of loading ids again
+    const bool lanes_hold_token = 64 % K == 0;
     int bad = 0;
-    for (int i = lane; i < chunk; i += kWave) {
-        int64_t sl = s0 + i;
-        if (sl < S) {
-            int t = (int)(sl / K), j = (int)(sl - (int64_t)t * K);
-            int e = (int)idx[(int64_t)t * stride + j];
-            if (e >= E) {
+    for (int i0 = 0; i0 < chunk; i0 += kWave * kPermBatch) {
+        int ev[kPermBatch];
+#pragma unroll
+        for (int u = 0; u < kPermBatch; ++u) {
+            const int sl = s0 + i0 + u * kWave + lane;
+            ev[u] = -1;
+            if (i0 + u * kWave < chunk && sl < S) {
+                int t, j;
+                split(sl, t, j);
+                ev[u] = (int)idx[(int64_t)t * stride + j];
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < kPermBatch; ++u) {
+            const int sl = s0 + i0 + u * kWave + lane;
+            int e = ev[u];
+            const bool live = e >= 0;
+            if (live && e >= E) {
                 bad |= R3_DATA_IDX_RANGE;
                 e = E - 1;
             }
-            for (int jj = 0; jj < j; ++jj)
-                if ((int)idx[(int64_t)t * stride + jj] == e) bad |= R3_DATA_IDX_DUP;
-            atomicAdd(&hist[e], 1);
+            if (lanes_hold_token) {
+                const int j = lane % K;   // (sl % K: chunk starts and steps are multiples of 64)
+                for (int back = 1; back < K; ++back) {
+                    const int other = __shfl(e, lane - back);
+                    if (live && back <= j && other == e) bad |= R3_DATA_IDX_DUP;
+                }
+            } else if (live) {
+                int t, j;
+                split(sl, t, j);
+                for (int jj = 0; jj < j; ++jj)
+                    if (min((int)idx[(int64_t)t * stride + jj], E - 1) == e) bad |= R3_DATA_IDX_DUP;
+            }
+            if (live) atomicAdd(&hist[e], 1);
         }
     }
     // LDS atomics of one wave are complete before its later LDS reads
@@ -405,33 +451,64 @@ permute_hist_kernel(int T, int E, int K, const IdxT *__restrict__ idx, int64_t s
 }
 
 // One block of 1024 threads.  chunk_base [nchunks,E] receives the exclusive running count of
-// chunk_hist over chunks (separate arrays, so the loads of one expert's column pipeline);
-// counts/offsets are written.
+// chunk_hist over chunks; counts/offsets are written.  An expert's column of chunk_hist is shared out
+// among G = 1024 / E' threads (E' = E rounded up to a power of two), each taking a contiguous range of
+// chunks: sums of the ranges first, then every thread walks its range again from its own base.  (One
+// thread per expert walking all chunks paid a memory round trip per 8 chunks, 16 in a row at 128
+// chunks, with 7 of 8 threads idle at E = 128.)
 __global__ void __launch_bounds__(1024)
 permute_scan_kernel(int E, int nchunks, const int32_t *__restrict__ chunk_hist, int32_t *__restrict__ chunk_base,
                     int32_t *__restrict__ counts, int32_t *__restrict__ offsets) {
     __shared__ int32_t tot[kMaxE];
     __shared__ int32_t part[1024];
-    for (int e = threadIdx.x; e < E; e += blockDim.x) {
-        int32_t run = 0;
-        int c = 0;
-        for (; c + 8 <= nchunks; c += 8) {
+    int Ep = 1;
+    while (Ep < E && Ep < 1024) Ep <<= 1;
+    const int G = E <= 1024 ? 1024 / Ep : 1;                 // threads per expert
+    const int per_g = (nchunks + G - 1) / G;                 // chunks per thread
+    const int g = E <= 1024 ? threadIdx.x / Ep : 0;
+    const int c0 = min(g * per_g, nchunks), c1 = min(c0 + per_g, nchunks);
+    auto walk = [&](int e, int32_t run, bool write) {
+        int c = c0;
+        for (; c + 8 <= c1; c += 8) {
             int32_t h[8];
 #pragma unroll
             for (int u = 0; u < 8; ++u) h[u] = chunk_hist[(int64_t)(c + u) * E + e];
 #pragma unroll
             for (int u = 0; u < 8; ++u) {
-                chunk_base[(int64_t)(c + u) * E + e] = run;
+                if (write) chunk_base[(int64_t)(c + u) * E + e] = run;
                 run += h[u];
             }
         }
-        for (; c < nchunks; ++c) {
+        for (; c < c1; ++c) {
             const int32_t h = chunk_hist[(int64_t)c * E + e];
-            chunk_base[(int64_t)c * E + e] = run;
+            if (write) chunk_base[(int64_t)c * E + e] = run;
             run += h;
         }
-        tot[e] = run;
-        counts[e] = run;
+        return run;
+    };
+    if (E <= 1024) {
+        const int e = threadIdx.x % Ep;
+        part[threadIdx.x] = e < E ? walk(e, 0, false) : 0;
+        __syncthreads();
+        int32_t base = 0, all = 0;
+        for (int gg = 0; gg < G; ++gg) {
+            const int32_t v = part[gg * Ep + e];
+            base += gg < g ? v : 0;
+            all += v;
+        }
+        if (e < E) {
+            walk(e, base, true);
+            if (g == 0) {
+                tot[e] = all;
+                counts[e] = all;
+            }
+        }
+    } else {
+        for (int e = threadIdx.x; e < E; e += blockDim.x) {
+            const int32_t all = walk(e, 0, true);
+            tot[e] = all;
+            counts[e] = all;
+        }
     }
     __syncthreads();
     // exclusive scan of tot[0..E): each thread owns a contiguous span
@@ -471,36 +548,47 @@ permute_place_kernel(int T, int E, int K, const IdxT *__restrict__ idx, int64_t 
         for (int e = lane; e < E; e += kWave) cnt[e] = offsets[e] + chunk_base[(int64_t)c * E + e];
     __syncthreads();
     if (c >= nchunks) return;
-    const int64_t S = (int64_t)T * K;
-    const int64_t s0 = (int64_t)c * chunk;
+    const int S = T * K, s0 = c * chunk;
+    const SlotSplit split(K);
     int ebits = 1;
     while ((1 << ebits) < E) ++ebits;
     const uint64_t lt = (1ull << lane) - 1ull;
-    for (int i = 0; i < chunk; i += kWave) {
-        int64_t sl = s0 + i + lane;
-        bool live = sl < S;
-        int e = 0;
-        if (live) {
-            int t = (int)(sl / K), j = (int)(sl - (int64_t)t * K);
-            e = min((int)idx[(int64_t)t * stride + j], E - 1);
+    for (int i0 = 0; i0 < chunk; i0 += kWave * kPermBatch) {
+        int ev[kPermBatch];
+#pragma unroll
+        for (int u = 0; u < kPermBatch; ++u) {
+            const int sl = s0 + i0 + u * kWave + lane;
+            ev[u] = -1;
+            if (i0 + u * kWave < chunk && sl < S) {
+                int t, j;
+                split(sl, t, j);
+                ev[u] = min((int)idx[(int64_t)t * stride + j], E - 1);
+            }
         }
-        // lanes holding the same expert
-        uint64_t same = __ballot(live);
-        for (int b = 0; b < ebits; ++b) {
-            uint64_t bal = __ballot((e >> b) & 1);
-            same &= ((e >> b) & 1) ? bal : ~bal;
+#pragma unroll
+        for (int u = 0; u < kPermBatch; ++u) {
+            const int sl = s0 + i0 + u * kWave + lane;
+            const bool live = ev[u] >= 0;
+            const int e = live ? ev[u] : 0;
+            // lanes holding the same expert
+            uint64_t same = __ballot(live);
+            for (int b = 0; b < ebits; ++b) {
+                uint64_t bal = __ballot((e >> b) & 1);
+                same &= ((e >> b) & 1) ? bal : ~bal;
+            }
+            if (live) {
+                int row = cnt[e] + __popcll(same & lt);
+                inv_perm[sl] = row;
+                perm[row] = (int32_t)sl;
+            }
+            // (LDS traffic only: the stores above need not have landed)
+            __builtin_amdgcn_s_waitcnt(kWaitLds);
+            __builtin_amdgcn_wave_barrier();
+            // the highest lane of each group advances the group's counter
+            if (live && (same >> lane) == 1ull) cnt[e] += __popcll(same);
+            __builtin_amdgcn_s_waitcnt(kWaitLds);
+            __builtin_amdgcn_wave_barrier();
         }
-        if (live) {
-            int row = cnt[e] + __popcll(same & lt);
-            inv_perm[sl] = row;
-            perm[row] = (int32_t)sl;
-        }
-        __builtin_amdgcn_s_waitcnt(0);
-        __builtin_amdgcn_wave_barrier();
-        // the highest lane of each group advances the group's counter
-        if (live && (same >> lane) == 1ull) cnt[e] += __popcll(same);
-        __builtin_amdgcn_s_waitcnt(0);
-        __builtin_amdgcn_wave_barrier();
     }
 }
 
