@@ -51,6 +51,42 @@ __device__ __forceinline__ int dealt_position(int rank, int n) {
     const int j = rank >> 3, c = rank & 7;
     return ((j & 1) ? 7 - c : c) * (n >> 3) + j;
 }
+// rnk[i] = number of items that come before item i when the n items are sorted by descending key, ties
+// by index.  A block of 1024 threads; an item's comparisons are shared out among 1024 / n' threads (n' = n
+// rounded up to a power of two) and added up in LDS.  (One thread per item walking all n keys is a
+// chain of n dependent LDS reads: 6 us at n = 128.)
+template <class Key>
+__device__ __forceinline__ void block_ranks(int n, Key key, int32_t *rnk) {
+    for (int i = threadIdx.x; i < n; i += 1024) rnk[i] = 0;
+    __syncthreads();
+    if (n <= 1024) {
+        int np2 = 1;
+        while (np2 < n) np2 <<= 1;
+        const int sub = 1024 / np2, i = threadIdx.x % np2, part = threadIdx.x / np2;
+        const int per = (n + sub - 1) / sub, o0 = min(n, part * per), o1 = min(n, o0 + per);
+        if (i < n) {
+            const int k = key(i);
+            int r = 0;
+            for (int o = o0; o < o1; ++o) {
+                const int m = key(o);
+                r += (m > k) || (m == k && o < i);
+            }
+            if (r) atomicAdd(&rnk[i], r);
+        }
+    } else {
+        for (int i = threadIdx.x; i < n; i += 1024) {
+            const int k = key(i);
+            int r = 0;
+            for (int o = 0; o < n; ++o) {
+                const int m = key(o);
+                r += (m > k) || (m == k && o < i);
+            }
+            rnk[i] = r;
+        }
+    }
+    __syncthreads();
+}
+
 __global__ void __launch_bounds__(1024)
 build_row_tiles_kernel(int E, int BQ, const int32_t *__restrict__ offsets, int32_t *__restrict__ tiles,
                        int split_rows) {
@@ -58,6 +94,7 @@ build_row_tiles_kernel(int E, int BQ, const int32_t *__restrict__ offsets, int32
     __shared__ int32_t off[kMaxE + 1];
     __shared__ int32_t seg0[kMaxE + 1];     // first segment of expert e
     __shared__ int32_t seglen[kMaxSegs];    // rows of every segment (-1: padding)
+    __shared__ int32_t rnk[kMaxSegs];
     __shared__ int32_t nseg_s;
     // the offsets come in once, in parallel (read one by one by a single thread they cost a memory
     // round trip each, and this kernel sits between two others on every pass)
@@ -121,16 +158,9 @@ build_row_tiles_kernel(int E, int BQ, const int32_t *__restrict__ offsets, int32
         tiles[1] = nseg_s;
     }
     if (threadIdx.x < 64) tiles[2 + threadIdx.x] = 0;
-    for (int e = threadIdx.x; e < E; e += blockDim.x) {
-        const int n = off[e + 1] - off[e];
-        int rank = 0;
-        for (int o = 0; o < E; ++o) {
-            const int m = off[o + 1] - off[o];
-            rank += (m > n) || (m == n && o < e);
-        }
-        tiles[kTileOrder + (E % 8 == 0 ? dealt_position(rank, E) : rank)] = e;
-    }
-    __syncthreads();
+    block_ranks(E, [&](int e) { return off[e + 1] - off[e]; }, rnk);
+    for (int e = threadIdx.x; e < E; e += blockDim.x)
+        tiles[kTileOrder + (E % 8 == 0 ? dealt_position(rnk[e], E) : rnk[e])] = e;
     for (int e = threadIdx.x; e < E; e += blockDim.x) {
         const int n = start[e + 1] - start[e];
         for (int i = 0; i < n; ++i) {
@@ -149,15 +179,14 @@ build_row_tiles_kernel(int E, int BQ, const int32_t *__restrict__ offsets, int32
     for (int i = seg0[E] + threadIdx.x; i < nseg; i += blockDim.x) seglen[i] = -1;
     __syncthreads();
     // rank every segment by length (ties by position) and write it where it is dealt to
+    block_ranks(nseg, [&](int i) { return seglen[i]; }, rnk);
     for (int e = threadIdx.x; e < E; e += blockDim.x) {
         const int n = off[e + 1] - off[e], parts = seg0[e + 1] - seg0[e];
         const int len = parts > 1 ? ((n + parts - 1) / parts + 31) & ~31 : n;
         const int slot = seg0[e] - e;   // slots were handed out in expert order (used if parts > 1)
         for (int p = 0; p < parts; ++p) {
             const int i = seg0[e] + p, m = seglen[i];
-            int rank = 0;
-            for (int o = 0; o < nseg; ++o) rank += (seglen[o] > m) || (seglen[o] == m && o < i);
-            int32_t *sg = tiles + kTileSeg + 4 * dealt_position(rank, nseg);
+            int32_t *sg = tiles + kTileSeg + 4 * dealt_position(rnk[i], nseg);
             const int r0 = off[e] + min(p * len, n);
             sg[0] = e;
             sg[1] = r0;
@@ -166,9 +195,7 @@ build_row_tiles_kernel(int E, int BQ, const int32_t *__restrict__ offsets, int32
         }
     }
     for (int i = seg0[E] + threadIdx.x; i < nseg; i += blockDim.x) {
-        int rank = 0;
-        for (int o = 0; o < nseg; ++o) rank += (seglen[o] > -1) || (seglen[o] == -1 && o < i);
-        int32_t *sg = tiles + kTileSeg + 4 * dealt_position(rank, nseg);
+        int32_t *sg = tiles + kTileSeg + 4 * dealt_position(rnk[i], nseg);
         sg[0] = 0; sg[1] = 0; sg[2] = 0; sg[3] = -2;
     }
 }
