@@ -271,14 +271,16 @@ int r3_moe_forward(const r3_layer_desc *desc, const void *x, const void *W_r, co
     // down projection yields gated rows and the combination is a plain sum of each token's K rows
     int32_t *tok = (int32_t *)(base + w.tok);
     float *grow = (float *)(base + w.grow);
-    if (mfma_row_tokens((int)m.S, m.K, perm, gates, tok, grow, s) != hipSuccess) return R3_ERR_HIP;
     if (use_mfma_ffn(m)) {
         int32_t *tiles = (int32_t *)(base + w.ffn);
-        if (mfma_build_tiles(m.E, offsets, tiles, -1, s) != hipSuccess) return R3_ERR_HIP;
+        if (mfma_build_tiles_and_row_tokens(m.E, offsets, tiles, -1, (int)m.S, m.K, perm, gates, tok, grow, s) !=
+            hipSuccess)
+            return R3_ERR_HIP;
         if (mfma_ffn_forward(m.S, m.d, m.E, m.F, x, perm, m.K, m.T, offsets, tiles, W_gate, W_up, W_down, Yp, H,
                              FA_save, FB_save, grow, s) != hipSuccess)
             return R3_ERR_HIP;
     } else {
+        if (mfma_row_tokens((int)m.S, m.K, perm, gates, tok, grow, s) != hipSuccess) return R3_ERR_HIP;
         if (simt_ffn1((int)m.S, m.d, m.E, m.F, m.act, x, perm, m.K, offsets, W_gate, W_up, H, FA_save, FB_save, grow,
                       s) != hipSuccess)
             return R3_ERR_HIP;
@@ -328,12 +330,12 @@ int r3_moe_backward(const r3_layer_desc *desc, const void *dy, const void *x, co
         int32_t *tiles = (int32_t *)(base + w.tiles), *tok = (int32_t *)(base + w.tok);
         float *grow = (float *)(base + w.grow), *wpart = (float *)(base + w.wpart);
         void *Hg = gated ? nullptr : base + w.Hg;
-        if (mfma_row_tokens(S, m.K, perm, gates, tok, grow, s) != hipSuccess) return R3_ERR_HIP;
         // a heavily loaded expert's dW_down reduction is cut into parts; their partial products sit in
         // the dXp buffer, which nothing uses before the parts are summed
         const size_t slot_bytes = (size_t)m.F * m.d * sizeof(float);
         const int split = mfma_wgrad_split_rows(m.S, (m.F / 256) * (m.d / 256), (size_t)m.S * m.d * m.eb, slot_bytes);
-        if (mfma_build_tiles(m.E, offsets, tiles, split, s) != hipSuccess) return R3_ERR_HIP;
+        if (mfma_build_tiles_and_row_tokens(m.E, offsets, tiles, split, S, m.K, perm, gates, tok, grow, s) != hipSuccess)
+            return R3_ERR_HIP;
         if (mfma_ffn_dh(m.S, m.d, m.E, m.F, dy, tok, m.T, grow, offsets, tiles, W_down, FA, FB, H, dA, dB, Hg, wpart,
                         s) != hipSuccess)
             return R3_ERR_HIP;

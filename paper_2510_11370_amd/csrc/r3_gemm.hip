@@ -89,7 +89,21 @@ __device__ __forceinline__ void block_ranks(int n, Key key, int32_t *rnk) {
 
 __global__ void __launch_bounds__(1024)
 build_row_tiles_kernel(int E, int BQ, const int32_t *__restrict__ offsets, int32_t *__restrict__ tiles,
-                       int split_rows) {
+                       int split_rows, int S, int K, const int32_t *__restrict__ perm,
+                       const float *__restrict__ gates, int32_t *__restrict__ tok, float *__restrict__ grow) {
+    // Work-groups past the first make the row -> token list (and the per-row gates) of the same pass: the
+    // two jobs wait for the same inputs and are both too short to be worth a launch of their own.
+    if (blockIdx.x > 0) {
+        const int r = (blockIdx.x - 1) * 1024 + threadIdx.x;
+        if (r < S) {
+            const int slot = perm[r];
+            tok[r] = slot / K;
+            if (gates) grow[r] = gates[slot];
+        } else if (r < S + kRowTokensPad) {
+            tok[r] = 0;
+        }
+        return;
+    }
     __shared__ int32_t start[kMaxE + 1];
     __shared__ int32_t off[kMaxE + 1];
     __shared__ int32_t seg0[kMaxE + 1];     // first segment of expert e
@@ -1011,7 +1025,16 @@ static void allow_lds(K kernel, int bytes) {
 }
 
 hipError_t mfma_build_tiles(int E, const int32_t *offsets, int32_t *tiles, int split_rows, hipStream_t s) {
-    build_row_tiles_kernel<<<1, 1024, 0, s>>>(E, kTile, offsets, tiles, split_rows);
+    build_row_tiles_kernel<<<1, 1024, 0, s>>>(E, kTile, offsets, tiles, split_rows, 0, 1, nullptr, nullptr, nullptr,
+                                              nullptr);
+    return hipGetLastError();
+}
+
+hipError_t mfma_build_tiles_and_row_tokens(int E, const int32_t *offsets, int32_t *tiles, int split_rows, int S, int K,
+                                           const int32_t *perm, const float *gates, int32_t *tok, float *grow,
+                                           hipStream_t s) {
+    build_row_tiles_kernel<<<1 + (S + kRowTokensPad + 1023) / 1024, 1024, 0, s>>>(E, kTile, offsets, tiles, split_rows,
+                                                                                  S, K, perm, gates, tok, grow);
     return hipGetLastError();
 }
 

@@ -96,6 +96,10 @@ size_t mfma_dwr_ws_bytes(int T, int d, int E);
 // down-projection weight gradient (mfma_wgrad_split_rows picks it); 0: never; < 0: the pass has no
 // weight gradients and the table gets no reduction segments at all
 hipError_t mfma_build_tiles(int E, const int32_t *offsets, int32_t *tiles, int split_rows, hipStream_t s);
+// the same launch also makes the row -> token list and the per-row gates (see mfma_row_tokens)
+hipError_t mfma_build_tiles_and_row_tokens(int E, const int32_t *offsets, int32_t *tiles, int split_rows, int S, int K,
+                                           const int32_t *perm, const float *gates, int32_t *tok, float *grow,
+                                           hipStream_t s);
 // 0 unless `part_bytes_available` holds the partial products of every slot a split may use
 int mfma_wgrad_split_rows(int64_t S, int tiles_per_seg, size_t part_bytes_available, size_t bytes_per_slot);
 // perm != NULL: `Xp` is x [T,d] (T*d*2 bytes readable) and the first contraction gathers its rows
