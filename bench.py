@@ -141,6 +141,8 @@ def measured_ceilings(torch, r3, dev):
     out = {"mfma_bf16_constant_operands_TFLOPs": round(timed(lambda: r3.profile_mfma(20000, False, sink)) * 1e-12, 1),
            "mfma_bf16_varied_operands_TFLOPs": round(timed(lambda: r3.profile_mfma(20000, True, sink)) * 1e-12, 1),
            "gemm_instruction_mix_TFLOPs": round(timed(lambda: r3.profile_gemm_mix(20000, mix_src, sink)) * 1e-12, 1),
+           "gemm_instruction_mix_4waves_128x128_TFLOPs": round(
+               timed(lambda: r3.profile_gemm_mix(20000, mix_src, sink, shape=1)) * 1e-12, 1),
            "hbm_copy_GBs": round(timed(copy) * 1e-9, 1)}
     del src, dst
     return out

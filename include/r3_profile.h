@@ -61,8 +61,12 @@ double r3_profile_mfma_flops(int iters);
  * bf16 values; stays cache-resident).  No barriers, epilogues or HBM misses:
  * the rate a perfect schedule of that instruction mix reaches under the power
  * limit.  Same FLOP count as r3_profile_mfma (r3_profile_mfma_flops).
+ * shape 0: the kernels' shape, 8 waves of 128 x 64 per work-group.  shape 1: 4
+ * waves of 128 x 128 (8 fragment reads per 16 MFMAs, the same global->LDS
+ * bytes per FLOP): the ceiling of the other shape the GEMM header can be built
+ * for.  Any other shape: R3_ERR_INVALID_ARG.
  */
-int r3_profile_gemm_mix(int iters, const void *src_1mib, float *sink, void *stream);
+int r3_profile_gemm_mix(int shape, int iters, const void *src_1mib, float *sink, void *stream);
 
 #ifdef __cplusplus
 }

@@ -135,6 +135,52 @@ __global__ void __launch_bounds__(512, 2) calib_mix_kernel(int iters, const uint
     if (s == 1.2345678f) *sink = s;
 }
 
+// The same for the other tile shape the GEMM header can be built for: 4 waves of 128 x 128 per work-group
+// (one per SIMD, 256 accumulator registers each).  Per 16 MFMAs a wave reads 8 fragments -- a third fewer LDS
+// bytes per FLOP -- and the work-group's global->LDS traffic per FLOP is the same (per 32 MFMAs of each wave it
+// brings 32 KB).  Same FLOP per iteration and work-group as calib_mix_kernel (4 waves x 16 MFMAs).
+__global__ void __launch_bounds__(256) calib_mix4_kernel(int iters, const uint32_t *src, float *sink) {
+    __shared__ __attribute__((aligned(16))) char lds[4][32768];
+    uint32_t h = (threadIdx.x + blockIdx.x * 977u) * 2654435761u;
+    for (int i = threadIdx.x; i < 4 * 32768 / 4; i += 256) {
+        h = h * 1664525u + 1013904223u;
+        ((uint32_t *)lds)[i] = (0x3c00u + ((h >> 9) & 0x83ffu)) | ((0x3c00u + ((h >> 3) & 0x83ffu)) << 16);
+    }
+    __syncthreads();
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    cal_f32x16_t acc[4][4];
+    for (int i = 0; i < 4; ++i)
+        for (int j = 0; j < 4; ++j)
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
+    cal_bf16x8_t a[4], b[4];
+    __amdgpu_buffer_rsrc_t r = __builtin_amdgcn_make_buffer_rsrc((void *)src, (short)0, 1 << 20, 0x00020000);
+    for (int it = 0; it < iters; ++it) {
+        const char *st = lds[it & 3];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) a[i] = *(const cal_bf16x8_t *)(st + (w & 1) * 4096 + i * 1024 + lane * 16);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) b[i] = *(const cal_bf16x8_t *)(st + 16384 + (w >> 1) * 4096 + i * 1024 + lane * 16);
+        if (it & 1) {
+            char *dst = lds[(it + 2) & 3];
+#pragma unroll
+            for (int c = 0; c < 8; ++c)
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(
+                    r, (__attribute__((address_space(3))) void *)(dst + c * 4096 + w * 1024), 16,
+                    ((it * 8 + c) * 4096 + (int)threadIdx.x * 16) & ((1 << 20) - 1), 0, 0, 0);
+        }
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
+    }
+    __builtin_amdgcn_s_waitcnt(0);
+    float s = 0.0f;
+    for (int i = 0; i < 4; ++i)
+        for (int j = 0; j < 4; ++j)
+            for (int v = 0; v < 16; ++v) s += acc[i][j][v];
+    if (s == 1.2345678f) *sink = s;
+}
+
 static int calib_grid() {
     int dev = 0, n = 0;
     if (hipGetDevice(&dev) != hipSuccess) dev = 0;
@@ -191,9 +237,14 @@ int r3_profile_mfma(int iters, int random_operands, float *sink, void *stream) {
     return hipGetLastError() == hipSuccess ? R3_OK : R3_ERR_HIP;
 }
 
-int r3_profile_gemm_mix(int iters, const void *src_1mib, float *sink, void *stream) {
-    if (iters < 1 || iters > (1 << 24) || !sink || !src_1mib || ((uintptr_t)src_1mib & 15)) return R3_ERR_INVALID_ARG;
-    calib_mix_kernel<<<dim3(calib_grid()), dim3(512), 0, (hipStream_t)stream>>>(iters, (const uint32_t *)src_1mib, sink);
+int r3_profile_gemm_mix(int shape, int iters, const void *src_1mib, float *sink, void *stream) {
+    if (iters < 1 || iters > (1 << 24) || !sink || !src_1mib || ((uintptr_t)src_1mib & 15) || shape < 0 || shape > 1)
+        return R3_ERR_INVALID_ARG;
+    if (shape == 1)
+        calib_mix4_kernel<<<dim3(calib_grid()), dim3(256), 0, (hipStream_t)stream>>>(iters, (const uint32_t *)src_1mib,
+                                                                                   sink);
+    else
+        calib_mix_kernel<<<dim3(calib_grid()), dim3(512), 0, (hipStream_t)stream>>>(iters, (const uint32_t *)src_1mib, sink);
     return hipGetLastError() == hipSuccess ? R3_OK : R3_ERR_HIP;
 }
 

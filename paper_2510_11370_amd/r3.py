@@ -281,10 +281,12 @@ def profile_mfma(iters, random_operands, sink):
     return float(lib().r3_profile_mfma_flops(C.c_int(iters)))
 
 
-def profile_gemm_mix(iters, src, sink):
-    """Launch the MFMA + LDS-read + global->LDS loop; src: 1 MiB of finite bf16 values on the device."""
+def profile_gemm_mix(iters, src, sink, shape=0):
+    """Launch the MFMA + LDS-read + global->LDS loop; src: 1 MiB of finite bf16 values on the device.
+    shape 0: 8 waves of 128 x 64 (the kernels' shape); 1: 4 waves of 128 x 128."""
     assert src.numel() * src.element_size() >= 1 << 20
-    _check(lib().r3_profile_gemm_mix(C.c_int(iters), _p(src), _p(sink), _stream()), "r3_profile_gemm_mix")
+    _check(lib().r3_profile_gemm_mix(C.c_int(shape), C.c_int(iters), _p(src), _p(sink), _stream()),
+           "r3_profile_gemm_mix")
     return float(lib().r3_profile_mfma_flops(C.c_int(iters)))
 
 
