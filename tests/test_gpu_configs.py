@@ -57,19 +57,42 @@ def test_config2_forward_4k_every_output():
     r3.forward(buf2, c.t["x"], c.t["Wr"], rec, c.t["Wg"], c.t["Wu"], c.t["Wd"])
     torch.cuda.synchronize()
     assert torch.equal(buf.y, buf2.y) and torch.equal(buf.H, buf2.H)
+    # what bench.py launches for this configuration: the forward as one call, gate folded into H and Yp
+    buf3 = r3.LayerBuffers(D, backward=False, gathered_copy=False)
+    r3.forward_one_call(buf3, c.t["x"], c.t["Wr"], rec, c.t["Wg"], c.t["Wu"], c.t["Wd"])
+    torch.cuda.synchronize()
+    assert int(buf3.status.item()) == 0
+    _check_permutation(buf3, c.idx, sh.E)
+    assert_gates_close(buf3.gates.cpu().numpy(), ref["g"])
+    grow = ref["g"].reshape(-1)[ref["perm"]]
+    assert_close(host(buf3.H), grow[:, None] * ref["h"], "g*H (one call)", c.rel)
+    assert_close(host(buf3.Yp), grow[:, None] * ref["o"], "g*Yp (one call)", c.rel)
+    assert_close(host(buf3.y), ref["y"], "y (one call)", c.rel)
 
 
 # ------------------------------------------------------------------ config 5: Zipf-skewed load, T=65536
 @pytest.fixture(scope="module")
-def zipf():
+def zipf_case():
     c = Case(synth.CONFIGS["zipf_64k"], backward=True)
-    sh, D = c.shape, c.D
-    rec = _record_on_gpu(D, c.s_infer)
-    buf = r3.LayerBuffers(D, backward=True)
-    r3.forward(buf, c.t["x"], c.t["Wr"], rec, c.t["Wg"], c.t["Wu"], c.t["Wd"], bias=c.t["bias"])
+    return c, _record_on_gpu(c.D, c.s_infer)
+
+
+# "bench": what bench.py launches (the forward as one call, no expert-sorted copy, gate folded into H and Yp,
+# the backward told so); "six_calls": the forward as separate calls with the gathered copy
+@pytest.fixture(scope="module", params=["bench", "six_calls"])
+def zipf(request, zipf_case):
+    c, rec = zipf_case
+    if request.param == "bench":
+        buf = r3.LayerBuffers(c.D, backward=True, gathered_copy=False)
+        r3.forward_one_call(buf, c.t["x"], c.t["Wr"], rec, c.t["Wg"], c.t["Wu"], c.t["Wd"], bias=c.t["bias"])
+    else:
+        buf = r3.LayerBuffers(c.D, backward=True)
+        r3.forward(buf, c.t["x"], c.t["Wr"], rec, c.t["Wg"], c.t["Wu"], c.t["Wd"], bias=c.t["bias"])
     torch.cuda.synchronize()
-    assert int(buf.status.item()) == 0
-    return c, rec, buf
+    assert int(buf.status.item()) == 0 and buf.gated == (request.param == "bench")
+    yield c, rec, buf
+    del buf
+    torch.cuda.empty_cache()
 
 
 def test_config5_record_permutation_gates(zipf):
@@ -148,14 +171,16 @@ def test_config5_down_projection_gradient_dense_dy(zipf):
     hu = buf.H.double() @ u                                             # [S]
     dyv = (c.t["dy"].double() @ v)[slot // sh.K]                        # [S]
     g = buf.gates.double().reshape(-1)[slot]
-    per_row = hu * g * dyv
+    if not buf.gated:        # (the one-call forward left g*H in buf.H)
+        hu = hu * g
+    per_row = hu * dyv
     seg = torch.repeat_interleave(torch.arange(sh.E, device="cuda"), buf.counts.long())
     zero = torch.zeros(sh.E, dtype=torch.float64, device="cuda")
     want = zero.clone().index_add_(0, seg, per_row)
     l2 = zero.clone().index_add_(0, seg, per_row * per_row).sqrt()
     l1 = zero.clone().index_add_(0, seg, per_row.abs())
     got = torch.einsum("f,efd,d->e", u, buf.dW_down.double(), v)
-    # the kernel rounds g*dy to bf16 (2^-9 relative, independent per element) before the contraction and sums
+    # the kernel rounds g*H to bf16 (2^-9 relative, independent per element) before the contraction and sums
     # in f32: the error of a segment's sum grows like 2^-9 * l2, so a dropped 256-row tile of even the
     # 65536-row segment (16 typical terms) stands far outside the bar
     err = (got - want).abs()
@@ -187,8 +212,11 @@ def test_config5_expert_gradients_dense_dy_against_the_oracle(zipf, which):
     g = sparse.replay_gate(c.s[tok], c.idx[tok])[np.arange(len(tok)), j]
     dO = g[:, None] * n["dy"][tok].astype(np.float64)
     _, _, dXp, dWg, dWu, dWd = sparse.grouped_ffn_backward(Xp, off1, *W, a, b, h, dO)
-    assert_close(host(buf.H[r0:r1]), h, "config5 H[e=%d]" % e, c.rel)
-    assert_close(host(buf.Yp[r0:r1]), o, "config5 Yp[e=%d]" % e, c.rel)
+    # (the one-call forward stores gate-scaled rows: taken back to the rows' own scale, so that the
+    # least-loaded expert's few rows, whose gates differ by orders of magnitude, share one element scale)
+    scale = g[:, None] if buf.gated else 1.0
+    assert_close(host(buf.H[r0:r1]) / scale, h, "config5 H[e=%d]" % e, c.rel)
+    assert_close(host(buf.Yp[r0:r1]) / scale, o, "config5 Yp[e=%d]" % e, c.rel)
     for got, want, name in ((buf.dW_gate[e], dWg[0], "dW_gate"), (buf.dW_up[e], dWu[0], "dW_up"),
                             (buf.dW_down[e], dWd[0], "dW_down")):
         assert_close(got.cpu().numpy(), want, "config5 %s[%d] (%d rows, dense dy)" % (name, e, r1 - r0), c.rel)
@@ -226,7 +254,8 @@ def test_config4_stack_record_replay_agreement():
         s_infer = logits + noise
         r3.record_topk(D, s_infer, record[l], status)
         # training side: replay the record
-        r3.forward(buf, x, Wr, record[l], W["Wg"], W["Wu"], W["Wd"], logits_out=logits, agree_out=agree[l])
+        r3.forward_one_call(buf, x, Wr, record[l], W["Wg"], W["Wu"], W["Wd"], logits_out=logits,
+                            agree_out=agree[l])      # (as bench.py launches it, plus the logits)
         torch.cuda.synchronize()
         assert int(status.item()) == 0 and int(buf.status.item()) == 0, l
         idx = sparse.topk_mask(s_infer.cpu().numpy(), K)

@@ -138,3 +138,32 @@ def test_without_the_gathered_copy_bit_identical(full):
     assert buf2.Xp is None and int(buf2.status.item()) == 0
     for k in ("y", "Yp", "H", "gates", "dx", "dW_r", "dW_gate", "dW_up", "dW_down"):
         assert torch.equal(getattr(buf, k), getattr(buf2, k)), k
+
+
+def test_bench_configuration_one_call_forward_and_gated_backward(full, ref):
+    """Exactly what bench.py launches: r3_moe_forward (one call, no expert-sorted copy, the gate folded into H
+    and Yp) and r3_moe_backward told so.  Every output against the oracle: H and Yp as g*h and g*o on every row,
+    y and dx on every token, dW_r under the full upstream gradient, all 128 experts' weight gradients."""
+    sh, t, n = full["sh"], full["t"], full["n"]
+    fwd, bwd = ref
+    buf = r3.LayerBuffers(full["D"], backward=True, gathered_copy=False)
+    r3.forward_one_call(buf, t["x"], t["Wr"], full["rec"], t["Wg"], t["Wu"], t["Wd"])
+    r3.backward(buf, t["dy"], t["x"], t["Wr"], full["rec"], t["Wg"], t["Wu"], t["Wd"])
+    torch.cuda.synchronize()
+    assert buf.gated and buf.Xp is None and int(buf.status.item()) == 0
+    for k in ("counts", "offsets", "inv_perm", "perm"):
+        assert torch.equal(getattr(buf, k), getattr(full["buf"], k)), k
+    assert_gates_close(buf.gates.cpu().numpy(), fwd["g"])
+    grow = fwd["g"].reshape(-1)[fwd["perm"]]
+    assert_close(host(buf.H), grow[:, None] * fwd["h"], "g*H (all rows, one call)", 1e-2)
+    assert_close(host(buf.Yp), grow[:, None] * fwd["o"], "g*Yp (all rows, one call)", 1e-2)
+    assert_close(host(buf.y), fwd["y"], "y (all tokens, one call)", 1e-2)
+    assert_close(host(buf.dx), bwd["dx"], "dx (all tokens, one call)", 1e-2)
+    sig, _ = router_gradient_sigma(n["x"], n["dy"], full["idx"], fwd, sh.E)
+    assert_close(buf.dW_r.cpu().numpy(), bwd["dWr"], "dW_r (dense dy, one call)", 1e-2, sigma=sig)
+    for got, want, name in ((buf.dW_gate, bwd["dWg"], "dW_gate"), (buf.dW_up, bwd["dWu"], "dW_up"),
+                            (buf.dW_down, bwd["dWd"], "dW_down")):
+        for e0 in range(0, sh.E, 16):
+            g = got[e0:e0 + 16].cpu().numpy()
+            for e in range(e0, min(e0 + 16, sh.E)):
+                assert_close(g[e - e0], want[e], "%s[%d] (one call)" % (name, e), 1e-2)

@@ -40,7 +40,8 @@ def assert_close(gpu, ref, name, rel, sigma=None, elem_c=None):
     2. every row (last dim), norm-wise: <= 2 rel |row|_2 + rel rms(ref) sqrt(n)
        (a single wrong token or feature row cannot hide in the tensor norm)
     3. every element: |gpu-ref| <= rel |ref| + ELEM_C rel rms(row) rms(column) / rms(ref)
-       (a misplaced element is off by about the magnitude its row and column have)
+       (a misplaced element is off by about the magnitude its row and column have; with fewer than 16
+       rows the column factor is dropped: rms(row) alone)
     `sigma` (same shape as ref, optional): modelled standard deviation of the error that the bf16
     storage of an upstream tensor induces in this one; 8 sigma is added to bars 2 and 3.  Used for the
     router gradients, where a token's dz = g (dg - sum g dg) is a difference of nearly equal numbers
@@ -65,7 +66,8 @@ def assert_close(gpu, ref, name, rel, sigma=None, elem_c=None):
     row_use = rerr / np.maximum(2 * rel * rref + rel * rms * np.sqrt(n) + rslack, 1e-300)
     # element bar: what multiple of rel * s_ij each element needs beyond rel*|ref| (and the sigma term)
     rrms = rref / np.sqrt(n)
-    crms = np.linalg.norm(ref2, axis=0) / np.sqrt(ref2.shape[0]) if ref2.shape[0] > 1 else np.full(n, rms)
+    # (a column's magnitude cannot be told from a handful of rows: below 16 rows the row scale alone is used)
+    crms = np.linalg.norm(ref2, axis=0) / np.sqrt(ref2.shape[0]) if ref2.shape[0] >= 16 else np.full(n, rms)
     scale = np.maximum(rrms[:, None] * crms[None, :] / rms, 1e-300)
     over = diff - rel * np.abs(ref2)
     need_plain = (over / (rel * scale)).max() if over.size else 0.0
