@@ -23,7 +23,10 @@ namespace r3 {
 //     to the 8 XCD shares of a tile list;
 //   tiles[kTileSeg ..)  = reduction segments (expert, row0, row1, slot), longest first, dealt the same way;
 //   tiles[kTileHot ..)  = number of split experts, then (expert, first slot, slots) for each;
-//   tiles[kTileHdr ..)  = row tiles as (expert, row0) pairs, experts ascending, rows ascending.
+//   tiles[kTileX .. +9) = where each XCD's share of the row tiles starts (and where the last one ends);
+//   tiles[kTileHdr ..)  = row tiles as (expert, row0) pairs, experts ascending, rows ascending (tiles
+//     that share a weight panel are neighbours and meet in one L2); XCD x's share is the eighth
+//     [tiles[kTileX + x], tiles[kTileX + x + 1]) of them, which its work-groups take from a counter.
 // The weight-gradient kernels' tiles last as long as their expert has rows: taken longest first from a
 // shared counter, a heavily loaded expert no longer starts late and finishes alone.  A segment is an
 // expert's whole row range, or, when `split_rows` > 0, one of ceil(n / split_rows) equal parts of it
@@ -38,7 +41,8 @@ namespace r3 {
 constexpr int kRowTokensPad = 64;   // zeros after the row->token list
 constexpr int kMaxSplitSlots = 32;
 constexpr int kMaxSegs = kMaxE + kMaxSplitSlots + 8;
-constexpr int kTileOrder = 2 + 64;
+constexpr int kTileX = 2 + 64;               // 9 ints: first row tile of every XCD's share, and the end
+constexpr int kTileOrder = kTileX + 16;
 constexpr int kTileSeg = kTileOrder + kMaxE;
 constexpr int kTileHot = kTileSeg + 4 * kMaxSegs;
 constexpr int kTileHdr = kTileHot + 1 + 3 * kMaxSplitSlots + 3;
@@ -119,32 +123,34 @@ build_row_tiles_kernel(int E, int BQ, const int32_t *__restrict__ offsets, int32
     // thread adding them up one after the other pays an LDS round trip per expert: 6 us for 128 experts,
     // in a kernel that sits between two others on every pass.)
     constexpr int PER = kMaxE / 1024;
-    __shared__ int32_t scan[3][1024];
-    int nt[PER], np[PER], tot[3] = {0, 0, 0};
+    constexpr int NS = 3;                    // scanned: row tiles, parts, split experts
+    __shared__ int32_t scan[NS][1024];
+    int nt[PER], np[PER], tot[NS] = {0, 0, 0};
 #pragma unroll
     for (int i = 0; i < PER; ++i) {
         const int e = PER * threadIdx.x + i;
         const int n = e < E ? off[e + 1] - off[e] : 0;
-        nt[i] = e < E ? (n + BQ - 1) / BQ : 0;
+        nt[i] = (n + BQ - 1) / BQ;
         np[i] = e < E ? (split_rows > 0 ? max(1, (n + split_rows - 1) / split_rows) : 1) : 0;
         tot[0] += nt[i];
         tot[1] += np[i];
         tot[2] += np[i] > 1;
     }
-    for (int k = 0; k < 3; ++k) scan[k][threadIdx.x] = tot[k];
+    for (int k = 0; k < NS; ++k) scan[k][threadIdx.x] = tot[k];
     __syncthreads();
     for (int dlt = 1; dlt < 1024; dlt <<= 1) {
-        int v[3];
-        for (int k = 0; k < 3; ++k) v[k] = (int)threadIdx.x >= dlt ? scan[k][threadIdx.x - dlt] : 0;
+        int v[NS];
+        for (int k = 0; k < NS; ++k) v[k] = (int)threadIdx.x >= dlt ? scan[k][threadIdx.x - dlt] : 0;
         __syncthreads();
-        for (int k = 0; k < 3; ++k) scan[k][threadIdx.x] += v[k];
+        for (int k = 0; k < NS; ++k) scan[k][threadIdx.x] += v[k];
         __syncthreads();
     }
+    const int ntiles = scan[0][1023];
     // more parts than there are slots for (the caller's split_rows rules that out): no splitting at all
     const bool split = scan[1][1023] - E <= kMaxSplitSlots;
     {
-        int run[3];
-        for (int k = 0; k < 3; ++k) run[k] = scan[k][threadIdx.x] - tot[k];   // exclusive
+        int run[NS];
+        for (int k = 0; k < NS; ++k) run[k] = scan[k][threadIdx.x] - tot[k];   // exclusive
 #pragma unroll
         for (int i = 0; i < PER; ++i) {
             const int e = PER * threadIdx.x + i;
@@ -164,9 +170,9 @@ build_row_tiles_kernel(int E, int BQ, const int32_t *__restrict__ offsets, int32
     }
     if (threadIdx.x == 1023) {
         const int segs = split ? scan[1][1023] : E;
-        start[E] = scan[0][1023];
+        start[E] = ntiles;
         seg0[E] = segs;
-        tiles[0] = scan[0][1023];
+        tiles[0] = ntiles;
         tiles[kTileHot] = split ? scan[2][1023] : 0;
         nseg_s = (segs + 7) & ~7;
         tiles[1] = nseg_s;
@@ -175,6 +181,7 @@ build_row_tiles_kernel(int E, int BQ, const int32_t *__restrict__ offsets, int32
     block_ranks(E, [&](int e) { return off[e + 1] - off[e]; }, rnk);
     for (int e = threadIdx.x; e < E; e += blockDim.x)
         tiles[kTileOrder + (E % 8 == 0 ? dealt_position(rnk[e], E) : rnk[e])] = e;
+    if (threadIdx.x <= 8) tiles[kTileX + threadIdx.x] = (int)(((int64_t)ntiles * threadIdx.x) >> 3);
     for (int e = threadIdx.x; e < E; e += blockDim.x) {
         const int n = start[e + 1] - start[e];
         for (int i = 0; i < n; ++i) {
@@ -271,7 +278,8 @@ ffn1_kernel(int S, int d, int F, const bf16_t *__restrict__ Xp, const int32_t *_
     P.init(F * 2, 0, 64 * ((threadIdx.x >> 6) % kWP2));
     OpKC64<GATHER> Q;
     Q.init(d * 2, kWaveRowsQ * ((threadIdx.x >> 6) / kWP2));
-    RowTileLoop tl(tiles[0] * npt);
+    __shared__ int mailbox[2];
+    RowTileLoop tl(tiles + kTileX, npt, tile_counters(tiles, 0));
     struct Tile {
         int e, row0, row_end, f0;
     };
@@ -317,6 +325,7 @@ ffn1_kernel(int S, int d, int F, const bf16_t *__restrict__ Xp, const int32_t *_
     zero_acc2(acc);
     if (row_end - row0 <= kWaveRowsQ) mfma_tail_loop3(acc, d / kBK3, P, Q, lds);
     else mfma_mainloop3(acc, d / kBK3, P, Q, lds, row_end - row0);
+    tl.prefetch();
     if (more) aim(nxt);   // here, so that the row-index loads of a gathered tile hide behind the epilogue
 
     // per wave: 64 rows x 64 features of H (and FA, FB), 32 rows at a time through LDS
@@ -361,7 +370,7 @@ ffn1_kernel(int S, int d, int F, const bf16_t *__restrict__ Xp, const int32_t *_
             sb.flush((char *)FB + o, (int64_t)F * 2, valid);
         }
     }
-    const int after = tl.finish();
+    const int after = tl.finish(mailbox);
     slot = next;
     next = after;
     cur = nxt;
@@ -419,7 +428,8 @@ rowgemm_kernel(int S, int d, int F, const bf16_t *__restrict__ Q0, const bf16_t 
     }
     Q.init(KQ * 2, kWaveRowsQ * wq0, qstash);
     if constexpr (MODE == 2) Q.wswitch = F / kBK3;
-    RowTileLoop tl(tiles[0] * npt);
+    __shared__ int mailbox[2];
+    RowTileLoop tl(tiles + kTileX, npt, tile_counters(tiles, MODE == 1 ? 0 : 1));
     struct Tile {
         int e, row0, row_end, p0;
     };
@@ -484,6 +494,7 @@ rowgemm_kernel(int S, int d, int F, const bf16_t *__restrict__ Q0, const bf16_t 
     zero_acc2(acc);
     if (row_end - row0 <= kWaveRowsQ) mfma_tail_loop3(acc, nw, P, Q, lds);
     else mfma_mainloop3(acc, nw, P, Q, lds, row_end - row0);
+    tl.prefetch();
     if constexpr (GATHER)
         if (more) aim(nxt);   // here, so that the row-index loads of the next tile hide behind the epilogue
 
@@ -578,7 +589,7 @@ rowgemm_kernel(int S, int d, int F, const bf16_t *__restrict__ Q0, const bf16_t 
             st.flush((char *)out0 + o, (int64_t)NOUT * 2, valid);
         }
     }
-    const int after = tl.finish();
+    const int after = tl.finish(mailbox);
     slot = next;
     next = after;
     cur = nxt;

@@ -845,7 +845,7 @@ struct TileLoopT {
             // not __syncthreads(): its fence would also wait for this tile's global stores
             asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
             ++iter;
-            return *box;
+            return __builtin_amdgcn_readfirstlane(*box);   // wave-uniform, and visibly so: tile coordinates stay scalar
         } else {
             asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
             ++iter;
@@ -855,34 +855,50 @@ struct TileLoopT {
 };
 typedef TileLoopT<true> TileLoop;          // tiles of uneven length (weight gradients)
 
-// The row-tiled kernels' loop: XCD x owns the contiguous range [total x / 8, total (x + 1) / 8) of the
-// tile list (tiles that share an operand panel sit next to each other and so meet in one L2) and its
-// work-groups walk it round-robin.  Two orderings meant to cut the L2's re-fetches of operand panels
-// were measured on the 16384-token layer and dropped: listing the short tail tiles after all full
-// tiles (so that a tail does not knock its work-group half a tile out of step with the others that
-// share its panels) cut the fetched bytes by 7 % (SwiGLU) to 15 % (dXp) and ran 1-3 % slower; making
-// the work-groups of an XCD start each round of tiles together (a bounded wait on a per-XCD counter)
-// cut them by 20 % and ran 12-23 % slower.  An XCD's round of 32 tiles does not line up with an
-// expert's 24-30 tiles, so even in lockstep most weight panels are fetched in two rounds, and the
+// The row-tiled kernels' loop: XCD x owns the share [share[x], share[x + 1]) of the row-tile list, times the
+// column tiles (tiles that share an operand panel sit next to each other and so meet in one L2).  A
+// work-group's first two tiles are fixed (its index and its index plus the stride), the rest come from
+// the share's counter, asked for a tile ahead (prefetch() after the tile loop, finish() hands the answer
+// to all waves through `mailbox`, two ints of LDS outside the stage buffers).  Results do not depend on
+// who ran which tile.  Measured on the 16384-token layer against a fixed round-robin: -1.5 % (down
+// projection) and -2 % (dXp), the others unchanged.  Listing the short tail tiles last in every share, so
+// that they fill up the last round (13.5 tiles per compute unit: by tile counts alone worth 5-7 % on the
+// SwiGLU and dH kernels), made every row-tiled kernel 1-8 % slower instead: a tail tile then meets its
+// expert's weight panels cold, long after the full tiles that shared them.
+// Two ways of cutting the L2's re-fetches of operand panels were measured there as well and
+// dropped: short tiles last under a fixed round-robin (fetched bytes -7 % (SwiGLU) to -15 % (dXp), time
+// +1-3 %), and making the work-groups of an XCD start each round of tiles together (a bounded wait on a
+// per-XCD counter: fetched bytes -20 %, time +12-23 %).  An XCD's round of 32 tiles does not line up with
+// an expert's 24-30 tiles, so even in lockstep most weight panels are fetched in two rounds, and the
 // fabric was not what the kernels were waiting for.
 struct RowTileLoop {
-    int start, cnt, stride, iter;
-    __device__ __forceinline__ RowTileLoop(int total) : stride(gridDim.x >> 3), iter(0) {
+    int start, cnt, stride, iter, nxt;
+    int *ctr;
+    // share: 9 ints (row-tile units); npt: column tiles per row tile; ctr_row: the launch's 8 counters
+    __device__ __forceinline__ RowTileLoop(const int32_t *share, int npt, int *ctr_row)
+        : stride(gridDim.x >> 3), iter(0), nxt(0) {
         const int xcd = blockIdx.x & 7;
-        start = (int)(((int64_t)total * xcd) >> 3);
-        cnt = (int)(((int64_t)total * (xcd + 1)) >> 3) - start;
+        start = share[xcd] * npt;
+        cnt = (share[xcd + 1] - share[xcd]) * npt;
+        ctr = ctr_row + xcd;
     }
     __device__ __forceinline__ int first() const { return blockIdx.x >> 3; }
     __device__ __forceinline__ int second() const { return (blockIdx.x >> 3) + stride; }
     __device__ __forceinline__ bool valid(int slot) const { return slot < cnt; }
     __device__ __forceinline__ int id(int slot) const { return start + slot; }
+    // ask for the slot two after the current one; call after the tile loop
+    __device__ __forceinline__ void prefetch() {
+        if (threadIdx.x == kQueueThread) nxt = 2 * stride + atomicAdd(ctr, 1);
+    }
     // end of a tile: every wave's LDS traffic of the epilogue is complete and the waves have met
     // before anyone loads the next tile into the stage buffers; returns the slot two after the
     // current one.  (Not __syncthreads(): its fence would also wait for this tile's global stores.)
-    __device__ __forceinline__ int finish() {
+    __device__ __forceinline__ int finish(volatile int *mailbox) {
+        volatile int *box = mailbox + (iter & 1);
+        if (threadIdx.x == kQueueThread) *box = nxt;
         asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
         ++iter;
-        return first() + (iter + 1) * stride;
+        return __builtin_amdgcn_readfirstlane(*box);   // wave-uniform, and visibly so: tile coordinates stay scalar
     }
 };
 
