@@ -330,9 +330,10 @@ int r3_moe_backward(const r3_layer_desc *desc, const void *dy, const void *x, co
         int32_t *tiles = (int32_t *)(base + w.tiles), *tok = (int32_t *)(base + w.tok);
         float *grow = (float *)(base + w.grow), *wpart = (float *)(base + w.wpart);
         void *Hg = gated ? nullptr : base + w.Hg;
-        // a heavily loaded expert's dW_down reduction is cut into parts; their partial products sit in
-        // the dXp buffer, which nothing uses before the parts are summed
-        const size_t slot_bytes = (size_t)m.F * m.d * sizeof(float);
+        // a heavily loaded expert's weight-gradient reductions are cut into parts; their partial products
+        // sit in the dXp buffer, which nothing uses before the parts are summed (dW_down's first, then, in
+        // the same place, dW_gate's and dW_up's side by side)
+        const size_t slot_bytes = 2 * (size_t)m.F * m.d * sizeof(float);
         const int split = mfma_wgrad_split_rows(m.S, (m.F / 256) * (m.d / 256), (size_t)m.S * m.d * m.eb, slot_bytes);
         if (mfma_build_tiles_and_row_tokens(m.E, offsets, tiles, split, S, m.K, perm, gates, tok, grow, s) != hipSuccess)
             return R3_ERR_HIP;
@@ -345,8 +346,8 @@ int r3_moe_backward(const r3_layer_desc *desc, const void *dy, const void *x, co
         if (mfma_wgrad(m.E, m.F, m.d, gated ? H : Hg, dy, tok, m.T, tiles, 2, dW_down, split ? (float *)dXp : nullptr,
                        accumulate, s) != hipSuccess)
             return R3_ERR_HIP;
-        if (mfma_wgrad_pair(m.E, m.d, m.F, Xp ? Xp : x, Xp ? nullptr : tok, m.T, dA, dB, offsets, tiles, 3, dW_gate,
-                            dW_up, accumulate, s) != hipSuccess)
+        if (mfma_wgrad_pair(m.E, m.d, m.F, Xp ? Xp : x, Xp ? nullptr : tok, m.T, dA, dB, tiles, 3, dW_gate, dW_up,
+                            split ? (float *)dXp : nullptr, accumulate, s) != hipSuccess)
             return R3_ERR_HIP;
         if (mfma_ffn_dxp(m.S, m.d, m.E, m.F, dA, dB, offsets, tiles, W_gate, W_up, dXp, s) != hipSuccess)
             return R3_ERR_HIP;

@@ -19,9 +19,8 @@ namespace r3 {
 // Tile table, built by one block per pass:
 //   tiles[0] = number of row tiles; tiles[1] = number of reduction segments (a multiple of 8);
 //   tiles[2 .. 2+64) = the tile counters of up to eight persistent launches (8 XCDs each, zeroed here);
-//   tiles[kTileOrder ..) = the experts in descending order of row count (ties by id), dealt out evenly
-//     to the 8 XCD shares of a tile list;
-//   tiles[kTileSeg ..)  = reduction segments (expert, row0, row1, slot), longest first, dealt the same way;
+//   tiles[kTileSeg ..)  = reduction segments (expert, row0, row1, slot), longest first, dealt out evenly to
+//     the 8 XCD shares of a tile list;
 //   tiles[kTileHot ..)  = number of split experts, then (expert, first slot, slots) for each;
 //   tiles[kTileX .. +9) = where each XCD's share of the row tiles starts (and where the last one ends);
 //   tiles[kTileHdr ..)  = row tiles as (expert, row0) pairs, experts ascending, rows ascending (tiles
@@ -42,8 +41,7 @@ constexpr int kRowTokensPad = 64;   // zeros after the row->token list
 constexpr int kMaxSplitSlots = 32;
 constexpr int kMaxSegs = kMaxE + kMaxSplitSlots + 8;
 constexpr int kTileX = 2 + 64;               // 9 ints: first row tile of every XCD's share, and the end
-constexpr int kTileOrder = kTileX + 16;
-constexpr int kTileSeg = kTileOrder + kMaxE;
+constexpr int kTileSeg = kTileX + 16;
 constexpr int kTileHot = kTileSeg + 4 * kMaxSegs;
 constexpr int kTileHdr = kTileHot + 1 + 3 * kMaxSplitSlots + 3;
 __device__ __forceinline__ int *tile_counters(const int32_t *tiles, int launch) {
@@ -178,9 +176,7 @@ build_row_tiles_kernel(int E, int BQ, const int32_t *__restrict__ offsets, int32
         tiles[1] = nseg_s;
     }
     if (threadIdx.x < 64) tiles[2 + threadIdx.x] = 0;
-    block_ranks(E, [&](int e) { return off[e + 1] - off[e]; }, rnk);
-    for (int e = threadIdx.x; e < E; e += blockDim.x)
-        tiles[kTileOrder + (E % 8 == 0 ? dealt_position(rnk[e], E) : rnk[e])] = e;
+    __syncthreads();
     if (threadIdx.x <= 8) tiles[kTileX + threadIdx.x] = (int)(((int64_t)ntiles * threadIdx.x) >> 3);
     for (int e = threadIdx.x; e < E; e += blockDim.x) {
         const int n = start[e + 1] - start[e];
@@ -698,10 +694,10 @@ wgrad_kernel(int NQd, int NPd, const bf16_t *__restrict__ Qs, const bf16_t *__re
 // (dW_gate, dW_up straight from x: no gathered copy of the tokens is read).
 template <bool GATHER>
 __global__ void __launch_bounds__(kThreads2, kMinWavesPerSimd)
-wgrad_pair_kernel(int E, int NQd, int NPd, const bf16_t *__restrict__ Qs, const int32_t *__restrict__ tok, int nrows,
-                  const bf16_t *__restrict__ P0, const bf16_t *__restrict__ P1, const int32_t *__restrict__ offsets,
-                  float *__restrict__ out0, float *__restrict__ out1, int accumulate, int *ctr,
-                  const int32_t *__restrict__ order) {
+wgrad_pair_kernel(int NQd, int NPd, const bf16_t *__restrict__ Qs, const int32_t *__restrict__ tok, int nrows,
+                  const bf16_t *__restrict__ P0, const bf16_t *__restrict__ P1, const int32_t *__restrict__ tiles,
+                  float *__restrict__ out0, float *__restrict__ out1, float *__restrict__ part0,
+                  float *__restrict__ part1, int accumulate, int *ctr) {
     __shared__ __attribute__((aligned(1024))) char s0[kStageBytes];
     __shared__ __attribute__((aligned(1024))) char s1[kStageBytes];
     __shared__ __attribute__((aligned(1024))) char s2[kStageBytes];
@@ -720,15 +716,17 @@ wgrad_pair_kernel(int E, int NQd, int NPd, const bf16_t *__restrict__ Qs, const 
         Q.kswitch = 0x7fffffff;
         Q.init(NQd * 2, 0, kWaveRowsQ * wq0);
     }
-    TileLoop tl(E * nqt * npt, ctr);
+    // reduction segments as in wgrad_kernel: an expert's rows or one part of them
+    TileLoop tl(tiles[1] * nqt * npt, ctr);
     for (int slot = tl.first(), next = tl.second(); tl.valid(slot);) {
     const int id = tl.id(slot);
     const int eo = id / (nqt * npt);
     const int rem = id - eo * nqt * npt;
-    const int e = order[eo];
+    const int32_t *sg = tiles + kTileSeg + 4 * eo;
+    const int e = sg[0], r0 = sg[1], r1 = sg[2], pslot = sg[3];
     const int qt = rem / npt, pt = rem - qt * npt;
-    const int r0 = offsets[e], r1 = offsets[e + 1];
     const int q0 = qt * kTile, p0 = pt * BF;
+    if (pslot != -2) {
     const uint64_t pbytes = clamp_bytes(((int64_t)(r1 - r0) * NPd - p0) * 2);
     P.src[0] = Src{(const char *)(P0 + (int64_t)r0 * NPd + p0), pbytes, (uint32_t)(kBK2 * NPd * 2)};
     P.src[1] = Src{(const char *)(P1 + (int64_t)r0 * NPd + p0), pbytes, (uint32_t)(kBK2 * NPd * 2)};
@@ -763,10 +761,14 @@ wgrad_pair_kernel(int E, int NQd, int NPd, const bf16_t *__restrict__ Qs, const 
                              make_float4(acc[tp][tq][4 * g], acc[tp][tq][4 * g + 1], acc[tp][tq][4 * g + 2],
                                          acc[tp][tq][4 * g + 3]));
                 }
-            char *o = (char *)((half ? out1 : out0) + (int64_t)e * NQd * NPd);
+            char *o = (char *)(pslot < 0 ? (half ? out1 : out0) + (int64_t)e * NQd * NPd
+                                         : (half ? part1 : part0) + (int64_t)pslot * NQd * NPd);
             const int64_t off = ((int64_t)(q0 + wq * kWaveRowsQ + tq * 32) * NPd + p0 + wp * 64) * 4;
-            st.flush_f32(o + off, (int64_t)NPd * 4, 32, accumulate);
+            st.flush_f32(o + off, (int64_t)NPd * 4, 32, pslot < 0 ? accumulate : 0);
         }
+    } else {
+        tl.prefetch();
+    }
     const int after = tl.finish(mailbox);
     slot = next;
     next = after;
@@ -996,22 +998,27 @@ split_reduce_kernel(int d, int E, int nsplit, const float *__restrict__ part, fl
 
 // ---------------------------------------------------------------------------
 // The partial products of split reductions into their gradients: for every split expert, in slot order
-// (a fixed order: the sum does not depend on the launch shape).  n4 = float4s per expert matrix.
+// (a fixed order: the sum does not depend on the launch shape).  n4 = float4s per expert matrix; a
+// second gradient with slots of its own (out1, part1) is optional.
 // ---------------------------------------------------------------------------
 __global__ void __launch_bounds__(256)
-wgrad_parts_kernel(int64_t n4, const int32_t *__restrict__ tiles, float *__restrict__ out,
-                   const float *__restrict__ part) {
+wgrad_parts_kernel(int64_t n4, const int32_t *__restrict__ tiles, float *__restrict__ out0,
+                   const float *__restrict__ part0, float *__restrict__ out1, const float *__restrict__ part1) {
     const int hot = tiles[kTileHot];
     for (int j = 0; j < hot; ++j) {
         const int e = tiles[kTileHot + 1 + 3 * j], s0 = tiles[kTileHot + 2 + 3 * j], ns = tiles[kTileHot + 3 + 3 * j];
-        float4 *o = (float4 *)out + (int64_t)e * n4;
-        for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n4; i += (int64_t)gridDim.x * blockDim.x) {
-            float4 a = o[i];
-            for (int p = 0; p < ns; ++p) {
-                const float4 b = ((const float4 *)part)[(int64_t)(s0 + p) * n4 + i];
-                a.x += b.x; a.y += b.y; a.z += b.z; a.w += b.w;
+        for (int which = 0; which < (out1 ? 2 : 1); ++which) {
+            float4 *o = (float4 *)(which ? out1 : out0) + (int64_t)e * n4;
+            const float4 *p = (const float4 *)(which ? part1 : part0) + (int64_t)s0 * n4;
+            for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n4;
+                 i += (int64_t)gridDim.x * blockDim.x) {
+                float4 a = o[i];
+                for (int q = 0; q < ns; ++q) {
+                    const float4 b = p[(int64_t)q * n4 + i];
+                    a.x += b.x; a.y += b.y; a.z += b.z; a.w += b.w;
+                }
+                o[i] = a;
             }
-            o[i] = a;
         }
     }
 }
@@ -1126,23 +1133,26 @@ hipError_t mfma_wgrad(int E, int NQd, int NPd, const void *Qs, const void *Ps, c
         wgrad_kernel<false><<<persistent_grid(ntiles), kThreads2, 0, s>>>(
             NQd, NPd, (const bf16_t *)Qs, (const bf16_t *)Ps, nullptr, 0, tiles, out, part, accumulate,
             const_cast<int *>(tiles) + 2 + 8 * launch);
-    if (part) wgrad_parts_kernel<<<512, 256, 0, s>>>((int64_t)NQd * NPd / 4, tiles, out, part);
+    if (part) wgrad_parts_kernel<<<512, 256, 0, s>>>((int64_t)NQd * NPd / 4, tiles, out, part, nullptr, nullptr);
     return hipGetLastError();
 }
 
 hipError_t mfma_wgrad_pair(int E, int NQd, int NPd, const void *Qs, const int32_t *tok, int nrows, const void *P0,
-                           const void *P1, const int32_t *offsets, const int32_t *tiles, int launch, float *out0,
-                           float *out1, int accumulate, hipStream_t s) {
-    const int64_t ntiles = (int64_t)E * (NQd / kTile) * (NPd / 128);
+                           const void *P1, const int32_t *tiles, int launch, float *out0, float *out1, float *part,
+                           int accumulate, hipStream_t s) {
+    const int64_t ntiles = (int64_t)(E + kMaxSplitSlots + 8) * (NQd / kTile) * (NPd / 128);
+    const int64_t n = (int64_t)NQd * NPd;
+    float *part1 = part ? part + (int64_t)kMaxSplitSlots * n : nullptr;   // the second product's slots
     ProfScope ps(PROF_WGRAD_PAIR, s);
     if (tok)
         wgrad_pair_kernel<true><<<persistent_grid(ntiles), kThreads2, 0, s>>>(
-            E, NQd, NPd, (const bf16_t *)Qs, tok, nrows, (const bf16_t *)P0, (const bf16_t *)P1, offsets, out0, out1,
-            accumulate, const_cast<int *>(tiles) + 2 + 8 * launch, tiles + kTileOrder);
+            NQd, NPd, (const bf16_t *)Qs, tok, nrows, (const bf16_t *)P0, (const bf16_t *)P1, tiles, out0, out1, part,
+            part1, accumulate, const_cast<int *>(tiles) + 2 + 8 * launch);
     else
         wgrad_pair_kernel<false><<<persistent_grid(ntiles), kThreads2, 0, s>>>(
-            E, NQd, NPd, (const bf16_t *)Qs, nullptr, 0, (const bf16_t *)P0, (const bf16_t *)P1, offsets, out0, out1,
-            accumulate, const_cast<int *>(tiles) + 2 + 8 * launch, tiles + kTileOrder);
+            NQd, NPd, (const bf16_t *)Qs, nullptr, 0, (const bf16_t *)P0, (const bf16_t *)P1, tiles, out0, out1, part,
+            part1, accumulate, const_cast<int *>(tiles) + 2 + 8 * launch);
+    if (part) wgrad_parts_kernel<<<512, 256, 0, s>>>(n / 4, tiles, out0, part, out1, part1);
     return hipGetLastError();
 }
 

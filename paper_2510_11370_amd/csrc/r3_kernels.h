@@ -93,7 +93,7 @@ bool mfma_router_supported(int d, int E);
 size_t mfma_tiles_bytes(int64_t S, int E);
 size_t mfma_dwr_ws_bytes(int T, int d, int E);
 // split_rows > 0: experts with more rows than that are cut into parts of at most that many rows for the
-// down-projection weight gradient (mfma_wgrad_split_rows picks it); 0: never; < 0: the pass has no
+// weight gradients (mfma_wgrad_split_rows picks it); 0: never; < 0: the pass has no
 // weight gradients and the table gets no reduction segments at all
 hipError_t mfma_build_tiles(int E, const int32_t *offsets, int32_t *tiles, int split_rows, hipStream_t s);
 // the same launch also makes the row -> token list and the per-row gates (see mfma_row_tokens)
@@ -127,9 +127,11 @@ hipError_t mfma_wgrad(int E, int NQd, int NPd, const void *Qs, const void *Ps, c
 // out0 (+)= Qs^T P0 and out1 (+)= Qs^T P1 per expert in one pass over Qs.  tok != NULL: Qs is the
 // un-permuted [nrows, NQd] matrix and row r of the reduction is its row tok[r] (a list made by
 // mfma_row_tokens; nrows * NQd * 2 < 2^31)
+// `part` (split tables only, else NULL): room for the partial products of both gradients, 2 x the slots of
+// mfma_wgrad's
 hipError_t mfma_wgrad_pair(int E, int NQd, int NPd, const void *Qs, const int32_t *tok, int nrows, const void *P0,
-                           const void *P1, const int32_t *offsets, const int32_t *tiles, int launch, float *out0,
-                           float *out1, int accumulate, hipStream_t s);
+                           const void *P1, const int32_t *tiles, int launch, float *out0, float *out1, float *part,
+                           int accumulate, hipStream_t s);
 // tok[r] = perm[r] / K (r < S), padded; mfma_row_tokens_bytes(S) bytes.  gates != NULL: also
 // grow[r] = gates[perm[r]] (f32 [S])
 size_t mfma_row_tokens_bytes(int64_t S);   // (the kernel is plain: every path may use it)
