@@ -9,20 +9,27 @@ from paper_2510_11370_amd import r3, synth
 pytestmark = pytest.mark.gpu
 
 
-@pytest.mark.parametrize("gathered_copy", [False, True])
-def test_forward_backward_replays_from_a_graph(gathered_copy):
+# (gathered copy of the tokens, forward as one call); the middle case is what bench.py launches, the skewed one
+# also splits weight-gradient reductions (partial products summed by a second launch)
+@pytest.mark.parametrize("gathered_copy,one_call,skewed", [(False, False, False), (False, True, False),
+                                                           (True, False, False), (False, True, True)])
+def test_forward_backward_replays_from_a_graph(gathered_copy, one_call, skewed):
     sh = synth.LayerShape(T=1111, d=512, E=128, K=8, F=768, sigma=0.02, zipf_s=1.2, seed=41)
+    if skewed:
+        sh = synth.LayerShape(T=9216, d=256, E=128, K=4, F=256, sigma=0.02, zipf_s=2.5, seed=42)
     dev = "cuda"
     D = r3.desc(sh.T, sh.d, sh.E, sh.K, sh.F, sh.act)
     t = {k: synth.draw(sh, k, dev).to(torch.bfloat16) for k in ("x", "Wr", "Wg", "Wu", "Wd", "dy")}
-    logits = (t["x"].float() @ t["Wr"].float()) + synth.draw(sh, "noise", dev)
+    bias = synth.draw(sh, "bias", dev)
+    logits = (t["x"].float() @ t["Wr"].float()) + bias + synth.draw(sh, "noise", dev)
     rec = torch.zeros(sh.T, sh.K, dtype=torch.uint8, device=dev)
     buf = r3.LayerBuffers(D, backward=True, gathered_copy=gathered_copy)
     outs = ("y", "dx", "dW_r", "dW_gate", "dW_up", "dW_down", "gates", "perm")
 
     def step():
         r3.record_topk(D, logits, rec, buf.status)
-        r3.forward(buf, t["x"], t["Wr"], rec, t["Wg"], t["Wu"], t["Wd"])
+        (r3.forward_one_call if one_call else r3.forward)(buf, t["x"], t["Wr"], rec, t["Wg"], t["Wu"], t["Wd"],
+                                                          bias=bias)
         r3.backward(buf, t["dy"], t["x"], t["Wr"], rec, t["Wg"], t["Wu"], t["Wd"])
 
     step()
